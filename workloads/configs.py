@@ -1,0 +1,80 @@
+"""The five benchmark configurations, as shapes only.
+
+These describe the layer shapes, token counts and schedules of the workloads
+the build measures; they hold no arithmetic of the method.  Image-token keep
+counts come from the caller (library helper or oracle), never from here.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Tuple
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    dtype: str                 # "bf16" | "f32"
+    batch: int
+    layers: int
+    hidden: int                # C
+    n_q_heads: int             # H_q
+    n_kv_heads: int            # H_kv
+    head_dim: int              # d
+    n_sys: int                 # tokens before the image span
+    n_img: int
+    n_text: int                # instruction tokens after the image span
+    n_clusters: int            # Gaussian cluster centres of the image hidden states
+    cluster_tile: int = 0      # >0: clusters are drawn per tile of this many image tokens
+    noise_sigma: float = 0.1
+    merge_layers: Tuple[int, ...] = ()
+    final_keep: Tuple[float, ...] = ()      # final image keep fractions to run
+    kv_first_layer: int = 5
+    kv_beta: float = 0.995
+    kv_budget: int = 0         # per-head entry budget during decode (0 = none)
+    decode_steps: int = 0
+    salient_frac: float = 0.0  # fraction of image keys with a logit bias
+    salient_bias: float = 0.0
+    drift_sigma: float = 0.0   # random-walk step of the decode q/k mean
+    seed: int = 0
+    notes: str = ""
+
+    @property
+    def seq_len(self) -> int:
+        return self.n_sys + self.n_img + self.n_text
+
+    @property
+    def group(self) -> int:
+        return self.n_q_heads // self.n_kv_heads
+
+
+CFG1 = Workload(
+    name="cfg1_tiny_fp32", dtype="f32", batch=1, layers=1, hidden=256, n_q_heads=4, n_kv_heads=4,
+    head_dim=64, n_sys=32, n_img=576, n_text=32, n_clusters=16, merge_layers=(0,), final_keep=(0.5,),
+    kv_first_layer=0, kv_budget=256, decode_steps=64,
+    notes="one pyramid step keeping 50 % of image tokens, then 64 decode steps with a 256-entry budget")
+
+CFG2 = Workload(
+    name="cfg2_qwen25vl7b_bf16", dtype="bf16", batch=1, layers=28, hidden=3584, n_q_heads=28,
+    n_kv_heads=4, head_dim=128, n_sys=64, n_img=2048, n_text=64, n_clusters=64,
+    merge_layers=(5, 9, 13), final_keep=(1.0, 0.35, 0.03), kv_first_layer=5, kv_budget=1024, decode_steps=1,
+    notes="Qwen2.5-VL-7B-shaped stack; merge at layers 5/9/13 (App. A.2)")
+
+CFG3 = Workload(
+    name="cfg3_internvl25_8b_bf16", dtype="bf16", batch=8, layers=32, hidden=4096, n_q_heads=32,
+    n_kv_heads=8, head_dim=128, n_sys=0, n_img=1792, n_text=96, n_clusters=32, cluster_tile=256,
+    merge_layers=(8, 16, 24), final_keep=(0.35,), kv_first_layer=8, salient_frac=0.05, salient_bias=3.0,
+    notes="7 tiles x 256 image tokens, 32 clusters per tile; quarter-depth merge layers")
+
+CFG4 = Workload(
+    name="cfg4_long_decode_bf16", dtype="bf16", batch=16, layers=28, hidden=3584, n_q_heads=28,
+    n_kv_heads=4, head_dim=128, n_sys=64, n_img=768, n_text=192, n_clusters=64,
+    kv_budget=1024, decode_steps=4096, drift_sigma=0.01,
+    notes="prefill 1024 tokens (768 image), 4096 generated tokens, eviction every step, budget 1024")
+
+CFG5 = Workload(
+    name="cfg5_internvl25_26b_bf16", dtype="bf16", batch=1, layers=48, hidden=6144, n_q_heads=48,
+    n_kv_heads=8, head_dim=128, n_sys=0, n_img=16384, n_text=128, n_clusters=256,
+    merge_layers=(12, 24, 36), final_keep=(0.03,), kv_first_layer=12, kv_budget=2048, decode_steps=2048,
+    notes="16384 image tokens down to 3 %, then 2048 decode steps with a 2048-entry budget")
+
+ALL = {w.name.split("_")[0]: w for w in (CFG1, CFG2, CFG3, CFG4, CFG5)}
