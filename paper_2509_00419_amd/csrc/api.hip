@@ -1,0 +1,293 @@
+// The C ABI: context, workspace bookkeeping, host helpers and argument
+// validation.  Nothing here touches the GPU except hipSetDevice before a
+// launch; every check runs on the host before anything is enqueued.
+#include <math.h>
+#include <stdarg.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+using namespace lvlm;
+
+namespace {
+
+lvlm_status fail(lvlm_ctx *ctx, lvlm_status st, const char *fmt, ...) {
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return st;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool float_dtype(int dt) { return dt == LVLM_BF16 || dt == LVLM_F32; }
+int elem_bytes(int dt) { return dt == LVLM_BF16 ? 2 : 4; }
+
+const char *check_score(const lvlm_score_desc *d) {
+    if (!d) return "null descriptor";
+    if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
+    if (d->hd != 64 && d->hd != 128) return "head dimension must be 64 or 128";
+    if (d->B < 1 || d->N < 1 || d->T < 1 || d->Hq < 1 || d->Hkv < 1) return "sizes must be positive";
+    if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
+    if (d->img_begin < 0 || d->n_img < 1 || (long long)d->img_begin + d->n_img > d->N) return "image span outside [0, N)";
+    if (d->q_pos0 < 0) return "q_pos0 must be non-negative";
+    const int vec = 16 / elem_bytes(d->dtype);
+    const long long s[6] = {d->q_stride_b, d->q_stride_t, d->q_stride_h, d->k_stride_b, d->k_stride_n, d->k_stride_h};
+    for (long long x : s)
+        if (x < 0 || x % vec != 0) return "strides must be non-negative multiples of 16 bytes";
+    if (d->q_stride_h < d->hd || d->k_stride_h < d->hd) return "head stride smaller than the head dimension";
+    return nullptr;
+}
+
+const char *check_merge(const lvlm_merge_desc *d, const lvlm_plane *planes) {
+    if (!d) return "null descriptor";
+    if (d->B < 1 || d->N < 1) return "sizes must be positive";
+    if (d->img_begin < 0 || d->n_img < 1 || (long long)d->img_begin + d->n_img > d->N) return "image span outside [0, N)";
+    if (d->n_keep < 1 || d->n_keep > d->n_img) return "n_keep must be in [1, n_img]";
+    if (d->n_planes < 1 || d->n_planes > LVLM_MAX_PLANES) return "n_planes must be in [1, LVLM_MAX_PLANES]";
+    if (!planes) return "null plane table";
+    const int r = d->n_img - d->n_keep;
+    for (int i = 0; i < d->n_planes; ++i) {
+        const lvlm_plane &p = planes[i];
+        if (!p.src || !p.dst) return "null plane pointer";
+        if (!aligned16(p.src) || !aligned16(p.dst)) return "plane pointers must be 16-byte aligned";
+        if (p.row_elems < 1) return "row_elems must be positive";
+        if (p.dtype != LVLM_BF16 && p.dtype != LVLM_F32 && p.dtype != LVLM_I32) return "unknown plane dtype";
+        if (p.merge_rule != LVLM_RULE_WEIGHTED && p.merge_rule != LVLM_RULE_TOP) return "unknown merge rule";
+        if (p.dtype == LVLM_I32 && p.merge_rule != LVLM_RULE_TOP) return "integer planes need LVLM_RULE_TOP";
+        if (p.src_stride_b < (long long)d->N * p.row_elems) return "src_stride_b smaller than one sequence";
+        if (p.dst_stride_b < (long long)(d->N - r) * p.row_elems) return "dst_stride_b smaller than one output sequence";
+        const size_t eb = elem_bytes(p.dtype);
+        const char *s0 = static_cast<const char *>(p.src);
+        const char *d0 = static_cast<const char *>(p.dst);
+        const char *s1 = s0 + ((size_t)(d->B - 1) * p.src_stride_b + (size_t)d->N * p.row_elems) * eb;
+        const char *d1 = d0 + ((size_t)(d->B - 1) * p.dst_stride_b + (size_t)(d->N - r) * p.row_elems) * eb;
+        if (s0 < d1 && d0 < s1) return "src and dst of a plane overlap";
+    }
+    return nullptr;
+}
+
+const char *check_kv(const lvlm_kv_desc *d) {
+    if (!d) return "null descriptor";
+    if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
+    if (d->hd != 64 && d->hd != 128) return "head dimension must be 64 or 128";
+    if (d->B < 1 || d->Hkv < 1 || d->Lmax < 1) return "sizes must be positive";
+    if (d->len_bound < 0 || d->len_bound > d->Lmax) return "len_bound must be in [0, Lmax]";
+    if (d->mode != LVLM_KV_THRESHOLD && d->mode != LVLM_KV_BUDGET) return "unknown mode";
+    if (d->order != LVLM_ORDER_STABLE && d->order != LVLM_ORDER_FILL) return "unknown order";
+    if (d->mode == LVLM_KV_BUDGET && d->budget < 1) return "budget must be at least 1";
+    if (d->mode == LVLM_KV_BUDGET && d->n_recent < 0) return "n_recent must be non-negative";
+    if (d->mode == LVLM_KV_THRESHOLD && !(d->beta == d->beta)) return "beta is NaN";
+    return nullptr;
+}
+
+const char *check_attn(const lvlm_attn_desc *d) {
+    if (!d) return "null descriptor";
+    if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
+    if (d->hd != 64 && d->hd != 128) return "head dimension must be 64 or 128";
+    if (d->B < 1 || d->Hq < 1 || d->Hkv < 1 || d->Lmax < 1) return "sizes must be positive";
+    if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
+    if (d->len_bound < 0 || d->len_bound > d->Lmax) return "len_bound must be in [0, Lmax]";
+    if (d->new_kind < 0 || d->new_kind > 255) return "new_kind out of range";
+    return nullptr;
+}
+
+lvlm_status need_ws(lvlm_ctx *ctx, size_t bytes) {
+    if (bytes == 0) return LVLM_OK;
+    if (!ctx->ws) return fail(ctx, LVLM_ERR_WORKSPACE, "no workspace attached (need %zu bytes)", bytes);
+    if (ctx->ws_bytes < bytes)
+        return fail(ctx, LVLM_ERR_WORKSPACE, "workspace too small: have %zu bytes, need %zu", ctx->ws_bytes, bytes);
+    return LVLM_OK;
+}
+
+lvlm_status after_launch(lvlm_ctx *ctx, hipError_t e) {
+    if (e != hipSuccess) return fail(ctx, LVLM_ERR_HIP, "launch failed: %s", hipGetErrorString(e));
+    return LVLM_OK;
+}
+
+lvlm_status bind_device(lvlm_ctx *ctx) {
+    const hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail(ctx, LVLM_ERR_HIP, "hipSetDevice(%d): %s", ctx->device, hipGetErrorString(e));
+    return LVLM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+lvlm_status lvlm_create(lvlm_ctx **ctx, int device) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    *ctx = nullptr;
+    if (device < 0) return LVLM_ERR_INVALID_ARG;
+    lvlm_ctx *c = new (std::nothrow) lvlm_ctx();
+    if (!c) return LVLM_ERR_HIP;
+    c->device = device;
+    c->ws = nullptr;
+    c->ws_bytes = 0;
+    c->err[0] = '\0';
+    *ctx = c;
+    return LVLM_OK;
+}
+
+lvlm_status lvlm_destroy(lvlm_ctx *ctx) {
+    delete ctx;
+    return LVLM_OK;
+}
+
+const char *lvlm_last_error(const lvlm_ctx *ctx) { return ctx ? ctx->err : "null context"; }
+
+lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const void *desc, size_t *bytes) {
+    lvlm_ctx *c = const_cast<lvlm_ctx *>(ctx);
+    if (!ctx || !desc || !bytes) return fail(c, LVLM_ERR_INVALID_ARG, "null argument");
+    const char *why = nullptr;
+    switch (op) {
+        case LVLM_OP_SCORE: {
+            const auto *d = static_cast<const lvlm_score_desc *>(desc);
+            if ((why = check_score(d))) break;
+            *bytes = score_ws(*d).total;
+            return LVLM_OK;
+        }
+        case LVLM_OP_MERGE: {
+            // only shapes matter for the size: plane pointers are not inspected
+            const auto *qy = static_cast<const lvlm_merge_query *>(desc);
+            const lvlm_merge_desc *d = qy->desc;
+            if (!d || !qy->planes) { why = "null merge query member"; break; }
+            if (d->B < 1 || d->N < 1 || d->n_img < 1 || d->n_img > d->N || d->n_planes < 1 ||
+                d->n_planes > LVLM_MAX_PLANES) { why = "bad merge descriptor"; break; }
+            for (int i = 0; i < d->n_planes; ++i)
+                if (qy->planes[i].row_elems < 1) why = "row_elems must be positive";
+            if (why) break;
+            *bytes = merge_ws(*d, qy->planes).total;
+            return LVLM_OK;
+        }
+        case LVLM_OP_KV_COMPRESS: {
+            const auto *d = static_cast<const lvlm_kv_desc *>(desc);
+            if ((why = check_kv(d))) break;
+            *bytes = kv_ws(*d).total;
+            return LVLM_OK;
+        }
+        case LVLM_OP_DECODE_ATTN: {
+            const auto *d = static_cast<const lvlm_attn_desc *>(desc);
+            if ((why = check_attn(d))) break;
+            if (d->Hq / d->Hkv > 8) { why = "more than 8 query heads per KV head"; break; }
+            *bytes = attn_ws(*d).total;
+            return LVLM_OK;
+        }
+        default: why = "unknown op";
+    }
+    return fail(c, LVLM_ERR_INVALID_ARG, "%s", why);
+}
+
+lvlm_status lvlm_set_workspace(lvlm_ctx *ctx, void *dev_ptr, size_t bytes) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (dev_ptr && (reinterpret_cast<uintptr_t>(dev_ptr) & 255u))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    ctx->ws = dev_ptr;
+    ctx->ws_bytes = dev_ptr ? bytes : 0;
+    return LVLM_OK;
+}
+
+lvlm_status lvlm_schedule(int n_img, double final_keep, int n_stages, int *n_keep_out) {
+    if (n_img < 1 || n_stages < 1 || !n_keep_out || !(final_keep > 0.0) || final_keep > 1.0) return LVLM_ERR_INVALID_ARG;
+    for (int s = 1; s <= n_stages; ++s) {
+        const double v = floor((double)n_img * pow(final_keep, (double)s / (double)n_stages) + 0.5);
+        int k = (int)v;
+        if (k < 1) k = 1;
+        if (k > n_img) k = n_img;
+        n_keep_out[s - 1] = k;
+    }
+    return LVLM_OK;
+}
+
+lvlm_status lvlm_merge_weights(lvlm_merge_mode mode, int m, float *w) {
+    if (m < 1 || !w) return LVLM_ERR_INVALID_ARG;
+    switch (mode) {
+        case LVLM_MERGE_LINEAR_RANK: {
+            const double sum = (double)m * ((double)m + 1.0) / 2.0;
+            for (int k = 0; k < m; ++k) w[k] = (float)((double)(m - k) / sum);
+            return LVLM_OK;
+        }
+        case LVLM_MERGE_PAIRWISE:
+            for (int k = 0; k < m; ++k) w[k] = (float)ldexp(1.0, -(k + 1));
+            w[m - 1] = (float)ldexp(1.0, -(m - 1));
+            return LVLM_OK;
+        case LVLM_MERGE_LINEAR_RAW:
+            for (int k = 0; k < m; ++k) w[k] = (float)(m - k);
+            return LVLM_OK;
+    }
+    return LVLM_ERR_INVALID_ARG;
+}
+
+lvlm_status lvlm_score_tokens(lvlm_ctx *ctx, void *stream, const lvlm_score_desc *d, const void *q, const void *k,
+                              const float *row_lse, float *score_head, float *score_mean) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (const char *why = check_score(d)) return fail(ctx, LVLM_ERR_INVALID_ARG, "score_tokens: %s", why);
+    if (!q || !k || !score_head || !score_mean) return fail(ctx, LVLM_ERR_INVALID_ARG, "score_tokens: null pointer");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(score_head) || !aligned16(score_mean) || !aligned16(row_lse))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "score_tokens: pointers must be 16-byte aligned");
+    const ScoreWs w = score_ws(*d);
+    if (lvlm_status st = need_ws(ctx, w.total)) return st;
+    if (lvlm_status st = bind_device(ctx)) return st;
+    return after_launch(ctx, launch_score(static_cast<hipStream_t>(stream), *d, w, static_cast<char *>(ctx->ws), q, k,
+                                          row_lse, score_head, score_mean));
+}
+
+lvlm_status lvlm_merge_compact(lvlm_ctx *ctx, void *stream, const lvlm_merge_desc *d, const float *score_mean,
+                               const float *w, const lvlm_plane *planes, int32_t *keep_idx, int32_t *merged_idx) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (const char *why = check_merge(d, planes)) return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_compact: %s", why);
+    if (!score_mean && d->n_keep < d->n_img) return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_compact: null score_mean");
+    if (!aligned16(score_mean) || !aligned16(w) || !aligned16(keep_idx) || !aligned16(merged_idx))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_compact: pointers must be 16-byte aligned");
+    const MergeWs mw = merge_ws(*d, planes);
+    if (lvlm_status st = need_ws(ctx, mw.total)) return st;
+    if (lvlm_status st = bind_device(ctx)) return st;
+    return after_launch(ctx, launch_merge(static_cast<hipStream_t>(stream), *d, mw, static_cast<char *>(ctx->ws),
+                                          score_mean, w, planes, keep_idx, merged_idx));
+}
+
+lvlm_status lvlm_kv_compress(lvlm_ctx *ctx, void *stream, const lvlm_kv_desc *d, void *k_cache, void *v_cache,
+                             float *score, uint8_t *kind, int32_t *orig_pos, int32_t *len, int32_t *n_evicted) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (const char *why = check_kv(d)) return fail(ctx, LVLM_ERR_INVALID_ARG, "kv_compress: %s", why);
+    if (!k_cache || !v_cache || !score || !kind || !orig_pos || !len)
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "kv_compress: null pointer");
+    if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(score) || !aligned16(kind) || !aligned16(orig_pos) ||
+        !aligned16(len) || !aligned16(n_evicted))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "kv_compress: pointers must be 16-byte aligned");
+    const KvWs w = kv_ws(*d);
+    if (lvlm_status st = need_ws(ctx, w.total)) return st;
+    if (lvlm_status st = bind_device(ctx)) return st;
+    return after_launch(ctx, launch_kv_compress(static_cast<hipStream_t>(stream), *d, w, static_cast<char *>(ctx->ws),
+                                                k_cache, v_cache, score, kind, orig_pos, len, n_evicted));
+}
+
+lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *d, const void *q, const void *k_new,
+                             const void *v_new, void *k_cache, void *v_cache, float *score, uint8_t *kind,
+                             int32_t *orig_pos, int32_t *len, void *out) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (const char *why = check_attn(d)) return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: %s", why);
+    if (d->Hq / d->Hkv > 8)
+        return fail(ctx, LVLM_ERR_UNSUPPORTED, "decode_attn: more than 8 query heads per KV head");
+    if (!q || !k_cache || !v_cache || !len || !out) return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: null pointer");
+    if ((k_new == nullptr) != (v_new == nullptr))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: k_new and v_new must be given together");
+    if (k_new && (!kind || !orig_pos))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: kind and orig_pos are needed to append");
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache) ||
+        !aligned16(score) || !aligned16(kind) || !aligned16(orig_pos) || !aligned16(len) || !aligned16(out))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: pointers must be 16-byte aligned");
+    const AttnWs w = attn_ws(*d);
+    if (lvlm_status st = need_ws(ctx, w.total)) return st;
+    if (lvlm_status st = bind_device(ctx)) return st;
+    return after_launch(ctx, launch_decode_attn(static_cast<hipStream_t>(stream), *d, w, static_cast<char *>(ctx->ws),
+                                                q, k_new, v_new, k_cache, v_cache, score, kind, orig_pos, len, out));
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Shared declarations of the library's translation units: the context, the
+// per-op launch entry points (host side) and a few device helpers.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/lvlm.h"
+
+struct lvlm_ctx {
+    int device;
+    void *ws;
+    size_t ws_bytes;
+    char err[256];
+};
+
+namespace lvlm {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- workspace layouts (host arithmetic shared by the size query and the launch) ----
+struct ScoreWs {
+    size_t part_m, part_l, lse2, total;
+    int nkb;       // key blocks of the normaliser pass
+    int block_keys;
+};
+ScoreWs score_ws(const lvlm_score_desc &d);
+
+struct MergeWs {
+    size_t rank_part, dst_of, partial, total;
+    int n_split;   // splits of the comparison loop in the rank kernel
+    int n_chunk;   // source-row chunks of the gather kernel (partial sums per chunk)
+    int rows_per_chunk;
+    int max_row_elems;
+};
+MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes);
+
+struct KvWs {
+    size_t src, total;
+};
+KvWs kv_ws(const lvlm_kv_desc &d);
+
+struct AttnWs {
+    size_t part_ml, part_o, logits, total;
+    int n_split, split_len;
+};
+AttnWs attn_ws(const lvlm_attn_desc &d);
+
+// ---- launches (defined in the .hip files; all asynchronous on `stream`) ----
+hipError_t launch_score(hipStream_t stream, const lvlm_score_desc &d, const ScoreWs &w, char *ws,
+                        const void *q, const void *k, const float *row_lse, float *score_head,
+                        float *score_mean);
+hipError_t launch_merge(hipStream_t stream, const lvlm_merge_desc &d, const MergeWs &w, char *ws,
+                        const float *score_mean, const float *wtab, const lvlm_plane *planes,
+                        int32_t *keep_idx, int32_t *merged_idx);
+hipError_t launch_kv_compress(hipStream_t stream, const lvlm_kv_desc &d, const KvWs &w, char *ws,
+                              void *k_cache, void *v_cache, float *score, uint8_t *kind,
+                              int32_t *orig_pos, int32_t *len, int32_t *n_evicted);
+hipError_t launch_decode_attn(hipStream_t stream, const lvlm_attn_desc &d, const AttnWs &w, char *ws,
+                              const void *q, const void *k_new, const void *v_new, void *k_cache,
+                              void *v_cache, float *score, uint8_t *kind, int32_t *orig_pos,
+                              int32_t *len, void *out);
+
+#if defined(__HIPCC__)
+// ---- device helpers ----
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Order-preserving map float -> u32: a < b  <=>  key(a) < key(b); -0 == +0;
+// NaN maps to 0, below -inf.  Descending importance = descending key.
+__device__ __forceinline__ uint32_t score_key(float x) {
+    if (x != x) return 0u;
+    x += 0.0f;
+    uint32_t b = __float_as_uint(x);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Exact fixed-point image of a score used for cumulative thresholds:
+// floor(clamp(score, 0, 2^16) * 2^32); NaN and negatives give 0.
+__device__ __forceinline__ unsigned long long score_fixed(float s) {
+    if (!(s > 0.0f)) return 0ull;
+    s = fminf(s, 65536.0f);
+    return (unsigned long long)(s * 4294967296.0f);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+#endif
+
+}  // namespace lvlm

@@ -1,0 +1,400 @@
+// Step 5 -- KV-cache compression, independently per (batch, KV head) (Sec. 3.2.2).
+//
+// Neither rule needs a sort.  Both ask for "the best entries until a quota is
+// met", where the quota is a number of entries (fixed budget) or an amount of
+// score mass (threshold beta).  A most-significant-digit radix descent over the
+// order-preserving 32-bit image of the score finds, in four histogram passes,
+// the key K* at which the quota is met: entries above K* stay, entries below go,
+// and among the entries equal to K* the lowest slots stay.  Score mass is summed
+// as exact integers, so the result does not depend on summation order.
+//
+//   kv_select_kernel  one workgroup per head: totals, radix descent, then one
+//                     pass in slot order that numbers survivors / holes.  With
+//                     LVLM_ORDER_FILL it also performs the (few, disjoint)
+//                     moves itself.
+//   kv_move_kernel    LVLM_ORDER_STABLE: survivors slide down in place.  A move
+//                     never goes up and sources are ascending, so processing
+//                     destination slots in ascending steps, each step reading
+//                     everything before writing anything, is safe; column
+//                     slices of the rows are independent and go to different
+//                     workgroups.
+#include "common.h"
+
+namespace lvlm {
+namespace {
+
+struct KvArgs {
+    char *k;
+    char *v;
+    float *score;
+    uint8_t *kind;
+    int32_t *pos;
+    int32_t *len;
+    int32_t *n_evicted;
+    int32_t *list_a;   // [B*Hkv, Lmax]  STABLE: source slot of each new slot; FILL: holes
+    int32_t *list_b;   // [B*Hkv, Lmax]  FILL: survivors beyond the new length
+    int32_t *meta;     // [B*Hkv, 2]     STABLE: {new length, first destination slot that moves}
+    int Hkv, Lmax, row_bytes, mode, order, budget, n_recent;
+    double beta;
+};
+
+struct Scan3 {
+    int wave_cnt[3][16];
+    int base[3];
+};
+
+// Exclusive prefix count, in thread order, of three flags at once; `base`
+// carries the totals from one 1024-slot chunk to the next.
+__device__ __forceinline__ void block_scan3(Scan3 &s, bool f0, bool f1, bool f2, int &p0, int &p1, int &p2) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const unsigned long long b0 = __ballot(f0), b1 = __ballot(f1), b2 = __ballot(f2);
+    if (lane == 0) {
+        s.wave_cnt[0][wave] = __popcll(b0);
+        s.wave_cnt[1][wave] = __popcll(b1);
+        s.wave_cnt[2][wave] = __popcll(b2);
+    }
+    __syncthreads();
+    p0 = s.base[0] + __popcll(b0 & below);
+    p1 = s.base[1] + __popcll(b1 & below);
+    p2 = s.base[2] + __popcll(b2 & below);
+    for (int w = 0; w < wave; ++w) {
+        p0 += s.wave_cnt[0][w];
+        p1 += s.wave_cnt[1][w];
+        p2 += s.wave_cnt[2][w];
+    }
+    __syncthreads();
+    if (tid < 3) {
+        int tot = 0;
+        for (int w = 0; w < 16; ++w) tot += s.wave_cnt[tid][w];
+        s.base[tid] += tot;
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
+    __shared__ unsigned long long hist_m[256];
+    __shared__ unsigned int hist_c[256];
+    __shared__ unsigned long long s_total, s_need;
+    __shared__ unsigned int s_ncand, s_cabove, s_digit;
+    __shared__ int s_first_hole;
+    __shared__ Scan3 scan;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hg = blockIdx.x;
+    const long long base = (long long)hg * a.Lmax;
+    const float *score = a.score + base;
+    const uint8_t *kind = a.kind + base;
+    const int L = min(a.len[hg], a.Lmax);
+    const bool budget_mode = a.mode == LVLM_KV_BUDGET;
+
+    auto nothing_to_do = [&]() {
+        if (tid == 0) {
+            if (a.n_evicted) a.n_evicted[hg] = 0;
+            a.meta[2 * hg] = L;
+            a.meta[2 * hg + 1] = L;
+        }
+    };
+    if ((budget_mode && L <= a.budget) || (!budget_mode && !(a.beta < 1.0)) || L <= 0) {
+        nothing_to_do();
+        return;
+    }
+    const int recent_lo = L - a.n_recent;
+    auto is_cand = [&](int slot, uint8_t kd) -> bool {
+        return budget_mode ? (kd != LVLM_KIND_PROTECTED && slot < recent_lo) : (kd == LVLM_KIND_IMAGE);
+    };
+
+    // ---- totals over the candidates
+    if (tid == 0) {
+        s_total = 0ull;
+        s_ncand = 0u;
+        s_cabove = 0u;
+        s_first_hole = L;
+        scan.base[0] = scan.base[1] = scan.base[2] = 0;
+    }
+    __syncthreads();
+    {
+        unsigned long long mloc = 0ull;
+        unsigned int cloc = 0u;
+        for (int slot = tid; slot < L; slot += 1024) {
+            if (is_cand(slot, kind[slot])) {
+                mloc += budget_mode ? 1ull : score_fixed(score[slot]);
+                ++cloc;
+            }
+        }
+        if (cloc) {
+            atomicAdd(&s_total, mloc);
+            atomicAdd(&s_ncand, cloc);
+        }
+    }
+    __syncthreads();
+    const unsigned int ncand = s_ncand;
+    const unsigned long long total = s_total;
+    const int n_fixed = L - (int)ncand;                 // entries that are never candidates
+    unsigned long long need;                            // quota still to be met inside the current bin
+    bool evict_all_cand = false;
+    if (budget_mode) {
+        const int room = a.budget - n_fixed;
+        evict_all_cand = room <= 0;
+        need = room > 0 ? (unsigned long long)room : 0ull;
+    } else {
+        if (ncand == 0u || total == 0ull) {
+            nothing_to_do();
+            return;
+        }
+        const double target = ceil(a.beta * (double)total);
+        need = target >= 1.0 ? (unsigned long long)target : 1ull;
+        if (need > total) need = total;
+    }
+
+    // ---- radix descent: most significant digit first
+    uint32_t kstar = 0xffffffffu;
+    unsigned long long tie_keep = 0ull;
+    if (!evict_all_cand) {
+        uint32_t prefix = 0u;
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            if (tid < 256) {
+                hist_m[tid] = 0ull;
+                hist_c[tid] = 0u;
+            }
+            __syncthreads();
+            for (int slot = tid; slot < L; slot += 1024) {
+                if (!is_cand(slot, kind[slot])) continue;
+                const float sc = score[slot];
+                const uint32_t key = score_key(sc);
+                if (pass > 0 && (key >> (shift + 8)) != (prefix >> (shift + 8))) continue;
+                const uint32_t dgt = (key >> shift) & 255u;
+                atomicAdd(&hist_m[dgt], budget_mode ? 1ull : score_fixed(sc));
+                atomicAdd(&hist_c[dgt], 1u);
+            }
+            __syncthreads();
+            if (wave == 0) {
+                // lane owns digits 4*lane .. 4*lane+3; suffix sums give the mass above each digit
+                unsigned long long hm[4];
+                unsigned int hc[4];
+                unsigned long long loc_m = 0ull;
+                unsigned int loc_c = 0u;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    hm[i] = hist_m[4 * lane + i];
+                    hc[i] = hist_c[4 * lane + i];
+                    loc_m += hm[i];
+                    loc_c += hc[i];
+                }
+                unsigned long long inc_m = loc_m;
+                unsigned int inc_c = loc_c;
+#pragma unroll
+                for (int o = 1; o < 64; o <<= 1) {
+                    const unsigned long long tm = __shfl_down(inc_m, o);
+                    const unsigned int tc = __shfl_down(inc_c, o);
+                    if (lane + o < 64) {
+                        inc_m += tm;
+                        inc_c += tc;
+                    }
+                }
+                unsigned long long above_m = inc_m - loc_m;
+                unsigned int above_c = inc_c - loc_c;
+#pragma unroll
+                for (int i = 3; i >= 0; --i) {
+                    if (above_m < need && need <= above_m + hm[i]) {
+                        s_digit = 4u * lane + i;
+                        s_need = need - above_m;
+                        s_cabove += above_c;     // exactly one lane takes this branch
+                    }
+                    above_m += hm[i];
+                    above_c += hc[i];
+                }
+            }
+            __syncthreads();
+            prefix |= s_digit << shift;
+            need = s_need;
+        }
+        kstar = prefix;
+        const uint32_t last = kstar & 255u;
+        if (budget_mode) {
+            tie_keep = need;
+        } else {
+            const unsigned long long u = hist_m[last] / hist_c[last];   // equal keys have equal mass
+            tie_keep = (need + u - 1ull) / u;
+        }
+    }
+    const int n_keep_cand = evict_all_cand ? 0 : (int)(s_cabove + (unsigned int)tie_keep);
+    const int n_new = n_fixed + n_keep_cand;
+    const int n_evict = L - n_new;
+    if (n_evict <= 0) {
+        nothing_to_do();
+        return;
+    }
+
+    // ---- one pass in slot order: number the survivors (STABLE) or holes / tail survivors (FILL)
+    int32_t *list_a = a.list_a + base;
+    int32_t *list_b = a.list_b + base;
+    const bool stable = a.order == LVLM_ORDER_STABLE;
+    for (int s0 = 0; s0 < L; s0 += 1024) {
+        const int slot = s0 + tid;
+        bool tie = false, keep = false, inside = slot < L;
+        if (inside) {
+            const uint8_t kd = kind[slot];
+            if (!is_cand(slot, kd)) {
+                keep = true;
+            } else {
+                const uint32_t key = score_key(score[slot]);
+                tie = key == kstar;
+                keep = key > kstar;
+            }
+        }
+        int tie_before, p1, p2;
+        if (stable) {
+            // survivors before this slot = sure survivors before + ties before that are kept
+            block_scan3(scan, tie, keep, false, tie_before, p1, p2);
+            const bool kept = keep || (tie && (unsigned long long)tie_before < tie_keep);
+            const int ties_kept_before = (int)min((unsigned long long)tie_before, tie_keep);
+            const int p = p1 + ties_kept_before;
+            if (inside) {
+                if (kept) list_a[p] = slot;
+                else atomicMin(&s_first_hole, p);
+            }
+        } else {
+            block_scan3(scan, tie, false, false, tie_before, p1, p2);
+            const bool kept = keep || (tie && (unsigned long long)tie_before < tie_keep);
+            const bool hole = inside && !kept && slot < n_new;
+            const bool tail = inside && kept && slot >= n_new;
+            int dummy, hi, ti;
+            // a second scan numbers holes and tail survivors (slot 0 of the scan keeps counting ties)
+            block_scan3(scan, false, hole, tail, dummy, hi, ti);
+            if (hole) list_a[hi] = slot;
+            if (tail) list_b[ti] = slot;
+        }
+    }
+    __syncthreads();
+
+    if (stable) {
+        if (tid == 0) {
+            a.meta[2 * hg] = n_new;
+            a.meta[2 * hg + 1] = s_first_hole;
+            a.len[hg] = n_new;
+            if (a.n_evicted) a.n_evicted[hg] = n_evict;
+        }
+        return;
+    }
+
+    // ---- FILL: sources (>= n_new) and destinations (< n_new) are disjoint
+    const int n_moves = scan.base[1];
+    const int units = a.row_bytes / 16;
+    char *kc = a.k + base * a.row_bytes;
+    char *vc = a.v + base * a.row_bytes;
+    for (int idx = tid; idx < n_moves * units; idx += 1024) {
+        const int i = idx / units, u = idx - i * units;
+        const long long src = (long long)list_b[i] * a.row_bytes + 16 * u;
+        const long long dst = (long long)list_a[i] * a.row_bytes + 16 * u;
+        *reinterpret_cast<uint4 *>(kc + dst) = *reinterpret_cast<const uint4 *>(kc + src);
+        *reinterpret_cast<uint4 *>(vc + dst) = *reinterpret_cast<const uint4 *>(vc + src);
+    }
+    for (int i = tid; i < n_moves; i += 1024) {
+        const int src = list_b[i], dst = list_a[i];
+        a.score[base + dst] = a.score[base + src];
+        a.kind[base + dst] = a.kind[base + src];
+        a.pos[base + dst] = a.pos[base + src];
+    }
+    if (tid == 0) {
+        a.meta[2 * hg] = n_new;
+        a.meta[2 * hg + 1] = n_new;
+        a.len[hg] = n_new;
+        if (a.n_evicted) a.n_evicted[hg] = n_evict;
+    }
+}
+
+constexpr int kSliceBytes = 64;   // column slice of a K or V row handled by one workgroup
+constexpr int kMoveUpt = 8;       // units per thread per step
+
+__global__ __launch_bounds__(256) void kv_move_kernel(KvArgs a) {
+    const int tid = threadIdx.x;
+    const int hg = blockIdx.y;
+    const int n_new = a.meta[2 * hg], first = a.meta[2 * hg + 1];
+    if (first >= n_new) return;
+    const long long base = (long long)hg * a.Lmax;
+    const int32_t *src_of = a.list_a + base;
+    const int slices = a.row_bytes / kSliceBytes;
+    const int sl = blockIdx.x;
+    if (sl < 2 * slices) {
+        char *cache = (sl < slices ? a.k : a.v) + base * a.row_bytes + (sl % slices) * kSliceBytes + 16 * (tid & 3);
+        constexpr int ROWS = 64 * kMoveUpt;
+        for (int p0 = first; p0 < n_new; p0 += ROWS) {
+            uint4 val[kMoveUpt];
+#pragma unroll
+            for (int x = 0; x < kMoveUpt; ++x) {
+                const int p = p0 + 64 * x + (tid >> 2);
+                if (p < n_new) val[x] = *reinterpret_cast<const uint4 *>(cache + (long long)src_of[p] * a.row_bytes);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int x = 0; x < kMoveUpt; ++x) {
+                const int p = p0 + 64 * x + (tid >> 2);
+                if (p < n_new) *reinterpret_cast<uint4 *>(cache + (long long)p * a.row_bytes) = val[x];
+            }
+        }
+    } else {
+        constexpr int ROWS = 256 * kMoveUpt;
+        for (int p0 = first; p0 < n_new; p0 += ROWS) {
+            float sc[kMoveUpt];
+            uint8_t kd[kMoveUpt];
+            int32_t ps[kMoveUpt];
+#pragma unroll
+            for (int x = 0; x < kMoveUpt; ++x) {
+                const int p = p0 + 256 * x + tid;
+                if (p < n_new) {
+                    const int s = src_of[p];
+                    sc[x] = a.score[base + s];
+                    kd[x] = a.kind[base + s];
+                    ps[x] = a.pos[base + s];
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int x = 0; x < kMoveUpt; ++x) {
+                const int p = p0 + 256 * x + tid;
+                if (p < n_new) {
+                    a.score[base + p] = sc[x];
+                    a.kind[base + p] = kd[x];
+                    a.pos[base + p] = ps[x];
+                }
+            }
+        }
+    }
+}
+
+}  // namespace
+
+KvWs kv_ws(const lvlm_kv_desc &d) {
+    KvWs w{};
+    const size_t heads = (size_t)d.B * d.Hkv;
+    w.src = 0;
+    // two slot lists per head, then two ints of bookkeeping per head
+    w.total = align_up(2 * heads * d.Lmax * sizeof(int32_t), 256) + align_up(heads * 2 * sizeof(int32_t), 256);
+    return w;
+}
+
+hipError_t launch_kv_compress(hipStream_t stream, const lvlm_kv_desc &d, const KvWs &w, char *ws, void *k_cache,
+                              void *v_cache, float *score, uint8_t *kind, int32_t *orig_pos, int32_t *len,
+                              int32_t *n_evicted) {
+    const size_t heads = (size_t)d.B * d.Hkv;
+    KvArgs a{};
+    a.k = static_cast<char *>(k_cache);
+    a.v = static_cast<char *>(v_cache);
+    a.score = score; a.kind = kind; a.pos = orig_pos; a.len = len; a.n_evicted = n_evicted;
+    a.list_a = reinterpret_cast<int32_t *>(ws + w.src);
+    a.list_b = a.list_a + heads * d.Lmax;
+    a.meta = reinterpret_cast<int32_t *>(ws + align_up(2 * heads * d.Lmax * sizeof(int32_t), 256));
+    a.Hkv = d.Hkv; a.Lmax = d.Lmax;
+    a.row_bytes = d.hd * (d.dtype == LVLM_BF16 ? 2 : 4);
+    a.mode = d.mode; a.order = d.order; a.budget = d.budget; a.n_recent = d.n_recent; a.beta = d.beta;
+    hipLaunchKernelGGL(kv_select_kernel, dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    if (d.order == LVLM_ORDER_STABLE) {
+        const int slices = a.row_bytes / kSliceBytes;
+        hipLaunchKernelGGL(kv_move_kernel, dim3(2 * slices + 1, (unsigned)heads), dim3(256), 0, stream, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace lvlm

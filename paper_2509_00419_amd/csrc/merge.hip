@@ -1,0 +1,400 @@
+// Steps 2-4 -- partition by importance, merge P_merged into one token, compact
+// every plane that shares the token axis (Sec. 3.2.1, par. 4).
+//
+//   rank_kernel      rank[j] = number of image tokens that precede j in
+//                    descending score order (ties: lower index first).  It is
+//                    the counting definition itself, spread over the chip:
+//                    a (token block) x (comparison range) grid, every thread
+//                    counting for one token against keys staged in LDS.
+//                    Nothing iterative, nothing data dependent.
+//   index_kernel     one workgroup per sequence: sums the partial counts,
+//                    prefix-scans the "kept" flags in index order and emits
+//                    keep_idx (ascending), merged_idx (rank order) and, per
+//                    source token, where it goes (row of P_unmerged or its
+//                    rank inside P_merged).
+//   gather_kernel    one streaming pass over every source row of every plane:
+//                    a kept row is copied to its new place with 128-bit loads
+//                    and stores, a merged row is multiplied by its rank weight
+//                    and accumulated in fp32 registers; each row chunk leaves
+//                    one partial sum.
+//   finalize_kernel  adds the partial sums in chunk order, rounds once and
+//                    writes P_new behind P_unmerged.
+#include "common.h"
+
+namespace lvlm {
+namespace {
+
+constexpr int kRankTile = 1024;   // keys staged in LDS per step of the rank kernel
+
+struct RankArgs {
+    const float *score;   // [B, n]
+    int32_t *rank_part;   // [B, n_split, n]
+    int n, n_split, split_len;
+};
+
+__global__ __launch_bounds__(256) void rank_kernel(RankArgs a) {
+    __shared__ __attribute__((aligned(16))) uint32_t keys[kRankTile];
+    const int tid = threadIdx.x;
+    const int b = blockIdx.z, split = blockIdx.y;
+    const int j0 = blockIdx.x * 256;
+    const int j = j0 + tid;
+    const float *score = a.score + (long long)b * a.n;
+    const uint32_t kj = j < a.n ? score_key(score[j]) : 0u;
+    const int i_lo = split * a.split_len;
+    const int i_hi = min(a.n, i_lo + a.split_len);
+    int cnt = 0;
+    for (int t0 = i_lo; t0 < i_hi; t0 += kRankTile) {
+        __syncthreads();
+        for (int x = tid; x < kRankTile; x += 256) {
+            const int i = t0 + x;
+            // a padding key must never count: give it the lowest key and let the index rule reject it
+            keys[x] = i < i_hi ? score_key(score[i]) : 0u;
+        }
+        __syncthreads();
+        const int lim = min(kRankTile, i_hi - t0);
+        if (t0 + kRankTile <= j0) {
+            // every i in the tile is below every j of the block: i precedes j when key_i >= key_j
+            for (int x = 0; x < lim; x += 4) {
+                const uint4 k4 = *reinterpret_cast<const uint4 *>(&keys[x]);
+                cnt += (k4.x >= kj) + ((x + 1 < lim) & (k4.y >= kj)) + ((x + 2 < lim) & (k4.z >= kj)) +
+                       ((x + 3 < lim) & (k4.w >= kj));
+            }
+        } else if (t0 >= j0 + 256) {
+            // every i is above every j: i precedes j only with a strictly larger key
+            for (int x = 0; x < lim; x += 4) {
+                const uint4 k4 = *reinterpret_cast<const uint4 *>(&keys[x]);
+                cnt += (k4.x > kj) + ((x + 1 < lim) & (k4.y > kj)) + ((x + 2 < lim) & (k4.z > kj)) +
+                       ((x + 3 < lim) & (k4.w > kj));
+            }
+        } else {
+            for (int x = 0; x < lim; ++x) {
+                const uint32_t ki = keys[x];
+                cnt += (ki > kj) | ((ki == kj) & (t0 + x < j));
+            }
+        }
+    }
+    if (j < a.n) a.rank_part[((long long)b * a.n_split + split) * a.n + j] = cnt;
+}
+
+struct IndexArgs {
+    const int32_t *rank_part;
+    int32_t *dst_of;       // [B, n]: >= 0 row inside the new image span; < 0: -(rank in P_merged) - 1
+    int32_t *keep_idx;     // [B, n_keep-1] or null
+    int32_t *merged_idx;   // [B, r+1] or null
+    int n, n_split, n_keep;
+};
+
+__global__ __launch_bounds__(1024) void index_kernel(IndexArgs a) {
+    __shared__ int wave_cnt[16];
+    __shared__ int base_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.x;
+    const int n_unmerged = a.n_keep - 1;
+    if (tid == 0) base_s = 0;
+    __syncthreads();
+    for (int j0 = 0; j0 < a.n; j0 += 1024) {
+        const int j = j0 + tid;
+        int rank = 0;
+        if (j < a.n)
+            for (int s = 0; s < a.n_split; ++s) rank += a.rank_part[((long long)b * a.n_split + s) * a.n + j];
+        const bool kept = j < a.n && rank < n_unmerged;
+        const unsigned long long bal = __ballot(kept);
+        const int before = __popcll(bal & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_cnt[wave] = __popcll(bal);
+        __syncthreads();
+        int off = base_s;
+        for (int w = 0; w < wave; ++w) off += wave_cnt[w];
+        if (j < a.n) {
+            if (kept) {
+                const int p = off + before;
+                a.dst_of[(long long)b * a.n + j] = p;
+                if (a.keep_idx) a.keep_idx[(long long)b * n_unmerged + p] = j;
+            } else {
+                const int k = rank - n_unmerged;
+                a.dst_of[(long long)b * a.n + j] = -k - 1;
+                if (a.merged_idx) a.merged_idx[(long long)b * (a.n - n_unmerged) + k] = j;
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int tot = 0;
+            for (int w = 0; w < 16; ++w) tot += wave_cnt[w];
+            base_s += tot;
+        }
+        __syncthreads();
+    }
+}
+
+// ---- gather -----------------------------------------------------------------
+
+struct PlaneDev {
+    const char *src;
+    char *dst;
+    long long src_stride_b, dst_stride_b;   // bytes
+    int row_bytes;
+    int row_elems;
+    int dtype;
+    int rule;
+    int unit_bytes;   // 16, 4 or 2
+    int tpr_log2;     // threads per row (power of two, <= 256)
+    int col_blocks;   // blocks of 256 units across a row
+    int n_sub;        // row sub-chunks (partial sums) of this plane
+};
+
+struct GatherArgs {
+    PlaneDev plane[LVLM_MAX_PLANES];
+    const int32_t *dst_of;   // null: identity (nothing removed)
+    const float *w;          // rank -> weight, or null for the linear table
+    float *partial;          // [B][n_planes][n_sub_max][max_row_elems]
+    int B, N, img_begin, n_img, n_keep, n_planes;
+    int rows_per_sub, n_sub_max, max_row_elems;
+    float lin_scale;         // 1 / (m (m+1) / 2)
+};
+
+template <int UB>
+struct Unit;
+template <>
+struct Unit<16> { using type = uint4; };
+template <>
+struct Unit<4> { using type = uint32_t; };
+template <>
+struct Unit<2> { using type = uint16_t; };
+
+template <int DT, int UB>
+struct Acc {
+    static constexpr int NE = UB / (DT == LVLM_BF16 ? 2 : 4);
+    float v[NE > 0 ? NE : 1];
+};
+
+template <int DT, int UB>
+__device__ __forceinline__ void accumulate(Acc<DT, UB> &acc, const typename Unit<UB>::type &u, float w) {
+    if constexpr (DT == LVLM_BF16 && UB == 16) {
+        const uint32_t d[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc.v[2 * i] = fmaf(w, __uint_as_float(d[i] << 16), acc.v[2 * i]);
+            acc.v[2 * i + 1] = fmaf(w, __uint_as_float(d[i] & 0xffff0000u), acc.v[2 * i + 1]);
+        }
+    } else if constexpr (DT == LVLM_BF16 && UB == 4) {
+        acc.v[0] = fmaf(w, __uint_as_float(u << 16), acc.v[0]);
+        acc.v[1] = fmaf(w, __uint_as_float(u & 0xffff0000u), acc.v[1]);
+    } else if constexpr (DT == LVLM_BF16 && UB == 2) {
+        acc.v[0] = fmaf(w, bf16_to_f32(u), acc.v[0]);
+    } else if constexpr (DT == LVLM_F32 && UB == 16) {
+        acc.v[0] = fmaf(w, __uint_as_float(u.x), acc.v[0]);
+        acc.v[1] = fmaf(w, __uint_as_float(u.y), acc.v[1]);
+        acc.v[2] = fmaf(w, __uint_as_float(u.z), acc.v[2]);
+        acc.v[3] = fmaf(w, __uint_as_float(u.w), acc.v[3]);
+    } else if constexpr (DT == LVLM_F32 && UB == 4) {
+        acc.v[0] = fmaf(w, __uint_as_float(u), acc.v[0]);
+    }
+}
+
+// One thread group walks `rows_per_sub` consecutive source rows of one plane,
+// one unit column per thread.
+template <int DT, int UB>
+__device__ __forceinline__ void gather_plane(const GatherArgs &a, const PlaneDev &p, int pi, int b) {
+    using U = typename Unit<UB>::type;
+    constexpr int RB = 4;   // rows in flight per thread
+    const int tid = threadIdx.x;
+    const int tpr = 1 << p.tpr_log2;
+    const int group = tid >> p.tpr_log2;
+    const int groups = 256 >> p.tpr_log2;
+    const int sub = blockIdx.x * groups + group;
+    const int unit = blockIdx.y * 256 + (tid & (tpr - 1));
+    const int row_units = p.row_bytes / UB;
+    if (sub >= p.n_sub || blockIdx.y >= p.col_blocks) return;
+    const bool active = unit < row_units;
+    const int r = a.n_img - a.n_keep;
+    const int m = r + 1;
+    const char *src = p.src + (long long)b * p.src_stride_b + (long long)unit * UB;
+    char *dst = p.dst + (long long)b * p.dst_stride_b + (long long)unit * UB;
+    const int32_t *dst_of = a.dst_of ? a.dst_of + (long long)b * a.n_img : nullptr;
+    const bool weighted = p.rule == LVLM_RULE_WEIGHTED && dst_of != nullptr;
+
+    Acc<DT, UB> acc;
+#pragma unroll
+    for (int i = 0; i < Acc<DT, UB>::NE; ++i) acc.v[i] = 0.f;
+
+    const int n_lo = sub * a.rows_per_sub;
+    const int n_hi = min(a.N, n_lo + a.rows_per_sub);
+    for (int n0 = n_lo; n0 < n_hi; n0 += RB) {
+        U val[RB];
+        int where[RB];   // >= 0: destination row; -1: skip; <= -2: merged with rank -(where) - 2
+#pragma unroll
+        for (int x = 0; x < RB; ++x) {
+            const int n = n0 + x;
+            where[x] = -1;
+            if (n < n_hi) {
+                if (active) val[x] = *reinterpret_cast<const U *>(src + (long long)n * p.row_bytes);
+                if (dst_of == nullptr || n < a.img_begin) {
+                    where[x] = n;
+                } else if (n >= a.img_begin + a.n_img) {
+                    where[x] = n - r;
+                } else {
+                    const int t = dst_of[n - a.img_begin];
+                    where[x] = t >= 0 ? a.img_begin + t : t - 1;
+                }
+            }
+        }
+#pragma unroll
+        for (int x = 0; x < RB; ++x) {
+            if (!active) continue;
+            if (where[x] >= 0) {
+                *reinterpret_cast<U *>(dst + (long long)where[x] * p.row_bytes) = val[x];
+            } else if (where[x] <= -2) {
+                const int k = -where[x] - 2;
+                if (weighted) {
+                    const float wk = a.w ? a.w[k] : (float)(m - k) * a.lin_scale;
+                    if constexpr (DT != LVLM_I32) accumulate<DT, UB>(acc, val[x], wk);
+                } else if (k == 0) {
+                    *reinterpret_cast<U *>(dst + (long long)(a.img_begin + a.n_keep - 1) * p.row_bytes) = val[x];
+                }
+            }
+        }
+    }
+    if constexpr (DT != LVLM_I32) {
+        if (weighted && active) {
+            constexpr int NE = Acc<DT, UB>::NE;
+            float *out = a.partial + (((long long)b * a.n_planes + pi) * a.n_sub_max + sub) * a.max_row_elems +
+                         (long long)unit * NE;
+#pragma unroll
+            for (int i = 0; i < NE; ++i) out[i] = acc.v[i];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
+    const int pi = blockIdx.z / a.B, b = blockIdx.z % a.B;
+    const PlaneDev &p = a.plane[pi];
+    if (p.dtype == LVLM_BF16) {
+        if (p.unit_bytes == 16) gather_plane<LVLM_BF16, 16>(a, p, pi, b);
+        else if (p.unit_bytes == 4) gather_plane<LVLM_BF16, 4>(a, p, pi, b);
+        else gather_plane<LVLM_BF16, 2>(a, p, pi, b);
+    } else if (p.dtype == LVLM_F32) {
+        if (p.unit_bytes == 16) gather_plane<LVLM_F32, 16>(a, p, pi, b);
+        else gather_plane<LVLM_F32, 4>(a, p, pi, b);
+    } else {
+        if (p.unit_bytes == 16) gather_plane<LVLM_I32, 16>(a, p, pi, b);
+        else gather_plane<LVLM_I32, 4>(a, p, pi, b);
+    }
+}
+
+// P_new[c] = sum over row chunks (in order) of the partial sums, rounded once.
+__global__ __launch_bounds__(256) void finalize_kernel(GatherArgs a) {
+    const int pi = blockIdx.y / a.B, b = blockIdx.y % a.B;
+    const PlaneDev &p = a.plane[pi];
+    if (p.rule != LVLM_RULE_WEIGHTED) return;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= p.row_elems) return;
+    const float *part = a.partial + ((long long)b * a.n_planes + pi) * a.n_sub_max * a.max_row_elems + c;
+    float s = 0.f;
+    for (int i = 0; i < p.n_sub; ++i) s += part[(long long)i * a.max_row_elems];
+    char *dst = p.dst + (long long)b * p.dst_stride_b + (long long)(a.img_begin + a.n_keep - 1) * p.row_bytes;
+    if (p.dtype == LVLM_BF16)
+        reinterpret_cast<uint16_t *>(dst)[c] = f32_to_bf16(s);
+    else
+        reinterpret_cast<float *>(dst)[c] = s;
+}
+
+int elem_bytes(int dtype) { return dtype == LVLM_BF16 ? 2 : 4; }
+
+}  // namespace
+
+MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes) {
+    MergeWs w{};
+    // rank kernel: aim at >= 1024 workgroups, each comparison range a multiple of the LDS tile
+    const long long jblocks = (long long)d.B * ((d.n_img + 255) / 256);
+    const int max_split = (d.n_img + kRankTile - 1) / kRankTile;
+    long long want = (1024 + jblocks - 1) / jblocks;
+    w.n_split = (int)(want < 1 ? 1 : (want > max_split ? max_split : want));
+    // gather kernel: rows per partial sum
+    int max_elems = 1;
+    long long units = 0;
+    for (int i = 0; i < d.n_planes; ++i) {
+        if (planes[i].row_elems > max_elems) max_elems = planes[i].row_elems;
+        units += ((long long)planes[i].row_elems * elem_bytes(planes[i].dtype) + 4095) / 4096;
+    }
+    // about three workgroups per CU; longer chunks mean fewer partial sums to write and re-read
+    long long rows = (long long)d.N * d.B * (units ? units : 1) / 768;
+    rows = rows / 4 * 4;
+    w.rows_per_chunk = (int)(rows < 8 ? 8 : (rows > 128 ? 128 : rows));
+    w.n_chunk = (d.N + w.rows_per_chunk - 1) / w.rows_per_chunk;
+    w.max_row_elems = max_elems;
+    w.rank_part = 0;
+    w.dst_of = align_up(w.rank_part + (size_t)d.B * w.n_split * d.n_img * sizeof(int32_t), 256);
+    w.partial = align_up(w.dst_of + (size_t)d.B * d.n_img * sizeof(int32_t), 256);
+    w.total = align_up(w.partial + (size_t)d.B * d.n_planes * w.n_chunk * max_elems * sizeof(float), 256);
+    return w;
+}
+
+hipError_t launch_merge(hipStream_t stream, const lvlm_merge_desc &d, const MergeWs &w, char *ws,
+                        const float *score_mean, const float *wtab, const lvlm_plane *planes, int32_t *keep_idx,
+                        int32_t *merged_idx) {
+    const int r = d.n_img - d.n_keep;
+    GatherArgs g{};
+    g.B = d.B; g.N = d.N; g.img_begin = d.img_begin; g.n_img = d.n_img; g.n_keep = d.n_keep;
+    g.n_planes = d.n_planes;
+    g.rows_per_sub = w.rows_per_chunk;
+    g.n_sub_max = w.n_chunk;
+    g.max_row_elems = w.max_row_elems;
+    g.partial = reinterpret_cast<float *>(ws + w.partial);
+    g.w = wtab;
+    const double m = (double)r + 1.0;
+    g.lin_scale = (float)(1.0 / (m * (m + 1.0) / 2.0));
+    g.dst_of = r > 0 ? reinterpret_cast<const int32_t *>(ws + w.dst_of) : nullptr;
+
+    int grid_x = 1, grid_y = 1;
+    bool any_weighted = false;
+    for (int i = 0; i < d.n_planes; ++i) {
+        PlaneDev &p = g.plane[i];
+        const int es = elem_bytes(planes[i].dtype);
+        p.src = static_cast<const char *>(planes[i].src);
+        p.dst = static_cast<char *>(planes[i].dst);
+        p.src_stride_b = planes[i].src_stride_b * es;
+        p.dst_stride_b = planes[i].dst_stride_b * es;
+        p.row_elems = planes[i].row_elems;
+        p.row_bytes = planes[i].row_elems * es;
+        p.dtype = planes[i].dtype;
+        p.rule = planes[i].merge_rule;
+        const bool vec = p.row_bytes % 16 == 0 && p.src_stride_b % 16 == 0 && p.dst_stride_b % 16 == 0;
+        p.unit_bytes = vec ? 16 : (p.row_bytes % 4 == 0 && p.src_stride_b % 4 == 0 && p.dst_stride_b % 4 == 0 ? 4 : 2);
+        const int row_units = p.row_bytes / p.unit_bytes;
+        int tl = 0;
+        while ((1 << tl) < row_units && tl < 8) ++tl;
+        p.tpr_log2 = tl;
+        p.col_blocks = (row_units + 255) / 256;
+        p.n_sub = w.n_chunk;
+        const int groups = 256 >> tl;
+        const int gx = (p.n_sub + groups - 1) / groups;
+        if (gx > grid_x) grid_x = gx;
+        if (p.col_blocks > grid_y) grid_y = p.col_blocks;
+        any_weighted |= p.rule == LVLM_RULE_WEIGHTED;
+    }
+
+    if (r > 0) {
+        RankArgs ra{};
+        ra.score = score_mean;
+        ra.rank_part = reinterpret_cast<int32_t *>(ws + w.rank_part);
+        ra.n = d.n_img;
+        ra.n_split = w.n_split;
+        const int tiles = (d.n_img + kRankTile - 1) / kRankTile;
+        ra.split_len = (tiles + w.n_split - 1) / w.n_split * kRankTile;
+        hipLaunchKernelGGL(rank_kernel, dim3((d.n_img + 255) / 256, w.n_split, d.B), dim3(256), 0, stream, ra);
+        IndexArgs ia{};
+        ia.rank_part = ra.rank_part;
+        ia.dst_of = reinterpret_cast<int32_t *>(ws + w.dst_of);
+        ia.keep_idx = keep_idx;
+        ia.merged_idx = merged_idx;
+        ia.n = d.n_img; ia.n_split = w.n_split; ia.n_keep = d.n_keep;
+        hipLaunchKernelGGL(index_kernel, dim3(d.B), dim3(1024), 0, stream, ia);
+    }
+    hipLaunchKernelGGL(gather_kernel, dim3(grid_x, grid_y, d.B * d.n_planes), dim3(256), 0, stream, g);
+    if (r > 0 && any_weighted) {
+        hipLaunchKernelGGL(finalize_kernel, dim3((w.max_row_elems + 255) / 256, d.B * d.n_planes), dim3(256), 0,
+                           stream, g);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace lvlm

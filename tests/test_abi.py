@@ -1,0 +1,107 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every
+symbol the header declares, its pure host helpers agree with the oracle, and
+argument errors are reported before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2509_00419_amd as lv
+from oracle import lvlm_oracle as O
+from paper_2509_00419_amd import binding as bd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "lvlm.h")).read()
+    declared = set(re.findall(r"LVLM_API[^;(]*?\b(lvlm_\w+)\s*\(", header))
+    assert {"lvlm_score_tokens", "lvlm_merge_compact", "lvlm_kv_compress", "lvlm_decode_attn"} <= declared
+    assert len(declared) >= 11
+    for name in declared:
+        assert hasattr(bd.lib, name), name
+
+
+def test_struct_sizes_match_the_header_layout():
+    # natural alignment, no packing: sizes follow from the field lists in the header
+    assert C.sizeof(bd.ScoreDesc) == 12 * 4 + 6 * 8
+    assert C.sizeof(bd.Plane) == 2 * 8 + 2 * 8 + 4 * 4
+    assert C.sizeof(bd.MergeDesc) == 6 * 4
+    assert C.sizeof(bd.KvDesc) == 10 * 4 + 8
+    assert C.sizeof(bd.AttnDesc) == 11 * 4
+
+
+def test_schedule_helper_matches_oracle():
+    for n_img, f, s in [(2048, 0.03, 3), (2048, 0.35, 3), (1792, 0.35, 3), (16384, 0.03, 3), (576, 0.5, 1),
+                        (2048, 1.0, 3), (7, 0.001, 4)]:
+        assert lv.schedule(n_img, f, s) == O.schedule(n_img, f, s)
+    with pytest.raises(lv.LvlmError):
+        lv.schedule(0, 0.5, 3)
+    with pytest.raises(lv.LvlmError):
+        lv.schedule(10, 0.0, 3)
+
+
+def test_merge_weight_helper_matches_oracle():
+    for mode in (lv.MERGE_LINEAR_RANK, lv.MERGE_PAIRWISE, lv.MERGE_LINEAR_RAW):
+        for m in (1, 2, 5, 1413):
+            got = lv.merge_weights(mode, m).numpy()
+            np.testing.assert_allclose(got, O.merge_weights(mode, m).astype(np.float32), rtol=1e-7)
+
+
+def _ctx():
+    return lv.Context(0)       # creating a context touches no GPU state
+
+
+def test_workspace_sizes_are_pure_host_arithmetic():
+    ctx = _ctx()
+    d = bd.ScoreDesc(bd.BF16, 1, 2176, 64, 2112, 28, 4, 128, 64, 2048, 1, 0.088, 28 * 128 * 64, 28 * 128, 128,
+                     2176 * 512, 512, 128)
+    assert ctx.workspace_bytes(bd.OP_SCORE, d) > 0
+    kd = bd.KvDesc(bd.BF16, 16, 4, 128, 1056, 0, bd.KV_BUDGET, bd.ORDER_FILL, 1024, 1, 0.995)
+    assert ctx.workspace_bytes(bd.OP_KV_COMPRESS, kd) >= 2 * 16 * 4 * 1056 * 4
+    ad = bd.AttnDesc(bd.BF16, 16, 28, 4, 128, 1056, 1025, 2, 0, 0.088, 0.9)
+    assert ctx.workspace_bytes(bd.OP_DECODE_ATTN, ad) > 0
+    md = bd.MergeDesc(1, 2176, 64, 2048, 636, 1)
+    planes = (bd.Plane * 1)(bd.Plane(0, 0, 2176 * 3584, 764 * 3584, 3584, bd.BF16, 0, 0))
+    assert ctx.workspace_bytes(bd.OP_MERGE, bd.MergeQuery(C.pointer(md), planes)) > 2048 * 4
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    ctx = _ctx()
+    bad = bd.ScoreDesc(bd.BF16, 1, 100, 4, 96, 6, 4, 128, 0, 50, 1, 1.0, 0, 0, 128, 0, 0, 128)   # Hq % Hkv != 0
+    with pytest.raises(lv.LvlmError) as e:
+        ctx.workspace_bytes(bd.OP_SCORE, bad)
+    assert e.value.status == 1 and "multiple" in str(e.value)
+    bad = bd.ScoreDesc(bd.BF16, 1, 100, 4, 96, 4, 4, 96, 0, 50, 1, 1.0, 0, 0, 96, 0, 0, 96)       # head_dim 96
+    with pytest.raises(lv.LvlmError):
+        ctx.workspace_bytes(bd.OP_SCORE, bad)
+    kd = bd.KvDesc(bd.BF16, 1, 1, 128, 64, 0, bd.KV_BUDGET, bd.ORDER_FILL, 0, 0, 0.5)              # budget 0
+    with pytest.raises(lv.LvlmError):
+        ctx.workspace_bytes(bd.OP_KV_COMPRESS, kd)
+    # hot-path calls: null pointers, bad n_keep, missing workspace -- all fail on the host
+    d = bd.ScoreDesc(bd.BF16, 1, 128, 4, 124, 4, 4, 128, 0, 64, 1, 1.0, 4 * 512, 512, 128, 128 * 512, 512, 128)
+    st = bd.lib.lvlm_score_tokens(ctx._h, None, C.byref(d), None, None, None, None, None)
+    assert st == 1 and b"null" in bd.lib.lvlm_last_error(ctx._h)
+    st = bd.lib.lvlm_score_tokens(ctx._h, None, C.byref(d), 4096, 8192, None, 12288, 16384)
+    assert st == 3 and b"workspace" in bd.lib.lvlm_last_error(ctx._h)
+    st = bd.lib.lvlm_score_tokens(ctx._h, None, C.byref(d), 4100, 8192, None, 12288, 16384)
+    assert st == 1 and b"aligned" in bd.lib.lvlm_last_error(ctx._h)
+    md = bd.MergeDesc(1, 100, 10, 50, 51, 1)                                                       # n_keep > n_img
+    planes = (bd.Plane * 1)(bd.Plane(4096, 1 << 20, 100 * 8, 100 * 8, 8, bd.BF16, 0, 0))
+    st = bd.lib.lvlm_merge_compact(ctx._h, None, C.byref(md), 256, None, planes, None, None)
+    assert st == 1 and b"n_keep" in bd.lib.lvlm_last_error(ctx._h)
+    md = bd.MergeDesc(1, 100, 10, 50, 20, 1)
+    planes = (bd.Plane * 1)(bd.Plane(4096, 4096 + 64, 100 * 8, 100 * 8, 8, bd.BF16, 0, 0))        # overlap
+    st = bd.lib.lvlm_merge_compact(ctx._h, None, C.byref(md), 256, None, planes, None, None)
+    assert st == 1 and b"overlap" in bd.lib.lvlm_last_error(ctx._h)
+    planes = (bd.Plane * 1)(bd.Plane(4096, 1 << 20, 100 * 8, 100 * 8, 8, bd.I32, 0, 0))           # int + weighted
+    st = bd.lib.lvlm_merge_compact(ctx._h, None, C.byref(md), 256, None, planes, None, None)
+    assert st == 1 and b"integer" in bd.lib.lvlm_last_error(ctx._h)
+    ad = bd.AttnDesc(bd.BF16, 1, 32, 2, 128, 64, 0, 2, 0, 1.0, 1.0)                                 # G = 16
+    st = bd.lib.lvlm_decode_attn(ctx._h, None, C.byref(ad), 256, None, None, 512, 768, None, None, None, 1024, 2048)
+    assert st == 2
+    ad = bd.AttnDesc(bd.BF16, 1, 4, 2, 128, 64, 0, 2, 0, 1.0, 1.0)
+    st = bd.lib.lvlm_decode_attn(ctx._h, None, C.byref(ad), 256, 512, None, 512, 768, None, None, None, 1024, 2048)
+    assert st == 1 and b"together" in bd.lib.lvlm_last_error(ctx._h)
