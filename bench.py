@@ -1,0 +1,377 @@
+#!/usr/bin/env python3
+"""Benchmark of the LightVLM token-reduction path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic batch of the
+Qwen2.5-VL-7B-shaped workload (config 2: 28 layers, 64 system + 2048 image +
+64 instruction tokens, bf16):
+
+  prefill, per decoder layer l >= 5:  lvlm_score_tokens (instruction queries x
+      all keys of layer l, written straight into that layer's cache scores);
+      at the pyramid layers 5 / 9 / 13: lvlm_merge_compact of the hidden states
+      and position ids down to 100 % / 35 % / 3 % of the image tokens;
+      then lvlm_kv_compress (threshold beta = 0.995, stable order) of layer l's
+      per-head cache;
+  decode, one generated token: per layer lvlm_decode_attn (append + GQA
+      attention over the retained entries + importance update), then
+      lvlm_kv_compress (fixed budget, fill order).
+
+Inputs are resident in HBM before the timed region.  Every step works on its
+own copy of the state (caches are modified in place), so no step re-reads
+buffers a previous step left in cache.  Each step is a pair of HIP graphs
+(prefill, decode) captured beforehand; the timed region replays them.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--profile-steps", type=int, default=3, help="eager steps timed per kernel with HIP events")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    return ap.parse_args()
+
+
+# ----------------------------------------------------------------------------- workload plan
+def plan(w, lv):
+    """Per-layer image-token counts and which calls run where (host arithmetic only)."""
+    if w.name.startswith("cfg2"):
+        # "keep fraction falls 100 % -> 35 % -> 3 % across the pyramid layers": explicit counts
+        keeps = [int(w.n_img * f + 0.5) for f in (1.0, 0.35, 0.03)]
+    elif w.merge_layers:
+        keeps = lv.schedule(w.n_img, w.final_keep[-1], len(w.merge_layers))
+    else:
+        keeps = []
+    layers = []
+    n_img = w.n_img
+    for l in range(w.layers):
+        entry = {"layer": l, "n_img": n_img, "score": bool(w.merge_layers) and l >= w.kv_first_layer,
+                 "merge_to": None, "kv_threshold": bool(w.merge_layers) and l >= w.kv_first_layer}
+        if l in w.merge_layers:
+            entry["merge_to"] = keeps[w.merge_layers.index(l)]
+        layers.append(entry)
+        if entry["merge_to"] is not None:
+            n_img = entry["merge_to"]
+    return layers
+
+
+class LayerState:
+    """Device buffers of one decoder layer for one step."""
+
+    def __init__(self, w, entry, master, torch, extra_slots=8):
+        B, H, d = w.batch, w.n_kv_heads, w.head_dim
+        self.entry = entry
+        self.n_img = entry["n_img"]
+        self.N = w.n_sys + self.n_img + w.n_text
+        self.Lmax = self.N + extra_slots
+        m = master[entry["layer"]]
+        self.q = m["q"].clone()                                   # [B,T,Hq,d]
+        self.k = m["k"].clone()                                   # [B,H,Lmax,d] head-major cache
+        self.v = m["v"].clone()
+        self.score = m["score"].clone()
+        self.kind = m["kind"].clone()
+        self.pos = m["pos"].clone()
+        self.len = m["len"].clone()
+        self.hidden = m["hidden"].clone() if "hidden" in m else None
+        self.pos_ids = m["pos_ids"].clone() if "pos_ids" in m else None
+        self.score_mean = torch.empty(B, self.n_img, dtype=torch.float32, device=self.q.device)
+        if entry["merge_to"] is not None:
+            r = self.n_img - entry["merge_to"]
+            self.hidden_out = torch.empty(B, self.N - r, w.hidden, dtype=self.hidden.dtype, device=self.q.device)
+            self.pos_out = torch.empty(B, self.N - r, 3, dtype=torch.int32, device=self.q.device)
+            self.keep_idx = torch.empty(B, max(entry["merge_to"] - 1, 1), dtype=torch.int32, device=self.q.device)
+            self.merged_idx = torch.empty(B, r + 1, dtype=torch.int32, device=self.q.device)
+        self.q_dec = m["q_dec"].clone()
+        self.k_dec = m["k_dec"].clone()
+        self.v_dec = m["v_dec"].clone()
+        self.out_dec = torch.empty_like(self.q_dec)
+        self.n_evicted = torch.empty(B, H, dtype=torch.int32, device=self.q.device)
+
+
+def build_master(w, layers, torch, synth, dev):
+    """One set of inputs per layer, generated on the GPU (seeded)."""
+    master = []
+    B, H, d = w.batch, w.n_kv_heads, w.head_dim
+    for entry in layers:
+        l, n_img = entry["layer"], entry["n_img"]
+        x = synth.layer_inputs(w, layer=l, n_img=n_img, device=dev)
+        N = x["k"].shape[1]
+        Lmax = N + 8
+        m = {"q": x["q"]}
+        for name in ("k", "v"):
+            cache = torch.zeros(B, H, Lmax, d, dtype=x[name].dtype, device=dev)
+            cache[:, :, :N] = x[name].permute(0, 2, 1, 3)
+            m[name] = cache
+        m["score"] = torch.zeros(B, H, Lmax, dtype=torch.float32, device=dev)
+        kind = torch.zeros(B, H, Lmax, dtype=torch.uint8, device=dev)
+        kind[:, :, w.n_sys:w.n_sys + n_img] = 1
+        m["kind"] = kind
+        m["pos"] = torch.arange(Lmax, dtype=torch.int32, device=dev).view(1, 1, Lmax).expand(B, H, Lmax).contiguous()
+        m["len"] = torch.full((B, H), N, dtype=torch.int32, device=dev)
+        if entry["merge_to"] is not None:
+            m["hidden"] = x["hidden"]
+            m["pos_ids"] = x["pos"].expand(B, N, 3).contiguous()
+        stream = synth.DecodeStream(w, layer=l, device=dev)
+        m["q_dec"], m["k_dec"], m["v_dec"] = stream.next()
+        master.append(m)
+    return master
+
+
+def run_prefill(ctx, lv, w, states, reserve):
+    for st in states:
+        e = st.entry
+        img0 = w.n_sys
+        if e["score"]:
+            k_view = st.k[:, :, :st.N].permute(0, 2, 1, 3)          # [B,N,H,d] view of the head-major cache
+            sh_view = st.score[:, :, img0:img0 + st.n_img]          # scores land in the cache's score array
+            ctx.score_tokens(st.q, k_view, q_pos0=img0 + st.n_img, img_begin=img0, n_img=st.n_img,
+                             score_head=sh_view, score_mean=st.score_mean, reserve=reserve)
+        if e["merge_to"] is not None:
+            ctx.merge_compact([st.hidden, st.pos_ids], st.score_mean, img_begin=img0, n_img=st.n_img,
+                              n_keep=e["merge_to"], rules=[lv.RULE_WEIGHTED, lv.RULE_TOP],
+                              outs=[st.hidden_out, st.pos_out], keep_idx=st.keep_idx, merged_idx=st.merged_idx,
+                              reserve=reserve)
+        if e["kv_threshold"]:
+            ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_THRESHOLD, beta=w.kv_beta,
+                            order=lv.ORDER_STABLE, len_bound=st.N, n_evicted=st.n_evicted, reserve=reserve)
+
+
+def run_decode(ctx, lv, w, states, reserve, step_pos=0):
+    for st in states:
+        bound = min(st.Lmax, max(st.N, w.kv_budget) + 1)
+        ctx.decode_attn(st.q_dec, st.k_dec, st.v_dec, st.k, st.v, st.score, st.kind, st.pos, st.len,
+                        score_decay=0.9, new_pos=w.seq_len + step_pos, len_bound=bound, out=st.out_dec,
+                        reserve=reserve)
+        ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_BUDGET, budget=w.kv_budget,
+                        n_recent=1, order=lv.ORDER_FILL, len_bound=bound, n_evicted=st.n_evicted, reserve=reserve)
+
+
+# ----------------------------------------------------------------------------- algorithmic work per kernel
+def kernel_work(w, layers, lens_after_prefill):
+    """Algorithmic bytes / flops of one launch-set of each kernel in one step (sum over layers)."""
+    e = 2 if w.dtype == "bf16" else 4
+    B, Hq, H, d, T = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_text
+    work = {}
+
+    def add(name, bound, amount, launches=1):
+        a = work.setdefault(name, {"bound": bound, "amount": 0.0, "launches": 0})
+        a["amount"] += amount
+        a["launches"] += launches
+
+    for i, en in enumerate(layers):
+        N = w.n_sys + en["n_img"] + T
+        if en["score"]:
+            add("score_pass0", "mfma", 2.0 * B * T * N * d * Hq)
+            add("score_pass1", "mfma", 2.0 * B * T * en["n_img"] * d * Hq)
+        if en["merge_to"] is not None:
+            r = en["n_img"] - en["merge_to"]
+            add("merge_gather", "hbm", B * (N + N - r) * (w.hidden * e + 3 * 4))
+        L = float(lens_after_prefill[i].double().mean()) + 1.0 if lens_after_prefill is not None else N + 1
+        add("attn_partial", "hbm", 2.0 * B * H * L * d * e)
+    return work
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2509_00419_amd as lv
+    from workloads import configs, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    w = configs.ALL[args.workload]
+    layers = plan(w, lv)
+    ctx = lv.Context(0)
+    t_setup = time.time()
+    master = build_master(w, layers, torch, synth, dev)
+    n_sets = 1 + args.warmup + args.steps + args.profile_steps
+    sets = [[LayerState(w, en, master, torch) for en in layers] for _ in range(n_sets)]
+    torch.cuda.synchronize()
+    print(f"[bench] {w.name}: {len(layers)} layers, {n_sets} state sets, setup {time.time() - t_setup:.1f}s",
+          file=sys.stderr, flush=True)
+
+    # dry run on set 0: sizes the workspace, gives the cache lengths used for the byte counts
+    run_prefill(ctx, lv, w, sets[0], reserve=True)
+    torch.cuda.synchronize()
+    lens_after_prefill = [st.len.clone() for st in sets[0]]
+    run_decode(ctx, lv, w, sets[0], reserve=True)
+    torch.cuda.synchronize()
+
+    # capture one (prefill, decode) graph pair per remaining set
+    use_graph = not args.no_graph
+    graphs = []
+    if use_graph:
+        for s in range(1, 1 + args.warmup + args.steps):
+            gp, gd = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gp):
+                run_prefill(ctx, lv, w, sets[s], reserve=False)
+            with torch.cuda.graph(gd):
+                run_decode(ctx, lv, w, sets[s], reserve=False)
+            graphs.append((gp, gd))
+        torch.cuda.synchronize()
+
+    def step(i):
+        if use_graph:
+            graphs[i][0].replay()
+            ev_mid[i].record()
+            graphs[i][1].replay()
+        else:
+            run_prefill(ctx, lv, w, sets[1 + i], reserve=False)
+            ev_mid[i].record()
+            run_decode(ctx, lv, w, sets[1 + i], reserve=False)
+
+    n_run = args.warmup + args.steps
+    ev_mid = [torch.cuda.Event(enable_timing=True) for _ in range(n_run)]
+    ev_beg = [torch.cuda.Event(enable_timing=True) for _ in range(n_run + 1)]
+    for i in range(args.warmup):
+        ev_beg[i].record()
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.warmup, n_run):
+        ev_beg[i].record()
+        step(i)
+    ev_beg[n_run].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = wall_ms / args.steps
+    prefill_ms = sum(ev_beg[i].elapsed_time(ev_mid[i]) for i in range(args.warmup, n_run)) / args.steps
+    decode_ms = sum(ev_mid[i].elapsed_time(ev_beg[i + 1]) for i in range(args.warmup, n_run)) / args.steps
+
+    # per-kernel durations: eager steps with every launch bracketed by HIP events on the launch stream
+    prof = {}
+    if args.profile_steps > 0:
+        ctx.profile(True)
+        agg = {}
+        for s in range(1 + n_run, n_sets):
+            run_prefill(ctx, lv, w, sets[s], reserve=False)
+            for name, (calls, tot, mn, mx) in ctx.profile_read().items():
+                a = agg.setdefault(name, [0, 0.0])
+                a[0] += calls
+                a[1] += tot
+            run_decode(ctx, lv, w, sets[s], reserve=False)
+            for name, (calls, tot, mn, mx) in ctx.profile_read().items():
+                a = agg.setdefault(name, [0, 0.0])
+                a[0] += calls
+                a[1] += tot
+        ctx.profile(False)
+        prof = {k: {"launches_per_step": v[0] / args.profile_steps, "us_per_step": v[1] * 1e3 / args.profile_steps,
+                    "avg_us": v[1] * 1e3 / max(v[0], 1)} for k, v in agg.items()}
+
+    work = kernel_work(w, layers, lens_after_prefill)
+    kernels = {}
+    for name, p in sorted(prof.items(), key=lambda kv: -kv[1]["us_per_step"]):
+        row = {"avg_us": round(p["avg_us"], 2), "launches_per_step": p["launches_per_step"],
+               "us_per_step": round(p["us_per_step"], 1)}
+        if name in work and p["us_per_step"] > 0:
+            amt = work[name]["amount"]
+            if work[name]["bound"] == "hbm":
+                row.update(bound="hbm", achieved_GBs=round(amt / p["us_per_step"] / 1e3, 1),
+                           frac=round(amt / p["us_per_step"] / 1e3 / HBM_PEAK_GBS, 4))
+            else:
+                row.update(bound="mfma", achieved_TFLOPs=round(amt / p["us_per_step"] / 1e6, 1),
+                           frac=round(amt / p["us_per_step"] / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4))
+        kernels[name] = row
+    roofline = None
+    for name, row in kernels.items():           # dominant kernel = most time per step among the modelled ones
+        if "bound" in row:
+            amt, per_launch = work[name]["amount"], work[name]["launches"]
+            if row["bound"] == "hbm":
+                roofline = {"kernel": name, "bound": "hbm", "achieved": row["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                            "unit": "GB/s", "frac": row["frac"], "traffic": None,
+                            "algorithmic_bytes_per_launch": amt / per_launch, "avg_launch_us": row["avg_us"]}
+            else:
+                roofline = {"kernel": name, "bound": "mfma", "achieved": row["achieved_TFLOPs"],
+                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": row["frac"], "traffic": None,
+                            "algorithmic_flops_per_launch": amt / per_launch, "avg_launch_us": row["avg_us"]}
+            break
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, layers, master, torch, lv)
+
+    out = {
+        "metric": "prefill merge tokens/s + compacted-KV decode steps/s; % HBM roofline",
+        "value": round(w.batch * w.n_img / (ms_per_step * 1e-3), 1),
+        "unit": "image tokens/s (whole step: prefill token reduction + one decode step over all layers)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "layers": w.layers, "seq": [w.n_sys, w.n_img, w.n_text],
+                   "image_tokens_per_layer": [en["n_img"] for en in layers if en["merge_to"] is not None] +
+                                             [layers[-1]["n_img"]],
+                   "kv_beta": w.kv_beta, "kv_budget": w.kv_budget, "graphs": use_graph},
+        "prefill_ms": round(prefill_ms, 4), "decode_step_ms": round(decode_ms, 4),
+        "prefill_image_tokens_per_s": round(w.batch * w.n_img / (prefill_ms * 1e-3), 1),
+        "decode_steps_per_s": round(1e3 / decode_ms, 1),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+# ----------------------------------------------------------------------------- oracle leg
+def cpu_baseline(w, layers, master, torch, lv):
+    """The oracle, as it stands, on one full step of the same inputs (host cores)."""
+    import numpy as np
+
+    from oracle import lvlm_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+
+    def f64(t):
+        return t.detach().double().cpu().numpy()
+
+    host = []
+    for m in master:
+        host.append({k: (f64(v) if v.dtype in (torch.bfloat16, torch.float32) else v.cpu().numpy())
+                     for k, v in m.items()})
+    t0 = time.perf_counter()
+    for en, m in zip(layers, host):
+        N = w.n_sys + en["n_img"] + w.n_text
+        img0 = w.n_sys
+        if en["score"]:
+            k = np.transpose(m["k"][:, :, :N], (0, 2, 1, 3))
+            sh, sm = O.score_tokens(m["q"], k, q_pos0=img0 + en["n_img"], img_begin=img0, n_img=en["n_img"])
+            m["score"][:, :, img0:img0 + en["n_img"]] = sh
+        if en["merge_to"] is not None:
+            O.merge_compact([m["hidden"], m["pos_ids"]], sm, img_begin=img0, n_img=en["n_img"],
+                            n_keep=en["merge_to"], rules=[O.RULE_WEIGHTED, O.RULE_TOP], dtypes=[w.dtype, "f32"])
+        state = [m["k"], m["v"], m["score"].astype(np.float32), m["kind"], m["pos"], m["len"]]
+        if en["kv_threshold"]:
+            state = list(O.kv_compress(*state, mode="threshold", beta=w.kv_beta, order=O.ORDER_STABLE)[:6])
+        res = O.decode_attn(m["q_dec"], m["k_dec"], m["v_dec"], *state, score_decay=0.9, new_pos=w.seq_len,
+                            out_dtype=w.dtype)
+        O.kv_compress(*res[1:], mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
+    sec = time.perf_counter() - t0
+    return {"value": round(w.batch * w.n_img / sec, 1), "unit": "image tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"one full step of {w.name} (all {w.layers} layers, same inputs), {sec:.2f} s"}
+
+
+if __name__ == "__main__":
+    main()

@@ -100,6 +100,19 @@ LVLM_API lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const
  * any time between calls; the library never frees it. */
 LVLM_API lvlm_status lvlm_set_workspace(lvlm_ctx *ctx, void *dev_ptr, size_t bytes);
 
+/* Per-kernel timing for benchmarks (not on the hot path, not usable during
+ * stream capture).  While enabled, every kernel the four calls launch is
+ * bracketed by a HIP event pair on the caller's stream (at most 4096 launches
+ * between reads).  lvlm_profile_read waits for those events, adds them up per
+ * kernel name into the caller's HOST array and clears the record. */
+typedef struct {
+    char name[48];
+    int32_t calls;
+    float total_ms, min_ms, max_ms;
+} lvlm_profile_entry;
+LVLM_API lvlm_status lvlm_profile(lvlm_ctx *ctx, int enable);
+LVLM_API lvlm_status lvlm_profile_read(lvlm_ctx *ctx, lvlm_profile_entry *out, int max_entries, int *n_entries);
+
 /* Pyramid schedule (App. A.2: merge layers use a constant reduction ratio set
  * by the budget).  n_keep_out[s-1] = floor(n_img * final_keep^(s/n_stages) + 0.5)
  * for s = 1..n_stages, taken from the original n_img and clamped to [1, n_img].
@@ -129,12 +142,16 @@ typedef struct {
     float scale;       /* logit scale, usually 1/sqrt(hd)                         */
     int64_t q_stride_b, q_stride_t, q_stride_h; /* q[b][i][h][0..hd)              */
     int64_t k_stride_b, k_stride_n, k_stride_h; /* k[b][j][g][0..hd)              */
+    int64_t sh_stride_b, sh_stride_h; /* score_head[b][g][0..n_img); both 0 = dense
+                                         [B,Hkv,n_img].  Lets the scores land in a
+                                         cache's score array (stride Lmax per head) */
 } lvlm_score_desc;
 
 /* q, k: device, dtype above.  row_lse: optional device fp32 [B,Hq,T] holding
  * the natural-log sum-exp of each row's scaled logits (as an attention kernel
  * produces); when NULL the library computes it with one more pass over k.
- * score_head [B,Hkv,n_img] fp32: mean over the G query heads of each KV head.
+ * score_head [B,Hkv,n_img] fp32 (strides above): mean over the G query heads of
+ * each KV head.
  * score_mean [B,n_img] fp32: mean over the KV heads (= over all heads).
  * Both outputs are written in full.  Workspace: LVLM_OP_SCORE. */
 LVLM_API lvlm_status lvlm_score_tokens(lvlm_ctx *ctx, void *stream, const lvlm_score_desc *d,

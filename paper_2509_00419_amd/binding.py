@@ -36,7 +36,8 @@ class ScoreDesc(C.Structure):
                 ("q_pos0", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32), ("hd", C.c_int32),
                 ("img_begin", C.c_int32), ("n_img", C.c_int32), ("causal", C.c_int32), ("scale", C.c_float),
                 ("q_stride_b", C.c_int64), ("q_stride_t", C.c_int64), ("q_stride_h", C.c_int64),
-                ("k_stride_b", C.c_int64), ("k_stride_n", C.c_int64), ("k_stride_h", C.c_int64)]
+                ("k_stride_b", C.c_int64), ("k_stride_n", C.c_int64), ("k_stride_h", C.c_int64),
+                ("sh_stride_b", C.c_int64), ("sh_stride_h", C.c_int64)]
 
 
 class Plane(C.Structure):
@@ -66,6 +67,11 @@ class AttnDesc(C.Structure):
                 ("new_pos", C.c_int32), ("scale", C.c_float), ("score_decay", C.c_float)]
 
 
+class ProfileEntry(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("calls", C.c_int32), ("total_ms", C.c_float), ("min_ms", C.c_float),
+                ("max_ms", C.c_float)]
+
+
 class LvlmError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"{STATUS.get(status, status)}: {message}")
@@ -90,7 +96,9 @@ def _load():
     lib.lvlm_merge_compact.argtypes = [vp, vp, C.POINTER(MergeDesc), f32p, f32p, C.POINTER(Plane), i32p, i32p]
     lib.lvlm_kv_compress.argtypes = [vp, vp, C.POINTER(KvDesc), vp, vp, f32p, vp, i32p, i32p, i32p]
     lib.lvlm_decode_attn.argtypes = [vp, vp, C.POINTER(AttnDesc), vp, vp, vp, vp, vp, f32p, vp, i32p, i32p, vp]
-    for name in ("lvlm_create", "lvlm_destroy", "lvlm_workspace_bytes", "lvlm_set_workspace", "lvlm_schedule",
+    lib.lvlm_profile.argtypes = [C.c_void_p, C.c_int]
+    lib.lvlm_profile_read.argtypes = [C.c_void_p, C.POINTER(ProfileEntry), C.c_int, C.POINTER(C.c_int)]
+    for name in ("lvlm_profile", "lvlm_profile_read", "lvlm_create", "lvlm_destroy", "lvlm_workspace_bytes", "lvlm_set_workspace", "lvlm_schedule",
                  "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_merge_compact", "lvlm_kv_compress",
                  "lvlm_decode_attn"):
         getattr(lib, name).restype = C.c_int
@@ -165,19 +173,34 @@ class Context:
         self._ws = ws
         self._check(lib.lvlm_set_workspace(self._h, _ptr(ws), 0 if ws is None else ws.numel()))
 
+    def profile(self, enable: bool):
+        """lvlm_profile: bracket every kernel launch with HIP events (eager mode only)."""
+        self._check(lib.lvlm_profile(self._h, int(enable)))
+
+    def profile_read(self):
+        """lvlm_profile_read -> {kernel name: (calls, total_ms, min_ms, max_ms)}; clears the record."""
+        arr = (ProfileEntry * 64)()
+        n = C.c_int()
+        self._check(lib.lvlm_profile_read(self._h, arr, 64, C.byref(n)))
+        return {arr[i].name.decode(): (arr[i].calls, arr[i].total_ms, arr[i].min_ms, arr[i].max_ms)
+                for i in range(n.value)}
+
     # ---- step 1 ----
-    def score_desc(self, q, k, *, q_pos0, img_begin, n_img, scale=None, causal=True) -> ScoreDesc:
+    def score_desc(self, q, k, *, q_pos0, img_begin, n_img, scale=None, causal=True, score_head=None) -> ScoreDesc:
         B, T, Hq, hd = q.shape
         _, N, Hkv, _ = k.shape
         assert q.stride(3) == 1 and k.stride(3) == 1, "head dimension must be contiguous"
         return ScoreDesc(_DTYPE[q.dtype], B, N, T, q_pos0, Hq, Hkv, hd, img_begin, n_img, int(causal),
                          float(hd ** -0.5 if scale is None else scale),
-                         q.stride(0), q.stride(1), q.stride(2), k.stride(0), k.stride(1), k.stride(2))
+                         q.stride(0), q.stride(1), q.stride(2), k.stride(0), k.stride(1), k.stride(2),
+                         0 if score_head is None else score_head.stride(0),
+                         0 if score_head is None else score_head.stride(1))
 
     def score_tokens(self, q, k, *, q_pos0, img_begin, n_img, scale=None, causal=True, row_lse=None,
                      score_head=None, score_mean=None, reserve=True):
         """lvlm_score_tokens.  q [B,T,Hq,d], k [B,N,Hkv,d] -> (score_head [B,Hkv,n_img], score_mean [B,n_img])."""
-        d = self.score_desc(q, k, q_pos0=q_pos0, img_begin=img_begin, n_img=n_img, scale=scale, causal=causal)
+        d = self.score_desc(q, k, q_pos0=q_pos0, img_begin=img_begin, n_img=n_img, scale=scale, causal=causal,
+                            score_head=score_head)
         if score_head is None:
             score_head = torch.empty(d.B, d.Hkv, n_img, dtype=torch.float32, device=q.device)
         if score_mean is None:

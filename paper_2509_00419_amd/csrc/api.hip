@@ -42,6 +42,9 @@ const char *check_score(const lvlm_score_desc *d) {
     for (long long x : s)
         if (x < 0 || x % vec != 0) return "strides must be non-negative multiples of 16 bytes";
     if (d->q_stride_h < d->hd || d->k_stride_h < d->hd) return "head stride smaller than the head dimension";
+    if ((d->sh_stride_b == 0) != (d->sh_stride_h == 0)) return "score_head strides must be both zero or both set";
+    if (d->sh_stride_h != 0 && (d->sh_stride_h < d->n_img || d->sh_stride_b < d->sh_stride_h))
+        return "score_head strides smaller than the rows they separate";
     return nullptr;
 }
 
@@ -131,12 +134,70 @@ lvlm_status lvlm_create(lvlm_ctx **ctx, int device) {
     c->ws = nullptr;
     c->ws_bytes = 0;
     c->err[0] = '\0';
+    c->prof_on = false;
+    c->prof_n = c->prof_cap = 0;
+    c->prof_ev = nullptr;
+    c->prof_name = nullptr;
     *ctx = c;
     return LVLM_OK;
 }
 
 lvlm_status lvlm_destroy(lvlm_ctx *ctx) {
+    if (ctx) {
+        for (int i = 0; i < 2 * ctx->prof_cap; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
+        delete[] ctx->prof_ev;
+        delete[] ctx->prof_name;
+    }
     delete ctx;
+    return LVLM_OK;
+}
+
+lvlm_status lvlm_profile(lvlm_ctx *ctx, int enable) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (enable && ctx->prof_cap == 0) {
+        constexpr int kCap = 4096;
+        if (lvlm_status st = bind_device(ctx)) return st;
+        ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * kCap];
+        ctx->prof_name = new (std::nothrow) const char *[kCap];
+        if (!ctx->prof_ev || !ctx->prof_name) return fail(ctx, LVLM_ERR_HIP, "out of host memory");
+        for (int i = 0; i < 2 * kCap; ++i) {
+            const hipError_t e = hipEventCreate(&ctx->prof_ev[i]);
+            if (e != hipSuccess) return fail(ctx, LVLM_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+            ctx->prof_cap = (i + 1) / 2;
+        }
+    }
+    ctx->prof_on = enable != 0;
+    if (enable) ctx->prof_n = 0;
+    return LVLM_OK;
+}
+
+lvlm_status lvlm_profile_read(lvlm_ctx *ctx, lvlm_profile_entry *out, int max_entries, int *n_entries) {
+    if (!ctx || !out || !n_entries || max_entries < 1) return LVLM_ERR_INVALID_ARG;
+    int n = 0;
+    for (int i = 0; i < ctx->prof_n; ++i) {
+        hipError_t e = hipEventSynchronize(ctx->prof_ev[2 * i + 1]);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]);
+        if (e != hipSuccess) return fail(ctx, LVLM_ERR_HIP, "profile read: %s", hipGetErrorString(e));
+        int k = 0;
+        while (k < n && strcmp(out[k].name, ctx->prof_name[i]) != 0) ++k;
+        if (k == n) {
+            if (n == max_entries) continue;
+            strncpy(out[k].name, ctx->prof_name[i], sizeof(out[k].name) - 1);
+            out[k].name[sizeof(out[k].name) - 1] = '\0';
+            out[k].calls = 0;
+            out[k].total_ms = 0.f;
+            out[k].min_ms = ms;
+            out[k].max_ms = ms;
+            ++n;
+        }
+        out[k].calls += 1;
+        out[k].total_ms += ms;
+        if (ms < out[k].min_ms) out[k].min_ms = ms;
+        if (ms > out[k].max_ms) out[k].max_ms = ms;
+    }
+    ctx->prof_n = 0;
+    *n_entries = n;
     return LVLM_OK;
 }
 
@@ -234,7 +295,7 @@ lvlm_status lvlm_score_tokens(lvlm_ctx *ctx, void *stream, const lvlm_score_desc
     const ScoreWs w = score_ws(*d);
     if (lvlm_status st = need_ws(ctx, w.total)) return st;
     if (lvlm_status st = bind_device(ctx)) return st;
-    return after_launch(ctx, launch_score(static_cast<hipStream_t>(stream), *d, w, static_cast<char *>(ctx->ws), q, k,
+    return after_launch(ctx, launch_score(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w, static_cast<char *>(ctx->ws), q, k,
                                           row_lse, score_head, score_mean));
 }
 
@@ -248,7 +309,7 @@ lvlm_status lvlm_merge_compact(lvlm_ctx *ctx, void *stream, const lvlm_merge_des
     const MergeWs mw = merge_ws(*d, planes);
     if (lvlm_status st = need_ws(ctx, mw.total)) return st;
     if (lvlm_status st = bind_device(ctx)) return st;
-    return after_launch(ctx, launch_merge(static_cast<hipStream_t>(stream), *d, mw, static_cast<char *>(ctx->ws),
+    return after_launch(ctx, launch_merge(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, mw, static_cast<char *>(ctx->ws),
                                           score_mean, w, planes, keep_idx, merged_idx));
 }
 
@@ -264,7 +325,7 @@ lvlm_status lvlm_kv_compress(lvlm_ctx *ctx, void *stream, const lvlm_kv_desc *d,
     const KvWs w = kv_ws(*d);
     if (lvlm_status st = need_ws(ctx, w.total)) return st;
     if (lvlm_status st = bind_device(ctx)) return st;
-    return after_launch(ctx, launch_kv_compress(static_cast<hipStream_t>(stream), *d, w, static_cast<char *>(ctx->ws),
+    return after_launch(ctx, launch_kv_compress(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w, static_cast<char *>(ctx->ws),
                                                 k_cache, v_cache, score, kind, orig_pos, len, n_evicted));
 }
 
@@ -286,7 +347,7 @@ lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *
     const AttnWs w = attn_ws(*d);
     if (lvlm_status st = need_ws(ctx, w.total)) return st;
     if (lvlm_status st = bind_device(ctx)) return st;
-    return after_launch(ctx, launch_decode_attn(static_cast<hipStream_t>(stream), *d, w, static_cast<char *>(ctx->ws),
+    return after_launch(ctx, launch_decode_attn(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w, static_cast<char *>(ctx->ws),
                                                 q, k_new, v_new, k_cache, v_cache, score, kind, orig_pos, len, out));
 }
 

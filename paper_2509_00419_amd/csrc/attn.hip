@@ -349,20 +349,25 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
 }
 
 template <int DT, int HD, int GP>
-void launch_both(hipStream_t stream, const AttnArgs &a, int B, int len_bound) {
+void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
+    hipStream_t stream = prof.stream;
+    prof.begin("attn_partial");
     hipLaunchKernelGGL((attn_partial_kernel<DT, HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
+    prof.end();
     const int chunks = a.update_score ? (len_bound + 1023) / 1024 : 1;
+    prof.begin("attn_combine");
     hipLaunchKernelGGL((attn_combine_kernel<DT, HD, GP>), dim3(chunks < 1 ? 1 : chunks, a.Hkv, B), dim3(256), 0,
                        stream, a);
+    prof.end();
 }
 
 template <int DT, int HD>
-void launch_gp(hipStream_t stream, const AttnArgs &a, int B, int len_bound, int gp) {
+void launch_gp(const Prof &prof, const AttnArgs &a, int B, int len_bound, int gp) {
     switch (gp) {
-        case 1: launch_both<DT, HD, 1>(stream, a, B, len_bound); break;
-        case 2: launch_both<DT, HD, 2>(stream, a, B, len_bound); break;
-        case 4: launch_both<DT, HD, 4>(stream, a, B, len_bound); break;
-        default: launch_both<DT, HD, 8>(stream, a, B, len_bound); break;
+        case 1: launch_both<DT, HD, 1>(prof, a, B, len_bound); break;
+        case 2: launch_both<DT, HD, 2>(prof, a, B, len_bound); break;
+        case 4: launch_both<DT, HD, 4>(prof, a, B, len_bound); break;
+        default: launch_both<DT, HD, 8>(prof, a, B, len_bound); break;
     }
 }
 
@@ -393,7 +398,7 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     return w;
 }
 
-hipError_t launch_decode_attn(hipStream_t stream, const lvlm_attn_desc &d, const AttnWs &w, char *ws, const void *q,
+hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const AttnWs &w, char *ws, const void *q,
                               const void *k_new, const void *v_new, void *k_cache, void *v_cache, float *score,
                               uint8_t *kind, int32_t *orig_pos, int32_t *len, void *out) {
     const int bound = d.len_bound > 0 ? d.len_bound : d.Lmax;
@@ -420,10 +425,10 @@ hipError_t launch_decode_attn(hipStream_t stream, const lvlm_attn_desc &d, const
     a.scale_log2 = d.scale * kLog2e;
     a.decay = d.score_decay;
     const int gp = group_pad(G);
-    if (d.dtype == LVLM_BF16 && d.hd == 128) launch_gp<LVLM_BF16, 128>(stream, a, d.B, bound, gp);
-    else if (d.dtype == LVLM_BF16 && d.hd == 64) launch_gp<LVLM_BF16, 64>(stream, a, d.B, bound, gp);
-    else if (d.dtype == LVLM_F32 && d.hd == 128) launch_gp<LVLM_F32, 128>(stream, a, d.B, bound, gp);
-    else launch_gp<LVLM_F32, 64>(stream, a, d.B, bound, gp);
+    if (d.dtype == LVLM_BF16 && d.hd == 128) launch_gp<LVLM_BF16, 128>(prof, a, d.B, bound, gp);
+    else if (d.dtype == LVLM_BF16 && d.hd == 64) launch_gp<LVLM_BF16, 64>(prof, a, d.B, bound, gp);
+    else if (d.dtype == LVLM_F32 && d.hd == 128) launch_gp<LVLM_F32, 128>(prof, a, d.B, bound, gp);
+    else launch_gp<LVLM_F32, 64>(prof, a, d.B, bound, gp);
     return hipGetLastError();
 }
 

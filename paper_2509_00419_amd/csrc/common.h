@@ -13,6 +13,11 @@ struct lvlm_ctx {
     void *ws;
     size_t ws_bytes;
     char err[256];
+    // optional per-kernel timing (eager launches only): one event pair per launch
+    bool prof_on;
+    int prof_n, prof_cap;
+    hipEvent_t *prof_ev;        // 2 * prof_cap events
+    const char **prof_name;     // prof_cap static strings
 };
 
 namespace lvlm {
@@ -50,17 +55,33 @@ struct AttnWs {
 };
 AttnWs attn_ws(const lvlm_attn_desc &d);
 
+// Brackets one kernel launch with a HIP event pair when profiling is on.
+struct Prof {
+    lvlm_ctx *ctx;
+    hipStream_t stream;
+    void begin(const char *name) const {
+        if (!ctx->prof_on || ctx->prof_n >= ctx->prof_cap) return;
+        ctx->prof_name[ctx->prof_n] = name;
+        (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n], stream);
+    }
+    void end() const {
+        if (!ctx->prof_on || ctx->prof_n >= ctx->prof_cap) return;
+        (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n + 1], stream);
+        ++ctx->prof_n;
+    }
+};
+
 // ---- launches (defined in the .hip files; all asynchronous on `stream`) ----
-hipError_t launch_score(hipStream_t stream, const lvlm_score_desc &d, const ScoreWs &w, char *ws,
+hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreWs &w, char *ws,
                         const void *q, const void *k, const float *row_lse, float *score_head,
                         float *score_mean);
-hipError_t launch_merge(hipStream_t stream, const lvlm_merge_desc &d, const MergeWs &w, char *ws,
+hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeWs &w, char *ws,
                         const float *score_mean, const float *wtab, const lvlm_plane *planes,
                         int32_t *keep_idx, int32_t *merged_idx);
-hipError_t launch_kv_compress(hipStream_t stream, const lvlm_kv_desc &d, const KvWs &w, char *ws,
+hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvWs &w, char *ws,
                               void *k_cache, void *v_cache, float *score, uint8_t *kind,
                               int32_t *orig_pos, int32_t *len, int32_t *n_evicted);
-hipError_t launch_decode_attn(hipStream_t stream, const lvlm_attn_desc &d, const AttnWs &w, char *ws,
+hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const AttnWs &w, char *ws,
                               const void *q, const void *k_new, const void *v_new, void *k_cache,
                               void *v_cache, float *score, uint8_t *kind, int32_t *orig_pos,
                               int32_t *len, void *out);

@@ -375,7 +375,7 @@ KvWs kv_ws(const lvlm_kv_desc &d) {
     return w;
 }
 
-hipError_t launch_kv_compress(hipStream_t stream, const lvlm_kv_desc &d, const KvWs &w, char *ws, void *k_cache,
+hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvWs &w, char *ws, void *k_cache,
                               void *v_cache, float *score, uint8_t *kind, int32_t *orig_pos, int32_t *len,
                               int32_t *n_evicted) {
     const size_t heads = (size_t)d.B * d.Hkv;
@@ -389,10 +389,15 @@ hipError_t launch_kv_compress(hipStream_t stream, const lvlm_kv_desc &d, const K
     a.Hkv = d.Hkv; a.Lmax = d.Lmax;
     a.row_bytes = d.hd * (d.dtype == LVLM_BF16 ? 2 : 4);
     a.mode = d.mode; a.order = d.order; a.budget = d.budget; a.n_recent = d.n_recent; a.beta = d.beta;
+    hipStream_t stream = prof.stream;
+    prof.begin("kv_select");
     hipLaunchKernelGGL(kv_select_kernel, dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    prof.end();
     if (d.order == LVLM_ORDER_STABLE) {
         const int slices = a.row_bytes / kSliceBytes;
+        prof.begin("kv_move");
         hipLaunchKernelGGL(kv_move_kernel, dim3(2 * slices + 1, (unsigned)heads), dim3(256), 0, stream, a);
+        prof.end();
     }
     return hipGetLastError();
 }

@@ -328,9 +328,10 @@ MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes) {
     return w;
 }
 
-hipError_t launch_merge(hipStream_t stream, const lvlm_merge_desc &d, const MergeWs &w, char *ws,
+hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeWs &w, char *ws,
                         const float *score_mean, const float *wtab, const lvlm_plane *planes, int32_t *keep_idx,
                         int32_t *merged_idx) {
+    hipStream_t stream = prof.stream;
     const int r = d.n_img - d.n_keep;
     GatherArgs g{};
     g.B = d.B; g.N = d.N; g.img_begin = d.img_begin; g.n_img = d.n_img; g.n_keep = d.n_keep;
@@ -380,19 +381,27 @@ hipError_t launch_merge(hipStream_t stream, const lvlm_merge_desc &d, const Merg
         ra.n_split = w.n_split;
         const int tiles = (d.n_img + kRankTile - 1) / kRankTile;
         ra.split_len = (tiles + w.n_split - 1) / w.n_split * kRankTile;
+        prof.begin("merge_rank");
         hipLaunchKernelGGL(rank_kernel, dim3((d.n_img + 255) / 256, w.n_split, d.B), dim3(256), 0, stream, ra);
+        prof.end();
         IndexArgs ia{};
         ia.rank_part = ra.rank_part;
         ia.dst_of = reinterpret_cast<int32_t *>(ws + w.dst_of);
         ia.keep_idx = keep_idx;
         ia.merged_idx = merged_idx;
         ia.n = d.n_img; ia.n_split = w.n_split; ia.n_keep = d.n_keep;
+        prof.begin("merge_index");
         hipLaunchKernelGGL(index_kernel, dim3(d.B), dim3(1024), 0, stream, ia);
+        prof.end();
     }
+    prof.begin("merge_gather");
     hipLaunchKernelGGL(gather_kernel, dim3(grid_x, grid_y, d.B * d.n_planes), dim3(256), 0, stream, g);
+    prof.end();
     if (r > 0 && any_weighted) {
+        prof.begin("merge_finalize");
         hipLaunchKernelGGL(finalize_kernel, dim3((w.max_row_elems + 255) / 256, d.B * d.n_planes), dim3(256), 0,
                            stream, g);
+        prof.end();
     }
     return hipGetLastError();
 }

@@ -38,7 +38,7 @@ struct ScoreArgs {
     float *score_mean;
     int B, N, T, q_pos0, Hq, Hkv, G, img_begin, n_img, causal, nkb;
     float scale_log2;
-    long long qsb, qst, qsh, ksb, ksn, ksh;
+    long long qsb, qst, qsh, ksb, ksn, ksh, shb, shh;
 };
 
 template <int DT>
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(256) void score_pass_kernel(ScoreArgs a) {
             const float tot = colsum[s] + __shfl_xor(colsum[s], 32);
             const int j = jbase + 32 * s + l32;
             if (hf == 0 && j < key_hi)
-                a.score_head[((long long)b * a.Hkv + g) * a.n_img + (j - a.img_begin)] = tot * inv_g;
+                a.score_head[(long long)b * a.shb + (long long)g * a.shh + (j - a.img_begin)] = tot * inv_g;
         }
     }
 }
@@ -300,29 +300,38 @@ __global__ __launch_bounds__(256) void score_lse_kernel(const float *part_m, con
 
 // score_mean[b][j] = mean over KV heads, summed in head order.
 __global__ __launch_bounds__(256) void score_mean_kernel(const float *score_head, float *score_mean, int Hkv,
-                                                         int n_img) {
+                                                         int n_img, long long shb, long long shh) {
     const int j = blockIdx.x * 256 + threadIdx.x;
     const int b = blockIdx.y;
     if (j >= n_img) return;
     float s = 0.f;
-    for (int g = 0; g < Hkv; ++g) s += score_head[((long long)b * Hkv + g) * n_img + j];
+    for (int g = 0; g < Hkv; ++g) s += score_head[(long long)b * shb + (long long)g * shh + j];
     score_mean[(long long)b * n_img + j] = s / (float)Hkv;
 }
 
 template <int DT, int HD, int KPW>
-void launch_passes(hipStream_t stream, const ScoreArgs &a, bool need_lse) {
+void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse) {
+    hipStream_t stream = prof.stream;
     constexpr int BN = 4 * KPW * 32;
     if (need_lse) {
         dim3 grid0((a.N + BN - 1) / BN, a.Hkv, a.B);
+        prof.begin("score_pass0");
         hipLaunchKernelGGL((score_pass_kernel<DT, HD, KPW, 0>), grid0, dim3(256), 0, stream, a);
+        prof.end();
         const int rows = a.B * a.Hq * a.T;
+        prof.begin("score_lse");
         hipLaunchKernelGGL(score_lse_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, a.part_m, a.part_l,
                            a.lse2, rows, a.nkb);
+        prof.end();
     }
     dim3 grid1((a.n_img + BN - 1) / BN, a.Hkv, a.B);
+    prof.begin("score_pass1");
     hipLaunchKernelGGL((score_pass_kernel<DT, HD, KPW, 1>), grid1, dim3(256), 0, stream, a);
+    prof.end();
+    prof.begin("score_mean");
     hipLaunchKernelGGL(score_mean_kernel, dim3((a.n_img + 255) / 256, a.B), dim3(256), 0, stream, a.score_head,
-                       a.score_mean, a.Hkv, a.n_img);
+                       a.score_mean, a.Hkv, a.n_img, a.shb, a.shh);
+    prof.end();
 }
 
 }  // namespace
@@ -341,7 +350,7 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
     return w;
 }
 
-hipError_t launch_score(hipStream_t stream, const lvlm_score_desc &d, const ScoreWs &w, char *ws, const void *q,
+hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreWs &w, char *ws, const void *q,
                         const void *k, const float *row_lse, float *score_head, float *score_mean) {
     ScoreArgs a{};
     a.q = static_cast<const char *>(q);
@@ -357,18 +366,21 @@ hipError_t launch_score(hipStream_t stream, const lvlm_score_desc &d, const Scor
     a.scale_log2 = d.scale * kLog2e;
     a.qsb = d.q_stride_b; a.qst = d.q_stride_t; a.qsh = d.q_stride_h;
     a.ksb = d.k_stride_b; a.ksn = d.k_stride_n; a.ksh = d.k_stride_h;
+    const bool dense = d.sh_stride_b == 0 && d.sh_stride_h == 0;
+    a.shh = dense ? d.n_img : d.sh_stride_h;
+    a.shb = dense ? (long long)d.Hkv * d.n_img : d.sh_stride_b;
     const bool need_lse = row_lse == nullptr;
     const bool wide = w.block_keys == 256;
     if (d.dtype == LVLM_BF16 && d.hd == 128) {
-        if (wide) launch_passes<LVLM_BF16, 128, 2>(stream, a, need_lse);
-        else launch_passes<LVLM_BF16, 128, 1>(stream, a, need_lse);
+        if (wide) launch_passes<LVLM_BF16, 128, 2>(prof, a, need_lse);
+        else launch_passes<LVLM_BF16, 128, 1>(prof, a, need_lse);
     } else if (d.dtype == LVLM_BF16 && d.hd == 64) {
-        if (wide) launch_passes<LVLM_BF16, 64, 2>(stream, a, need_lse);
-        else launch_passes<LVLM_BF16, 64, 1>(stream, a, need_lse);
+        if (wide) launch_passes<LVLM_BF16, 64, 2>(prof, a, need_lse);
+        else launch_passes<LVLM_BF16, 64, 1>(prof, a, need_lse);
     } else if (d.dtype == LVLM_F32 && d.hd == 128) {
-        launch_passes<LVLM_F32, 128, 1>(stream, a, need_lse);
+        launch_passes<LVLM_F32, 128, 1>(prof, a, need_lse);
     } else {
-        launch_passes<LVLM_F32, 64, 1>(stream, a, need_lse);
+        launch_passes<LVLM_F32, 64, 1>(prof, a, need_lse);
     }
     return hipGetLastError();
 }

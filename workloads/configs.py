@@ -56,7 +56,7 @@ CFG1 = Workload(
 CFG2 = Workload(
     name="cfg2_qwen25vl7b_bf16", dtype="bf16", batch=1, layers=28, hidden=3584, n_q_heads=28,
     n_kv_heads=4, head_dim=128, n_sys=64, n_img=2048, n_text=64, n_clusters=64,
-    merge_layers=(5, 9, 13), final_keep=(1.0, 0.35, 0.03), kv_first_layer=5, kv_budget=1024, decode_steps=1,
+    merge_layers=(5, 9, 13), final_keep=(1.0, 0.35, 0.03), kv_first_layer=5, kv_budget=4096, decode_steps=1,
     notes="Qwen2.5-VL-7B-shaped stack; merge at layers 5/9/13 (App. A.2)")
 
 CFG3 = Workload(
