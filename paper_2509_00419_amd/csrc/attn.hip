@@ -38,7 +38,7 @@ struct AttnArgs {
     char *out;
     float *part_ml;     // [B*Hkv][n_split][GP][2]
     float *part_o;      // [B*Hkv][n_split][GP][HD]
-    float *logits;      // [B*Hkv][G][Lcap]
+    float *logits;      // [B*Hkv][Lcap][GP]  log2-domain logits of every entry and head
     int32_t *cur_len;   // [B*Hkv]
     int Hq, Hkv, G, Lmax, Lcap, n_split, split_len, append, new_kind, new_pos, update_score;
     float scale_log2, decay;
@@ -76,23 +76,25 @@ __device__ __forceinline__ void mma_tile(f32x16 &acc, const HalfRow<DT, HD> &a, 
 
 __device__ __forceinline__ int acc_row(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
 
-// Elements of one 16-byte unit as floats.
-template <int DT>
-__device__ __forceinline__ void unpack(const uint4 &u, float (&f)[16 / esize<DT>()]) {
-    if constexpr (DT == LVLM_BF16) {
-        const uint32_t d[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            f[2 * i] = __uint_as_float(d[i] << 16);
-            f[2 * i + 1] = __uint_as_float(d[i] & 0xffff0000u);
-        }
-    } else {
-        f[0] = __uint_as_float(u.x);
-        f[1] = __uint_as_float(u.y);
-        f[2] = __uint_as_float(u.z);
-        f[3] = __uint_as_float(u.w);
-    }
+// One operand fragment of the P.V product: 8 probabilities as bf16 (round-to-nearest-even).
+__device__ __forceinline__ bf16x8 pack_bf16x8(const float *p) {
+    uint4 u;
+    u.x = (uint32_t)f32_to_bf16(p[0]) | ((uint32_t)f32_to_bf16(p[1]) << 16);
+    u.y = (uint32_t)f32_to_bf16(p[2]) | ((uint32_t)f32_to_bf16(p[3]) << 16);
+    u.z = (uint32_t)f32_to_bf16(p[4]) | ((uint32_t)f32_to_bf16(p[5]) << 16);
+    u.w = (uint32_t)f32_to_bf16(p[6]) | ((uint32_t)f32_to_bf16(p[7]) << 16);
+    return __builtin_bit_cast(bf16x8, u);
 }
+
+template <int DT, int HD>
+struct TileRegs {
+    static constexpr int ROWB = HD * esize<DT>();
+    static constexpr int UPR = ROWB / 16;
+    static constexpr int KSUB = 64 / UPR;
+    static constexpr int VPL = 32 / KSUB;
+    HalfRow<DT, HD> kf;   // K rows as the MFMA A operand: lane = (entry l32, half hf)
+    uint4 vv[VPL];        // V rows in natural layout: lane = (unit lane % UPR, entry lane / UPR + KSUB * i)
+};
 
 template <int DT, int HD, int GP>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
@@ -102,11 +104,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     constexpr int UPR = ROWB / 16;        // 16-byte units per row
     constexpr int KSUB = 64 / UPR;        // rows a wave covers with one load instruction
     constexpr int VPL = 32 / KSUB;        // V units per lane per 32-entry tile
-    constexpr int EPU = 16 / ES;          // elements per unit
+    constexpr int NB = HD / 32;           // 32-row blocks of the transposed output
+    constexpr int VPITCH = ROWB + 16;     // LDS row pitch of the V tile: the two lane halves hit different banks
     static_assert(UPR <= 64 && KSUB >= 1, "row too long for one wave");
 
-    __shared__ __attribute__((aligned(16))) float p_lds[4][32][GP];
-    __shared__ __attribute__((aligned(16))) float alpha_lds[4][GP];
+    __shared__ __attribute__((aligned(16))) char v_lds[4][32 * VPITCH];
     __shared__ float wm[4][GP], wl[4][GP];
     __shared__ __attribute__((aligned(16))) float wo[4][GP][HD];
 
@@ -115,27 +117,26 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int hg = b * a.Hkv + g;
     const long long cbase = (long long)hg * a.Lmax;
-    const int L = min(a.len[hg] + (a.append ? 1 : 0), a.Lmax);
-    const int new_slot = a.append ? L - 1 : -1;
     const char *kc = a.k + cbase * ROWB;
     const char *vc = a.v + cbase * ROWB;
-    const char *kn = a.k_new ? a.k_new + (long long)hg * ROWB : nullptr;
-    const char *vn = a.v_new ? a.v_new + (long long)hg * ROWB : nullptr;
+    const int vunit = lane % UPR, vsub = lane / UPR;
+    const int s_lo = split * a.split_len;
 
-    // the appended entry is stored by split 0; nobody reads that slot from the cache in this kernel
-    if (split == 0 && a.append) {
-        if (tid < UPR)
-            *reinterpret_cast<uint4 *>(a.k + (cbase + new_slot) * ROWB + 16 * tid) =
-                *reinterpret_cast<const uint4 *>(kn + 16 * tid);
-        else if (tid < 2 * UPR)
-            *reinterpret_cast<uint4 *>(a.v + (cbase + new_slot) * ROWB + 16 * (tid - UPR)) =
-                *reinterpret_cast<const uint4 *>(vn + 16 * (tid - UPR));
-        else if (tid == 2 * UPR) {
-            a.kind[cbase + new_slot] = (uint8_t)a.new_kind;
-            a.pos[cbase + new_slot] = a.new_pos;
+    // Loads do not wait for the length: any slot below Lmax is readable, stale rows are masked later.
+    auto load_tile = [&](int j0, TileRegs<DT, HD> &t) {
+        const int jk = min(j0 + l32, a.Lmax - 1);
+        const char *ks = kc + (long long)jk * ROWB + hf * (ROWB / 2);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) t.kf.v[i] = *reinterpret_cast<const uint4 *>(ks + 16 * i);
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            const int jv = min(j0 + vsub + KSUB * i, a.Lmax - 1);
+            t.vv[i] = *reinterpret_cast<const uint4 *>(vc + (long long)jv * ROWB + 16 * vunit);
         }
-    }
-    if (split == 0 && tid == 0) a.cur_len[hg] = L;
+    };
+    TileRegs<DT, HD> cur;
+    const int j_first = s_lo + 32 * wave;
+    if (j_first < a.Lmax) load_tile(j_first, cur);
 
     // query operand: column l32 of the product is head l32 of the group (zero beyond G)
     HalfRow<DT, HD> qf;
@@ -147,49 +148,69 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
         for (int i = 0; i < NV; ++i) qf.v[i] = make_uint4(0, 0, 0, 0);
     }
+    // the entry being appended, in both operand layouts (split 0 also stores it into the cache)
+    HalfRow<DT, HD> kn_f;
+    uint4 vn_u = make_uint4(0, 0, 0, 0);
+    if (a.append) {
+        const char *kn = a.k_new + (long long)hg * ROWB;
+        const char *vn = a.v_new + (long long)hg * ROWB;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) kn_f.v[i] = *reinterpret_cast<const uint4 *>(kn + hf * (ROWB / 2) + 16 * i);
+        vn_u = *reinterpret_cast<const uint4 *>(vn + 16 * vunit);
+    }
 
-    const int s_lo = split * a.split_len;
+    const int L = min(a.len[hg] + (a.append ? 1 : 0), a.Lmax);
+    const int new_slot = a.append ? L - 1 : -1;
     const int s_hi = min(L, s_lo + a.split_len);
-    const int vunit = lane % UPR, vsub = lane / UPR;
-
-    float m_run = -INFINITY, l_run = 0.f;   // of head l32 (both halves hold the same value)
-    float o[GP][EPU];
-#pragma unroll
-    for (int h = 0; h < GP; ++h)
-#pragma unroll
-        for (int e = 0; e < EPU; ++e) o[h][e] = 0.f;
-
-    for (int j0 = s_lo + 32 * wave; j0 < s_hi; j0 += 128) {
-        // ---- loads: K as MFMA operand (lane = entry), V in natural layout
-        HalfRow<DT, HD> kf;
-        {
-            const int j = j0 + l32;
-            if (j < s_hi) {
-                const char *src = (j == new_slot ? kn : kc + (long long)j * ROWB) + hf * (ROWB / 2);
-#pragma unroll
-                for (int i = 0; i < NV; ++i) kf.v[i] = *reinterpret_cast<const uint4 *>(src + 16 * i);
-            } else {
-#pragma unroll
-                for (int i = 0; i < NV; ++i) kf.v[i] = make_uint4(0, 0, 0, 0);
+    if (split == 0) {
+        if (a.append) {
+            if (tid < UPR)
+                *reinterpret_cast<uint4 *>(a.k + (cbase + new_slot) * ROWB + 16 * tid) =
+                    *reinterpret_cast<const uint4 *>(a.k_new + (long long)hg * ROWB + 16 * tid);
+            else if (tid < 2 * UPR)
+                *reinterpret_cast<uint4 *>(a.v + (cbase + new_slot) * ROWB + 16 * (tid - UPR)) =
+                    *reinterpret_cast<const uint4 *>(a.v_new + (long long)hg * ROWB + 16 * (tid - UPR));
+            else if (tid == 2 * UPR) {
+                a.kind[cbase + new_slot] = (uint8_t)a.new_kind;
+                a.pos[cbase + new_slot] = a.new_pos;
             }
         }
-        uint4 vv[VPL];
+        if (tid == 0) a.cur_len[hg] = L;
+    }
+
+    float m_run = -INFINITY, l_run = 0.f;   // of head l32 (both lane halves hold the same value)
+    f32x16 oacc[NB];                        // O^T: rows = output channels of block nb, column = head l32
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int j = j0 + vsub + KSUB * i;
-            if (j < s_hi) {
-                const char *src = (j == new_slot ? vn : vc + (long long)j * ROWB) + 16 * vunit;
-                vv[i] = *reinterpret_cast<const uint4 *>(src);
-            } else {
-                vv[i] = make_uint4(0, 0, 0, 0);
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[nb][r] = 0.f;
+
+    char *vt = &v_lds[wave][0];
+    for (int j0 = j_first; j0 < s_hi; j0 += 128) {
+        TileRegs<DT, HD> nxt;
+        const bool more = j0 + 128 < s_hi;
+        if (more) load_tile(j0 + 128, nxt);
+
+        // substitute the appended entry, zero the rows beyond the range (their V must not reach the MFMA)
+        if (j0 + 32 > s_hi || (new_slot >= j0 && new_slot < j0 + 32)) {
+            if (j0 + l32 == new_slot) cur.kf = kn_f;
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) {
+                const int j = j0 + vsub + KSUB * i;
+                if (j == new_slot) cur.vv[i] = vn_u;
+                if (j >= s_hi) cur.vv[i] = make_uint4(0, 0, 0, 0);
             }
         }
+        // V tile to LDS in natural layout
+#pragma unroll
+        for (int i = 0; i < VPL; ++i)
+            *reinterpret_cast<uint4 *>(vt + (vsub + KSUB * i) * VPITCH + 16 * vunit) = cur.vv[i];
 
-        // ---- logits: rows = entries, columns = heads
+        // logits: rows = entries, columns = heads
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        mma_tile<DT, HD>(acc, kf, qf);
+        mma_tile<DT, HD>(acc, cur.kf, qf);
 
         float tmax = -INFINITY;
 #pragma unroll
@@ -202,74 +223,83 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
         const float m_new = fmaxf(m_run, tmax);          // finite: the tile holds at least one entry
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        if (a.update_score && l32 < a.G) {
+            float *lg = a.logits + (long long)hg * a.Lcap * GP + l32;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = j0 + acc_row(r, hf);
+                if (j < s_hi) lg[(long long)j * GP] = acc[r];
+            }
+        }
+        float p[16];
         float psum = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(acc[r] - m_new);
-            psum += p;
-            if (l32 < GP) p_lds[wave][acc_row(r, hf)][l32] = p;
+            p[r] = __builtin_amdgcn_exp2f(acc[r] - m_new);
+            psum += p[r];
         }
         psum += __shfl_xor(psum, 32);
         l_run = l_run * alpha + psum;
         m_run = m_new;
-        if (lane < GP) alpha_lds[wave][lane] = alpha;
-        if (a.update_score && l32 < a.G) {
-            float *lg = a.logits + ((long long)hg * a.G + l32) * a.Lcap;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int j = j0 + acc_row(r, hf);
-                if (j < s_hi) lg[j] = acc[r];
-            }
-        }
-        // the tile is private to this wave: order the LDS traffic, no workgroup barrier
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[nb][r] *= alpha;
+
+        // the V tile is private to this wave: order the LDS traffic, no workgroup barrier
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // ---- o = o * alpha + P^T V on the vector ALUs
-        float al[GP];
+        // O^T += V^T P^T on the matrix cores.  The contraction index is free, so it is numbered the way
+        // the probabilities already sit in this lane's registers: step s, slot i <-> entry
+        // 16 s + 8 (i/4) + 4 hf + i%4 (bf16) or entry acc_row(s, hf) (fp32).  V is read transposed from LDS.
+        if constexpr (DT == LVLM_BF16) {
 #pragma unroll
-        for (int h = 0; h < GP; ++h) al[h] = alpha_lds[wave][h];
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const bf16x8 pb = pack_bf16x8(&p[8 * s2]);
 #pragma unroll
-        for (int h = 0; h < GP; ++h)
+                for (int nb = 0; nb < NB; ++nb) {
+                    uint32_t w[4];
 #pragma unroll
-            for (int e = 0; e < EPU; ++e) o[h][e] *= al[h];
+                    for (int i2 = 0; i2 < 4; ++i2) {
+                        const int e0 = 16 * s2 + 8 * ((2 * i2) >> 2) + 4 * hf + ((2 * i2) & 3);
+                        const uint32_t lo = *reinterpret_cast<const uint16_t *>(vt + e0 * VPITCH + 2 * (32 * nb + l32));
+                        const uint32_t hi =
+                            *reinterpret_cast<const uint16_t *>(vt + (e0 + 1) * VPITCH + 2 * (32 * nb + l32));
+                        w[i2] = lo | (hi << 16);
+                    }
+                    const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+                    oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, oacc[nb], 0, 0, 0);
+                }
+            }
+        } else {
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            float vf[EPU];
-            unpack<DT>(vv[i], vf);
-            const float *pr = &p_lds[wave][vsub + KSUB * i][0];
+            for (int s2 = 0; s2 < 16; ++s2) {
+                const int e0 = acc_row(s2, hf);
 #pragma unroll
-            for (int h = 0; h < GP; ++h) {
-                const float p = pr[h];
-#pragma unroll
-                for (int e = 0; e < EPU; ++e) o[h][e] = fmaf(p, vf[e], o[h][e]);
+                for (int nb = 0; nb < NB; ++nb) {
+                    const float va = *reinterpret_cast<const float *>(vt + e0 * VPITCH + 4 * (32 * nb + l32));
+                    oacc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(va, p[s2], oacc[nb], 0, 0, 0);
+                }
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (more) cur = nxt;
     }
 
-    // ---- fold the lanes that hold the same V unit, then the four waves
+    // ---- fold the four waves: lane (head l32 < G, half hf) holds 16 channels of every block
+    if (l32 < GP) {
 #pragma unroll
-    for (int h = 0; h < GP; ++h)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int e = 0; e < EPU; ++e) {
-            float x = o[h][e];
-#pragma unroll
-            for (int off = UPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
-            o[h][e] = x;
+            for (int r = 0; r < 16; ++r) wo[wave][l32][32 * nb + acc_row(r, hf)] = oacc[nb][r];
+        if (hf == 0) {
+            wm[wave][l32] = m_run;
+            wl[wave][l32] = l_run;
         }
-    if (vsub == 0) {
-#pragma unroll
-        for (int h = 0; h < GP; ++h)
-#pragma unroll
-            for (int e = 0; e < EPU; ++e) wo[wave][h][vunit * EPU + e] = o[h][e];
-    }
-    if (lane < GP) {
-        wm[wave][lane] = m_run;
-        wl[wave][lane] = l_run;
     }
     __syncthreads();
     float *po = a.part_o + ((long long)hg * a.n_split + split) * GP * HD;
@@ -279,40 +309,270 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
         for (int w = 1; w < 4; ++w) mx = fmaxf(mx, wm[w][h]);
         const float ms = (mx == -INFINITY) ? 0.f : mx;
-        float s = 0.f;
+        float sacc = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) s += wo[w][h][e] * __builtin_amdgcn_exp2f(wm[w][h] - ms);
-        po[idx] = s;
+        for (int w = 0; w < 4; ++w) sacc += wo[w][h][e] * __builtin_amdgcn_exp2f(wm[w][h] - ms);
+        po[idx] = sacc;
     }
     if (tid < GP) {
         float mx = wm[0][tid];
 #pragma unroll
         for (int w = 1; w < 4; ++w) mx = fmaxf(mx, wm[w][tid]);
         const float ms = (mx == -INFINITY) ? 0.f : mx;
-        float s = 0.f;
+        float sacc = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) s += wl[w][tid] * __builtin_amdgcn_exp2f(wm[w][tid] - ms);
+        for (int w = 0; w < 4; ++w) sacc += wl[w][tid] * __builtin_amdgcn_exp2f(wm[w][tid] - ms);
         float *pml = a.part_ml + (((long long)hg * a.n_split + split) * GP + tid) * 2;
         pml[0] = mx;
-        pml[1] = s;
+        pml[1] = sacc;
     }
 }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// bf16 variant on 16x16x32 MFMA tiles: a group has at most 8 query heads, so a 16-wide head axis wastes
+// half as much as a 32-wide one, and the accumulators (32 + 8 registers) leave room for three waves per
+// SIMD.  Lane = (l16, kg): for Q.K^T the A operand row is entry l16 of a 16-entry block and kg selects
+// the quarter of the head vector the lane contracts (the contraction index is free); the result holds
+// head l16 in column position and entries 4 kg + r in its 4 registers.  Those 8 probabilities per lane
+// (two blocks) are exactly one B operand of the P.V product when the contraction slot i of lane group kg
+// is numbered entry 16 (i/4) + 4 kg + i%4; V^T is read from the wave's LDS tile with the same numbering.
+template <int HD, int GP>
+__global__ __launch_bounds__(256) void attn_partial_bf16_kernel(AttnArgs a) {
+    constexpr int ROWB = HD * 2;
+    constexpr int UPR = ROWB / 16;
+    constexpr int KSUB = 64 / UPR;
+    constexpr int VPL = 32 / KSUB;
+    constexpr int QV = HD / 32;           // 16-byte words of a quarter row
+    constexpr int NB = HD / 16;           // 16-channel blocks of the output
+    constexpr int VPITCH = ROWB + 16;
+
+    __shared__ __attribute__((aligned(16))) char v_lds[4][32 * VPITCH];
+    __shared__ float wm[4][GP], wl[4][GP];
+    __shared__ __attribute__((aligned(16))) float wo[4][GP][HD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kg = lane >> 4;
+    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int hg = b * a.Hkv + g;
+    const long long cbase = (long long)hg * a.Lmax;
+    const char *kc = a.k + cbase * ROWB;
+    const char *vc = a.v + cbase * ROWB;
+    const int vunit = lane % UPR, vsub = lane / UPR;
+    const int s_lo = split * a.split_len;
+    const int j_first = s_lo + 32 * wave;
+
+    uint4 kf[2][QV];
+    uint4 vv[VPL];
+    // Loads do not wait for the length: any slot below Lmax is readable, stale rows are masked later.
+    auto load_tile = [&](int j0) {
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            const int jk = min(j0 + 16 * blk + l16, a.Lmax - 1);
+            const char *ks = kc + (long long)jk * ROWB + kg * (ROWB / 4);
+#pragma unroll
+            for (int i = 0; i < QV; ++i) kf[blk][i] = *reinterpret_cast<const uint4 *>(ks + 16 * i);
+        }
+#pragma unroll
+        for (int i = 0; i < VPL; ++i) {
+            const int jv = min(j0 + vsub + KSUB * i, a.Lmax - 1);
+            vv[i] = *reinterpret_cast<const uint4 *>(vc + (long long)jv * ROWB + 16 * vunit);
+        }
+    };
+    if (j_first < a.Lmax) load_tile(j_first);
+
+    uint4 qf[QV];
+    if (l16 < a.G) {
+        const char *src = a.q + ((long long)b * a.Hq + g * a.G + l16) * ROWB + kg * (ROWB / 4);
+#pragma unroll
+        for (int i = 0; i < QV; ++i) qf[i] = *reinterpret_cast<const uint4 *>(src + 16 * i);
+    } else {
+#pragma unroll
+        for (int i = 0; i < QV; ++i) qf[i] = make_uint4(0, 0, 0, 0);
+    }
+
+    const int L = min(a.len[hg] + (a.append ? 1 : 0), a.Lmax);
+    const int new_slot = a.append ? L - 1 : -1;
+    const int s_hi = min(L, s_lo + a.split_len);
+    if (split == 0) {
+        // the appended entry goes into the cache here; every reader below takes it from k_new / v_new
+        if (a.append) {
+            if (tid < UPR)
+                *reinterpret_cast<uint4 *>(a.k + (cbase + new_slot) * ROWB + 16 * tid) =
+                    *reinterpret_cast<const uint4 *>(a.k_new + (long long)hg * ROWB + 16 * tid);
+            else if (tid < 2 * UPR)
+                *reinterpret_cast<uint4 *>(a.v + (cbase + new_slot) * ROWB + 16 * (tid - UPR)) =
+                    *reinterpret_cast<const uint4 *>(a.v_new + (long long)hg * ROWB + 16 * (tid - UPR));
+            else if (tid == 2 * UPR) {
+                a.kind[cbase + new_slot] = (uint8_t)a.new_kind;
+                a.pos[cbase + new_slot] = a.new_pos;
+            }
+        }
+        if (tid == 0) a.cur_len[hg] = L;
+    }
+
+    float m_run = -INFINITY, l_run = 0.f;   // of head l16 (all four lane groups hold the same value)
+    f32x4 oacc[NB];                         // O^T block nb: channels 16 nb + 4 kg + r, head l16
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) oacc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    char *vt = &v_lds[wave][0];
+    for (int j0 = j_first; j0 < s_hi; j0 += 128) {
+        // the appended entry comes from k_new / v_new; rows beyond the range must not reach the MFMA
+        if (j0 + 32 > s_hi || (new_slot >= j0 && new_slot < j0 + 32)) {
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk) {
+                if (j0 + 16 * blk + l16 == new_slot) {
+                    const char *kn = a.k_new + (long long)hg * ROWB + kg * (ROWB / 4);
+#pragma unroll
+                    for (int i = 0; i < QV; ++i) kf[blk][i] = *reinterpret_cast<const uint4 *>(kn + 16 * i);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < VPL; ++i) {
+                const int j = j0 + vsub + KSUB * i;
+                if (j == new_slot) vv[i] = *reinterpret_cast<const uint4 *>(a.v_new + (long long)hg * ROWB + 16 * vunit);
+                if (j >= s_hi) vv[i] = make_uint4(0, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < VPL; ++i)
+            *reinterpret_cast<uint4 *>(vt + (vsub + KSUB * i) * VPITCH + 16 * vunit) = vv[i];
+
+        f32x4 acc[2];
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            acc[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < QV; ++i)
+                acc[blk] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf[blk][i]),
+                                                                   __builtin_bit_cast(bf16x8, qf[i]), acc[blk], 0, 0, 0);
+        }
+        // next tile's loads go out while this one is reduced (registers are free again)
+        if (j0 + 128 < s_hi) load_tile(j0 + 128);
+
+        float t[8];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int j = j0 + 16 * (i >> 2) + 4 * kg + (i & 3);
+            t[i] = (j < s_hi) ? acc[i >> 2][i & 3] * a.scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, t[i]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run, tmax);          // finite: the tile holds at least one entry
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        if (a.update_score && l16 < a.G) {
+            float *lg = a.logits + (long long)hg * a.Lcap * GP + l16;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int j = j0 + 16 * (i >> 2) + 4 * kg + (i & 3);
+                if (j < s_hi) lg[(long long)j * GP] = t[i];
+            }
+        }
+        float p[8];
+        float psum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            p[i] = __builtin_amdgcn_exp2f(t[i] - m_new);
+            psum += p[i];
+        }
+        psum += __shfl_xor(psum, 16);
+        psum += __shfl_xor(psum, 32);
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        const bf16x8 pb = pack_bf16x8(p);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) oacc[nb] *= alpha;
+
+        // the V tile is private to this wave: order the LDS traffic, no workgroup barrier
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            uint32_t w[4];
+#pragma unroll
+            for (int i2 = 0; i2 < 4; ++i2) {
+                const int e0 = 16 * (i2 >> 1) + 4 * kg + 2 * (i2 & 1);      // slots 2 i2 and 2 i2 + 1
+                const uint32_t lo = *reinterpret_cast<const uint16_t *>(vt + e0 * VPITCH + 2 * (16 * nb + l16));
+                const uint32_t hi = *reinterpret_cast<const uint16_t *>(vt + (e0 + 1) * VPITCH + 2 * (16 * nb + l16));
+                w[i2] = lo | (hi << 16);
+            }
+            const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, oacc[nb], 0, 0, 0);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+
+    // ---- fold the four waves
+    if (l16 < GP) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+            *reinterpret_cast<float4 *>(&wo[wave][l16][16 * nb + 4 * kg]) =
+                make_float4(oacc[nb][0], oacc[nb][1], oacc[nb][2], oacc[nb][3]);
+        if (kg == 0) {
+            wm[wave][l16] = m_run;
+            wl[wave][l16] = l_run;
+        }
+    }
+    __syncthreads();
+    float *po = a.part_o + ((long long)hg * a.n_split + split) * GP * HD;
+    for (int idx = tid; idx < GP * HD; idx += 256) {
+        const int h = idx / HD, e = idx % HD;
+        float mx = wm[0][h];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) mx = fmaxf(mx, wm[w][h]);
+        const float ms = (mx == -INFINITY) ? 0.f : mx;
+        float sacc = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) sacc += wo[w][h][e] * __builtin_amdgcn_exp2f(wm[w][h] - ms);
+        po[idx] = sacc;
+    }
+    if (tid < GP) {
+        float mx = wm[0][tid];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) mx = fmaxf(mx, wm[w][tid]);
+        const float ms = (mx == -INFINITY) ? 0.f : mx;
+        float sacc = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) sacc += wl[w][tid] * __builtin_amdgcn_exp2f(wm[w][tid] - ms);
+        float *pml = a.part_ml + (((long long)hg * a.n_split + split) * GP + tid) * 2;
+        pml[0] = mx;
+        pml[1] = sacc;
+    }
+}
+
+constexpr int kMaxSplit = 64;   // splits one combine workgroup can fold (checked on the host)
+
 template <int DT, int HD, int GP>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
+    __shared__ float s_pm[kMaxSplit][GP], s_pl[kMaxSplit][GP];   // per split: max, then weight exp2(m_s - M)
     __shared__ float s_m[GP], s_inv[GP];
     const int tid = threadIdx.x;
     const int chunk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int hg = b * a.Hkv + g;
     const int L = a.cur_len[hg];
     const float *pml = a.part_ml + (long long)hg * a.n_split * GP * 2;
+    for (int i = tid; i < a.n_split * GP; i += 256) {
+        const float2 ml = *reinterpret_cast<const float2 *>(pml + 2 * i);
+        s_pm[i / GP][i % GP] = ml.x;
+        s_pl[i / GP][i % GP] = ml.y;
+    }
+    __syncthreads();
     if (tid < GP) {
         float mx = -INFINITY;
-        for (int s = 0; s < a.n_split; ++s) mx = fmaxf(mx, pml[(s * GP + tid) * 2]);
+        for (int s = 0; s < a.n_split; ++s) mx = fmaxf(mx, s_pm[s][tid]);
         const float ms = (mx == -INFINITY) ? 0.f : mx;
         float l = 0.f;
-        for (int s = 0; s < a.n_split; ++s)
-            l += pml[(s * GP + tid) * 2 + 1] * exp2f(pml[(s * GP + tid) * 2] - ms);
+        for (int s = 0; s < a.n_split; ++s) {
+            const float wgt = exp2f(s_pm[s][tid] - ms);
+            l += s_pl[s][tid] * wgt;
+            s_pl[s][tid] = wgt;                      // reused below as the split's weight
+        }
         s_m[tid] = ms;
         s_inv[tid] = l > 0.f ? 1.0f / l : 0.f;
     }
@@ -323,8 +583,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
         for (int idx = tid; idx < a.G * HD; idx += 256) {
             const int h = idx / HD, e = idx % HD;
             float acc = 0.f;
-            for (int s = 0; s < a.n_split; ++s)
-                acc += po[((long long)s * GP + h) * HD + e] * exp2f(pml[(s * GP + h) * 2] - s_m[h]);
+#pragma unroll 4
+            for (int s = 0; s < a.n_split; ++s) acc += po[((long long)s * GP + h) * HD + e] * s_pl[s][h];
             acc *= s_inv[h];
             const long long oi = ((long long)b * a.Hq + g * a.G + h) * HD + e;
             if constexpr (DT == LVLM_BF16)
@@ -338,10 +598,12 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     if (a.update_score) {
         const long long cbase = (long long)hg * a.Lmax;
         const float inv_g = 1.0f / (float)a.G;
+        const float *lg = a.logits + (long long)hg * a.Lcap * GP;
         for (int j = chunk * 1024 + tid; j < min(L, (chunk + 1) * 1024); j += 256) {
             float pm = 0.f;
-            for (int h = 0; h < a.G; ++h)
-                pm += exp2f(a.logits[((long long)hg * a.G + h) * a.Lcap + j] - s_m[h]) * s_inv[h];
+#pragma unroll
+            for (int h = 0; h < GP; ++h)
+                if (h < a.G) pm += exp2f(lg[(long long)j * GP + h] - s_m[h]) * s_inv[h];
             const float old = (a.append && j == L - 1) ? 0.f : a.score[cbase + j];
             a.score[cbase + j] = a.decay * old + pm * inv_g;
         }
@@ -352,7 +614,10 @@ template <int DT, int HD, int GP>
 void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
     hipStream_t stream = prof.stream;
     prof.begin("attn_partial");
-    hipLaunchKernelGGL((attn_partial_kernel<DT, HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
+    if constexpr (DT == LVLM_BF16)
+        hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((attn_partial_kernel<DT, HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
     prof.end();
     const int chunks = a.update_score ? (len_bound + 1023) / 1024 : 1;
     prof.begin("attn_combine");
@@ -382,6 +647,7 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     const int max_split = (bound + 127) / 128;
     long long want = (1024 + heads - 1) / heads;
     int n_split = (int)(want < 1 ? 1 : (want > max_split ? max_split : want));
+    if (n_split > 64) n_split = 64;               // kMaxSplit of the combine kernel
     if (n_split < 1) n_split = 1;
     int split_len = ((bound + n_split - 1) / n_split + 127) / 128 * 128;
     n_split = (bound + split_len - 1) / split_len;
@@ -393,8 +659,9 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     w.part_ml = 0;
     w.part_o = align_up(w.part_ml + (size_t)heads * n_split * gp * 2 * sizeof(float), 256);
     w.logits = align_up(w.part_o + (size_t)heads * n_split * gp * d.hd * sizeof(float), 256);
-    const size_t cur_len = align_up(w.logits + (size_t)heads * G * lcap * sizeof(float), 256);
-    w.total = align_up(cur_len + (size_t)heads * sizeof(int32_t), 256);
+    w.lcap = lcap;
+    w.cur_len = align_up(w.logits + (size_t)heads * gp * lcap * sizeof(float), 256);
+    w.total = align_up(w.cur_len + (size_t)heads * sizeof(int32_t), 256);
     return w;
 }
 
@@ -415,9 +682,8 @@ hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const A
     a.part_ml = reinterpret_cast<float *>(ws + w.part_ml);
     a.part_o = reinterpret_cast<float *>(ws + w.part_o);
     a.logits = reinterpret_cast<float *>(ws + w.logits);
-    const int lcap = (bound + 3) / 4 * 4;
-    a.cur_len = reinterpret_cast<int32_t *>(ws + align_up(w.logits + (size_t)heads * G * lcap * sizeof(float), 256));
-    a.Hq = d.Hq; a.Hkv = d.Hkv; a.G = G; a.Lmax = d.Lmax; a.Lcap = lcap;
+    a.cur_len = reinterpret_cast<int32_t *>(ws + w.cur_len);
+    a.Hq = d.Hq; a.Hkv = d.Hkv; a.G = G; a.Lmax = d.Lmax; a.Lcap = w.lcap;
     a.n_split = w.n_split; a.split_len = w.split_len;
     a.append = k_new != nullptr;
     a.new_kind = d.new_kind; a.new_pos = d.new_pos;

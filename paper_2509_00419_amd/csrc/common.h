@@ -37,7 +37,7 @@ ScoreWs score_ws(const lvlm_score_desc &d);
 
 struct MergeWs {
     size_t rank_part, dst_of, partial, total;
-    int n_split;   // splits of the comparison loop in the rank kernel
+    int n_split;   // always 1: the rank kernel leaves complete ranks
     int n_chunk;   // source-row chunks of the gather kernel (partial sums per chunk)
     int rows_per_chunk;
     int max_row_elems;
@@ -50,8 +50,8 @@ struct KvWs {
 KvWs kv_ws(const lvlm_kv_desc &d);
 
 struct AttnWs {
-    size_t part_ml, part_o, logits, total;
-    int n_split, split_len;
+    size_t part_ml, part_o, logits, cur_len, total;
+    int n_split, split_len, lcap;
 };
 AttnWs attn_ws(const lvlm_attn_desc &d);
 

@@ -104,6 +104,70 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         return budget_mode ? (kd != LVLM_KIND_PROTECTED && slot < recent_lo) : (kd == LVLM_KIND_IMAGE);
     };
 
+    // ---- steady-state decode: the head is exactly one entry over budget and holes are filled from
+    // the tail.  One pass finds the candidate that is last in importance order (lowest key, highest
+    // slot among equals); the entry in the last slot takes its place.
+    if (budget_mode && a.order == LVLM_ORDER_FILL && L - a.budget == 1) {
+        __shared__ unsigned long long w_best[16];
+        __shared__ int w_cnt[16];
+        unsigned long long best = ~0ull;
+        int cnt = 0;
+        for (int slot = tid; slot < L; slot += 1024) {
+            if (is_cand(slot, kind[slot])) {
+                ++cnt;
+                const unsigned long long c =
+                    ((unsigned long long)score_key(score[slot]) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)slot);
+                best = c < best ? c : best;
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const unsigned long long ob = __shfl_xor(best, o);
+            best = ob < best ? ob : best;
+            cnt += __shfl_xor(cnt, o);
+        }
+        if (lane == 0) {
+            w_best[wave] = best;
+            w_cnt[wave] = cnt;
+        }
+        __syncthreads();
+        best = w_best[0];
+        cnt = w_cnt[0];
+#pragma unroll
+        for (int w = 1; w < 16; ++w) {
+            best = w_best[w] < best ? w_best[w] : best;
+            cnt += w_cnt[w];
+        }
+        if (a.budget - (L - cnt) > 0) {           // room for all but one candidate
+            const int victim = (int)(0xffffffffu - (uint32_t)(best & 0xffffffffull));
+            const int last = L - 1;
+            if (victim != last) {
+                const int units = a.row_bytes / 16;
+                char *kc = a.k + base * a.row_bytes;
+                char *vc = a.v + base * a.row_bytes;
+                if (tid < units)
+                    *reinterpret_cast<uint4 *>(kc + (long long)victim * a.row_bytes + 16 * tid) =
+                        *reinterpret_cast<const uint4 *>(kc + (long long)last * a.row_bytes + 16 * tid);
+                else if (tid < 2 * units)
+                    *reinterpret_cast<uint4 *>(vc + (long long)victim * a.row_bytes + 16 * (tid - units)) =
+                        *reinterpret_cast<const uint4 *>(vc + (long long)last * a.row_bytes + 16 * (tid - units));
+                else if (tid == 2 * units) {
+                    a.score[base + victim] = a.score[base + last];
+                    a.kind[base + victim] = a.kind[base + last];
+                    a.pos[base + victim] = a.pos[base + last];
+                }
+            }
+            if (tid == 0) {
+                a.meta[2 * hg] = last;
+                a.meta[2 * hg + 1] = last;
+                a.len[hg] = last;
+                if (a.n_evicted) a.n_evicted[hg] = 1;
+            }
+            return;
+        }
+        __syncthreads();     // protected entries alone exceed the budget: general path below
+    }
+
     // ---- totals over the candidates
     if (tid == 0) {
         s_total = 0ull;

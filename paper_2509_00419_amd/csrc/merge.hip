@@ -4,11 +4,10 @@
 //   rank_kernel      rank[j] = number of image tokens that precede j in
 //                    descending score order (ties: lower index first).  It is
 //                    the counting definition itself, spread over the chip:
-//                    a (token block) x (comparison range) grid, every thread
-//                    counting for one token against keys staged in LDS.
-//                    Nothing iterative, nothing data dependent.
-//   index_kernel     one workgroup per sequence: sums the partial counts,
-//                    prefix-scans the "kept" flags in index order and emits
+//                    64 tokens per workgroup, the keys staged in LDS and split
+//                    over the 16 waves.  Nothing iterative or data dependent.
+//   index_kernel     one workgroup per sequence: prefix-scans the "kept" flags
+//                    in index order and emits
 //                    keep_idx (ascending), merged_idx (rank order) and, per
 //                    source token, where it goes (row of P_unmerged or its
 //                    rank inside P_merged).
@@ -24,103 +23,157 @@
 namespace lvlm {
 namespace {
 
-constexpr int kRankTile = 1024;   // keys staged in LDS per step of the rank kernel
+constexpr int kRankTile = 8192;   // keys staged in LDS per step of the rank kernel (32 KB)
+constexpr int kRankBlock = 64;    // tokens ranked by one workgroup (one per lane; the 16 waves split the keys)
 
 struct RankArgs {
     const float *score;   // [B, n]
-    int32_t *rank_part;   // [B, n_split, n]
-    int n, n_split, split_len;
+    int32_t *rank;        // [B, n]
+    int n;
 };
 
-__global__ __launch_bounds__(256) void rank_kernel(RankArgs a) {
+// rank[j] = #{i : key_i > key_j, or key_i == key_j and i < j}.  A workgroup ranks 64 tokens: every wave
+// holds the same 64 tokens (one per lane) and counts over its own sixteenth of the staged keys, read
+// from LDS as broadcast 128-bit words; the sixteen counts are added through LDS.
+__global__ __launch_bounds__(1024) void rank_kernel(RankArgs a) {
     __shared__ __attribute__((aligned(16))) uint32_t keys[kRankTile];
-    const int tid = threadIdx.x;
-    const int b = blockIdx.z, split = blockIdx.y;
-    const int j0 = blockIdx.x * 256;
-    const int j = j0 + tid;
+    __shared__ int cnt_lds[16][kRankBlock];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.y;
+    const int j0 = blockIdx.x * kRankBlock;
+    const int j = j0 + lane;
     const float *score = a.score + (long long)b * a.n;
     const uint32_t kj = j < a.n ? score_key(score[j]) : 0u;
-    const int i_lo = split * a.split_len;
-    const int i_hi = min(a.n, i_lo + a.split_len);
     int cnt = 0;
-    for (int t0 = i_lo; t0 < i_hi; t0 += kRankTile) {
+    for (int t0 = 0; t0 < a.n; t0 += kRankTile) {
+        const int tile_n = min(kRankTile, a.n - t0);
+        const int share = ((tile_n + 15) / 16 + 3) & ~3;          // keys per wave, a multiple of 4
         __syncthreads();
-        for (int x = tid; x < kRankTile; x += 256) {
+        for (int x = tid; x < 16 * share && x < kRankTile; x += 1024) {
             const int i = t0 + x;
-            // a padding key must never count: give it the lowest key and let the index rule reject it
-            keys[x] = i < i_hi ? score_key(score[i]) : 0u;
+            // Padding sits above every real index, so it only ever meets the ">" rule (or the full
+            // rule with i > j): the lowest key can never precede anything.
+            keys[x] = i < a.n ? score_key(score[i]) : 0u;
         }
         __syncthreads();
-        const int lim = min(kRankTile, i_hi - t0);
-        if (t0 + kRankTile <= j0) {
-            // every i in the tile is below every j of the block: i precedes j when key_i >= key_j
-            for (int x = 0; x < lim; x += 4) {
-                const uint4 k4 = *reinterpret_cast<const uint4 *>(&keys[x]);
-                cnt += (k4.x >= kj) + ((x + 1 < lim) & (k4.y >= kj)) + ((x + 2 < lim) & (k4.z >= kj)) +
-                       ((x + 3 < lim) & (k4.w >= kj));
-            }
-        } else if (t0 >= j0 + 256) {
-            // every i is above every j: i precedes j only with a strictly larger key
-            for (int x = 0; x < lim; x += 4) {
-                const uint4 k4 = *reinterpret_cast<const uint4 *>(&keys[x]);
-                cnt += (k4.x > kj) + ((x + 1 < lim) & (k4.y > kj)) + ((x + 2 < lim) & (k4.z > kj)) +
-                       ((x + 3 < lim) & (k4.w > kj));
-            }
-        } else {
-            for (int x = 0; x < lim; ++x) {
-                const uint32_t ki = keys[x];
-                cnt += (ki > kj) | ((ki == kj) & (t0 + x < j));
-            }
+        const int x_lo = wave * share, x_hi = min(kRankTile, x_lo + share);
+        // Groups of four keys: entirely below the block (i < j: ">=" precedes), entirely above
+        // (i > j: only ">" precedes), or overlapping the block's own indices (full rule).
+        const int below_end = min(x_hi, max(x_lo, (j0 - t0) & ~3));
+        const int above_beg = max(x_lo, min(x_hi, (j0 + kRankBlock - t0 + 3) & ~3));
+#pragma unroll 8
+        for (int x = x_lo; x < below_end; x += 4) {
+            const uint4 k4 = *reinterpret_cast<const uint4 *>(&keys[x]);
+            cnt += (k4.x >= kj) + (k4.y >= kj) + (k4.z >= kj) + (k4.w >= kj);
+        }
+#pragma unroll 4
+        for (int x = below_end; x < above_beg; x += 4) {
+            const uint4 k4 = *reinterpret_cast<const uint4 *>(&keys[x]);
+            const int i = t0 + x;
+            cnt += ((k4.x > kj) | ((k4.x == kj) & (i < j))) + ((k4.y > kj) | ((k4.y == kj) & (i + 1 < j))) +
+                   ((k4.z > kj) | ((k4.z == kj) & (i + 2 < j))) + ((k4.w > kj) | ((k4.w == kj) & (i + 3 < j)));
+        }
+#pragma unroll 8
+        for (int x = above_beg; x < x_hi; x += 4) {
+            const uint4 k4 = *reinterpret_cast<const uint4 *>(&keys[x]);
+            cnt += (k4.x > kj) + (k4.y > kj) + (k4.z > kj) + (k4.w > kj);
         }
     }
-    if (j < a.n) a.rank_part[((long long)b * a.n_split + split) * a.n + j] = cnt;
+    cnt_lds[wave][lane] = cnt;
+    __syncthreads();
+    if (wave == 0 && j < a.n) {
+        int tot = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) tot += cnt_lds[w][lane];
+        a.rank[(long long)b * a.n + j] = tot;
+    }
 }
 
 struct IndexArgs {
-    const int32_t *rank_part;
+    const int32_t *rank;
     int32_t *dst_of;       // [B, n]: >= 0 row inside the new image span; < 0: -(rank in P_merged) - 1
     int32_t *keep_idx;     // [B, n_keep-1] or null
     int32_t *merged_idx;   // [B, r+1] or null
-    int n, n_split, n_keep;
+    int n, n_keep;
 };
 
+// One workgroup per sequence.  Tokens are taken 16384 at a time as four coalesced 4096-token chunks
+// (thread t holds tokens 4t..4t+3 of each chunk, all loads issued together); one block-wide scan of the
+// four per-chunk counts gives every kept token its row in P_unmerged.  Then keep_idx (ascending),
+// merged_idx (by rank) and the per-token destination are written.
 __global__ __launch_bounds__(1024) void index_kernel(IndexArgs a) {
-    __shared__ int wave_cnt[16];
+    constexpr int NC = 4;
+    __shared__ int wave_tot[NC][16];
     __shared__ int base_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b = blockIdx.x;
     const int n_unmerged = a.n_keep - 1;
+    const int32_t *rank = a.rank + (long long)b * a.n;
+    int32_t *dst_of = a.dst_of + (long long)b * a.n;
     if (tid == 0) base_s = 0;
     __syncthreads();
-    for (int j0 = 0; j0 < a.n; j0 += 1024) {
-        const int j = j0 + tid;
-        int rank = 0;
-        if (j < a.n)
-            for (int s = 0; s < a.n_split; ++s) rank += a.rank_part[((long long)b * a.n_split + s) * a.n + j];
-        const bool kept = j < a.n && rank < n_unmerged;
-        const unsigned long long bal = __ballot(kept);
-        const int before = __popcll(bal & ((1ull << lane) - 1ull));
-        if (lane == 0) wave_cnt[wave] = __popcll(bal);
-        __syncthreads();
-        int off = base_s;
-        for (int w = 0; w < wave; ++w) off += wave_cnt[w];
-        if (j < a.n) {
-            if (kept) {
-                const int p = off + before;
-                a.dst_of[(long long)b * a.n + j] = p;
-                if (a.keep_idx) a.keep_idx[(long long)b * n_unmerged + p] = j;
+    for (int s0 = 0; s0 < a.n; s0 += NC * 4096) {
+        int rk[NC][4];
+        int cnt[NC], incl[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int j = s0 + c * 4096 + 4 * tid;
+            if (j + 3 < a.n && (a.n & 3) == 0) {
+                const int4 v = *reinterpret_cast<const int4 *>(rank + j);
+                rk[c][0] = v.x; rk[c][1] = v.y; rk[c][2] = v.z; rk[c][3] = v.w;
             } else {
-                const int k = rank - n_unmerged;
-                a.dst_of[(long long)b * a.n + j] = -k - 1;
-                if (a.merged_idx) a.merged_idx[(long long)b * (a.n - n_unmerged) + k] = j;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) rk[c][e] = j + e < a.n ? rank[j + e] : 0x7fffffff;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            cnt[c] = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) cnt[c] += rk[c][e] < n_unmerged;
+            incl[c] = cnt[c];
+        }
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+                const int t = __shfl_up(incl[c], o);
+                if (lane >= o) incl[c] += t;
+            }
+        }
+        if (lane == 63) {
+#pragma unroll
+            for (int c = 0; c < NC; ++c) wave_tot[c][wave] = incl[c];
+        }
+        __syncthreads();
+        int run = base_s;                    // kept tokens before this chunk
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            int p = run + incl[c] - cnt[c];
+            int chunk_tot = 0;
+            for (int w = 0; w < 16; ++w) {
+                const int t = wave_tot[c][w];
+                p += w < wave ? t : 0;
+                chunk_tot += t;
+            }
+            run += chunk_tot;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = s0 + c * 4096 + 4 * tid + e;
+                if (j >= a.n) continue;
+                if (rk[c][e] < n_unmerged) {
+                    dst_of[j] = p;
+                    if (a.keep_idx) a.keep_idx[(long long)b * n_unmerged + p] = j;
+                    ++p;
+                } else {
+                    const int k = rk[c][e] - n_unmerged;
+                    dst_of[j] = -k - 1;
+                    if (a.merged_idx) a.merged_idx[(long long)b * (a.n - n_unmerged) + k] = j;
+                }
             }
         }
         __syncthreads();
-        if (tid == 0) {
-            int tot = 0;
-            for (int w = 0; w < 16; ++w) tot += wave_cnt[w];
-            base_s += tot;
-        }
+        if (tid == 0) base_s = run;
         __syncthreads();
     }
 }
@@ -280,21 +333,37 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     }
 }
 
-// P_new[c] = sum over row chunks (in order) of the partial sums, rounded once.
+// P_new[c] = sum of the chunks' partial sums, rounded once.  A workgroup owns 16 columns; its 16 thread
+// rows each add a contiguous share of the chunks (independent loads, unrolled), then the shares are
+// added in order -- a fixed summation tree, so the result is reproducible.
 __global__ __launch_bounds__(256) void finalize_kernel(GatherArgs a) {
+    __shared__ float share[16][17];
     const int pi = blockIdx.y / a.B, b = blockIdx.y % a.B;
     const PlaneDev &p = a.plane[pi];
     if (p.rule != LVLM_RULE_WEIGHTED) return;
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= p.row_elems) return;
-    const float *part = a.partial + ((long long)b * a.n_planes + pi) * a.n_sub_max * a.max_row_elems + c;
+    const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const int c = blockIdx.x * 16 + col;
+    if (blockIdx.x * 16 >= p.row_elems) return;
+    const int per = (p.n_sub + 15) / 16;
+    const int i_lo = grp * per, i_hi = min(p.n_sub, i_lo + per);
     float s = 0.f;
-    for (int i = 0; i < p.n_sub; ++i) s += part[(long long)i * a.max_row_elems];
-    char *dst = p.dst + (long long)b * p.dst_stride_b + (long long)(a.img_begin + a.n_keep - 1) * p.row_bytes;
-    if (p.dtype == LVLM_BF16)
-        reinterpret_cast<uint16_t *>(dst)[c] = f32_to_bf16(s);
-    else
-        reinterpret_cast<float *>(dst)[c] = s;
+    if (c < p.row_elems) {
+        const float *part = a.partial + ((long long)b * a.n_planes + pi) * a.n_sub_max * a.max_row_elems + c;
+#pragma unroll 8
+        for (int i = i_lo; i < i_hi; ++i) s += part[(long long)i * a.max_row_elems];
+    }
+    share[grp][col] = s;
+    __syncthreads();
+    if (grp == 0 && c < p.row_elems) {
+        float t = 0.f;
+#pragma unroll
+        for (int g2 = 0; g2 < 16; ++g2) t += share[g2][col];
+        char *dst = p.dst + (long long)b * p.dst_stride_b + (long long)(a.img_begin + a.n_keep - 1) * p.row_bytes;
+        if (p.dtype == LVLM_BF16)
+            reinterpret_cast<uint16_t *>(dst)[c] = f32_to_bf16(t);
+        else
+            reinterpret_cast<float *>(dst)[c] = t;
+    }
 }
 
 int elem_bytes(int dtype) { return dtype == LVLM_BF16 ? 2 : 4; }
@@ -303,11 +372,7 @@ int elem_bytes(int dtype) { return dtype == LVLM_BF16 ? 2 : 4; }
 
 MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes) {
     MergeWs w{};
-    // rank kernel: aim at >= 1024 workgroups, each comparison range a multiple of the LDS tile
-    const long long jblocks = (long long)d.B * ((d.n_img + 255) / 256);
-    const int max_split = (d.n_img + kRankTile - 1) / kRankTile;
-    long long want = (1024 + jblocks - 1) / jblocks;
-    w.n_split = (int)(want < 1 ? 1 : (want > max_split ? max_split : want));
+    w.n_split = 1;
     // gather kernel: rows per partial sum
     int max_elems = 1;
     long long units = 0;
@@ -376,20 +441,17 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
     if (r > 0) {
         RankArgs ra{};
         ra.score = score_mean;
-        ra.rank_part = reinterpret_cast<int32_t *>(ws + w.rank_part);
+        ra.rank = reinterpret_cast<int32_t *>(ws + w.rank_part);
         ra.n = d.n_img;
-        ra.n_split = w.n_split;
-        const int tiles = (d.n_img + kRankTile - 1) / kRankTile;
-        ra.split_len = (tiles + w.n_split - 1) / w.n_split * kRankTile;
         prof.begin("merge_rank");
-        hipLaunchKernelGGL(rank_kernel, dim3((d.n_img + 255) / 256, w.n_split, d.B), dim3(256), 0, stream, ra);
+        hipLaunchKernelGGL(rank_kernel, dim3((d.n_img + kRankBlock - 1) / kRankBlock, d.B), dim3(1024), 0, stream, ra);
         prof.end();
         IndexArgs ia{};
-        ia.rank_part = ra.rank_part;
+        ia.rank = ra.rank;
         ia.dst_of = reinterpret_cast<int32_t *>(ws + w.dst_of);
         ia.keep_idx = keep_idx;
         ia.merged_idx = merged_idx;
-        ia.n = d.n_img; ia.n_split = w.n_split; ia.n_keep = d.n_keep;
+        ia.n = d.n_img; ia.n_keep = d.n_keep;
         prof.begin("merge_index");
         hipLaunchKernelGGL(index_kernel, dim3(d.B), dim3(1024), 0, stream, ia);
         prof.end();
@@ -399,7 +461,7 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
     prof.end();
     if (r > 0 && any_weighted) {
         prof.begin("merge_finalize");
-        hipLaunchKernelGGL(finalize_kernel, dim3((w.max_row_elems + 255) / 256, d.B * d.n_planes), dim3(256), 0,
+        hipLaunchKernelGGL(finalize_kernel, dim3((w.max_row_elems + 15) / 16, d.B * d.n_planes), dim3(256), 0,
                            stream, g);
         prof.end();
     }

@@ -181,8 +181,9 @@ __global__ __launch_bounds__(256) void score_pass_kernel(ScoreArgs a) {
                 }
                 const int hl = rho / a.T, i = rho - hl * a.T;
                 const long long ridx = ((long long)b * a.Hq + g * a.G + hl) * a.T + i;
-                a.part_m[ridx * a.nkb + kb] = m;
-                a.part_l[ridx * a.nkb + kb] = l;
+                const long long rows = (long long)a.B * a.Hq * a.T;
+                a.part_m[kb * rows + ridx] = m;      // [key block][row]: coalesced here and in the fold
+                a.part_l[kb * rows + ridx] = l;
             }
         }
     };
@@ -283,18 +284,21 @@ __global__ __launch_bounds__(256) void score_pass_kernel(ScoreArgs a) {
     }
 }
 
-// Fold the per-block (max, sum) pairs of each row into a log2-domain LSE.
+// Fold the per-block (max, sum) pairs of each row into a log2-domain LSE (online, in block order).
 __global__ __launch_bounds__(256) void score_lse_kernel(const float *part_m, const float *part_l, float *lse2,
                                                         int rows, int nkb) {
     const int row = blockIdx.x * 256 + threadIdx.x;
     if (row >= rows) return;
-    const float *pm = part_m + (long long)row * nkb;
-    const float *pl = part_l + (long long)row * nkb;
-    float m = -INFINITY;
-    for (int i = 0; i < nkb; ++i) m = fmaxf(m, pm[i]);
-    const float ms = (m == -INFINITY) ? 0.f : m;
-    float l = 0.f;
-    for (int i = 0; i < nkb; ++i) l += (pm[i] == -INFINITY) ? 0.f : pl[i] * exp2f(pm[i] - ms);
+    float m = -INFINITY, l = 0.f;
+#pragma unroll 8
+    for (int i = 0; i < nkb; ++i) {
+        const float mi = part_m[(long long)i * rows + row];
+        const float li = part_l[(long long)i * rows + row];
+        const float mn = fmaxf(m, mi);
+        const float ms = (mn == -INFINITY) ? 0.f : mn;
+        l = l * exp2f(m - ms) + li * exp2f(mi - ms);      // exp2(-inf) = 0 covers empty blocks
+        m = mn;
+    }
     lse2[row] = (l > 0.f) ? m + log2f(l) : INFINITY;   // a row that sees no key contributes nothing
 }
 
