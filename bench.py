@@ -157,12 +157,14 @@ def run_prefill(ctx, lv, w, states, reserve):
 
 def run_decode(ctx, lv, w, states, reserve, step_pos=0):
     for st in states:
-        bound = min(st.Lmax, max(st.N, w.kv_budget) + 1)
+        bound = min(st.Lmax, st.N + 1)
         ctx.decode_attn(st.q_dec, st.k_dec, st.v_dec, st.k, st.v, st.score, st.kind, st.pos, st.len,
                         score_decay=0.9, new_pos=w.seq_len + step_pos, len_bound=bound, out=st.out_dec,
                         reserve=reserve)
-        ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_BUDGET, budget=w.kv_budget,
-                        n_recent=1, order=lv.ORDER_FILL, len_bound=bound, n_evicted=st.n_evicted, reserve=reserve)
+        if w.kv_budget > 0:
+            ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_BUDGET, budget=w.kv_budget,
+                            n_recent=1, order=lv.ORDER_FILL, len_bound=bound, n_evicted=st.n_evicted,
+                            reserve=reserve)
 
 
 # ----------------------------------------------------------------------------- algorithmic work per kernel
@@ -222,12 +224,14 @@ def main():
 
     # capture one (prefill, decode) graph pair per remaining set
     use_graph = not args.no_graph
+    has_prefill = any(en["score"] or en["merge_to"] is not None or en["kv_threshold"] for en in layers)
     graphs = []
     if use_graph:
         for s in range(1, 1 + args.warmup + args.steps):
-            gp, gd = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gp):
-                run_prefill(ctx, lv, w, sets[s], reserve=False)
+            gp, gd = torch.cuda.CUDAGraph() if has_prefill else None, torch.cuda.CUDAGraph()
+            if has_prefill:
+                with torch.cuda.graph(gp):
+                    run_prefill(ctx, lv, w, sets[s], reserve=False)
             with torch.cuda.graph(gd):
                 run_decode(ctx, lv, w, sets[s], reserve=False)
             graphs.append((gp, gd))
@@ -235,7 +239,8 @@ def main():
 
     def step(i):
         if use_graph:
-            graphs[i][0].replay()
+            if has_prefill:
+                graphs[i][0].replay()
             ev_mid[i].record()
             graphs[i][1].replay()
         else:
@@ -367,7 +372,8 @@ def cpu_baseline(w, layers, master, torch, lv):
             state = list(O.kv_compress(*state, mode="threshold", beta=w.kv_beta, order=O.ORDER_STABLE)[:6])
         res = O.decode_attn(m["q_dec"], m["k_dec"], m["v_dec"], *state, score_decay=0.9, new_pos=w.seq_len,
                             out_dtype=w.dtype)
-        O.kv_compress(*res[1:], mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
+        if w.kv_budget > 0:
+            O.kv_compress(*res[1:], mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
     sec = time.perf_counter() - t0
     return {"value": round(w.batch * w.n_img / sec, 1), "unit": "image tokens/s", "cores": cores, "kind": "oracle",
             "sample": f"one full step of {w.name} (all {w.layers} layers, same inputs), {sec:.2f} s"}

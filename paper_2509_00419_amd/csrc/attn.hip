@@ -187,7 +187,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 
     char *vt = &v_lds[wave][0];
     for (int j0 = j_first; j0 < s_hi; j0 += 128) {
-        TileRegs<DT, HD> nxt;
+        TileRegs<DT, HD> nxt = cur;     // always defined (a conditionally written local would live in scratch)
         const bool more = j0 + 128 < s_hi;
         if (more) load_tile(j0 + 128, nxt);
 
@@ -338,7 +338,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // (two blocks) are exactly one B operand of the P.V product when the contraction slot i of lane group kg
 // is numbered entry 16 (i/4) + 4 kg + i%4; V^T is read from the wave's LDS tile with the same numbering.
 template <int HD, int GP>
-__global__ __launch_bounds__(256) void attn_partial_bf16_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
     constexpr int ROWB = HD * 2;
     constexpr int UPR = ROWB / 16;
     constexpr int KSUB = 64 / UPR;
@@ -548,12 +548,15 @@ __global__ __launch_bounds__(256) void attn_partial_bf16_kernel(AttnArgs a) {
 
 constexpr int kMaxSplit = 64;   // splits one combine workgroup can fold (checked on the host)
 
+// Workgroup x = 0 folds the splits into the output rows; workgroups x >= 1 each turn 1024 entries' logits
+// into normalised probabilities for the importance update.  All of them first rebuild the per-head
+// normalisers from the splits' (max, sum) pairs.
 template <int DT, int HD, int GP>
 __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     __shared__ float s_pm[kMaxSplit][GP], s_pl[kMaxSplit][GP];   // per split: max, then weight exp2(m_s - M)
     __shared__ float s_m[GP], s_inv[GP];
     const int tid = threadIdx.x;
-    const int chunk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int g = blockIdx.y, b = blockIdx.z;
     const int hg = b * a.Hkv + g;
     const int L = a.cur_len[hg];
     const float *pml = a.part_ml + (long long)hg * a.n_split * GP * 2;
@@ -578,13 +581,19 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
     }
     __syncthreads();
 
-    if (chunk == 0) {
+    if (blockIdx.x == 0) {
         const float *po = a.part_o + (long long)hg * a.n_split * GP * HD;
         for (int idx = tid; idx < a.G * HD; idx += 256) {
             const int h = idx / HD, e = idx % HD;
             float acc = 0.f;
-#pragma unroll 4
-            for (int s = 0; s < a.n_split; ++s) acc += po[((long long)s * GP + h) * HD + e] * s_pl[s][h];
+            for (int s0 = 0; s0 < a.n_split; s0 += 8) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    v[u] = s0 + u < a.n_split ? po[((long long)(s0 + u) * GP + h) * HD + e] : 0.f;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += s0 + u < a.n_split ? v[u] * s_pl[s0 + u][h] : 0.f;
+            }
             acc *= s_inv[h];
             const long long oi = ((long long)b * a.Hq + g * a.G + h) * HD + e;
             if constexpr (DT == LVLM_BF16)
@@ -593,19 +602,34 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
                 reinterpret_cast<float *>(a.out)[oi] = acc;
         }
         if (tid == 0 && a.append) a.len[hg] = L;
+        return;
     }
 
-    if (a.update_score) {
-        const long long cbase = (long long)hg * a.Lmax;
-        const float inv_g = 1.0f / (float)a.G;
-        const float *lg = a.logits + (long long)hg * a.Lcap * GP;
-        for (int j = chunk * 1024 + tid; j < min(L, (chunk + 1) * 1024); j += 256) {
-            float pm = 0.f;
+    const int chunk = blockIdx.x - 1;
+    const long long cbase = (long long)hg * a.Lmax;
+    const float inv_g = 1.0f / (float)a.G;
+    const float *lg = a.logits + (long long)hg * a.Lcap * GP;
+    float old[4], pm[4];
+    float lv[4][GP];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = chunk * 1024 + 256 * i + tid;
+        old[i] = 0.f;
+        if (j < L) {
+#pragma unroll
+            for (int h = 0; h < GP; ++h) lv[i][h] = lg[(long long)j * GP + h];
+            if (!(a.append && j == L - 1)) old[i] = a.score[cbase + j];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = chunk * 1024 + 256 * i + tid;
+        if (j < L) {
+            pm[i] = 0.f;
 #pragma unroll
             for (int h = 0; h < GP; ++h)
-                if (h < a.G) pm += exp2f(lg[(long long)j * GP + h] - s_m[h]) * s_inv[h];
-            const float old = (a.append && j == L - 1) ? 0.f : a.score[cbase + j];
-            a.score[cbase + j] = a.decay * old + pm * inv_g;
+                if (h < a.G) pm[i] += exp2f(lv[i][h] - s_m[h]) * s_inv[h];
+            a.score[cbase + j] = a.decay * old[i] + pm[i] * inv_g;
         }
     }
 }
@@ -619,10 +643,9 @@ void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
     else
         hipLaunchKernelGGL((attn_partial_kernel<DT, HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
     prof.end();
-    const int chunks = a.update_score ? (len_bound + 1023) / 1024 : 1;
+    const int chunks = a.update_score ? (len_bound + 1023) / 1024 : 0;
     prof.begin("attn_combine");
-    hipLaunchKernelGGL((attn_combine_kernel<DT, HD, GP>), dim3(chunks < 1 ? 1 : chunks, a.Hkv, B), dim3(256), 0,
-                       stream, a);
+    hipLaunchKernelGGL((attn_combine_kernel<DT, HD, GP>), dim3(1 + chunks, a.Hkv, B), dim3(256), 0, stream, a);
     prof.end();
 }
 

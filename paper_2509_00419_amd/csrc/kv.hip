@@ -6,7 +6,8 @@
 // order-preserving 32-bit image of the score finds, in four histogram passes,
 // the key K* at which the quota is met: entries above K* stay, entries below go,
 // and among the entries equal to K* the lowest slots stay.  Score mass is summed
-// as exact integers, so the result does not depend on summation order.
+// as exact integers, so the result does not depend on summation order.  (Four
+// 8-bit digits: four histogram passes over the scores; the first also gives the totals.)
 //
 //   kv_select_kernel  one workgroup per head: totals, radix descent, then one
 //                     pass in slot order that numbers survivors / holes.  With
@@ -38,47 +39,72 @@ struct KvArgs {
     double beta;
 };
 
-struct Scan3 {
-    int wave_cnt[3][16];
+constexpr int kScanChunks = 4;    // 1024-slot chunks numbered per barrier round in the slot-order pass
+constexpr int kBins = 256;        // radix: four 8-bit digits of the 32-bit key
+
+struct ScanState {
+    int wave_cnt[3][kScanChunks][16];   // per-wave counts, turned into exclusive prefixes in place
+    int tot[3][kScanChunks];
     int base[3];
 };
 
-// Exclusive prefix count, in thread order, of three flags at once; `base`
-// carries the totals from one 1024-slot chunk to the next.
-__device__ __forceinline__ void block_scan3(Scan3 &s, bool f0, bool f1, bool f2, int &p0, int &p1, int &p2) {
+// Exclusive prefix counts, in slot order, of three flags over kScanChunks consecutive 1024-slot chunks
+// (thread t holds slot c * 1024 + t of chunk c).  `base` carries the totals to the next round.
+__device__ __forceinline__ void block_scan3(ScanState &s, const bool (&f0)[kScanChunks], const bool (&f1)[kScanChunks],
+                                            const bool (&f2)[kScanChunks], int (&p0)[kScanChunks],
+                                            int (&p1)[kScanChunks], int (&p2)[kScanChunks]) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const unsigned long long below = (1ull << lane) - 1ull;
-    const unsigned long long b0 = __ballot(f0), b1 = __ballot(f1), b2 = __ballot(f2);
-    if (lane == 0) {
-        s.wave_cnt[0][wave] = __popcll(b0);
-        s.wave_cnt[1][wave] = __popcll(b1);
-        s.wave_cnt[2][wave] = __popcll(b2);
+#pragma unroll
+    for (int c = 0; c < kScanChunks; ++c) {
+        const unsigned long long b0 = __ballot(f0[c]), b1 = __ballot(f1[c]), b2 = __ballot(f2[c]);
+        p0[c] = __popcll(b0 & below);
+        p1[c] = __popcll(b1 & below);
+        p2[c] = __popcll(b2 & below);
+        if (lane == 0) {
+            s.wave_cnt[0][c][wave] = __popcll(b0);
+            s.wave_cnt[1][c][wave] = __popcll(b1);
+            s.wave_cnt[2][c][wave] = __popcll(b2);
+        }
     }
     __syncthreads();
-    p0 = s.base[0] + __popcll(b0 & below);
-    p1 = s.base[1] + __popcll(b1 & below);
-    p2 = s.base[2] + __popcll(b2 & below);
-    for (int w = 0; w < wave; ++w) {
-        p0 += s.wave_cnt[0][w];
-        p1 += s.wave_cnt[1][w];
-        p2 += s.wave_cnt[2][w];
+    if (tid < 3 * kScanChunks) {
+        const int k = tid / kScanChunks, c = tid % kScanChunks;
+        int run = 0;
+        for (int w = 0; w < 16; ++w) {
+            const int v = s.wave_cnt[k][c][w];
+            s.wave_cnt[k][c][w] = run;
+            run += v;
+        }
+        s.tot[k][c] = run;
     }
     __syncthreads();
-    if (tid < 3) {
-        int tot = 0;
-        for (int w = 0; w < 16; ++w) tot += s.wave_cnt[tid][w];
-        s.base[tid] += tot;
+    int run0 = s.base[0], run1 = s.base[1], run2 = s.base[2];
+#pragma unroll
+    for (int c = 0; c < kScanChunks; ++c) {
+        p0[c] += run0 + s.wave_cnt[0][c][wave];
+        p1[c] += run1 + s.wave_cnt[1][c][wave];
+        p2[c] += run2 + s.wave_cnt[2][c][wave];
+        run0 += s.tot[0][c];
+        run1 += s.tot[1][c];
+        run2 += s.tot[2][c];
+    }
+    __syncthreads();
+    if (tid == 0) {
+        s.base[0] = run0;
+        s.base[1] = run1;
+        s.base[2] = run2;
     }
     __syncthreads();
 }
 
 __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
-    __shared__ unsigned long long hist_m[256];
-    __shared__ unsigned int hist_c[256];
-    __shared__ unsigned long long s_total, s_need;
+    __shared__ unsigned long long hist_m[kBins];
+    __shared__ unsigned int hist_c[kBins];
+    __shared__ unsigned long long s_total, s_need, s_need_next;
     __shared__ unsigned int s_ncand, s_cabove, s_digit;
     __shared__ int s_first_hole;
-    __shared__ Scan3 scan;
+    __shared__ ScanState scan;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hg = blockIdx.x;
@@ -168,119 +194,143 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         __syncthreads();     // protected entries alone exceed the budget: general path below
     }
 
-    // ---- totals over the candidates
+    // ---- radix descent, most significant digit first.  The first histogram also yields the totals.
     if (tid == 0) {
-        s_total = 0ull;
-        s_ncand = 0u;
         s_cabove = 0u;
         s_first_hole = L;
         scan.base[0] = scan.base[1] = scan.base[2] = 0;
     }
-    __syncthreads();
-    {
-        unsigned long long mloc = 0ull;
-        unsigned int cloc = 0u;
-        for (int slot = tid; slot < L; slot += 1024) {
-            if (is_cand(slot, kind[slot])) {
-                mloc += budget_mode ? 1ull : score_fixed(score[slot]);
-                ++cloc;
-            }
-        }
-        if (cloc) {
-            atomicAdd(&s_total, mloc);
-            atomicAdd(&s_ncand, cloc);
-        }
-    }
-    __syncthreads();
-    const unsigned int ncand = s_ncand;
-    const unsigned long long total = s_total;
-    const int n_fixed = L - (int)ncand;                 // entries that are never candidates
-    unsigned long long need;                            // quota still to be met inside the current bin
+    unsigned long long need = 0ull;      // quota still to be met inside the current bin
+    int n_fixed = 0;                     // entries that are never candidates
     bool evict_all_cand = false;
-    if (budget_mode) {
-        const int room = a.budget - n_fixed;
-        evict_all_cand = room <= 0;
-        need = room > 0 ? (unsigned long long)room : 0ull;
-    } else {
-        if (ncand == 0u || total == 0ull) {
-            nothing_to_do();
-            return;
+    uint32_t prefix = 0u;
+    unsigned long long last_m = 0ull;
+    unsigned int last_c = 1u;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        for (int i = tid; i < kBins; i += 1024) {
+            hist_m[i] = 0ull;
+            hist_c[i] = 0u;
         }
-        const double target = ceil(a.beta * (double)total);
-        need = target >= 1.0 ? (unsigned long long)target : 1ull;
-        if (need > total) need = total;
-    }
-
-    // ---- radix descent: most significant digit first
-    uint32_t kstar = 0xffffffffu;
-    unsigned long long tie_keep = 0ull;
-    if (!evict_all_cand) {
-        uint32_t prefix = 0u;
-        for (int pass = 0; pass < 4; ++pass) {
-            const int shift = 24 - 8 * pass;
-            if (tid < 256) {
-                hist_m[tid] = 0ull;
-                hist_c[tid] = 0u;
-            }
-            __syncthreads();
+        __syncthreads();
+        {
+            // Scores cluster in few digits, so a thread first adds up runs of equal digits in registers
+            // and only then touches the shared histogram (far fewer colliding LDS atomics).
+            uint32_t run_d = 0xffffffffu;
+            unsigned long long run_m = 0ull;
+            unsigned int run_c = 0u;
             for (int slot = tid; slot < L; slot += 1024) {
                 if (!is_cand(slot, kind[slot])) continue;
                 const float sc = score[slot];
                 const uint32_t key = score_key(sc);
                 if (pass > 0 && (key >> (shift + 8)) != (prefix >> (shift + 8))) continue;
                 const uint32_t dgt = (key >> shift) & 255u;
-                atomicAdd(&hist_m[dgt], budget_mode ? 1ull : score_fixed(sc));
-                atomicAdd(&hist_c[dgt], 1u);
-            }
-            __syncthreads();
-            if (wave == 0) {
-                // lane owns digits 4*lane .. 4*lane+3; suffix sums give the mass above each digit
-                unsigned long long hm[4];
-                unsigned int hc[4];
-                unsigned long long loc_m = 0ull;
-                unsigned int loc_c = 0u;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    hm[i] = hist_m[4 * lane + i];
-                    hc[i] = hist_c[4 * lane + i];
-                    loc_m += hm[i];
-                    loc_c += hc[i];
-                }
-                unsigned long long inc_m = loc_m;
-                unsigned int inc_c = loc_c;
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const unsigned long long tm = __shfl_down(inc_m, o);
-                    const unsigned int tc = __shfl_down(inc_c, o);
-                    if (lane + o < 64) {
-                        inc_m += tm;
-                        inc_c += tc;
+                if (dgt != run_d) {
+                    if (run_c) {
+                        atomicAdd(&hist_m[run_d], run_m);
+                        atomicAdd(&hist_c[run_d], run_c);
                     }
+                    run_d = dgt;
+                    run_m = 0ull;
+                    run_c = 0u;
                 }
-                unsigned long long above_m = inc_m - loc_m;
-                unsigned int above_c = inc_c - loc_c;
-#pragma unroll
-                for (int i = 3; i >= 0; --i) {
-                    if (above_m < need && need <= above_m + hm[i]) {
-                        s_digit = 4u * lane + i;
-                        s_need = need - above_m;
-                        s_cabove += above_c;     // exactly one lane takes this branch
-                    }
-                    above_m += hm[i];
-                    above_c += hc[i];
-                }
+                run_m += budget_mode ? 1ull : score_fixed(sc);
+                ++run_c;
             }
-            __syncthreads();
-            prefix |= s_digit << shift;
-            need = s_need;
+            if (run_c) {
+                atomicAdd(&hist_m[run_d], run_m);
+                atomicAdd(&hist_c[run_d], run_c);
+            }
         }
+        __syncthreads();
+        if (wave == 0) {
+            // lane owns 4 consecutive digits; suffix sums give the mass above each digit
+            constexpr int PER = kBins / 64;
+            unsigned long long loc_m = 0ull;
+            unsigned int loc_c = 0u;
+            for (int i = 0; i < PER; ++i) {
+                loc_m += hist_m[PER * lane + i];
+                loc_c += hist_c[PER * lane + i];
+            }
+            unsigned long long inc_m = loc_m;
+            unsigned int inc_c = loc_c;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const unsigned long long tm = __shfl_down(inc_m, o);
+                const unsigned int tc = __shfl_down(inc_c, o);
+                if (lane + o < 64) {
+                    inc_m += tm;
+                    inc_c += tc;
+                }
+            }
+            if (pass == 0) {
+                // totals over all candidates (lane 0 holds the full suffix sum) fix the quota
+                const unsigned long long total = __shfl(inc_m, 0);
+                const unsigned int ncand = __shfl(inc_c, 0);
+                if (lane == 0) {
+                    s_total = total;
+                    s_ncand = ncand;
+                    unsigned long long nd;
+                    if (budget_mode) {
+                        const int room = a.budget - (L - (int)ncand);
+                        nd = room > 0 ? (unsigned long long)room : 0ull;
+                    } else {
+                        const double target = ceil(a.beta * (double)total);
+                        nd = target >= 1.0 ? (unsigned long long)target : 1ull;
+                        if (nd > total) nd = total;
+                    }
+                    s_need = nd;
+                }
+            }
+            // every lane needs the quota of this pass
+            unsigned long long nd = pass == 0 ? 0ull : need;
+            if (pass == 0) {
+                nd = __shfl(lane == 0 ? s_need : 0ull, 0);
+            }
+            unsigned long long above_m = inc_m - loc_m;
+            unsigned int above_c = inc_c - loc_c;
+            if (nd > 0ull) {
+                for (int i = PER - 1; i >= 0; --i) {
+                    const unsigned long long hm = hist_m[PER * lane + i];
+                    if (above_m < nd && nd <= above_m + hm) {
+                        s_digit = (unsigned int)(PER * lane + i);
+                        s_need_next = nd - above_m;
+                        s_cabove += above_c;     // exactly one lane and one digit take this branch
+                    }
+                    above_m += hm;
+                    above_c += hist_c[PER * lane + i];
+                }
+            }
+        }
+        __syncthreads();
+        if (pass == 0) {
+            const unsigned int ncand = s_ncand;
+            n_fixed = L - (int)ncand;
+            if (budget_mode) {
+                evict_all_cand = a.budget - n_fixed <= 0;
+            } else if (ncand == 0u || s_total == 0ull) {
+                nothing_to_do();
+                return;
+            }
+            if (evict_all_cand) break;
+        }
+        prefix |= s_digit << shift;
+        need = s_need_next;
+        if (pass == 3) {
+            last_m = hist_m[s_digit];
+            last_c = hist_c[s_digit];
+        }
+        __syncthreads();
+    }
+    uint32_t kstar = 0xffffffffu;
+    unsigned long long tie_keep = 0ull;
+    if (!evict_all_cand) {
         kstar = prefix;
-        const uint32_t last = kstar & 255u;
         if (budget_mode) {
             tie_keep = need;
         } else {
-            const unsigned long long u = hist_m[last] / hist_c[last];   // equal keys have equal mass
-            tie_keep = (need + u - 1ull) / u;
+            const unsigned long long u = last_m / (last_c ? last_c : 1u);   // equal keys have equal mass
+            tie_keep = u ? (need + u - 1ull) / u : (unsigned long long)last_c;
         }
     }
     const int n_keep_cand = evict_all_cand ? 0 : (int)(s_cabove + (unsigned int)tie_keep);
@@ -295,40 +345,53 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
     int32_t *list_a = a.list_a + base;
     int32_t *list_b = a.list_b + base;
     const bool stable = a.order == LVLM_ORDER_STABLE;
-    for (int s0 = 0; s0 < L; s0 += 1024) {
-        const int slot = s0 + tid;
-        bool tie = false, keep = false, inside = slot < L;
-        if (inside) {
-            const uint8_t kd = kind[slot];
-            if (!is_cand(slot, kd)) {
-                keep = true;
-            } else {
-                const uint32_t key = score_key(score[slot]);
-                tie = key == kstar;
-                keep = key > kstar;
+    for (int s0 = 0; s0 < L; s0 += kScanChunks * 1024) {
+        bool tie[kScanChunks], keep[kScanChunks], inside[kScanChunks], none[kScanChunks];
+        int slot[kScanChunks];
+#pragma unroll
+        for (int c = 0; c < kScanChunks; ++c) {
+            slot[c] = s0 + c * 1024 + tid;
+            inside[c] = slot[c] < L;
+            tie[c] = keep[c] = none[c] = false;
+            if (inside[c]) {
+                if (!is_cand(slot[c], kind[slot[c]])) {
+                    keep[c] = true;
+                } else {
+                    const uint32_t key = score_key(score[slot[c]]);
+                    tie[c] = key == kstar;
+                    keep[c] = key > kstar;
+                }
             }
         }
-        int tie_before, p1, p2;
+        int tie_before[kScanChunks], p1[kScanChunks], p2[kScanChunks];
         if (stable) {
-            // survivors before this slot = sure survivors before + ties before that are kept
-            block_scan3(scan, tie, keep, false, tie_before, p1, p2);
-            const bool kept = keep || (tie && (unsigned long long)tie_before < tie_keep);
-            const int ties_kept_before = (int)min((unsigned long long)tie_before, tie_keep);
-            const int p = p1 + ties_kept_before;
-            if (inside) {
-                if (kept) list_a[p] = slot;
+            // survivors before a slot = sure survivors before it + kept ties before it
+            block_scan3(scan, tie, keep, none, tie_before, p1, p2);
+#pragma unroll
+            for (int c = 0; c < kScanChunks; ++c) {
+                if (!inside[c]) continue;
+                const bool kept = keep[c] || (tie[c] && (unsigned long long)tie_before[c] < tie_keep);
+                const int p = p1[c] + (int)min((unsigned long long)tie_before[c], tie_keep);
+                if (kept) list_a[p] = slot[c];
                 else atomicMin(&s_first_hole, p);
             }
         } else {
-            block_scan3(scan, tie, false, false, tie_before, p1, p2);
-            const bool kept = keep || (tie && (unsigned long long)tie_before < tie_keep);
-            const bool hole = inside && !kept && slot < n_new;
-            const bool tail = inside && kept && slot >= n_new;
-            int dummy, hi, ti;
-            // a second scan numbers holes and tail survivors (slot 0 of the scan keeps counting ties)
-            block_scan3(scan, false, hole, tail, dummy, hi, ti);
-            if (hole) list_a[hi] = slot;
-            if (tail) list_b[ti] = slot;
+            block_scan3(scan, tie, none, none, tie_before, p1, p2);
+            bool hole[kScanChunks], tail[kScanChunks];
+#pragma unroll
+            for (int c = 0; c < kScanChunks; ++c) {
+                const bool kept = keep[c] || (tie[c] && (unsigned long long)tie_before[c] < tie_keep);
+                hole[c] = inside[c] && !kept && slot[c] < n_new;
+                tail[c] = inside[c] && kept && slot[c] >= n_new;
+            }
+            int dummy[kScanChunks], hi[kScanChunks], ti[kScanChunks];
+            // a second scan numbers holes and tail survivors (counter 0 keeps counting ties)
+            block_scan3(scan, none, hole, tail, dummy, hi, ti);
+#pragma unroll
+            for (int c = 0; c < kScanChunks; ++c) {
+                if (hole[c]) list_a[hi[c]] = slot[c];
+                if (tail[c]) list_b[ti[c]] = slot[c];
+            }
         }
     }
     __syncthreads();
@@ -370,7 +433,7 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
 }
 
 constexpr int kSliceBytes = 64;   // column slice of a K or V row handled by one workgroup
-constexpr int kMoveUpt = 8;       // units per thread per step
+constexpr int kMoveUpt = 16;      // units per thread per step (1024 rows of a 64-byte slice)
 
 __global__ __launch_bounds__(256) void kv_move_kernel(KvArgs a) {
     const int tid = threadIdx.x;
@@ -389,6 +452,7 @@ __global__ __launch_bounds__(256) void kv_move_kernel(KvArgs a) {
 #pragma unroll
             for (int x = 0; x < kMoveUpt; ++x) {
                 const int p = p0 + 64 * x + (tid >> 2);
+                val[x] = make_uint4(0, 0, 0, 0);   // always defined, or the array is placed in scratch memory
                 if (p < n_new) val[x] = *reinterpret_cast<const uint4 *>(cache + (long long)src_of[p] * a.row_bytes);
             }
             __syncthreads();
@@ -407,6 +471,9 @@ __global__ __launch_bounds__(256) void kv_move_kernel(KvArgs a) {
 #pragma unroll
             for (int x = 0; x < kMoveUpt; ++x) {
                 const int p = p0 + 256 * x + tid;
+                sc[x] = 0.f;
+                kd[x] = 0;
+                ps[x] = 0;
                 if (p < n_new) {
                     const int s = src_of[p];
                     sc[x] = a.score[base + s];

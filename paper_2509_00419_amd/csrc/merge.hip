@@ -271,40 +271,53 @@ __device__ __forceinline__ void gather_plane(const GatherArgs &a, const PlaneDev
 
     const int n_lo = sub * a.rows_per_sub;
     const int n_hi = min(a.N, n_lo + a.rows_per_sub);
-    for (int n0 = n_lo; n0 < n_hi; n0 += RB) {
-        U val[RB];
-        int where[RB];   // >= 0: destination row; -1: skip; <= -2: merged with rank -(where) - 2
+
+    // Two batches of RB rows are in flight: the next batch's loads are issued before the current one
+    // is copied / accumulated.
+    U val[2][RB];
+    int where[2][RB];   // >= 0: destination row; -1: skip; <= -2: merged with rank -(where) - 2
+    auto issue = [&](int n0, U (&v)[RB], int (&wh)[RB]) {
 #pragma unroll
         for (int x = 0; x < RB; ++x) {
             const int n = n0 + x;
-            where[x] = -1;
+            wh[x] = -1;
+            v[x] = U{};      // always defined: a conditionally written local array would live in scratch memory
             if (n < n_hi) {
-                if (active) val[x] = *reinterpret_cast<const U *>(src + (long long)n * p.row_bytes);
+                if (active) v[x] = *reinterpret_cast<const U *>(src + (long long)n * p.row_bytes);
                 if (dst_of == nullptr || n < a.img_begin) {
-                    where[x] = n;
+                    wh[x] = n;
                 } else if (n >= a.img_begin + a.n_img) {
-                    where[x] = n - r;
+                    wh[x] = n - r;
                 } else {
                     const int t = dst_of[n - a.img_begin];
-                    where[x] = t >= 0 ? a.img_begin + t : t - 1;
+                    wh[x] = t >= 0 ? a.img_begin + t : t - 1;
                 }
             }
         }
+    };
+    auto consume = [&](const U (&v)[RB], const int (&wh)[RB]) {
 #pragma unroll
         for (int x = 0; x < RB; ++x) {
             if (!active) continue;
-            if (where[x] >= 0) {
-                *reinterpret_cast<U *>(dst + (long long)where[x] * p.row_bytes) = val[x];
-            } else if (where[x] <= -2) {
-                const int k = -where[x] - 2;
+            if (wh[x] >= 0) {
+                *reinterpret_cast<U *>(dst + (long long)wh[x] * p.row_bytes) = v[x];
+            } else if (wh[x] <= -2) {
+                const int k = -wh[x] - 2;
                 if (weighted) {
                     const float wk = a.w ? a.w[k] : (float)(m - k) * a.lin_scale;
-                    if constexpr (DT != LVLM_I32) accumulate<DT, UB>(acc, val[x], wk);
+                    if constexpr (DT != LVLM_I32) accumulate<DT, UB>(acc, v[x], wk);
                 } else if (k == 0) {
-                    *reinterpret_cast<U *>(dst + (long long)(a.img_begin + a.n_keep - 1) * p.row_bytes) = val[x];
+                    *reinterpret_cast<U *>(dst + (long long)(a.img_begin + a.n_keep - 1) * p.row_bytes) = v[x];
                 }
             }
         }
+    };
+    issue(n_lo, val[0], where[0]);
+    for (int n0 = n_lo; n0 < n_hi; n0 += 2 * RB) {
+        issue(n0 + RB, val[1], where[1]);
+        consume(val[0], where[0]);
+        issue(n0 + 2 * RB, val[0], where[0]);
+        consume(val[1], where[1]);
     }
     if constexpr (DT != LVLM_I32) {
         if (weighted && active) {
