@@ -36,7 +36,7 @@ struct ScoreWs {
 ScoreWs score_ws(const lvlm_score_desc &d);
 
 struct MergeWs {
-    size_t rank_part, dst_of, partial, total;
+    size_t rank_part, dst_of, wgt, partial, total;
     int n_split;   // always 1: the rank kernel leaves complete ranks
     int n_chunk;   // source-row chunks of the gather kernel (partial sums per chunk)
     int rows_per_chunk;

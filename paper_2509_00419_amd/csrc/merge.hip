@@ -91,9 +91,13 @@ __global__ __launch_bounds__(1024) void rank_kernel(RankArgs a) {
 
 struct IndexArgs {
     const int32_t *rank;
-    int32_t *dst_of;       // [B, n]: >= 0 row inside the new image span; < 0: -(rank in P_merged) - 1
+    int32_t *dst_of;       // [B, n]: >= 0 row inside the new image span; -1: most important merged token;
+                           //         -2: any other merged token
+    float *wgt;            // [B, n]: merge weight of the token (0 for kept tokens)
     int32_t *keep_idx;     // [B, n_keep-1] or null
     int32_t *merged_idx;   // [B, r+1] or null
+    const float *w;        // rank -> weight table, or null for the linear table
+    float lin_scale;       // 1 / (m (m+1) / 2)
     int n, n_keep;
 };
 
@@ -110,6 +114,8 @@ __global__ __launch_bounds__(1024) void index_kernel(IndexArgs a) {
     const int n_unmerged = a.n_keep - 1;
     const int32_t *rank = a.rank + (long long)b * a.n;
     int32_t *dst_of = a.dst_of + (long long)b * a.n;
+    float *wgt = a.wgt + (long long)b * a.n;
+    const int m = a.n - n_unmerged;
     if (tid == 0) base_s = 0;
     __syncthreads();
     for (int s0 = 0; s0 < a.n; s0 += NC * 4096) {
@@ -163,12 +169,14 @@ __global__ __launch_bounds__(1024) void index_kernel(IndexArgs a) {
                 if (j >= a.n) continue;
                 if (rk[c][e] < n_unmerged) {
                     dst_of[j] = p;
+                    wgt[j] = 0.f;
                     if (a.keep_idx) a.keep_idx[(long long)b * n_unmerged + p] = j;
                     ++p;
                 } else {
                     const int k = rk[c][e] - n_unmerged;
-                    dst_of[j] = -k - 1;
-                    if (a.merged_idx) a.merged_idx[(long long)b * (a.n - n_unmerged) + k] = j;
+                    dst_of[j] = k == 0 ? -1 : -2;
+                    wgt[j] = a.w ? a.w[k] : (float)(m - k) * a.lin_scale;
+                    if (a.merged_idx) a.merged_idx[(long long)b * m + k] = j;
                 }
             }
         }
@@ -197,11 +205,10 @@ struct PlaneDev {
 struct GatherArgs {
     PlaneDev plane[LVLM_MAX_PLANES];
     const int32_t *dst_of;   // null: identity (nothing removed)
-    const float *w;          // rank -> weight, or null for the linear table
+    const float *wgt;        // per-token merge weight
     float *partial;          // [B][n_planes][n_sub_max][max_row_elems]
     int B, N, img_begin, n_img, n_keep, n_planes;
     int rows_per_sub, n_sub_max, max_row_elems;
-    float lin_scale;         // 1 / (m (m+1) / 2)
 };
 
 template <int UB>
@@ -243,81 +250,75 @@ __device__ __forceinline__ void accumulate(Acc<DT, UB> &acc, const typename Unit
     }
 }
 
-// One thread group walks `rows_per_sub` consecutive source rows of one plane,
-// one unit column per thread.
+// One thread group walks `rows_per_sub` consecutive source rows of one plane, one unit column per thread.
+// The loop is free of data-dependent branches before its stores: row data, destination code and weight
+// of a batch of RB rows are loaded unconditionally (indices clamped into range), so the loads of many
+// rows are in flight at once; then kept rows are stored and every row is multiplied by its weight (zero
+// unless it is merged) and accumulated.
 template <int DT, int UB>
 __device__ __forceinline__ void gather_plane(const GatherArgs &a, const PlaneDev &p, int pi, int b) {
     using U = typename Unit<UB>::type;
-    constexpr int RB = 4;   // rows in flight per thread
+    constexpr int RB = 8;   // rows per batch (all of a batch's loads are in flight together)
     const int tid = threadIdx.x;
     const int tpr = 1 << p.tpr_log2;
     const int group = tid >> p.tpr_log2;
     const int groups = 256 >> p.tpr_log2;
     const int sub = blockIdx.x * groups + group;
-    const int unit = blockIdx.y * 256 + (tid & (tpr - 1));
     const int row_units = p.row_bytes / UB;
     if (sub >= p.n_sub || blockIdx.y >= p.col_blocks) return;
-    const bool active = unit < row_units;
+    const int unit_raw = blockIdx.y * 256 + (tid & (tpr - 1));
+    const bool active = unit_raw < row_units;
+    const int unit = active ? unit_raw : row_units - 1;
     const int r = a.n_img - a.n_keep;
-    const int m = r + 1;
     const char *src = p.src + (long long)b * p.src_stride_b + (long long)unit * UB;
     char *dst = p.dst + (long long)b * p.dst_stride_b + (long long)unit * UB;
-    const int32_t *dst_of = a.dst_of ? a.dst_of + (long long)b * a.n_img : nullptr;
-    const bool weighted = p.rule == LVLM_RULE_WEIGHTED && dst_of != nullptr;
+    const int n_lo = sub * a.rows_per_sub;
+    const int n_hi = min(a.N, n_lo + a.rows_per_sub);
+    if (a.dst_of == nullptr) {
+        // nothing is removed (kernel-uniform case): plain row copy
+        if (active) {
+#pragma unroll 4
+            for (int n = n_lo; n < n_hi; ++n)
+                *reinterpret_cast<U *>(dst + (long long)n * p.row_bytes) =
+                    *reinterpret_cast<const U *>(src + (long long)n * p.row_bytes);
+        }
+        return;
+    }
+    const int32_t *dst_of = a.dst_of + (long long)b * a.n_img;
+    const float *wgt = a.wgt + (long long)b * a.n_img;
+    const bool weighted = p.rule == LVLM_RULE_WEIGHTED;             // uniform per plane
+    const int new_row = a.img_begin + a.n_keep - 1;
 
     Acc<DT, UB> acc;
 #pragma unroll
     for (int i = 0; i < Acc<DT, UB>::NE; ++i) acc.v[i] = 0.f;
 
-    const int n_lo = sub * a.rows_per_sub;
-    const int n_hi = min(a.N, n_lo + a.rows_per_sub);
-
-    // Two batches of RB rows are in flight: the next batch's loads are issued before the current one
-    // is copied / accumulated.
-    U val[2][RB];
-    int where[2][RB];   // >= 0: destination row; -1: skip; <= -2: merged with rank -(where) - 2
-    auto issue = [&](int n0, U (&v)[RB], int (&wh)[RB]) {
+    for (int n0 = n_lo; n0 < n_hi; n0 += RB) {
+        // all loads of the batch first (clamped row / token indices keep every address valid) ...
+        U val[RB];
+        int code[RB];
+        float wk[RB];
+#pragma unroll
+        for (int x = 0; x < RB; ++x) {
+            const int n = min(n0 + x, n_hi - 1);
+            const int j = min(max(n - a.img_begin, 0), a.n_img - 1);
+            val[x] = *reinterpret_cast<const U *>(src + (long long)n * p.row_bytes);
+            code[x] = dst_of[j];
+            wk[x] = wgt[j];
+        }
+        // ... then the stores and the weighted accumulation
 #pragma unroll
         for (int x = 0; x < RB; ++x) {
             const int n = n0 + x;
-            wh[x] = -1;
-            v[x] = U{};      // always defined: a conditionally written local array would live in scratch memory
-            if (n < n_hi) {
-                if (active) v[x] = *reinterpret_cast<const U *>(src + (long long)n * p.row_bytes);
-                if (dst_of == nullptr || n < a.img_begin) {
-                    wh[x] = n;
-                } else if (n >= a.img_begin + a.n_img) {
-                    wh[x] = n - r;
-                } else {
-                    const int t = dst_of[n - a.img_begin];
-                    wh[x] = t >= 0 ? a.img_begin + t : t - 1;
-                }
+            const bool valid = active && n < n_hi;
+            const bool in_img = n >= a.img_begin && n < a.img_begin + a.n_img;
+            int dest = n < a.img_begin ? n : n - r;                  // rows outside the image span
+            if (in_img) dest = code[x] >= 0 ? a.img_begin + code[x] : (code[x] == -1 && !weighted ? new_row : -1);
+            if (valid && dest >= 0) *reinterpret_cast<U *>(dst + (long long)dest * p.row_bytes) = val[x];
+            if constexpr (DT != LVLM_I32) {
+                if (weighted) accumulate<DT, UB>(acc, val[x], valid && in_img ? wk[x] : 0.f);
             }
         }
-    };
-    auto consume = [&](const U (&v)[RB], const int (&wh)[RB]) {
-#pragma unroll
-        for (int x = 0; x < RB; ++x) {
-            if (!active) continue;
-            if (wh[x] >= 0) {
-                *reinterpret_cast<U *>(dst + (long long)wh[x] * p.row_bytes) = v[x];
-            } else if (wh[x] <= -2) {
-                const int k = -wh[x] - 2;
-                if (weighted) {
-                    const float wk = a.w ? a.w[k] : (float)(m - k) * a.lin_scale;
-                    if constexpr (DT != LVLM_I32) accumulate<DT, UB>(acc, v[x], wk);
-                } else if (k == 0) {
-                    *reinterpret_cast<U *>(dst + (long long)(a.img_begin + a.n_keep - 1) * p.row_bytes) = v[x];
-                }
-            }
-        }
-    };
-    issue(n_lo, val[0], where[0]);
-    for (int n0 = n_lo; n0 < n_hi; n0 += 2 * RB) {
-        issue(n0 + RB, val[1], where[1]);
-        consume(val[0], where[0]);
-        issue(n0 + 2 * RB, val[0], where[0]);
-        consume(val[1], where[1]);
     }
     if constexpr (DT != LVLM_I32) {
         if (weighted && active) {
@@ -401,7 +402,8 @@ MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes) {
     w.max_row_elems = max_elems;
     w.rank_part = 0;
     w.dst_of = align_up(w.rank_part + (size_t)d.B * w.n_split * d.n_img * sizeof(int32_t), 256);
-    w.partial = align_up(w.dst_of + (size_t)d.B * d.n_img * sizeof(int32_t), 256);
+    w.wgt = align_up(w.dst_of + (size_t)d.B * d.n_img * sizeof(int32_t), 256);
+    w.partial = align_up(w.wgt + (size_t)d.B * d.n_img * sizeof(float), 256);
     w.total = align_up(w.partial + (size_t)d.B * d.n_planes * w.n_chunk * max_elems * sizeof(float), 256);
     return w;
 }
@@ -418,10 +420,9 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
     g.n_sub_max = w.n_chunk;
     g.max_row_elems = w.max_row_elems;
     g.partial = reinterpret_cast<float *>(ws + w.partial);
-    g.w = wtab;
     const double m = (double)r + 1.0;
-    g.lin_scale = (float)(1.0 / (m * (m + 1.0) / 2.0));
     g.dst_of = r > 0 ? reinterpret_cast<const int32_t *>(ws + w.dst_of) : nullptr;
+    g.wgt = reinterpret_cast<const float *>(ws + w.wgt);
 
     int grid_x = 1, grid_y = 1;
     bool any_weighted = false;
@@ -462,6 +463,9 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
         IndexArgs ia{};
         ia.rank = ra.rank;
         ia.dst_of = reinterpret_cast<int32_t *>(ws + w.dst_of);
+        ia.wgt = reinterpret_cast<float *>(ws + w.wgt);
+        ia.w = wtab;
+        ia.lin_scale = (float)(1.0 / (m * (m + 1.0) / 2.0));
         ia.keep_idx = keep_idx;
         ia.merged_idx = merged_idx;
         ia.n = d.n_img; ia.n_keep = d.n_keep;
