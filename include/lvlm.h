@@ -139,7 +139,7 @@ typedef struct {
     int32_t img_begin; /* first image key                                         */
     int32_t n_img;     /* number of image keys; img_begin + n_img <= N            */
     int32_t causal;    /* 0 / 1                                                   */
-    float scale;       /* logit scale, usually 1/sqrt(hd)                         */
+    float scale;       /* logit scale >= 0, usually 1/sqrt(hd)                    */
     int64_t q_stride_b, q_stride_t, q_stride_h; /* q[b][i][h][0..hd)              */
     int64_t k_stride_b, k_stride_n, k_stride_h; /* k[b][j][g][0..hd)              */
     int64_t sh_stride_b, sh_stride_h; /* score_head[b][g][0..n_img); both 0 = dense

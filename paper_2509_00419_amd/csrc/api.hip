@@ -35,8 +35,10 @@ const char *check_score(const lvlm_score_desc *d) {
     if (d->hd != 64 && d->hd != 128) return "head dimension must be 64 or 128";
     if (d->B < 1 || d->N < 1 || d->T < 1 || d->Hq < 1 || d->Hkv < 1) return "sizes must be positive";
     if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
+    if ((long long)(d->Hq / d->Hkv) * d->T >= 65536) return "query rows per KV head (Hq/Hkv * T) must be below 65536";
     if (d->img_begin < 0 || d->n_img < 1 || (long long)d->img_begin + d->n_img > d->N) return "image span outside [0, N)";
     if (d->q_pos0 < 0) return "q_pos0 must be non-negative";
+    if (!(d->scale >= 0.0f)) return "scale must be non-negative";
     const int vec = 16 / elem_bytes(d->dtype);
     const long long s[6] = {d->q_stride_b, d->q_stride_t, d->q_stride_h, d->k_stride_b, d->k_stride_n, d->k_stride_h};
     for (long long x : s)

@@ -29,9 +29,10 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- workspace layouts (host arithmetic shared by the size query and the launch) ----
 struct ScoreWs {
-    size_t part_m, part_l, lse2, total;
+    size_t part_m, part_l, lse2, colpart, total;
     int nkb;       // key blocks of the normaliser pass
     int block_keys;
+    int rs, cps;   // row splits per key block, query chunks per split
 };
 ScoreWs score_ws(const lvlm_score_desc &d);
 

@@ -31,12 +31,16 @@ struct ScoreArgs {
     const char *q;
     const char *k;
     const float *row_lse;
-    float *part_m;
-    float *part_l;
-    float *lse2;
+    float *part_m;      // [nkb * 4][rows]   per key block and wave: row max (log2 domain)
+    float *part_l;      // [nkb * 4][rows]   ... and sum of exp2(logit - max)
+    float *lse2;        // [rows]
+    float *colpart;     // [RS][B][Hkv][n_img]  column sums of each row split
     float *score_head;
     float *score_mean;
     int B, N, T, q_pos0, Hq, Hkv, G, img_begin, n_img, causal, nkb;
+    int rs;             // row splits: workgroups that share a key block and take different query chunks
+    int cps;            // chunks per split
+    unsigned t_magic;   // floor(2^32 / T) + 1: rho / T == umulhi(rho, t_magic) for rho, T < 65536
     float scale_log2;
     long long qsb, qst, qsh, ksb, ksn, ksh, shb, shh;
 };
@@ -77,7 +81,7 @@ __device__ __forceinline__ void mma_tile(f32x16 &acc, const HalfRow<DT, HD> &a, 
 __device__ __forceinline__ int acc_row(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
 
 template <int DT, int HD, int KPW, int PASS>
-__global__ __launch_bounds__(256) void score_pass_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     constexpr int ES = esize<DT>();
     constexpr int ROWB = HD * ES;
     constexpr int PITCH = ROWB + 16;        // odd multiple of 16 B: conflict-free 128-bit LDS reads
@@ -85,122 +89,102 @@ __global__ __launch_bounds__(256) void score_pass_kernel(ScoreArgs a) {
     constexpr int UPT = 32 * UPR / 256;     // units each thread stages per chunk
     constexpr int BN = 4 * KPW * 32;
     constexpr int NV = HalfRow<DT, HD>::NV;
-    static_assert(UPT >= 1, "chunk smaller than the workgroup");
+    constexpr int NBUF = 3;
+    static_assert(UPT >= 1 && UPT <= 4, "staging covers 1..4 units per thread");
 
-    __shared__ __attribute__((aligned(16))) char q_lds[2][32 * PITCH];
-    __shared__ __attribute__((aligned(16))) int pos_lds[2][32];
-    __shared__ __attribute__((aligned(16))) float lse_lds[2][32];
-    __shared__ float red_m[2][4][32];
-    __shared__ float red_l[2][4][32];
+    __shared__ __attribute__((aligned(16))) char q_lds[NBUF][32 * PITCH];
+    __shared__ __attribute__((aligned(16))) int pos_lds[NBUF][32];
+    __shared__ __attribute__((aligned(16))) float lse_lds[NBUF][32];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int kb = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int kb = blockIdx.x / a.rs, rs = blockIdx.x % a.rs;
+    const int g = blockIdx.y, b = blockIdx.z;
     const int GT = a.G * a.T;
     const int n_chunks = (GT + 31) >> 5;
+    const int c_lo = rs * a.cps, c_hi = min(n_chunks, c_lo + a.cps);
     const int key_lo = PASS == 0 ? 0 : a.img_begin;
     const int key_hi = PASS == 0 ? a.N : a.img_begin + a.n_img;
     const int jbase = key_lo + kb * BN + wave * (KPW * 32);
+    const long long rowbase = ((long long)b * a.Hq + (long long)g * a.G) * a.T;   // row index of chunk row rho: rowbase + rho
+    const long long rows_total = (long long)a.B * a.Hq * a.T;
+
+    // rho / T without a hardware divide (exact for rho, T < 65536; T == 1 has no 32-bit magic number)
+    auto div_t = [&](int rho) -> int { return a.T == 1 ? rho : (int)__umulhi((unsigned)rho, a.t_magic); };
 
     // this wave's key tiles, resident for the whole kernel
     HalfRow<DT, HD> kf[KPW];
 #pragma unroll
     for (int s = 0; s < KPW; ++s) {
         const int j = jbase + 32 * s + l32;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) kf[s].v[i] = make_uint4(0, 0, 0, 0);
         if (j < key_hi) {
             const char *src = a.k + ((long long)b * a.ksb + (long long)j * a.ksn + (long long)g * a.ksh) * ES +
                               hf * (ROWB / 2);
 #pragma unroll
             for (int i = 0; i < NV; ++i) kf[s].v[i] = *reinterpret_cast<const uint4 *>(src + 16 * i);
-        } else {
-#pragma unroll
-            for (int i = 0; i < NV; ++i) kf[s].v[i] = make_uint4(0, 0, 0, 0);
         }
     }
 
-    uint4 stage[UPT];
-    int stage_pos = -1;
-    float stage_lse = 0.f;
-
-    auto load_chunk = [&](int c) {
-#pragma unroll
-        for (int x = 0; x < UPT; ++x) {
-            const int u = tid + 256 * x;
-            const int row = u / UPR, cu = u % UPR;
-            const int rho = c * 32 + row;
-            if (rho < GT) {
-                const int hl = rho / a.T, i = rho - hl * a.T;
-                const char *src = a.q + ((long long)b * a.qsb + (long long)i * a.qst +
-                                         (long long)(g * a.G + hl) * a.qsh) * ES + 16 * cu;
-                stage[x] = *reinterpret_cast<const uint4 *>(src);
-            } else {
-                stage[x] = make_uint4(0, 0, 0, 0);
-            }
-        }
-        if (tid < 32) {
-            const int rho = c * 32 + tid;
-            stage_pos = -1;          // padding row: sees no key
-            stage_lse = 0.f;
-            if (rho < GT) {
-                const int hl = rho / a.T, i = rho - hl * a.T;
-                stage_pos = a.causal ? a.q_pos0 + i : INT_MAX;
-                if (PASS == 1) {
-                    const long long ridx = ((long long)b * a.Hq + g * a.G + hl) * a.T + i;
-                    stage_lse = a.row_lse ? a.row_lse[ridx] * kLog2e : a.lse2[ridx];
-                }
-            }
-        }
+    // Two chunks of 32 query rows are on their way from global memory to LDS at any time (stages A and
+    // B).  Named scalars, not arrays or structs: the values are carried around the chunk loop and must
+    // stay in registers.
+    uint4 stA0 = make_uint4(0, 0, 0, 0), stA1 = stA0, stA2 = stA0, stA3 = stA0;
+    uint4 stB0 = stA0, stB1 = stA0, stB2 = stA0, stB3 = stA0;
+    int stA_pos = -1, stB_pos = -1;
+    float stA_lse = 0.f, stB_lse = 0.f;
+    auto chunk_src = [&](int c, int x) -> const uint4 * {
+        const int u = tid + 256 * x;
+        const int row = u / UPR, cu = u % UPR;
+        const int rho = min(c * 32 + row, GT - 1);            // padding rows repeat the last row; masked below
+        const int hl = div_t(rho), i = rho - hl * a.T;
+        return reinterpret_cast<const uint4 *>(
+            a.q + ((long long)b * a.qsb + (long long)i * a.qst + (long long)(g * a.G + hl) * a.qsh) * ES + 16 * cu);
     };
-    auto store_chunk = [&](int buf) {
-#pragma unroll
-        for (int x = 0; x < UPT; ++x) {
-            const int u = tid + 256 * x;
-            const int row = u / UPR, cu = u % UPR;
-            *reinterpret_cast<uint4 *>(&q_lds[buf][row * PITCH + 16 * cu]) = stage[x];
-        }
-        if (tid < 32) {
-            pos_lds[buf][tid] = stage_pos;
-            lse_lds[buf][tid] = stage_lse;
-        }
+    auto chunk_dst = [&](int buf, int x) -> uint4 * {
+        const int u = tid + 256 * x;
+        const int row = u / UPR, cu = u % UPR;
+        return reinterpret_cast<uint4 *>(&q_lds[buf][row * PITCH + 16 * cu]);
     };
-    // pass 0: fold the four waves' (max, sum) of chunk c and write the block's partial
-    auto flush_partial = [&](int c) {
+    auto row_meta = [&](int c, int &pos, float &lse) {
+        pos = -1;             // padding row: sees no key
+        lse = 0.f;
         if (tid < 32) {
             const int rho = c * 32 + tid;
             if (rho < GT) {
-                const int buf = c & 1;
-                float m = red_m[buf][0][tid];
-#pragma unroll
-                for (int w = 1; w < 4; ++w) m = fmaxf(m, red_m[buf][w][tid]);
-                const float ms = (m == -INFINITY) ? 0.f : m;
-                float l = 0.f;
-#pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const float mw = red_m[buf][w][tid];
-                    l += (mw == -INFINITY) ? 0.f : red_l[buf][w][tid] * __builtin_amdgcn_exp2f(mw - ms);
-                }
-                const int hl = rho / a.T, i = rho - hl * a.T;
-                const long long ridx = ((long long)b * a.Hq + g * a.G + hl) * a.T + i;
-                const long long rows = (long long)a.B * a.Hq * a.T;
-                a.part_m[kb * rows + ridx] = m;      // [key block][row]: coalesced here and in the fold
-                a.part_l[kb * rows + ridx] = l;
+                pos = a.causal ? a.q_pos0 + (rho - div_t(rho) * a.T) : INT_MAX;
+                if (PASS == 1) lse = a.row_lse ? a.row_lse[rowbase + rho] * kLog2e : a.lse2[rowbase + rho];
             }
         }
     };
+#define LVLM_STAGE_FUNCS(S)                                              \
+    auto load_##S = [&](int c) {                                         \
+        st##S##0 = *chunk_src(c, 0);                                     \
+        if constexpr (UPT > 1) st##S##1 = *chunk_src(c, 1);              \
+        if constexpr (UPT > 2) st##S##2 = *chunk_src(c, 2);              \
+        if constexpr (UPT > 3) st##S##3 = *chunk_src(c, 3);              \
+        row_meta(c, st##S##_pos, st##S##_lse);                           \
+    };                                                                   \
+    auto store_##S = [&](int buf) {                                      \
+        *chunk_dst(buf, 0) = st##S##0;                                   \
+        if constexpr (UPT > 1) *chunk_dst(buf, 1) = st##S##1;            \
+        if constexpr (UPT > 2) *chunk_dst(buf, 2) = st##S##2;            \
+        if constexpr (UPT > 3) *chunk_dst(buf, 3) = st##S##3;            \
+        if (tid < 32) {                                                  \
+            pos_lds[buf][tid] = st##S##_pos;                             \
+            lse_lds[buf][tid] = st##S##_lse;                             \
+        }                                                                \
+    };
+    LVLM_STAGE_FUNCS(A)
+    LVLM_STAGE_FUNCS(B)
+#undef LVLM_STAGE_FUNCS
 
     float colsum[KPW];
 #pragma unroll
     for (int s = 0; s < KPW; ++s) colsum[s] = 0.f;
 
-    load_chunk(0);
-    store_chunk(0);
-    __syncthreads();
-
-    for (int c = 0; c < n_chunks; ++c) {
-        const int buf = c & 1;
-        if (c + 1 < n_chunks) load_chunk(c + 1);
-        if (PASS == 0 && c > 0) flush_partial(c - 1);
-
+    auto compute = [&](int c, int buf) {
         HalfRow<DT, HD> qa;
         {
             const char *src = &q_lds[buf][l32 * PITCH + hf * (ROWB / 2)];
@@ -217,100 +201,179 @@ __global__ __launch_bounds__(256) void score_pass_kernel(ScoreArgs a) {
             else
                 mma_tile<DT, HD>(acc[s], qa, kf[s]);   // rows = queries, cols = keys
         }
+        // Is any element of this 32 x (KPW*32) block masked?  Uniform over the workgroup's wave:
+        // keys beyond the range, padding rows, or a key ahead of the earliest query position of the chunk.
+        const int rho0 = c * 32, rho1 = min(rho0 + 31, GT - 1);
+        const int h0 = div_t(rho0), h1 = div_t(rho1);
+        const int min_i = (h0 != h1) ? 0 : rho0 - h0 * a.T;
+        const bool masked = jbase + KPW * 32 > key_hi || rho0 + 32 > GT ||
+                            (a.causal && jbase + KPW * 32 - 1 > a.q_pos0 + min_i);
 
         if (PASS == 0) {
             // this lane: query l32 of the chunk, 16 keys per tile
-            const int pos = pos_lds[buf][l32];
-            float m = -INFINITY;
+            float m = -INFINITY, l = 0.f;
+            if (!masked) {
 #pragma unroll
-            for (int s = 0; s < KPW; ++s) {
+                for (int s = 0; s < KPW; ++s)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int j = jbase + 32 * s + acc_row(r, hf);
-                    float t = acc[s][r] * a.scale_log2;
-                    t = (j <= pos && j < key_hi) ? t : -INFINITY;
-                    acc[s][r] = t;
-                    m = fmaxf(m, t);
+                    for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[s][r]);
+                m = fmaxf(m, __shfl_xor(m, 32)) * a.scale_log2;      // scale >= 0 (checked on the host)
+#pragma unroll
+                for (int s = 0; s < KPW; ++s)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) l += __builtin_amdgcn_exp2f(fmaf(acc[s][r], a.scale_log2, -m));
+            } else {
+                const int pos = pos_lds[buf][l32];
+#pragma unroll
+                for (int s = 0; s < KPW; ++s) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int j = jbase + 32 * s + acc_row(r, hf);
+                        const float t = (j <= pos && j < key_hi) ? acc[s][r] * a.scale_log2 : -INFINITY;
+                        acc[s][r] = t;
+                        m = fmaxf(m, t);
+                    }
                 }
-            }
-            m = fmaxf(m, __shfl_xor(m, 32));
-            const float ms = (m == -INFINITY) ? 0.f : m;
-            float l = 0.f;
+                m = fmaxf(m, __shfl_xor(m, 32));
+                const float ms = (m == -INFINITY) ? 0.f : m;
 #pragma unroll
-            for (int s = 0; s < KPW; ++s) {
+                for (int s = 0; s < KPW; ++s)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) l += __builtin_amdgcn_exp2f(acc[s][r] - ms);   // exp2(-inf) = 0
+                    for (int r = 0; r < 16; ++r) l += __builtin_amdgcn_exp2f(acc[s][r] - ms);   // exp2(-inf) = 0
             }
             l += __shfl_xor(l, 32);
-            if (hf == 0) {
-                red_m[buf][wave][l32] = m;
-                red_l[buf][wave][l32] = l;
+            const int rho = rho0 + l32;
+            if (hf == 0 && rho < GT) {
+                const long long pidx = ((long long)kb * 4 + wave) * rows_total + rowbase + rho;
+                a.part_m[pidx] = m;
+                a.part_l[pidx] = l;
             }
         } else {
             // this lane: key l32 of each tile, 16 query rows of the chunk
 #pragma unroll
             for (int qd = 0; qd < 4; ++qd) {
-                const int4 pos4 = *reinterpret_cast<const int4 *>(&pos_lds[buf][8 * qd + 4 * hf]);
                 const float4 lse4 = *reinterpret_cast<const float4 *>(&lse_lds[buf][8 * qd + 4 * hf]);
-                const int pos[4] = {pos4.x, pos4.y, pos4.z, pos4.w};
                 const float lse[4] = {lse4.x, lse4.y, lse4.z, lse4.w};
+                if (!masked) {
 #pragma unroll
-                for (int s = 0; s < KPW; ++s) {
-                    const int j = jbase + 32 * s + l32;
+                    for (int s = 0; s < KPW; ++s)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(acc[s][4 * qd + e] * a.scale_log2 - lse[e]);
-                        colsum[s] += (j <= pos[e]) ? p : 0.f;
+                        for (int e = 0; e < 4; ++e)
+                            colsum[s] += __builtin_amdgcn_exp2f(fmaf(acc[s][4 * qd + e], a.scale_log2, -lse[e]));
+                } else {
+                    const int4 pos4 = *reinterpret_cast<const int4 *>(&pos_lds[buf][8 * qd + 4 * hf]);
+                    const int pos[4] = {pos4.x, pos4.y, pos4.z, pos4.w};
+#pragma unroll
+                    for (int s = 0; s < KPW; ++s) {
+                        const int j = jbase + 32 * s + l32;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float p = __builtin_amdgcn_exp2f(fmaf(acc[s][4 * qd + e], a.scale_log2, -lse[e]));
+                            colsum[s] += (j <= pos[e]) ? p : 0.f;
+                        }
                     }
                 }
             }
         }
+    };
 
-        if (c + 1 < n_chunks) store_chunk(buf ^ 1);
+    // Pipeline over the chunks k = 0 .. nc-1 of this workgroup: chunk k is loaded from global memory into
+    // a register stage two iterations before it is computed (even chunks in A, odd ones in B), copied
+    // into one of three LDS buffers one iteration before, and one barrier per chunk publishes the copy.
+    // Loads and copies past the last chunk harmlessly repeat it.
+    const int nc = c_hi - c_lo;
+    auto chunk_at = [&](int k) { return min(c_lo + k, c_hi - 1); };
+    load_A(chunk_at(0));
+    store_A(0);
+    load_B(chunk_at(1));
+    load_A(chunk_at(2));
+    __syncthreads();
+    for (int k = 0; k < nc; k += 2) {
+        store_B((k + 1) % NBUF);          // chunk k+1
+        load_B(chunk_at(k + 3));
+        compute(c_lo + k, k % NBUF);
+        __syncthreads();
+        if (k + 1 >= nc) break;
+        store_A((k + 2) % NBUF);          // chunk k+2
+        load_A(chunk_at(k + 4));
+        compute(c_lo + k + 1, (k + 1) % NBUF);
         __syncthreads();
     }
 
-    if (PASS == 0) {
-        flush_partial(n_chunks - 1);
-    } else {
-        const float inv_g = 1.0f / (float)a.G;
+    if (PASS == 1) {
 #pragma unroll
         for (int s = 0; s < KPW; ++s) {
             const float tot = colsum[s] + __shfl_xor(colsum[s], 32);
             const int j = jbase + 32 * s + l32;
             if (hf == 0 && j < key_hi)
-                a.score_head[(long long)b * a.shb + (long long)g * a.shh + (j - a.img_begin)] = tot * inv_g;
+                a.colpart[(((long long)rs * a.B + b) * a.Hkv + g) * a.n_img + (j - a.img_begin)] = tot;
         }
     }
 }
 
-// Fold the per-block (max, sum) pairs of each row into a log2-domain LSE (online, in block order).
+// Fold the per-block, per-wave (max, sum) pairs of each row into a log2-domain LSE.  Eight lanes share a
+// row: each folds every eighth pair online, then the eight partial (max, sum) states are merged.
 __global__ __launch_bounds__(256) void score_lse_kernel(const float *part_m, const float *part_l, float *lse2,
-                                                        int rows, int nkb) {
-    const int row = blockIdx.x * 256 + threadIdx.x;
-    if (row >= rows) return;
+                                                        int rows, int nparts) {
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const int row = t >> 3, sub = t & 7;
     float m = -INFINITY, l = 0.f;
-#pragma unroll 8
-    for (int i = 0; i < nkb; ++i) {
-        const float mi = part_m[(long long)i * rows + row];
-        const float li = part_l[(long long)i * rows + row];
-        const float mn = fmaxf(m, mi);
+    if (row < rows) {
+#pragma unroll 4
+        for (int i = sub; i < nparts; i += 8) {
+            const float mi = part_m[(long long)i * rows + row];
+            const float li = part_l[(long long)i * rows + row];
+            const float mn = fmaxf(m, mi);
+            const float ms = (mn == -INFINITY) ? 0.f : mn;
+            l = l * exp2f(m - ms) + li * exp2f(mi - ms);      // exp2(-inf) = 0 covers empty blocks
+            m = mn;
+        }
+    }
+#pragma unroll
+    for (int o = 1; o < 8; o <<= 1) {
+        const float mo = __shfl_xor(m, o), lo = __shfl_xor(l, o);
+        const float mn = fmaxf(m, mo);
         const float ms = (mn == -INFINITY) ? 0.f : mn;
-        l = l * exp2f(m - ms) + li * exp2f(mi - ms);      // exp2(-inf) = 0 covers empty blocks
+        l = l * exp2f(m - ms) + lo * exp2f(mo - ms);
         m = mn;
     }
-    lse2[row] = (l > 0.f) ? m + log2f(l) : INFINITY;   // a row that sees no key contributes nothing
+    if (row < rows && sub == 0) lse2[row] = (l > 0.f) ? m + log2f(l) : INFINITY;   // no visible key: contributes nothing
 }
 
-// score_mean[b][j] = mean over KV heads, summed in head order.
-__global__ __launch_bounds__(256) void score_mean_kernel(const float *score_head, float *score_mean, int Hkv,
-                                                         int n_img, long long shb, long long shh) {
+// score_head[b][g][j] = (sum over row splits of the column sums) / G;  score_mean[b][j] = mean over g.
+// Four heads x up to eight splits are loaded together so that the loads overlap.
+constexpr int kMaxRowSplit = 8;
+
+__global__ __launch_bounds__(256) void score_finalize_kernel(ScoreArgs a) {
     const int j = blockIdx.x * 256 + threadIdx.x;
     const int b = blockIdx.y;
-    if (j >= n_img) return;
-    float s = 0.f;
-    for (int g = 0; g < Hkv; ++g) s += score_head[(long long)b * shb + (long long)g * shh + j];
-    score_mean[(long long)b * n_img + j] = s / (float)Hkv;
+    if (j >= a.n_img) return;
+    const float inv_g = 1.0f / (float)a.G;
+    const long long split_stride = (long long)a.B * a.Hkv * a.n_img;
+    float mean = 0.f;
+    for (int g0 = 0; g0 < a.Hkv; g0 += 4) {
+        float v[4][kMaxRowSplit];
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg)
+#pragma unroll
+            for (int r = 0; r < kMaxRowSplit; ++r) {
+                const bool on = g0 + gg < a.Hkv && r < a.rs;
+                const int gc = min(g0 + gg, a.Hkv - 1), rc = min(r, a.rs - 1);
+                const float x = a.colpart[rc * split_stride + ((long long)b * a.Hkv + gc) * a.n_img + j];
+                v[gg][r] = on ? x : 0.f;
+            }
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+            if (g0 + gg >= a.Hkv) break;
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < kMaxRowSplit; ++r) s += v[gg][r];
+            s *= inv_g;
+            a.score_head[(long long)b * a.shb + (long long)(g0 + gg) * a.shh + j] = s;
+            mean += s;
+        }
+    }
+    a.score_mean[(long long)b * a.n_img + j] = mean / (float)a.Hkv;
 }
 
 template <int DT, int HD, int KPW>
@@ -318,23 +381,22 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse) {
     hipStream_t stream = prof.stream;
     constexpr int BN = 4 * KPW * 32;
     if (need_lse) {
-        dim3 grid0((a.N + BN - 1) / BN, a.Hkv, a.B);
+        dim3 grid0(((a.N + BN - 1) / BN) * a.rs, a.Hkv, a.B);
         prof.begin("score_pass0");
         hipLaunchKernelGGL((score_pass_kernel<DT, HD, KPW, 0>), grid0, dim3(256), 0, stream, a);
         prof.end();
         const int rows = a.B * a.Hq * a.T;
         prof.begin("score_lse");
-        hipLaunchKernelGGL(score_lse_kernel, dim3((rows + 255) / 256), dim3(256), 0, stream, a.part_m, a.part_l,
-                           a.lse2, rows, a.nkb);
+        hipLaunchKernelGGL(score_lse_kernel, dim3((rows * 8 + 255) / 256), dim3(256), 0, stream, a.part_m, a.part_l,
+                           a.lse2, rows, a.nkb * 4);
         prof.end();
     }
-    dim3 grid1((a.n_img + BN - 1) / BN, a.Hkv, a.B);
+    dim3 grid1(((a.n_img + BN - 1) / BN) * a.rs, a.Hkv, a.B);
     prof.begin("score_pass1");
     hipLaunchKernelGGL((score_pass_kernel<DT, HD, KPW, 1>), grid1, dim3(256), 0, stream, a);
     prof.end();
-    prof.begin("score_mean");
-    hipLaunchKernelGGL(score_mean_kernel, dim3((a.n_img + 255) / 256, a.B), dim3(256), 0, stream, a.score_head,
-                       a.score_mean, a.Hkv, a.n_img, a.shb, a.shh);
+    prof.begin("score_finalize");
+    hipLaunchKernelGGL(score_finalize_kernel, dim3((a.n_img + 255) / 256, a.B), dim3(256), 0, stream, a);
     prof.end();
 }
 
@@ -346,11 +408,21 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
     const long long wide = (long long)d.B * d.Hkv * ((d.N + 255) / 256);
     w.block_keys = (d.dtype == LVLM_BF16 && wide >= 512) ? 256 : 128;
     w.nkb = (d.N + w.block_keys - 1) / w.block_keys;
+    // Few workgroups: split the query chunks of a key block over several workgroups (>= 2 chunks each).
+    const int n_chunks = (d.Hq / d.Hkv * d.T + 31) / 32;
+    const long long wgs = (long long)d.B * d.Hkv * w.nkb;
+    int rs = (int)((512 + wgs - 1) / wgs);
+    if (rs > (n_chunks + 1) / 2) rs = (n_chunks + 1) / 2;
+    if (rs > 8) rs = 8;            // kMaxRowSplit of the finalize kernel
+    if (rs < 1) rs = 1;
+    w.cps = (n_chunks + rs - 1) / rs;
+    w.rs = (n_chunks + w.cps - 1) / w.cps;
     const size_t rows = (size_t)d.B * d.Hq * d.T;
     w.part_m = 0;
-    w.part_l = align_up(w.part_m + rows * w.nkb * sizeof(float), 256);
-    w.lse2 = align_up(w.part_l + rows * w.nkb * sizeof(float), 256);
-    w.total = align_up(w.lse2 + rows * sizeof(float), 256);
+    w.part_l = align_up(w.part_m + rows * w.nkb * 4 * sizeof(float), 256);
+    w.lse2 = align_up(w.part_l + rows * w.nkb * 4 * sizeof(float), 256);
+    w.colpart = align_up(w.lse2 + rows * sizeof(float), 256);
+    w.total = align_up(w.colpart + (size_t)w.rs * d.B * d.Hkv * d.n_img * sizeof(float), 256);
     return w;
 }
 
@@ -363,6 +435,10 @@ hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreW
     a.part_m = reinterpret_cast<float *>(ws + w.part_m);
     a.part_l = reinterpret_cast<float *>(ws + w.part_l);
     a.lse2 = reinterpret_cast<float *>(ws + w.lse2);
+    a.colpart = reinterpret_cast<float *>(ws + w.colpart);
+    a.rs = w.rs;
+    a.cps = w.cps;
+    a.t_magic = (unsigned)(0x100000000ull / (unsigned long long)d.T) + 1u;
     a.score_head = score_head;
     a.score_mean = score_mean;
     a.B = d.B; a.N = d.N; a.T = d.T; a.q_pos0 = d.q_pos0; a.Hq = d.Hq; a.Hkv = d.Hkv; a.G = d.Hq / d.Hkv;
