@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--profile-steps", type=int, default=3, help="eager steps timed per kernel with HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run three plain 256 MiB device copies (a reference of known traffic for rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -163,8 +165,7 @@ def run_decode(ctx, lv, w, states, reserve, step_pos=0):
                         reserve=reserve)
         if w.kv_budget > 0:
             ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_BUDGET, budget=w.kv_budget,
-                            n_recent=1, order=lv.ORDER_FILL, len_bound=bound, n_evicted=st.n_evicted,
-                            reserve=reserve)
+                            n_recent=1, order=lv.ORDER_FILL, len_bound=bound, want_evicted=False, reserve=reserve)
 
 
 # ----------------------------------------------------------------------------- algorithmic work per kernel
@@ -286,6 +287,13 @@ def main():
         prof = {k: {"launches_per_step": v[0] / args.profile_steps, "us_per_step": v[1] * 1e3 / args.profile_steps,
                     "avg_us": v[1] * 1e3 / max(v[0], 1)} for k, v in agg.items()}
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)           # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+
     work = kernel_work(w, layers, lens_after_prefill)
     kernels = {}
     for name, p in sorted(prof.items(), key=lambda kv: -kv[1]["us_per_step"]):
@@ -300,17 +308,24 @@ def main():
                 row.update(bound="mfma", achieved_TFLOPs=round(amt / p["us_per_step"] / 1e6, 1),
                            frac=round(amt / p["us_per_step"] / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4))
         kernels[name] = row
+    # HBM traffic per launch measured separately with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if recorded
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = {k: v.get("fetch_bytes", 0) + v.get("write_bytes", 0) for k, v in json.load(f)["kernels"].items()}
     roofline = None
     for name, row in kernels.items():           # dominant kernel = most time per step among the modelled ones
         if "bound" in row:
             amt, per_launch = work[name]["amount"], work[name]["launches"]
             if row["bound"] == "hbm":
                 roofline = {"kernel": name, "bound": "hbm", "achieved": row["achieved_GBs"], "peak": HBM_PEAK_GBS,
-                            "unit": "GB/s", "frac": row["frac"], "traffic": None,
+                            "unit": "GB/s", "frac": row["frac"], "traffic": traffic.get(name),
                             "algorithmic_bytes_per_launch": amt / per_launch, "avg_launch_us": row["avg_us"]}
             else:
                 roofline = {"kernel": name, "bound": "mfma", "achieved": row["achieved_TFLOPs"],
-                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": row["frac"], "traffic": None,
+                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": row["frac"],
+                            "traffic": traffic.get(name),
                             "algorithmic_flops_per_launch": amt / per_launch, "avg_launch_us": row["avg_us"]}
             break
 

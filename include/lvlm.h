@@ -241,7 +241,8 @@ typedef struct {
  * Survivors are then compacted in place in the chosen order, all five arrays
  * together, and len is updated.  n_evicted [B,Hkv] i32 (device, optional)
  * receives old len - new len.  Slots at or beyond the new len keep stale data.
- * A call that evicts nothing changes nothing.  Workspace: LVLM_OP_KV_COMPRESS. */
+ * A call that evicts nothing changes nothing; LVLM_KV_BUDGET with len_bound (or
+ * Lmax) <= budget and no n_evicted launches nothing.  Workspace: LVLM_OP_KV_COMPRESS. */
 LVLM_API lvlm_status lvlm_kv_compress(lvlm_ctx *ctx, void *stream, const lvlm_kv_desc *d,
                              void *k_cache, void *v_cache, float *score, uint8_t *kind,
                              int32_t *orig_pos, int32_t *len, int32_t *n_evicted);

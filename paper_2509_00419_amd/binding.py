@@ -246,12 +246,12 @@ class Context:
 
     # ---- step 5 ----
     def kv_compress(self, k_cache, v_cache, score, kind, orig_pos, length, *, mode, order=ORDER_STABLE,
-                    beta=0.995, budget=0, n_recent=0, len_bound=0, n_evicted=None, reserve=True):
-        """lvlm_kv_compress (in place).  Caches [B,Hkv,Lmax,d]; returns n_evicted [B,Hkv]."""
+                    beta=0.995, budget=0, n_recent=0, len_bound=0, n_evicted=None, reserve=True, want_evicted=True):
+        """lvlm_kv_compress (in place).  Caches [B,Hkv,Lmax,d]; returns n_evicted [B,Hkv] (None if not wanted)."""
         B, Hkv, Lmax, hd = k_cache.shape
         assert k_cache.is_contiguous() and v_cache.is_contiguous() and score.is_contiguous()
         d = KvDesc(_DTYPE[k_cache.dtype], B, Hkv, hd, Lmax, len_bound, mode, order, budget, n_recent, float(beta))
-        if n_evicted is None:
+        if n_evicted is None and want_evicted:
             n_evicted = torch.empty(B, Hkv, dtype=torch.int32, device=k_cache.device)
         if reserve:
             self.reserve(self.workspace_bytes(OP_KV_COMPRESS, d))

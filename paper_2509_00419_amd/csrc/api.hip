@@ -324,6 +324,10 @@ lvlm_status lvlm_kv_compress(lvlm_ctx *ctx, void *stream, const lvlm_kv_desc *d,
     if (!aligned16(k_cache) || !aligned16(v_cache) || !aligned16(score) || !aligned16(kind) || !aligned16(orig_pos) ||
         !aligned16(len) || !aligned16(n_evicted))
         return fail(ctx, LVLM_ERR_INVALID_ARG, "kv_compress: pointers must be 16-byte aligned");
+    // A budget no head can exceed (the host-known bound on every length is within it) evicts nothing:
+    // with no n_evicted to fill in there is nothing to launch.
+    const int bound = d->len_bound > 0 ? d->len_bound : d->Lmax;
+    if (d->mode == LVLM_KV_BUDGET && bound <= d->budget && n_evicted == nullptr) return LVLM_OK;
     const KvWs w = kv_ws(*d);
     if (lvlm_status st = need_ws(ctx, w.total)) return st;
     if (lvlm_status st = bind_device(ctx)) return st;

@@ -98,8 +98,13 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int kb = blockIdx.x / a.rs, rs = blockIdx.x % a.rs;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id, and grid.x is a multiple of 8, so
+    // blockIdx.x % 8 names the XCD (and its private L2).  The row splits of one key block are placed on
+    // the same XCD: they read the same keys.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int kb = (slot / a.rs) * 8 + xcd, rs = slot % a.rs;
     const int g = blockIdx.y, b = blockIdx.z;
+    if (kb * BN >= (PASS == 0 ? a.N : a.n_img)) return;      // padding of the key-block count to a multiple of 8
     const int GT = a.G * a.T;
     const int n_chunks = (GT + 31) >> 5;
     const int c_lo = rs * a.cps, c_hi = min(n_chunks, c_lo + a.cps);
@@ -381,7 +386,7 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse) {
     hipStream_t stream = prof.stream;
     constexpr int BN = 4 * KPW * 32;
     if (need_lse) {
-        dim3 grid0(((a.N + BN - 1) / BN) * a.rs, a.Hkv, a.B);
+        dim3 grid0(((a.N + BN - 1) / BN + 7) / 8 * 8 * a.rs, a.Hkv, a.B);
         prof.begin("score_pass0");
         hipLaunchKernelGGL((score_pass_kernel<DT, HD, KPW, 0>), grid0, dim3(256), 0, stream, a);
         prof.end();
@@ -391,7 +396,7 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse) {
                            a.lse2, rows, a.nkb * 4);
         prof.end();
     }
-    dim3 grid1(((a.n_img + BN - 1) / BN) * a.rs, a.Hkv, a.B);
+    dim3 grid1(((a.n_img + BN - 1) / BN + 7) / 8 * 8 * a.rs, a.Hkv, a.B);
     prof.begin("score_pass1");
     hipLaunchKernelGGL((score_pass_kernel<DT, HD, KPW, 1>), grid1, dim3(256), 0, stream, a);
     prof.end();

@@ -404,3 +404,78 @@ def test_config1_full_pipeline_stepwise(ctx):
         ref = O.kv_compress(*before, mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
         check_state(ref[:6])
         assert int(state[5].min()) == w.kv_budget and int(state[5].max()) == w.kv_budget
+
+
+# --------------------------------------------------------------------------- full-size cases of configs 3-5
+def test_score_config5_full_size(ctx):
+    # T=128, N=16512, 48/8 heads: 24 row chunks per key block, 256-key blocks, the largest score launch
+    w = configs.CFG5
+    q = _rand((1, w.n_text, w.n_q_heads, w.head_dim), torch.bfloat16, 80)
+    k = _rand((1, w.seq_len, w.n_kv_heads, w.head_dim), torch.bfloat16, 81)
+    kw = dict(q_pos0=w.n_sys + w.n_img, img_begin=w.n_sys, n_img=w.n_img)
+    sh, sm = ctx.score_tokens(q.to(DEV), k.to(DEV), **kw)
+    osh, osm = O.score_tokens(f64(q), f64(k), **kw)
+    assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
+
+
+def test_merge_compact_config5_first_stage(ctx):
+    # 16384 -> 5091 image tokens of 6144 channels (two rank tiles, 11294 merged rows)
+    w = configs.CFG5
+    n_keep = lv.schedule(w.n_img, 0.03, 3)[0]
+    assert n_keep == 5091
+    _merge_case(ctx, torch.bfloat16, 1, w.n_sys, w.n_img, w.n_text, w.hidden, n_keep, extra_planes=False, seed=82)
+
+
+def test_merge_compact_config3_first_stage(ctx):
+    w = configs.CFG3
+    n_keep = lv.schedule(w.n_img, 0.35, 3)[0]
+    assert n_keep == 1263
+    _merge_case(ctx, torch.bfloat16, w.batch, w.n_sys, w.n_img, w.n_text, w.hidden, n_keep, seed=83)
+
+
+def test_config4_decode_steps_stepwise(ctx):
+    """Config 4 shape (B=16, 28/4 heads, budget 1024): 6 decode steps with eviction every step, each GPU
+    call checked against the oracle applied to the GPU state just before it."""
+    w = configs.CFG4
+    B, H, d = w.batch, w.n_kv_heads, w.head_dim
+    host = _cache(torch.bfloat16, B, H, w.kv_budget + 8, d, [w.kv_budget] * (B * H), 84, protected=256, image_only=True)
+    state = [t.to(DEV) for t in host]
+    stream = synth.DecodeStream(w)
+
+    def snapshot():
+        s = [t.cpu() for t in state]
+        return [f64(s[0]), f64(s[1]), s[2].numpy(), s[3].numpy(), s[4].numpy(), s[5].numpy()]
+
+    for t in range(6):
+        qt, kt, vt = stream.next()
+        before = snapshot()
+        out = ctx.decode_attn(qt.to(DEV), kt.to(DEV), vt.to(DEV), *state, score_decay=0.9, new_pos=1024 + t,
+                              len_bound=w.kv_budget + 1)
+        ref = O.decode_attn(f64(qt), f64(kt), f64(vt), *before, score_decay=0.9, new_pos=1024 + t, out_dtype="bf16")
+        assert rel_err(f64(out.cpu()), ref[0]) < 2e-2, t
+        now = snapshot()
+        assert np.array_equal(now[5], ref[6])
+        assert rel_err(now[2][:, :, :w.kv_budget + 1], ref[3][:, :, :w.kv_budget + 1]) < 1e-5
+        before = now
+        ctx.kv_compress(*state, mode=lv.KV_BUDGET, budget=w.kv_budget, n_recent=1, order=lv.ORDER_FILL,
+                        len_bound=w.kv_budget + 1)
+        ref = O.kv_compress(*before, mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
+        now = snapshot()
+        assert np.array_equal(now[5], ref[5]) and int(now[5].min()) == w.kv_budget
+        n = w.kv_budget
+        for i in (0, 1, 2, 3, 4):
+            assert np.array_equal(now[i][:, :, :n], ref[i][:, :, :n]), (t, i)
+
+
+def test_degenerate_sizes(ctx):
+    # one image token, one query row, one key; a cache with a single entry; nothing to keep but the merged slot
+    q, k = _rand((1, 1, 2, 64), torch.float32, 90), _rand((1, 1, 2, 64), torch.float32, 91)
+    sh, sm = ctx.score_tokens(q.to(DEV), k.to(DEV), q_pos0=0, img_begin=0, n_img=1)
+    assert torch.allclose(sh.cpu(), torch.ones(1, 2, 1)) and torch.allclose(sm.cpu(), torch.ones(1, 1))
+    _merge_case(ctx, torch.float32, 1, 0, 1, 0, 4, 1, extra_planes=False, seed=92)       # n_img = n_keep = 1
+    _merge_case(ctx, torch.float32, 1, 0, 2, 0, 4, 1, extra_planes=False, seed=93)       # two tokens into one
+    _merge_case(ctx, torch.bfloat16, 2, 1, 3, 1, 8, 2, seed=94)
+    _attn_case(ctx, torch.bfloat16, 1, 2, 2, 128, 4, [0, 0], 95)                          # empty caches + append
+    _attn_case(ctx, torch.bfloat16, 1, 2, 2, 128, 4, [1, 3], 96, append=False)
+    _kv_case(ctx, torch.bfloat16, 1, 2, 8, 128, [0, 1], 97, mode=lv.KV_THRESHOLD, beta=0.5)
+    _kv_case(ctx, torch.bfloat16, 1, 2, 8, 128, [8, 1], 98, mode=lv.KV_BUDGET, budget=1, n_recent=0, order=lv.ORDER_FILL)
