@@ -286,17 +286,16 @@ def merge_compact(planes, score_mean, *, img_begin: int, n_img: int, n_keep: int
 # --------------------------------------------------------------------------
 
 
-def merge_similarity(hidden, size, score, n_keep: int, dtype: str = "f32"):
-    """One row's similarity merge.  hidden [n, C], size [n], score [n].
+def similarity_assign(hidden, score, n_keep: int):
+    """Dominant set and nearest-dominant assignment of one row of tokens.
 
-    Dominant = the n_keep highest-scoring tokens.  Every other token goes to
-    the dominant token with the largest cosine similarity (ties: lower index);
-    each dominant token becomes the size-weighted mean of itself and the
-    tokens assigned to it, and sizes add.  Output in ascending original index.
-    Returns (rows [n_keep, C], new_size [n_keep], dom_idx [n_keep], assign [n-n_keep]).
+    hidden [n, C], score [n].  Dominant = the n_keep highest-scoring tokens, listed in ascending index
+    (position p = 0..n_keep-1).  Every other token is assigned to the dominant token with the largest
+    cosine similarity (ties: lower position).  Returns (dom_idx [n_keep], assign [n] = position of the
+    dominant token each token ends up in (its own position for a dominant token), cos [n-n_keep, n_keep],
+    rest_idx [n-n_keep] ascending).
     """
     hidden = np.asarray(hidden, dtype=np.float64)
-    size = np.asarray(size, dtype=np.float64)
     n = hidden.shape[0]
     order = order_desc(score)
     dom = np.sort(order[:n_keep])
@@ -304,15 +303,79 @@ def merge_similarity(hidden, size, score, n_keep: int, dtype: str = "f32"):
     norm = np.sqrt((hidden * hidden).sum(axis=1))
     norm = np.where(norm > 0, norm, 1.0)
     unit = hidden / norm[:, None]
-    cos = unit[rest] @ unit[dom].T                                  # [n-n_keep, n_keep]
-    assign = np.argmax(cos, axis=1) if rest.size else np.zeros(0, dtype=np.int64)
-    acc = hidden[dom] * size[dom, None]
-    tot = size[dom].copy()
-    for t, a in zip(rest, assign):
-        acc[a] += size[t] * hidden[t]
-        tot[a] += size[t]
+    cos = unit[rest] @ unit[dom].T
+    assign = np.zeros(n, dtype=np.int32)
+    assign[dom] = np.arange(n_keep)
+    if rest.size:
+        assign[rest] = np.argmax(cos, axis=1)          # first maximum = lower position on ties
+    return dom.astype(np.int32), assign, cos, rest.astype(np.int32)
+
+
+def merge_similarity(hidden, size, score, n_keep: int, dtype: str = "f32"):
+    """One row's similarity merge.  hidden [n, C], size [n], score [n].
+
+    Each dominant token becomes the size-weighted mean of itself and the tokens assigned to it
+    (similarity_assign), and sizes add.  Output in ascending original index.
+    Returns (rows [n_keep, C], new_size [n_keep], dom_idx [n_keep], assign of the non-dominant tokens).
+    """
+    hidden = np.asarray(hidden, dtype=np.float64)
+    size = np.asarray(size, dtype=np.float64)
+    dom, assign, _, rest = similarity_assign(hidden, score, n_keep)
+    acc = np.zeros((n_keep, hidden.shape[1]), dtype=np.float64)
+    tot = np.zeros(n_keep, dtype=np.float64)
+    for t in range(hidden.shape[0]):                    # ascending token order
+        acc[assign[t]] += size[t] * hidden[t]
+        tot[assign[t]] += size[t]
     rows = round_out(acc / tot[:, None], dtype)
-    return rows, tot.astype(np.float32), dom.astype(np.int32), assign.astype(np.int32)
+    return rows, tot.astype(np.float32), dom, assign[rest]
+
+
+def merge_similar(planes, score_mean, *, img_begin: int, n_img: int, n_keep: int, size=None, rules=None,
+                  dtypes=None, assign=None):
+    """Similarity merge of a batch, every plane (this build's definition, not the paper's).
+
+    planes[0] is the plane the similarity is measured on.  Output row order: rows before the image
+    span, the n_keep dominant tokens in ascending original index (each replaced by its cluster's
+    size-weighted mean on RULE_WEIGHTED planes, kept as is on RULE_TOP planes), rows after the span.
+    size [B, n_img] (default all ones).  `assign` [B, n_img] overrides the nearest-dominant choice
+    (used to check merged values under a given assignment).  n_keep == n_img changes nothing.
+    Returns (out_planes, keep_idx [B,n_keep], assign [B,n_img], new_size [B,n_keep]).
+    """
+    score_mean = np.asarray(score_mean)
+    B = score_mean.shape[0]
+    r = n_img - n_keep
+    rules = rules or [RULE_WEIGHTED] * len(planes)
+    dtypes = dtypes or ["f32"] * len(planes)
+    size = np.ones((B, n_img)) if size is None else np.asarray(size, dtype=np.float64)
+    keep_idx = np.zeros((B, n_keep), dtype=np.int32)
+    assign_out = np.zeros((B, n_img), dtype=np.int32)
+    new_size = np.zeros((B, n_keep), dtype=np.float64)
+    base = np.asarray(planes[0])
+    for b in range(B):
+        dom, a, _, _ = similarity_assign(base[b, img_begin:img_begin + n_img], score_mean[b], n_keep)
+        if assign is not None:
+            a = np.asarray(assign[b])
+        keep_idx[b], assign_out[b] = dom, a
+        np.add.at(new_size[b], a, size[b])
+    outs = []
+    for plane, rule, dt in zip(planes, rules, dtypes):
+        plane = np.asarray(plane)
+        N, C = plane.shape[1], plane.shape[2]
+        out = np.zeros((B, N - r, C), dtype=plane.dtype)
+        for b in range(B):
+            img = plane[b, img_begin:img_begin + n_img]
+            out[b, :img_begin] = plane[b, :img_begin]
+            out[b, img_begin + n_keep:] = plane[b, img_begin + n_img:]
+            if rule == RULE_WEIGHTED and r > 0:
+                acc = np.zeros((n_keep, C), dtype=np.float64)
+                for t in range(n_img):
+                    acc[assign_out[b, t]] += size[b, t] * img[t].astype(np.float64)
+                tot = np.where(new_size[b] > 0, new_size[b], 1.0)      # an empty cluster (imposed assignment only)
+                out[b, img_begin:img_begin + n_keep] = round_out(acc / tot[:, None], dt).astype(plane.dtype)
+            else:
+                out[b, img_begin:img_begin + n_keep] = img[keep_idx[b]]
+        outs.append(out)
+    return outs, keep_idx, assign_out, new_size.astype(np.float32)
 
 
 # --------------------------------------------------------------------------

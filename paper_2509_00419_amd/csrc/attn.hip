@@ -18,12 +18,11 @@
 //       logits into normalised probabilities for the importance update and
 //       publishes the new length.
 #include "common.h"
+#include "mma.h"
 
 namespace lvlm {
 namespace {
 
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 struct AttnArgs {
     const char *q;
@@ -44,37 +43,6 @@ struct AttnArgs {
     float scale_log2, decay;
 };
 
-template <int DT>
-__host__ __device__ constexpr int esize() {
-    return DT == LVLM_BF16 ? 2 : 4;
-}
-
-template <int DT, int HD>
-struct HalfRow {
-    static constexpr int NV = (HD / 2) * esize<DT>() / 16;
-    uint4 v[NV];
-};
-
-template <int DT, int HD>
-__device__ __forceinline__ void mma_tile(f32x16 &acc, const HalfRow<DT, HD> &a, const HalfRow<DT, HD> &b) {
-    constexpr int NV = HalfRow<DT, HD>::NV;
-    if constexpr (DT == LVLM_BF16) {
-#pragma unroll
-        for (int i = 0; i < NV; ++i)
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a.v[i]),
-                                                          __builtin_bit_cast(bf16x8, b.v[i]), acc, 0, 0, 0);
-    } else {
-#pragma unroll
-        for (int i = 0; i < NV; ++i) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.v[i].x), __uint_as_float(b.v[i].x), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.v[i].y), __uint_as_float(b.v[i].y), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.v[i].z), __uint_as_float(b.v[i].z), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.v[i].w), __uint_as_float(b.v[i].w), acc, 0, 0, 0);
-        }
-    }
-}
-
-__device__ __forceinline__ int acc_row(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
 
 // One operand fragment of the P.V product: 8 probabilities as bf16 (round-to-nearest-even).
 __device__ __forceinline__ bf16x8 pack_bf16x8(const float *p) {
@@ -328,7 +296,6 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     }
 }
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // bf16 variant on 16x16x32 MFMA tiles: a group has at most 8 query heads, so a 16-wide head axis wastes
 // half as much as a 32-wide one, and the accumulators (32 + 8 registers) leave room for three waves per

@@ -73,6 +73,7 @@ struct Prof {
 };
 
 // ---- launches (defined in the .hip files; all asynchronous on `stream`) ----
+void launch_rank(hipStream_t stream, const float *score, int32_t *rank, int n, int B);
 hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreWs &w, char *ws,
                         const void *q, const void *k, const float *row_lse, float *score_head,
                         float *score_mean);

@@ -19,6 +19,7 @@
 //   finalize_kernel  adds the partial sums in chunk order, rounds once and
 //                    writes P_new behind P_unmerged.
 #include "common.h"
+#include "planes.h"
 
 namespace lvlm {
 namespace {
@@ -188,20 +189,6 @@ __global__ __launch_bounds__(1024) void index_kernel(IndexArgs a) {
 
 // ---- gather -----------------------------------------------------------------
 
-struct PlaneDev {
-    const char *src;
-    char *dst;
-    long long src_stride_b, dst_stride_b;   // bytes
-    int row_bytes;
-    int row_elems;
-    int dtype;
-    int rule;
-    int unit_bytes;   // 16, 4 or 2
-    int tpr_log2;     // threads per row (power of two, <= 256)
-    int col_blocks;   // blocks of 256 units across a row
-    int n_sub;        // row sub-chunks (partial sums) of this plane
-};
-
 struct GatherArgs {
     PlaneDev plane[LVLM_MAX_PLANES];
     const int32_t *dst_of;   // null: identity (nothing removed)
@@ -210,45 +197,6 @@ struct GatherArgs {
     int B, N, img_begin, n_img, n_keep, n_planes;
     int rows_per_sub, n_sub_max, max_row_elems;
 };
-
-template <int UB>
-struct Unit;
-template <>
-struct Unit<16> { using type = uint4; };
-template <>
-struct Unit<4> { using type = uint32_t; };
-template <>
-struct Unit<2> { using type = uint16_t; };
-
-template <int DT, int UB>
-struct Acc {
-    static constexpr int NE = UB / (DT == LVLM_BF16 ? 2 : 4);
-    float v[NE > 0 ? NE : 1];
-};
-
-template <int DT, int UB>
-__device__ __forceinline__ void accumulate(Acc<DT, UB> &acc, const typename Unit<UB>::type &u, float w) {
-    if constexpr (DT == LVLM_BF16 && UB == 16) {
-        const uint32_t d[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            acc.v[2 * i] = fmaf(w, __uint_as_float(d[i] << 16), acc.v[2 * i]);
-            acc.v[2 * i + 1] = fmaf(w, __uint_as_float(d[i] & 0xffff0000u), acc.v[2 * i + 1]);
-        }
-    } else if constexpr (DT == LVLM_BF16 && UB == 4) {
-        acc.v[0] = fmaf(w, __uint_as_float(u << 16), acc.v[0]);
-        acc.v[1] = fmaf(w, __uint_as_float(u & 0xffff0000u), acc.v[1]);
-    } else if constexpr (DT == LVLM_BF16 && UB == 2) {
-        acc.v[0] = fmaf(w, bf16_to_f32(u), acc.v[0]);
-    } else if constexpr (DT == LVLM_F32 && UB == 16) {
-        acc.v[0] = fmaf(w, __uint_as_float(u.x), acc.v[0]);
-        acc.v[1] = fmaf(w, __uint_as_float(u.y), acc.v[1]);
-        acc.v[2] = fmaf(w, __uint_as_float(u.z), acc.v[2]);
-        acc.v[3] = fmaf(w, __uint_as_float(u.w), acc.v[3]);
-    } else if constexpr (DT == LVLM_F32 && UB == 4) {
-        acc.v[0] = fmaf(w, __uint_as_float(u), acc.v[0]);
-    }
-}
 
 // One thread group walks `rows_per_sub` consecutive source rows of one plane, one unit column per thread.
 // The loop is free of data-dependent branches before its stores: row data, destination code and weight
@@ -380,9 +328,15 @@ __global__ __launch_bounds__(256) void finalize_kernel(GatherArgs a) {
     }
 }
 
-int elem_bytes(int dtype) { return dtype == LVLM_BF16 ? 2 : 4; }
-
 }  // namespace
+
+void launch_rank(hipStream_t stream, const float *score, int32_t *rank, int n, int B) {
+    RankArgs ra{};
+    ra.score = score;
+    ra.rank = rank;
+    ra.n = n;
+    hipLaunchKernelGGL(rank_kernel, dim3((n + kRankBlock - 1) / kRankBlock, B), dim3(1024), 0, stream, ra);
+}
 
 MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes) {
     MergeWs w{};
@@ -428,24 +382,9 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
     bool any_weighted = false;
     for (int i = 0; i < d.n_planes; ++i) {
         PlaneDev &p = g.plane[i];
-        const int es = elem_bytes(planes[i].dtype);
-        p.src = static_cast<const char *>(planes[i].src);
-        p.dst = static_cast<char *>(planes[i].dst);
-        p.src_stride_b = planes[i].src_stride_b * es;
-        p.dst_stride_b = planes[i].dst_stride_b * es;
-        p.row_elems = planes[i].row_elems;
-        p.row_bytes = planes[i].row_elems * es;
-        p.dtype = planes[i].dtype;
-        p.rule = planes[i].merge_rule;
-        const bool vec = p.row_bytes % 16 == 0 && p.src_stride_b % 16 == 0 && p.dst_stride_b % 16 == 0;
-        p.unit_bytes = vec ? 16 : (p.row_bytes % 4 == 0 && p.src_stride_b % 4 == 0 && p.dst_stride_b % 4 == 0 ? 4 : 2);
-        const int row_units = p.row_bytes / p.unit_bytes;
-        int tl = 0;
-        while ((1 << tl) < row_units && tl < 8) ++tl;
-        p.tpr_log2 = tl;
-        p.col_blocks = (row_units + 255) / 256;
+        p = make_plane_dev(planes[i]);
         p.n_sub = w.n_chunk;
-        const int groups = 256 >> tl;
+        const int groups = 256 >> p.tpr_log2;
         const int gx = (p.n_sub + groups - 1) / groups;
         if (gx > grid_x) grid_x = gx;
         if (p.col_blocks > grid_y) grid_y = p.col_blocks;
@@ -453,15 +392,12 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
     }
 
     if (r > 0) {
-        RankArgs ra{};
-        ra.score = score_mean;
-        ra.rank = reinterpret_cast<int32_t *>(ws + w.rank_part);
-        ra.n = d.n_img;
+        int32_t *rank = reinterpret_cast<int32_t *>(ws + w.rank_part);
         prof.begin("merge_rank");
-        hipLaunchKernelGGL(rank_kernel, dim3((d.n_img + kRankBlock - 1) / kRankBlock, d.B), dim3(1024), 0, stream, ra);
+        launch_rank(stream, score_mean, rank, d.n_img, d.B);
         prof.end();
         IndexArgs ia{};
-        ia.rank = ra.rank;
+        ia.rank = rank;
         ia.dst_of = reinterpret_cast<int32_t *>(ws + w.dst_of);
         ia.wgt = reinterpret_cast<float *>(ws + w.wgt);
         ia.w = wtab;

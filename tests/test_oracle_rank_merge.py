@@ -202,6 +202,41 @@ def test_similarity_merge_conserves_mass_and_assigns_nearest():
         assert int(np.argmax(cos)) == a
 
 
+def test_merge_similar_batch_planes_and_identity():
+    rng = np.random.default_rng(6)
+    B, n_sys, n_img, n_txt, C, n_keep = 2, 2, 24, 3, 5, 6
+    N = n_sys + n_img + n_txt
+    hid = rng.standard_normal((B, N, C))
+    ids = np.arange(B * N, dtype=np.int32).reshape(B, N, 1)
+    score = rng.random((B, n_img)).astype(np.float32)
+    size = rng.integers(1, 4, (B, n_img)).astype(np.float64)
+    (out, oid), keep, assign, new_size = O.merge_similar([hid, ids], score, img_begin=n_sys, n_img=n_img,
+                                                         n_keep=n_keep, size=size, rules=[O.RULE_WEIGHTED, O.RULE_TOP])
+    assert out.shape == (B, N - (n_img - n_keep), C)
+    assert np.array_equal(out[:, :n_sys], hid[:, :n_sys]) and np.array_equal(out[:, n_sys + n_keep:], hid[:, n_sys + n_img:])
+    for b in range(B):
+        img = hid[b, n_sys:n_sys + n_img]
+        rows, ns, dom, a_rest = O.merge_similarity(img, size[b], score[b], n_keep)       # the one-row form agrees
+        np.testing.assert_allclose(out[b, n_sys:n_sys + n_keep], rows, rtol=1e-6)
+        assert np.array_equal(keep[b], dom) and np.allclose(new_size[b], ns)
+        assert list(keep[b]) == sorted(np.argsort(-score[b], kind="stable")[:n_keep])     # dominant = top scores
+        assert all(assign[b, keep[b][p]] == p for p in range(n_keep))
+        # size-weighted mass is conserved per channel, and sizes add up
+        np.testing.assert_allclose((out[b, n_sys:n_sys + n_keep] * new_size[b][:, None]).sum(0),
+                                   (img * size[b][:, None]).sum(0), rtol=1e-5, atol=1e-6)
+        assert abs(new_size[b].sum() - size[b].sum()) < 1e-6
+        assert np.array_equal(oid[b, n_sys:n_sys + n_keep, 0], ids[b, n_sys + keep[b], 0])  # ids of the dominant tokens
+    # an imposed assignment is honoured
+    forced = np.zeros((B, n_img), dtype=np.int32)
+    (out2, _), _, a2, ns2 = O.merge_similar([hid, ids], score, img_begin=n_sys, n_img=n_img, n_keep=n_keep,
+                                            assign=forced, rules=[O.RULE_WEIGHTED, O.RULE_TOP])
+    np.testing.assert_allclose(out2[:, n_sys], hid[:, n_sys:n_sys + n_img].mean(axis=1), rtol=1e-6)
+    assert (ns2[:, 0] == n_img).all() and (ns2[:, 1:] == 0).all()
+    # n_keep == n_img: nothing changes
+    (out3, _), keep3, _, ns3 = O.merge_similar([hid, ids], score, img_begin=n_sys, n_img=n_img, n_keep=n_img)
+    assert np.array_equal(out3, hid) and (ns3 == 1).all() and list(keep3[0]) == list(range(n_img))
+
+
 # ---------------------------------------------------------------- schedule
 def test_schedule_golden_and_properties():
     with open(os.path.join(GOLDEN, "paper_constants.json")) as f:
