@@ -51,7 +51,8 @@ typedef enum {
     LVLM_OP_SCORE = 0,
     LVLM_OP_MERGE = 1,
     LVLM_OP_KV_COMPRESS = 2,
-    LVLM_OP_DECODE_ATTN = 3
+    LVLM_OP_DECODE_ATTN = 3,
+    LVLM_OP_MERGE_SIMILAR = 4
 } lvlm_op;
 
 /* Rank -> weight tables for the merged token (Sec. 3.2.1, par. 4). */
@@ -92,7 +93,7 @@ LVLM_API lvlm_status lvlm_destroy(lvlm_ctx *ctx);
 LVLM_API const char *lvlm_last_error(const lvlm_ctx *ctx);
 
 /* Bytes of scratch the given call needs.  `desc` points to the lvlm_*_desc of
- * that op; for LVLM_OP_MERGE it points to an lvlm_merge_query (descriptor plus
+ * that op; for LVLM_OP_MERGE / LVLM_OP_MERGE_SIMILAR to an lvlm_merge_query (descriptor plus
  * plane table: only row_elems and dtype of each plane are read).  Pure host
  * arithmetic; the size never depends on pointer values or on n_keep. */
 LVLM_API lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const void *desc, size_t *bytes);
@@ -204,6 +205,31 @@ LVLM_API lvlm_status lvlm_merge_compact(lvlm_ctx *ctx, void *stream, const lvlm_
                                const float *score_mean, const float *w,
                                const lvlm_plane *planes,
                                int32_t *keep_idx, int32_t *merged_idx);
+
+/* ---- step 3b: similarity merge -------------------------------------------- */
+
+/* A merge by similarity instead of by rank weights.  This variant is named by the
+ * task this library was built for, not by the paper (whose Sec. 3.2.1 deliberately
+ * avoids clustering); its definition is this library's:
+ *   dominant tokens = the n_keep highest-scoring image tokens (order as in
+ *   lvlm_merge_compact); every other image token is assigned to the dominant token
+ *   with the largest cosine similarity between their rows of planes[0] (bf16 / fp32
+ *   plane whose row is a multiple of 64 bytes; ties: lower dominant position; the
+ *   dot products run in the plane's dtype on the matrix cores with fp32
+ *   accumulation); on LVLM_RULE_WEIGHTED planes each dominant token becomes
+ *   sum(size * row) / sum(size) over itself and its assigned tokens (fp32, members in
+ *   ascending index), on LVLM_RULE_TOP planes it keeps its own row.
+ * Every plane is rewritten as [rows before the span | the n_keep dominant tokens in
+ * ascending original index | rows after the span]; dst has N - (n_img - n_keep) rows.
+ * size_in  [B, n_img] fp32 or NULL (all ones); size_out [B, n_keep] fp32 or NULL.
+ * keep_idx [B, n_keep] i32: dominant tokens, ascending.  assign [B, n_img] i32: for
+ * every token the position (0..n_keep-1) of the dominant token it ends up in.  Either
+ * may be NULL.  n_keep == n_img copies every plane unchanged.
+ * Workspace: LVLM_OP_MERGE_SIMILAR (queried with an lvlm_merge_query). */
+LVLM_API lvlm_status lvlm_merge_similar(lvlm_ctx *ctx, void *stream, const lvlm_merge_desc *d,
+                                        const float *score_mean, const lvlm_plane *planes,
+                                        const float *size_in, float *size_out,
+                                        int32_t *keep_idx, int32_t *assign);
 
 /* ---- step 5: KV-cache compression ---------------------------------------- */
 

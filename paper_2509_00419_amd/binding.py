@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "liblvlm.so")
 
 # ---- enums (include/lvlm.h) ----
 BF16, F32, I32 = 0, 1, 2
-OP_SCORE, OP_MERGE, OP_KV_COMPRESS, OP_DECODE_ATTN = 0, 1, 2, 3
+OP_SCORE, OP_MERGE, OP_KV_COMPRESS, OP_DECODE_ATTN, OP_MERGE_SIMILAR = 0, 1, 2, 3, 4
 MERGE_LINEAR_RANK, MERGE_PAIRWISE, MERGE_LINEAR_RAW = 0, 1, 2
 RULE_WEIGHTED, RULE_TOP = 0, 1
 KV_THRESHOLD, KV_BUDGET = 0, 1
@@ -94,12 +94,14 @@ def _load():
     lib.lvlm_merge_weights.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_float)]
     lib.lvlm_score_tokens.argtypes = [vp, vp, C.POINTER(ScoreDesc), vp, vp, f32p, f32p, f32p]
     lib.lvlm_merge_compact.argtypes = [vp, vp, C.POINTER(MergeDesc), f32p, f32p, C.POINTER(Plane), i32p, i32p]
+    lib.lvlm_merge_similar.argtypes = [vp, vp, C.POINTER(MergeDesc), f32p, C.POINTER(Plane), f32p, f32p, i32p, i32p]
     lib.lvlm_kv_compress.argtypes = [vp, vp, C.POINTER(KvDesc), vp, vp, f32p, vp, i32p, i32p, i32p]
     lib.lvlm_decode_attn.argtypes = [vp, vp, C.POINTER(AttnDesc), vp, vp, vp, vp, vp, f32p, vp, i32p, i32p, vp]
     lib.lvlm_profile.argtypes = [C.c_void_p, C.c_int]
     lib.lvlm_profile_read.argtypes = [C.c_void_p, C.POINTER(ProfileEntry), C.c_int, C.POINTER(C.c_int)]
     for name in ("lvlm_profile", "lvlm_profile_read", "lvlm_create", "lvlm_destroy", "lvlm_workspace_bytes", "lvlm_set_workspace", "lvlm_schedule",
-                 "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_merge_compact", "lvlm_kv_compress",
+                 "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_merge_compact", "lvlm_merge_similar",
+                 "lvlm_kv_compress",
                  "lvlm_decode_attn"):
         getattr(lib, name).restype = C.c_int
     return lib
@@ -243,6 +245,30 @@ class Context:
                                            _ptr(keep_idx) if keep_idx.numel() else None,
                                            _ptr(merged_idx) if merged_idx.numel() else None))
         return outs, keep_idx, merged_idx
+
+    # ---- step 3b ----
+    def merge_similar(self, planes, score_mean, *, img_begin, n_img, n_keep, size=None, rules=None, outs=None,
+                      size_out=None, keep_idx=None, assign=None, reserve=True):
+        """lvlm_merge_similar.  planes: list of [B,N,row] tensors -> (outs, keep_idx, assign, size_out)."""
+        B, N = planes[0].shape[0], planes[0].shape[1]
+        r = n_img - n_keep
+        rules = list(rules) if rules is not None else [RULE_WEIGHTED] * len(planes)
+        dev = planes[0].device
+        if outs is None:
+            outs = [torch.empty(B, N - r, p.shape[2], dtype=p.dtype, device=p.device) for p in planes]
+        if keep_idx is None:
+            keep_idx = torch.empty(B, n_keep, dtype=torch.int32, device=dev)
+        if assign is None:
+            assign = torch.empty(B, n_img, dtype=torch.int32, device=dev)
+        if size_out is None:
+            size_out = torch.empty(B, n_keep, dtype=torch.float32, device=dev)
+        d = MergeDesc(B, N, img_begin, n_img, n_keep, len(planes))
+        arr = self._planes(planes, outs, rules)
+        if reserve:
+            self.reserve(self.workspace_bytes(OP_MERGE_SIMILAR, MergeQuery(C.pointer(d), arr)))
+        self._check(lib.lvlm_merge_similar(self._h, _stream(), C.byref(d), _ptr(score_mean), arr, _ptr(size),
+                                           _ptr(size_out), _ptr(keep_idx), _ptr(assign)))
+        return outs, keep_idx, assign, size_out
 
     # ---- step 5 ----
     def kv_compress(self, k_cache, v_cache, score, kind, orig_pos, length, *, mode, order=ORDER_STABLE,

@@ -216,7 +216,8 @@ lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const void *de
             *bytes = score_ws(*d).total;
             return LVLM_OK;
         }
-        case LVLM_OP_MERGE: {
+        case LVLM_OP_MERGE:
+        case LVLM_OP_MERGE_SIMILAR: {
             // only shapes matter for the size: plane pointers are not inspected
             const auto *qy = static_cast<const lvlm_merge_query *>(desc);
             const lvlm_merge_desc *d = qy->desc;
@@ -226,7 +227,12 @@ lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const void *de
             for (int i = 0; i < d->n_planes; ++i)
                 if (qy->planes[i].row_elems < 1) why = "row_elems must be positive";
             if (why) break;
-            *bytes = merge_ws(*d, qy->planes).total;
+            if (op == LVLM_OP_MERGE_SIMILAR) {
+                if (d->n_keep < 1 || d->n_keep > d->n_img) { why = "n_keep must be in [1, n_img]"; break; }
+                *bytes = sim_ws(*d).total;
+            } else {
+                *bytes = merge_ws(*d, qy->planes).total;
+            }
             return LVLM_OK;
         }
         case LVLM_OP_KV_COMPRESS: {
@@ -313,6 +319,27 @@ lvlm_status lvlm_merge_compact(lvlm_ctx *ctx, void *stream, const lvlm_merge_des
     if (lvlm_status st = bind_device(ctx)) return st;
     return after_launch(ctx, launch_merge(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, mw, static_cast<char *>(ctx->ws),
                                           score_mean, w, planes, keep_idx, merged_idx));
+}
+
+lvlm_status lvlm_merge_similar(lvlm_ctx *ctx, void *stream, const lvlm_merge_desc *d, const float *score_mean,
+                               const lvlm_plane *planes, const float *size_in, float *size_out, int32_t *keep_idx,
+                               int32_t *assign) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (const char *why = check_merge(d, planes)) return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_similar: %s", why);
+    if (!score_mean && d->n_keep < d->n_img) return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_similar: null score_mean");
+    if (!aligned16(score_mean) || !aligned16(size_in) || !aligned16(size_out) || !aligned16(keep_idx) ||
+        !aligned16(assign))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_similar: pointers must be 16-byte aligned");
+    if (!float_dtype(planes[0].dtype) || (planes[0].row_elems * elem_bytes(planes[0].dtype)) % 64 != 0 ||
+        (planes[0].src_stride_b * elem_bytes(planes[0].dtype)) % 16 != 0)
+        return fail(ctx, LVLM_ERR_UNSUPPORTED,
+                    "merge_similar: planes[0] must be bf16 or fp32 with rows that are a multiple of 64 bytes");
+    const SimWs w = sim_ws(*d);
+    if (lvlm_status st = need_ws(ctx, w.total)) return st;
+    if (lvlm_status st = bind_device(ctx)) return st;
+    return after_launch(ctx, launch_merge_similar(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w,
+                                                  static_cast<char *>(ctx->ws), score_mean, planes, size_in, size_out,
+                                                  keep_idx, assign));
 }
 
 lvlm_status lvlm_kv_compress(lvlm_ctx *ctx, void *stream, const lvlm_kv_desc *d, void *k_cache, void *v_cache,

@@ -45,6 +45,12 @@ struct MergeWs {
 };
 MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes);
 
+struct SimWs {
+    size_t rank, dom_of, keep_idx, rest_idx, inv_norm, pbest_val, pbest_idx, assign, key, rank2, order, total;
+    int NB;        // 128-row blocks of dominant tokens
+};
+SimWs sim_ws(const lvlm_merge_desc &d);
+
 struct KvWs {
     size_t src, total;
 };
@@ -80,6 +86,9 @@ hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreW
 hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeWs &w, char *ws,
                         const float *score_mean, const float *wtab, const lvlm_plane *planes,
                         int32_t *keep_idx, int32_t *merged_idx);
+hipError_t launch_merge_similar(const Prof &prof, const lvlm_merge_desc &d, const SimWs &w, char *ws,
+                                const float *score_mean, const lvlm_plane *planes, const float *size_in,
+                                float *size_out, int32_t *keep_idx, int32_t *assign);
 hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvWs &w, char *ws,
                               void *k_cache, void *v_cache, float *score, uint8_t *kind,
                               int32_t *orig_pos, int32_t *len, int32_t *n_evicted);

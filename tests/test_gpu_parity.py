@@ -479,3 +479,69 @@ def test_degenerate_sizes(ctx):
     _attn_case(ctx, torch.bfloat16, 1, 2, 2, 128, 4, [1, 3], 96, append=False)
     _kv_case(ctx, torch.bfloat16, 1, 2, 8, 128, [0, 1], 97, mode=lv.KV_THRESHOLD, beta=0.5)
     _kv_case(ctx, torch.bfloat16, 1, 2, 8, 128, [8, 1], 98, mode=lv.KV_BUDGET, budget=1, n_recent=0, order=lv.ORDER_FILL)
+
+
+# --------------------------------------------------------------------------- step 3b: similarity merge
+def _similar_case(ctx, dtype, B, n_sys, n_img, n_txt, C, n_keep, seed, clusters=0, with_size=True, extra=True,
+                  identical=False):
+    """GPU dominant set must equal the oracle's; each GPU assignment must be an arg-max of the oracle's
+    fp64 cosines up to 1e-5 (exactly the oracle's choice wherever its margin is larger than that); merged
+    values are checked against the oracle's merge under the GPU's assignment."""
+    N = n_sys + n_img + n_txt
+    g = torch.Generator().manual_seed(seed)
+    hid = torch.randn(B, N, C, generator=g)
+    if clusters:
+        centres = torch.randn(B, clusters, C, generator=g)
+        which = torch.randint(0, clusters, (B, n_img), generator=g)
+        hid[:, n_sys:n_sys + n_img] = torch.gather(centres, 1, which[:, :, None].expand(B, n_img, C)) + \
+            0.1 * torch.randn(B, n_img, C, generator=g)
+    if identical:
+        hid[:, n_sys:n_sys + n_img] = hid[:, n_sys:n_sys + 1]
+    hid = hid.to(dtype)
+    score = torch.rand(B, n_img, generator=g)
+    size = torch.randint(1, 4, (B, n_img), generator=g).float() if with_size else None
+    planes, rules, dts = [hid], [lv.RULE_WEIGHTED], ["bf16" if dtype == torch.bfloat16 else "f32"]
+    if extra:
+        planes += [_rand((B, N, 24), dtype, seed + 1), torch.arange(B * N, dtype=torch.int32).view(B, N, 1)]
+        rules += [lv.RULE_WEIGHTED, lv.RULE_TOP]
+        dts += [dts[0], "f32"]
+    outs, keep, assign, size_out = ctx.merge_similar([p.to(DEV) for p in planes], score.to(DEV), img_begin=n_sys,
+                                                     n_img=n_img, n_keep=n_keep, rules=rules,
+                                                     size=None if size is None else size.to(DEV))
+    keep, assign = keep.cpu().numpy(), assign.cpu().numpy()
+    np_planes = [f64(p) if p.dtype != torch.int32 else p.numpy() for p in planes]
+    for b in range(B):
+        dom, oassign, cos, rest = O.similarity_assign(np_planes[0][b, n_sys:n_sys + n_img], score[b].numpy(), n_keep)
+        assert np.array_equal(keep[b], dom)
+        assert np.array_equal(assign[b, dom], np.arange(n_keep))
+        if rest.size:
+            best = cos.max(axis=1)
+            chosen = cos[np.arange(rest.size), assign[b, rest]]
+            assert (chosen >= best - 1e-5).all()
+            second = np.sort(cos, axis=1)[:, -2] if n_keep > 1 else np.full(rest.size, -np.inf)
+            clear = best - second > 1e-5
+            assert np.array_equal(assign[b, rest][clear], oassign[rest][clear])
+            if identical:
+                assert (assign[b, rest] == 0).all()                    # all cosines equal: lowest position wins
+    oouts, _, _, onew = O.merge_similar(np_planes, score.numpy(), img_begin=n_sys, n_img=n_img, n_keep=n_keep,
+                                        size=None if size is None else size.numpy(), rules=rules, dtypes=dts,
+                                        assign=assign)
+    np.testing.assert_allclose(size_out.cpu().numpy(), onew, rtol=1e-6)
+    for got, ref, p in zip(outs, oouts, planes):
+        assert tuple(got.shape) == ref.shape
+        if p.dtype == torch.int32:
+            assert np.array_equal(got.cpu().numpy(), ref)
+        else:
+            got = f64(got.cpu())
+            assert np.array_equal(got[:, :n_sys], ref[:, :n_sys]) and np.array_equal(got[:, n_sys + n_keep:], ref[:, n_sys + n_keep:])
+            assert rel_err(got, ref) < TOL[dtype]
+
+
+def test_merge_similar(ctx):
+    _similar_case(ctx, torch.float32, 1, 32, 576, 32, 256, 288, 100, clusters=16)               # config 1 shape
+    _similar_case(ctx, torch.bfloat16, 1, 64, 2048, 64, 3584, 636, 101, clusters=64, extra=False)  # config 2 stage
+    _similar_case(ctx, torch.bfloat16, 2, 3, 333, 5, 160, 77, 102, clusters=8)                   # ragged tiles, batch
+    _similar_case(ctx, torch.bfloat16, 2, 3, 333, 5, 160, 77, 103, with_size=False)              # unclustered, unit sizes
+    _similar_case(ctx, torch.float32, 1, 0, 300, 0, 64, 1, 104)                                  # one dominant token
+    _similar_case(ctx, torch.float32, 1, 2, 200, 2, 64, 200, 105)                                # nothing removed
+    _similar_case(ctx, torch.bfloat16, 1, 1, 500, 1, 128, 130, 106, identical=True)              # all ties
