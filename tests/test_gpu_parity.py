@@ -299,6 +299,9 @@ def test_decode_attn_shapes(ctx):
     _attn_case(ctx, torch.bfloat16, 2, 14, 2, 128, 1100, [1024, 37, 5, 700], 55, append=False)   # no append
     _attn_case(ctx, torch.bfloat16, 2, 14, 2, 128, 1100, [1024, 37, 5, 700], 56, track=False)    # no importance
     _attn_case(ctx, torch.bfloat16, 2, 14, 2, 128, 4096, [1024, 37, 5, 700], 57, len_bound=1025)  # bound < Lmax
+    _attn_case(ctx, torch.bfloat16, 1, 14, 2, 128, 9100, [9000, 8193], 58)                       # long cache: separate fold
+    for seed in (59, 60, 61):                                                                    # same shape again and again:
+        _attn_case(ctx, torch.bfloat16, 2, 14, 2, 128, 1100, [1024, 37, 0, 700], seed)           # the fold's tickets restart
 
 
 def test_decode_attn_config4_layer_step(ctx):
