@@ -98,20 +98,124 @@ __device__ __forceinline__ void block_scan3(ScanState &s, const bool (&f0)[kScan
     __syncthreads();
 }
 
+// Exact fixed-point mass of a candidate, from its order-preserving key alone: keys with the top bit set
+// are the non-negative scores (bit pattern = key without that bit); negative scores and NaN weigh 0.
+__device__ __forceinline__ unsigned long long key_mass(uint32_t key) {
+    return (key & 0x80000000u) ? score_fixed(__uint_as_float(key & 0x7fffffffu)) : 0ull;
+}
+
+struct SelectShared {
+    unsigned long long hist_m[kBins];
+    unsigned int hist_c[kBins];
+    unsigned long long total, need, need_next;
+    unsigned int ncand, cabove, digit;
+    int first_hole;
+    ScanState scan;
+    unsigned long long w_best[16];   // per-wave partial results of the block reductions
+    unsigned long long w_mass[16];
+    uint32_t w_min[16], w_max[16];
+    int w_cnt[16];
+};
+
+// Wave 0, after a histogram pass: suffix sums over the digits give the mass (and count) above each
+// digit; the digit in which the quota `need` (> 0, at most the mass in the histogram) is met becomes the
+// next digit of the key.
+__device__ __forceinline__ void pick_digit(SelectShared &sh, unsigned long long need) {
+    const int lane = threadIdx.x & 63;
+    constexpr int PER = kBins / 64;     // lane owns 4 consecutive digits
+    unsigned long long loc_m = 0ull;
+    unsigned int loc_c = 0u;
+    unsigned long long hm[PER];
+    unsigned int hc[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        hm[i] = sh.hist_m[PER * lane + i];
+        hc[i] = sh.hist_c[PER * lane + i];
+        loc_m += hm[i];
+        loc_c += hc[i];
+    }
+    unsigned long long inc_m = loc_m;
+    unsigned int inc_c = loc_c;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const unsigned long long tm = __shfl_down(inc_m, o);
+        const unsigned int tc = __shfl_down(inc_c, o);
+        if (lane + o < 64) {
+            inc_m += tm;
+            inc_c += tc;
+        }
+    }
+    unsigned long long above_m = inc_m - loc_m;
+    unsigned int above_c = inc_c - loc_c;
+#pragma unroll
+    for (int i = PER - 1; i >= 0; --i) {
+        if (above_m < need && need <= above_m + hm[i]) {
+            sh.digit = (unsigned int)(PER * lane + i);
+            sh.need_next = need - above_m;
+            sh.cabove += above_c;     // exactly one lane and one digit take this branch
+        }
+        above_m += hm[i];
+        above_c += hc[i];
+    }
+}
+
+// One round of the slot-order pass over kScanChunks chunks of 1024 slots: numbers the survivors (STABLE)
+// or the holes and the tail survivors (FILL) and writes the slot lists.
+__device__ __forceinline__ void number_round(SelectShared &sh, bool stable, const bool (&tie)[kScanChunks],
+                                             const bool (&keep)[kScanChunks], const bool (&inside)[kScanChunks],
+                                             const int (&slot)[kScanChunks], unsigned long long tie_keep, int n_new,
+                                             int32_t *list_a, int32_t *list_b, int &first_hole) {
+    bool none[kScanChunks];
+#pragma unroll
+    for (int c = 0; c < kScanChunks; ++c) none[c] = false;
+    int tie_before[kScanChunks], p1[kScanChunks], p2[kScanChunks];
+    if (stable) {
+        // survivors before a slot = sure survivors before it + kept ties before it
+        block_scan3(sh.scan, tie, keep, none, tie_before, p1, p2);
+#pragma unroll
+        for (int c = 0; c < kScanChunks; ++c) {
+            if (!inside[c]) continue;
+            const bool kept = keep[c] || (tie[c] && (unsigned long long)tie_before[c] < tie_keep);
+            const int p = p1[c] + (int)min((unsigned long long)tie_before[c], tie_keep);
+            if (kept) list_a[p] = slot[c];
+            else first_hole = min(first_hole, p);      // folded over the workgroup once, after the last round
+        }
+    } else {
+        block_scan3(sh.scan, tie, none, none, tie_before, p1, p2);
+        bool hole[kScanChunks], tail[kScanChunks];
+#pragma unroll
+        for (int c = 0; c < kScanChunks; ++c) {
+            const bool kept = keep[c] || (tie[c] && (unsigned long long)tie_before[c] < tie_keep);
+            hole[c] = inside[c] && !kept && slot[c] < n_new;
+            tail[c] = inside[c] && kept && slot[c] >= n_new;
+        }
+        int dummy[kScanChunks], hi[kScanChunks], ti[kScanChunks];
+        // a second scan numbers holes and tail survivors (counter 0 keeps counting ties)
+        block_scan3(sh.scan, none, hole, tail, dummy, hi, ti);
+#pragma unroll
+        for (int c = 0; c < kScanChunks; ++c) {
+            if (hole[c]) list_a[hi[c]] = slot[c];
+            if (tail[c]) list_b[ti[c]] = slot[c];
+        }
+    }
+}
+
+// KPT > 0: every thread keeps the keys of its KPT slots (slot = 1024 i + thread) in registers, so the
+// scores are read once, with all loads in flight together; heads longer than 1024 KPT are not accepted
+// by the launch.  KPT == 0: any length, scores re-read from memory in every pass.
+template <int KPT>
 __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
-    __shared__ unsigned long long hist_m[kBins];
-    __shared__ unsigned int hist_c[kBins];
-    __shared__ unsigned long long s_total, s_need, s_need_next;
-    __shared__ unsigned int s_ncand, s_cabove, s_digit;
-    __shared__ int s_first_hole;
-    __shared__ ScanState scan;
+    __shared__ SelectShared sh;
+    constexpr int NREG = KPT > 0 ? KPT : 1;
+    constexpr int NROUND = (NREG + kScanChunks - 1) / kScanChunks;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hg = blockIdx.x;
     const long long base = (long long)hg * a.Lmax;
     const float *score = a.score + base;
     const uint8_t *kind = a.kind + base;
-    const int L = min(a.len[hg], a.Lmax);
+    int L = min(a.len[hg], a.Lmax);
+    if (KPT > 0) L = min(L, 1024 * KPT);
     const bool budget_mode = a.mode == LVLM_KV_BUDGET;
 
     auto nothing_to_do = [&]() {
@@ -130,20 +234,52 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         return budget_mode ? (kd != LVLM_KIND_PROTECTED && slot < recent_lo) : (kd == LVLM_KIND_IMAGE);
     };
 
+    // register-resident keys; bit i of `candm` marks slot 1024 i + tid as a candidate
+    uint32_t key[NREG];
+    uint32_t candm = 0u;
+    if constexpr (KPT > 0) {
+        float sc[NREG];
+        uint8_t kd[NREG];
+#pragma unroll
+        for (int i = 0; i < NREG; ++i) {
+            const int sl = min(1024 * i + tid, L - 1);     // clamped: every load is issued, none depends on another
+            sc[i] = score[sl];
+            kd[i] = kind[sl];
+        }
+#pragma unroll
+        for (int i = 0; i < NREG; ++i) {
+            const int slot = 1024 * i + tid;
+            key[i] = score_key(sc[i]);
+            if (slot < L && is_cand(slot, kd[i])) candm |= 1u << i;
+        }
+    } else {
+        key[0] = 0u;
+    }
+
     // ---- steady-state decode: the head is exactly one entry over budget and holes are filled from
     // the tail.  One pass finds the candidate that is last in importance order (lowest key, highest
     // slot among equals); the entry in the last slot takes its place.
     if (budget_mode && a.order == LVLM_ORDER_FILL && L - a.budget == 1) {
-        __shared__ unsigned long long w_best[16];
-        __shared__ int w_cnt[16];
         unsigned long long best = ~0ull;
         int cnt = 0;
-        for (int slot = tid; slot < L; slot += 1024) {
-            if (is_cand(slot, kind[slot])) {
-                ++cnt;
-                const unsigned long long c =
-                    ((unsigned long long)score_key(score[slot]) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)slot);
-                best = c < best ? c : best;
+        if constexpr (KPT > 0) {
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) {
+                if (candm & (1u << i)) {
+                    ++cnt;
+                    const unsigned long long c =
+                        ((unsigned long long)key[i] << 32) | (unsigned long long)(0xffffffffu - (uint32_t)(1024 * i + tid));
+                    best = c < best ? c : best;
+                }
+            }
+        } else {
+            for (int slot = tid; slot < L; slot += 1024) {
+                if (is_cand(slot, kind[slot])) {
+                    ++cnt;
+                    const unsigned long long c = ((unsigned long long)score_key(score[slot]) << 32) |
+                                                 (unsigned long long)(0xffffffffu - (uint32_t)slot);
+                    best = c < best ? c : best;
+                }
             }
         }
 #pragma unroll
@@ -153,16 +289,16 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
             cnt += __shfl_xor(cnt, o);
         }
         if (lane == 0) {
-            w_best[wave] = best;
-            w_cnt[wave] = cnt;
+            sh.w_best[wave] = best;
+            sh.w_cnt[wave] = cnt;
         }
         __syncthreads();
-        best = w_best[0];
-        cnt = w_cnt[0];
+        best = sh.w_best[0];
+        cnt = sh.w_cnt[0];
 #pragma unroll
         for (int w = 1; w < 16; ++w) {
-            best = w_best[w] < best ? w_best[w] : best;
-            cnt += w_cnt[w];
+            best = sh.w_best[w] < best ? sh.w_best[w] : best;
+            cnt += sh.w_cnt[w];
         }
         if (a.budget - (L - cnt) > 0) {           // room for all but one candidate
             const int victim = (int)(0xffffffffu - (uint32_t)(best & 0xffffffffull));
@@ -194,131 +330,136 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         __syncthreads();     // protected entries alone exceed the budget: general path below
     }
 
-    // ---- radix descent, most significant digit first.  The first histogram also yields the totals.
-    if (tid == 0) {
-        s_cabove = 0u;
-        s_first_hole = L;
-        scan.base[0] = scan.base[1] = scan.base[2] = 0;
+    // ---- totals and the key range of the candidates (one block reduction)
+    {
+        unsigned long long mass = 0ull;
+        int cnt = 0;
+        uint32_t kmin = 0xffffffffu, kmax = 0u;
+        auto see = [&](uint32_t k) {
+            ++cnt;
+            mass += budget_mode ? 1ull : key_mass(k);
+            kmin = min(kmin, k);
+            kmax = max(kmax, k);
+        };
+        if constexpr (KPT > 0) {
+#pragma unroll
+            for (int i = 0; i < NREG; ++i)
+                if (candm & (1u << i)) see(key[i]);
+        } else {
+            for (int slot = tid; slot < L; slot += 1024)
+                if (is_cand(slot, kind[slot])) see(score_key(score[slot]));
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            mass += __shfl_xor(mass, o);
+            cnt += __shfl_xor(cnt, o);
+            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
+            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
+        }
+        if (lane == 0) {
+            sh.w_mass[wave] = mass;
+            sh.w_cnt[wave] = cnt;
+            sh.w_min[wave] = kmin;
+            sh.w_max[wave] = kmax;
+        }
+        if (tid == 0) {
+            sh.cabove = 0u;
+            sh.first_hole = L;
+            sh.scan.base[0] = sh.scan.base[1] = sh.scan.base[2] = 0;
+        }
+        __syncthreads();
     }
-    unsigned long long need = 0ull;      // quota still to be met inside the current bin
-    int n_fixed = 0;                     // entries that are never candidates
+    unsigned long long total = 0ull;
+    int ncand = 0;
+    uint32_t kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        total += sh.w_mass[w];
+        ncand += sh.w_cnt[w];
+        kmin = min(kmin, sh.w_min[w]);
+        kmax = max(kmax, sh.w_max[w]);
+    }
+    const int n_fixed = L - ncand;                 // entries that are never candidates
     bool evict_all_cand = false;
-    uint32_t prefix = 0u;
-    unsigned long long last_m = 0ull;
-    unsigned int last_c = 1u;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
+    unsigned long long need;                       // quota still to be met among the keys that match `prefix`
+    if (budget_mode) {
+        const int room = a.budget - n_fixed;
+        evict_all_cand = room <= 0;
+        need = room > 0 ? (unsigned long long)room : 0ull;
+    } else {
+        if (ncand == 0 || total == 0ull) {
+            nothing_to_do();
+            return;
+        }
+        const double target = ceil(a.beta * (double)total);
+        need = target >= 1.0 ? (unsigned long long)target : 1ull;
+        if (need > total) need = total;
+    }
+
+    // ---- radix descent over the bits in which the candidates' keys differ, most significant digit
+    // first (scores of one head share their leading bits, so the digits that are looked at spread over
+    // the histogram instead of piling up in a few bins)
+    const int hb = 32 - __clz((int)(kmin ^ kmax));     // bits below the common prefix (0: all keys equal)
+    const int n_pass = evict_all_cand ? 0 : (hb + 7) / 8;
+    uint32_t prefix = hb >= 32 ? 0u : (kmin >> hb) << hb;
+    unsigned long long last_m = total;
+    unsigned int last_c = (unsigned int)ncand;
+    for (int pass = 0; pass < n_pass; ++pass) {
+        const int top = hb - 8 * pass;                 // bits still undecided
+        const int width = top < 8 ? top : 8;
+        const int shift = top - width;
+        const uint32_t dmask = (1u << width) - 1u;
         for (int i = tid; i < kBins; i += 1024) {
-            hist_m[i] = 0ull;
-            hist_c[i] = 0u;
+            sh.hist_m[i] = 0ull;
+            sh.hist_c[i] = 0u;
         }
         __syncthreads();
         {
-            // Scores cluster in few digits, so a thread first adds up runs of equal digits in registers
-            // and only then touches the shared histogram (far fewer colliding LDS atomics).
+            // a thread first adds up runs of equal digits in registers and only then touches the shared
+            // histogram (fewer colliding LDS atomics)
             uint32_t run_d = 0xffffffffu;
             unsigned long long run_m = 0ull;
             unsigned int run_c = 0u;
-            for (int slot = tid; slot < L; slot += 1024) {
-                if (!is_cand(slot, kind[slot])) continue;
-                const float sc = score[slot];
-                const uint32_t key = score_key(sc);
-                if (pass > 0 && (key >> (shift + 8)) != (prefix >> (shift + 8))) continue;
-                const uint32_t dgt = (key >> shift) & 255u;
+            auto add = [&](uint32_t k) {
+                const uint32_t dgt = (k >> shift) & dmask;
                 if (dgt != run_d) {
                     if (run_c) {
-                        atomicAdd(&hist_m[run_d], run_m);
-                        atomicAdd(&hist_c[run_d], run_c);
+                        atomicAdd(&sh.hist_m[run_d], run_m);
+                        atomicAdd(&sh.hist_c[run_d], run_c);
                     }
                     run_d = dgt;
                     run_m = 0ull;
                     run_c = 0u;
                 }
-                run_m += budget_mode ? 1ull : score_fixed(sc);
+                run_m += budget_mode ? 1ull : key_mass(k);
                 ++run_c;
+            };
+            // keys that agree with the prefix in every bit above the current digit
+            auto matches = [&](uint32_t k) { return pass == 0 || ((k ^ prefix) >> top) == 0u; };
+            if constexpr (KPT > 0) {
+#pragma unroll
+                for (int i = 0; i < NREG; ++i)
+                    if ((candm & (1u << i)) && matches(key[i])) add(key[i]);
+            } else {
+                for (int slot = tid; slot < L; slot += 1024) {
+                    if (!is_cand(slot, kind[slot])) continue;
+                    const uint32_t k = score_key(score[slot]);
+                    if (matches(k)) add(k);
+                }
             }
             if (run_c) {
-                atomicAdd(&hist_m[run_d], run_m);
-                atomicAdd(&hist_c[run_d], run_c);
+                atomicAdd(&sh.hist_m[run_d], run_m);
+                atomicAdd(&sh.hist_c[run_d], run_c);
             }
         }
         __syncthreads();
-        if (wave == 0) {
-            // lane owns 4 consecutive digits; suffix sums give the mass above each digit
-            constexpr int PER = kBins / 64;
-            unsigned long long loc_m = 0ull;
-            unsigned int loc_c = 0u;
-            for (int i = 0; i < PER; ++i) {
-                loc_m += hist_m[PER * lane + i];
-                loc_c += hist_c[PER * lane + i];
-            }
-            unsigned long long inc_m = loc_m;
-            unsigned int inc_c = loc_c;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const unsigned long long tm = __shfl_down(inc_m, o);
-                const unsigned int tc = __shfl_down(inc_c, o);
-                if (lane + o < 64) {
-                    inc_m += tm;
-                    inc_c += tc;
-                }
-            }
-            if (pass == 0) {
-                // totals over all candidates (lane 0 holds the full suffix sum) fix the quota
-                const unsigned long long total = __shfl(inc_m, 0);
-                const unsigned int ncand = __shfl(inc_c, 0);
-                if (lane == 0) {
-                    s_total = total;
-                    s_ncand = ncand;
-                    unsigned long long nd;
-                    if (budget_mode) {
-                        const int room = a.budget - (L - (int)ncand);
-                        nd = room > 0 ? (unsigned long long)room : 0ull;
-                    } else {
-                        const double target = ceil(a.beta * (double)total);
-                        nd = target >= 1.0 ? (unsigned long long)target : 1ull;
-                        if (nd > total) nd = total;
-                    }
-                    s_need = nd;
-                }
-            }
-            // every lane needs the quota of this pass
-            unsigned long long nd = pass == 0 ? 0ull : need;
-            if (pass == 0) {
-                nd = __shfl(lane == 0 ? s_need : 0ull, 0);
-            }
-            unsigned long long above_m = inc_m - loc_m;
-            unsigned int above_c = inc_c - loc_c;
-            if (nd > 0ull) {
-                for (int i = PER - 1; i >= 0; --i) {
-                    const unsigned long long hm = hist_m[PER * lane + i];
-                    if (above_m < nd && nd <= above_m + hm) {
-                        s_digit = (unsigned int)(PER * lane + i);
-                        s_need_next = nd - above_m;
-                        s_cabove += above_c;     // exactly one lane and one digit take this branch
-                    }
-                    above_m += hm;
-                    above_c += hist_c[PER * lane + i];
-                }
-            }
-        }
+        if (wave == 0) pick_digit(sh, need);
         __syncthreads();
-        if (pass == 0) {
-            const unsigned int ncand = s_ncand;
-            n_fixed = L - (int)ncand;
-            if (budget_mode) {
-                evict_all_cand = a.budget - n_fixed <= 0;
-            } else if (ncand == 0u || s_total == 0ull) {
-                nothing_to_do();
-                return;
-            }
-            if (evict_all_cand) break;
-        }
-        prefix |= s_digit << shift;
-        need = s_need_next;
-        if (pass == 3) {
-            last_m = hist_m[s_digit];
-            last_c = hist_c[s_digit];
+        prefix |= sh.digit << shift;
+        need = sh.need_next;
+        if (pass == n_pass - 1) {
+            last_m = sh.hist_m[sh.digit];
+            last_c = sh.hist_c[sh.digit];
         }
         __syncthreads();
     }
@@ -333,7 +474,7 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
             tie_keep = u ? (need + u - 1ull) / u : (unsigned long long)last_c;
         }
     }
-    const int n_keep_cand = evict_all_cand ? 0 : (int)(s_cabove + (unsigned int)tie_keep);
+    const int n_keep_cand = evict_all_cand ? 0 : (int)(sh.cabove + (unsigned int)tie_keep);
     const int n_new = n_fixed + n_keep_cand;
     const int n_evict = L - n_new;
     if (n_evict <= 0) {
@@ -345,61 +486,64 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
     int32_t *list_a = a.list_a + base;
     int32_t *list_b = a.list_b + base;
     const bool stable = a.order == LVLM_ORDER_STABLE;
-    for (int s0 = 0; s0 < L; s0 += kScanChunks * 1024) {
-        bool tie[kScanChunks], keep[kScanChunks], inside[kScanChunks], none[kScanChunks];
-        int slot[kScanChunks];
+    int first_hole = L;                  // lowest new slot whose entry moves (STABLE)
+    if constexpr (KPT > 0) {
 #pragma unroll
-        for (int c = 0; c < kScanChunks; ++c) {
-            slot[c] = s0 + c * 1024 + tid;
-            inside[c] = slot[c] < L;
-            tie[c] = keep[c] = none[c] = false;
-            if (inside[c]) {
-                if (!is_cand(slot[c], kind[slot[c]])) {
-                    keep[c] = true;
-                } else {
-                    const uint32_t key = score_key(score[slot[c]]);
-                    tie[c] = key == kstar;
-                    keep[c] = key > kstar;
+        for (int r = 0; r < NROUND; ++r) {
+            if (r * kScanChunks * 1024 >= L) break;
+            bool tie[kScanChunks], keep[kScanChunks], inside[kScanChunks];
+            int slot[kScanChunks];
+#pragma unroll
+            for (int c = 0; c < kScanChunks; ++c) {
+                const int i = r * kScanChunks + c;
+                slot[c] = 1024 * i + tid;
+                inside[c] = slot[c] < L;
+                tie[c] = keep[c] = false;
+                if (i < NREG && inside[c]) {
+                    const uint32_t k = key[i < NREG ? i : 0];
+                    if (!(candm & (1u << i))) {
+                        keep[c] = true;
+                    } else {
+                        tie[c] = k == kstar;
+                        keep[c] = k > kstar;
+                    }
                 }
             }
+            number_round(sh, stable, tie, keep, inside, slot, tie_keep, n_new, list_a, list_b, first_hole);
         }
-        int tie_before[kScanChunks], p1[kScanChunks], p2[kScanChunks];
-        if (stable) {
-            // survivors before a slot = sure survivors before it + kept ties before it
-            block_scan3(scan, tie, keep, none, tie_before, p1, p2);
+    } else {
+        for (int s0 = 0; s0 < L; s0 += kScanChunks * 1024) {
+            bool tie[kScanChunks], keep[kScanChunks], inside[kScanChunks];
+            int slot[kScanChunks];
 #pragma unroll
             for (int c = 0; c < kScanChunks; ++c) {
-                if (!inside[c]) continue;
-                const bool kept = keep[c] || (tie[c] && (unsigned long long)tie_before[c] < tie_keep);
-                const int p = p1[c] + (int)min((unsigned long long)tie_before[c], tie_keep);
-                if (kept) list_a[p] = slot[c];
-                else atomicMin(&s_first_hole, p);
+                slot[c] = s0 + c * 1024 + tid;
+                inside[c] = slot[c] < L;
+                tie[c] = keep[c] = false;
+                if (inside[c]) {
+                    if (!is_cand(slot[c], kind[slot[c]])) {
+                        keep[c] = true;
+                    } else {
+                        const uint32_t k = score_key(score[slot[c]]);
+                        tie[c] = k == kstar;
+                        keep[c] = k > kstar;
+                    }
+                }
             }
-        } else {
-            block_scan3(scan, tie, none, none, tie_before, p1, p2);
-            bool hole[kScanChunks], tail[kScanChunks];
-#pragma unroll
-            for (int c = 0; c < kScanChunks; ++c) {
-                const bool kept = keep[c] || (tie[c] && (unsigned long long)tie_before[c] < tie_keep);
-                hole[c] = inside[c] && !kept && slot[c] < n_new;
-                tail[c] = inside[c] && kept && slot[c] >= n_new;
-            }
-            int dummy[kScanChunks], hi[kScanChunks], ti[kScanChunks];
-            // a second scan numbers holes and tail survivors (counter 0 keeps counting ties)
-            block_scan3(scan, none, hole, tail, dummy, hi, ti);
-#pragma unroll
-            for (int c = 0; c < kScanChunks; ++c) {
-                if (hole[c]) list_a[hi[c]] = slot[c];
-                if (tail[c]) list_b[ti[c]] = slot[c];
-            }
+            number_round(sh, stable, tie, keep, inside, slot, tie_keep, n_new, list_a, list_b, first_hole);
         }
+    }
+    if (stable) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) first_hole = min(first_hole, __shfl_xor(first_hole, o));
+        if (lane == 0) atomicMin(&sh.first_hole, first_hole);
     }
     __syncthreads();
 
     if (stable) {
         if (tid == 0) {
             a.meta[2 * hg] = n_new;
-            a.meta[2 * hg + 1] = s_first_hole;
+            a.meta[2 * hg + 1] = sh.first_hole;
             a.len[hg] = n_new;
             if (a.n_evicted) a.n_evicted[hg] = n_evict;
         }
@@ -407,7 +551,7 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
     }
 
     // ---- FILL: sources (>= n_new) and destinations (< n_new) are disjoint
-    const int n_moves = scan.base[1];
+    const int n_moves = sh.scan.base[1];
     const int units = a.row_bytes / 16;
     char *kc = a.k + base * a.row_bytes;
     char *vc = a.v + base * a.row_bytes;
@@ -432,59 +576,78 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
     }
 }
 
-constexpr int kSliceBytes = 64;   // column slice of a K or V row handled by one workgroup
-constexpr int kMoveUpt = 16;      // units per thread per step (1024 rows of a 64-byte slice)
+constexpr int kMoveUpt = 8;       // 16-byte units per thread per step (two such sets are in flight)
 
-__global__ __launch_bounds__(256) void kv_move_kernel(KvArgs a) {
+// NT threads move one SLICE-byte column slice of NT / (SLICE / 16) * kMoveUpt rows per step.  A step's
+// sources all lie at or above its first destination, and above every destination of earlier steps, so
+// the only ordering that matters is inside a step: all of its loads go before any of its stores (the
+// barrier; a compute unit performs the vector memory operations of its waves in issue order).  The
+// loads of step s + 1 are issued before the stores of step s, so that reads and writes overlap.  With few heads the launch uses 1024-thread workgroups and narrower slices, so that
+// the few workgroups there are keep enough bytes in flight.
+template <int NT, int SLICE>
+__global__ __launch_bounds__(NT) void kv_move_kernel(KvArgs a) {
+    constexpr int TPR = SLICE / 16;              // threads per row slice
+    constexpr int RPS = NT / TPR;                // rows per load instruction of the workgroup
     const int tid = threadIdx.x;
     const int hg = blockIdx.y;
     const int n_new = a.meta[2 * hg], first = a.meta[2 * hg + 1];
     if (first >= n_new) return;
     const long long base = (long long)hg * a.Lmax;
     const int32_t *src_of = a.list_a + base;
-    const int slices = a.row_bytes / kSliceBytes;
+    const int slices = a.row_bytes / SLICE;
     const int sl = blockIdx.x;
     if (sl < 2 * slices) {
-        char *cache = (sl < slices ? a.k : a.v) + base * a.row_bytes + (sl % slices) * kSliceBytes + 16 * (tid & 3);
-        constexpr int ROWS = 64 * kMoveUpt;
+        char *cache = (sl < slices ? a.k : a.v) + base * a.row_bytes + (sl % slices) * SLICE + 16 * (tid % TPR);
+        constexpr int ROWS = RPS * kMoveUpt;
+        static_assert(kMoveUpt == 8, "the register sets below are written out for 8 units");
+        const int row = tid / TPR;
+        // Two register sets with named members: arrays carried around the loop would be placed in
+        // scratch memory.
+#define LVLM_MV_EACH(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7)
+#define LVLM_MV_DECL(x) uint4 c##x, n##x;
+#define LVLM_MV_LOAD_C(x) \
+    c##x = *reinterpret_cast<const uint4 *>(cache + (long long)src_of[min(first + RPS * x + row, n_new - 1)] * a.row_bytes);
+#define LVLM_MV_LOAD_N(x)                                                                                        \
+    n##x = c##x;                                                                                                 \
+    if (more)                                                                                                    \
+        n##x = *reinterpret_cast<const uint4 *>(cache +                                                          \
+                                                (long long)src_of[min(p0 + ROWS + RPS * x + row, n_new - 1)] * a.row_bytes);
+#define LVLM_MV_STORE(x)                                                                      \
+    if (p0 + RPS * x + row < n_new)                                                           \
+        *reinterpret_cast<uint4 *>(cache + (long long)(p0 + RPS * x + row) * a.row_bytes) = c##x;
+#define LVLM_MV_NEXT(x) c##x = n##x;
+        LVLM_MV_EACH(LVLM_MV_DECL)
+        LVLM_MV_EACH(LVLM_MV_LOAD_C)
         for (int p0 = first; p0 < n_new; p0 += ROWS) {
-            uint4 val[kMoveUpt];
-#pragma unroll
-            for (int x = 0; x < kMoveUpt; ++x) {
-                const int p = p0 + 64 * x + (tid >> 2);
-                val[x] = make_uint4(0, 0, 0, 0);   // always defined, or the array is placed in scratch memory
-                if (p < n_new) val[x] = *reinterpret_cast<const uint4 *>(cache + (long long)src_of[p] * a.row_bytes);
-            }
-            __syncthreads();
-#pragma unroll
-            for (int x = 0; x < kMoveUpt; ++x) {
-                const int p = p0 + 64 * x + (tid >> 2);
-                if (p < n_new) *reinterpret_cast<uint4 *>(cache + (long long)p * a.row_bytes) = val[x];
-            }
+            __syncthreads();                     // every load of this step was issued before any of its stores
+            const bool more = p0 + ROWS < n_new;
+            LVLM_MV_EACH(LVLM_MV_LOAD_N)
+            LVLM_MV_EACH(LVLM_MV_STORE)
+            LVLM_MV_EACH(LVLM_MV_NEXT)
         }
+#undef LVLM_MV_EACH
+#undef LVLM_MV_DECL
+#undef LVLM_MV_LOAD_C
+#undef LVLM_MV_LOAD_N
+#undef LVLM_MV_STORE
+#undef LVLM_MV_NEXT
     } else {
-        constexpr int ROWS = 256 * kMoveUpt;
+        constexpr int ROWS = NT * kMoveUpt;
         for (int p0 = first; p0 < n_new; p0 += ROWS) {
             float sc[kMoveUpt];
             uint8_t kd[kMoveUpt];
             int32_t ps[kMoveUpt];
 #pragma unroll
             for (int x = 0; x < kMoveUpt; ++x) {
-                const int p = p0 + 256 * x + tid;
-                sc[x] = 0.f;
-                kd[x] = 0;
-                ps[x] = 0;
-                if (p < n_new) {
-                    const int s = src_of[p];
-                    sc[x] = a.score[base + s];
-                    kd[x] = a.kind[base + s];
-                    ps[x] = a.pos[base + s];
-                }
+                const int s = src_of[min(p0 + NT * x + tid, n_new - 1)];
+                sc[x] = a.score[base + s];
+                kd[x] = a.kind[base + s];
+                ps[x] = a.pos[base + s];
             }
             __syncthreads();
 #pragma unroll
             for (int x = 0; x < kMoveUpt; ++x) {
-                const int p = p0 + 256 * x + tid;
+                const int p = p0 + NT * x + tid;
                 if (p < n_new) {
                     a.score[base + p] = sc[x];
                     a.kind[base + p] = kd[x];
@@ -522,12 +685,22 @@ hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvW
     a.mode = d.mode; a.order = d.order; a.budget = d.budget; a.n_recent = d.n_recent; a.beta = d.beta;
     hipStream_t stream = prof.stream;
     prof.begin("kv_select");
-    hipLaunchKernelGGL(kv_select_kernel, dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    const int bound = d.len_bound > 0 ? d.len_bound : d.Lmax;
+    if (bound <= 2048) hipLaunchKernelGGL(kv_select_kernel<2>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else if (bound <= 4096) hipLaunchKernelGGL(kv_select_kernel<4>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else if (bound <= 8192) hipLaunchKernelGGL(kv_select_kernel<8>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else if (bound <= 17408) hipLaunchKernelGGL(kv_select_kernel<17>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else hipLaunchKernelGGL(kv_select_kernel<0>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
     prof.end();
     if (d.order == LVLM_ORDER_STABLE) {
-        const int slices = a.row_bytes / kSliceBytes;
         prof.begin("kv_move");
-        hipLaunchKernelGGL(kv_move_kernel, dim3(2 * slices + 1, (unsigned)heads), dim3(256), 0, stream, a);
+        const int s64 = a.row_bytes / 64;
+        if (heads * (2 * s64 + 1) >= 1024)
+            hipLaunchKernelGGL((kv_move_kernel<256, 64>), dim3(2 * s64 + 1, (unsigned)heads), dim3(256), 0, stream, a);
+        else if (heads * (2 * s64 + 1) >= 256)
+            hipLaunchKernelGGL((kv_move_kernel<1024, 64>), dim3(2 * s64 + 1, (unsigned)heads), dim3(1024), 0, stream, a);
+        else
+            hipLaunchKernelGGL((kv_move_kernel<1024, 32>), dim3(4 * s64 + 1, (unsigned)heads), dim3(1024), 0, stream, a);
         prof.end();
     }
     return hipGetLastError();

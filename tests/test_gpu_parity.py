@@ -185,12 +185,14 @@ def test_merge_compact_full_config2_stage_from_gpu_scores(ctx):
 
 
 # --------------------------------------------------------------------------- step 5
-def _cache(dtype, B, H, Lmax, d, lens, seed, protected=4, dyadic=False, image_only=False):
+def _cache(dtype, B, H, Lmax, d, lens, seed, protected=4, dyadic=False, image_only=False, flat=False):
     g = torch.Generator().manual_seed(seed)
     k, v = _rand((B, H, Lmax, d), dtype, seed + 1), _rand((B, H, Lmax, d), dtype, seed + 2)
     score = torch.rand(B, H, Lmax, generator=g) ** 4
     if dyadic:
         score = (score * 16).floor() / 16
+    if flat:
+        score = torch.full_like(score, 0.25)
     kind = torch.randint(0, 3, (B, H, Lmax), generator=g).to(torch.uint8)
     if image_only:
         kind[:] = 1
@@ -201,7 +203,7 @@ def _cache(dtype, B, H, Lmax, d, lens, seed, protected=4, dyadic=False, image_on
 
 
 def _kv_case(ctx, dtype, B, H, Lmax, d, lens, seed, **kw):
-    host = _cache(dtype, B, H, Lmax, d, lens, seed, dyadic=kw.pop("dyadic", False),
+    host = _cache(dtype, B, H, Lmax, d, lens, seed, dyadic=kw.pop("dyadic", False), flat=kw.pop("flat", False),
                   image_only=kw.pop("image_only", False), protected=kw.pop("protected", 4))
     dev = [t.to(DEV) for t in host]
     nev = ctx.kv_compress(*dev, **kw)
@@ -258,6 +260,20 @@ def test_kv_compress_bulk_config5_head(ctx):
     new_len, _ = _kv_case(ctx, torch.bfloat16, 1, 8, L, 128, [L] * 8, 41, mode=lv.KV_THRESHOLD, beta=0.995,
                           order=lv.ORDER_STABLE, image_only=True, protected=128)
     assert (new_len < L).all() and (new_len > 128).all()
+
+
+@pytest.mark.parametrize("order", [lv.ORDER_STABLE, lv.ORDER_FILL])
+def test_kv_compress_every_length_class(ctx, order):
+    # the selection kernel keeps keys in registers up to 2048 / 4096 / 8192 / 17408 slots per head and
+    # re-reads them beyond that: one ragged case per class, both rules
+    for Lmax, lens in ((3000, [2999, 2500]), (6000, [5999, 4097]), (12000, [11111, 8193]), (20000, [19990, 17409])):
+        _kv_case(ctx, torch.bfloat16, 1, 2, Lmax, 64, lens, 42 + Lmax, mode=lv.KV_BUDGET, budget=Lmax // 2, n_recent=2,
+                 order=order)
+        _kv_case(ctx, torch.bfloat16, 1, 2, Lmax, 64, lens, 43 + Lmax, mode=lv.KV_THRESHOLD, beta=0.9, order=order)
+    # few distinct scores, and all candidates sharing one score (no bit of the keys differs)
+    _kv_case(ctx, torch.bfloat16, 1, 2, 3000, 64, [2999, 2500], 44, mode=lv.KV_THRESHOLD, beta=0.6, order=order, dyadic=True)
+    _kv_case(ctx, torch.bfloat16, 1, 2, 3000, 64, [2999, 2500], 45, mode=lv.KV_THRESHOLD, beta=0.6, order=order, flat=True)
+    _kv_case(ctx, torch.bfloat16, 1, 2, 3000, 64, [2999, 2500], 46, mode=lv.KV_BUDGET, budget=1700, order=order, flat=True)
 
 
 # --------------------------------------------------------------------------- step 6
