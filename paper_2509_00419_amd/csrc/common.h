@@ -120,10 +120,14 @@ __device__ __forceinline__ uint32_t score_key(float x) {
 
 // Exact fixed-point image of a score used for cumulative thresholds:
 // floor(clamp(score, 0, 2^16) * 2^32); NaN and negatives give 0.
+// Computed as two 32-bit halves (integer part, then the fraction scaled by 2^32: both conversions
+// truncate and both products are exact), which is much cheaper than a float -> u64 conversion.
 __device__ __forceinline__ unsigned long long score_fixed(float s) {
     if (!(s > 0.0f)) return 0ull;
     s = fminf(s, 65536.0f);
-    return (unsigned long long)(s * 4294967296.0f);
+    const unsigned int hi = (unsigned int)s;
+    const unsigned int lo = (unsigned int)((s - (float)hi) * 4294967296.0f);
+    return ((unsigned long long)hi << 32) | lo;
 }
 
 __device__ __forceinline__ float wave_max(float v) {

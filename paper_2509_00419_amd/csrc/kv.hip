@@ -13,6 +13,8 @@
 //                     pass in slot order that numbers survivors / holes.  With
 //                     LVLM_ORDER_FILL it also performs the (few, disjoint)
 //                     moves itself.
+//   kv_fill_kernel    LVLM_ORDER_FILL with many moves per head (bulk eviction): the
+//                     disjoint moves, spread over the chip.
 //   kv_move_kernel    LVLM_ORDER_STABLE: survivors slide down in place.  A move
 //                     never goes up and sources are ascending, so processing
 //                     destination slots in ascending steps, each step reading
@@ -37,66 +39,14 @@ struct KvArgs {
     int32_t *meta;     // [B*Hkv, 2]     STABLE: {new length, first destination slot that moves}
     int Hkv, Lmax, row_bytes, mode, order, budget, n_recent;
     double beta;
+    int fill_external;   // FILL order: the moves are left to kv_fill_kernel (meta[1] = their number)
 };
 
-constexpr int kScanChunks = 4;    // 1024-slot chunks numbered per barrier round in the slot-order pass
-constexpr int kBins = 256;        // radix: four 8-bit digits of the 32-bit key
-
-struct ScanState {
-    int wave_cnt[3][kScanChunks][16];   // per-wave counts, turned into exclusive prefixes in place
-    int tot[3][kScanChunks];
-    int base[3];
-};
-
-// Exclusive prefix counts, in slot order, of three flags over kScanChunks consecutive 1024-slot chunks
-// (thread t holds slot c * 1024 + t of chunk c).  `base` carries the totals to the next round.
-__device__ __forceinline__ void block_scan3(ScanState &s, const bool (&f0)[kScanChunks], const bool (&f1)[kScanChunks],
-                                            const bool (&f2)[kScanChunks], int (&p0)[kScanChunks],
-                                            int (&p1)[kScanChunks], int (&p2)[kScanChunks]) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const unsigned long long below = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int c = 0; c < kScanChunks; ++c) {
-        const unsigned long long b0 = __ballot(f0[c]), b1 = __ballot(f1[c]), b2 = __ballot(f2[c]);
-        p0[c] = __popcll(b0 & below);
-        p1[c] = __popcll(b1 & below);
-        p2[c] = __popcll(b2 & below);
-        if (lane == 0) {
-            s.wave_cnt[0][c][wave] = __popcll(b0);
-            s.wave_cnt[1][c][wave] = __popcll(b1);
-            s.wave_cnt[2][c][wave] = __popcll(b2);
-        }
-    }
-    __syncthreads();
-    if (tid < 3 * kScanChunks) {
-        const int k = tid / kScanChunks, c = tid % kScanChunks;
-        int run = 0;
-        for (int w = 0; w < 16; ++w) {
-            const int v = s.wave_cnt[k][c][w];
-            s.wave_cnt[k][c][w] = run;
-            run += v;
-        }
-        s.tot[k][c] = run;
-    }
-    __syncthreads();
-    int run0 = s.base[0], run1 = s.base[1], run2 = s.base[2];
-#pragma unroll
-    for (int c = 0; c < kScanChunks; ++c) {
-        p0[c] += run0 + s.wave_cnt[0][c][wave];
-        p1[c] += run1 + s.wave_cnt[1][c][wave];
-        p2[c] += run2 + s.wave_cnt[2][c][wave];
-        run0 += s.tot[0][c];
-        run1 += s.tot[1][c];
-        run2 += s.tot[2][c];
-    }
-    __syncthreads();
-    if (tid == 0) {
-        s.base[0] = run0;
-        s.base[1] = run1;
-        s.base[2] = run2;
-    }
-    __syncthreads();
-}
+constexpr int kDigitBits = 9;     // radix digit width: three passes cover 27 differing key bits
+constexpr int kBins = 1 << kDigitBits;
+constexpr int kSub = 2;           // copies of every histogram bin (lane % kSub picks one): scores of one head
+                                  // may crowd into few digits, and LDS atomics on one address go one at a time
+constexpr int kChunkMax = 17;     // most chunks (one slot per thread each) numbered per round of the slot-order pass
 
 // Exact fixed-point mass of a candidate, from its order-preserving key alone: keys with the top bit set
 // are the non-negative scores (bit pattern = key without that bit); negative scores and NaN weigh 0.
@@ -105,32 +55,37 @@ __device__ __forceinline__ unsigned long long key_mass(uint32_t key) {
 }
 
 struct SelectShared {
-    unsigned long long hist_m[kBins];
-    unsigned int hist_c[kBins];
-    unsigned long long total, need, need_next;
-    unsigned int ncand, cabove, digit;
+    unsigned long long hist_m[2][kBins][kSub];   // two histograms: one is cleared while the other is in use
+    unsigned int hist_c[2][kBins][kSub];
+    unsigned long long need_next, last_m;
+    unsigned int cabove, digit, last_c;
     int first_hole;
-    ScanState scan;
     unsigned long long w_best[16];   // per-wave partial results of the block reductions
     unsigned long long w_mass[16];
     uint32_t w_min[16], w_max[16];
     int w_cnt[16];
+    int cnt[2][kChunkMax * 16 + 1];  // slot-order pass: per (chunk, wave) counts of two flags, then their
+                                     // exclusive prefixes in (chunk, wave) order; last element: the total
 };
 
 // Wave 0, after a histogram pass: suffix sums over the digits give the mass (and count) above each
 // digit; the digit in which the quota `need` (> 0, at most the mass in the histogram) is met becomes the
 // next digit of the key.
-__device__ __forceinline__ void pick_digit(SelectShared &sh, unsigned long long need) {
+__device__ __forceinline__ void pick_digit(SelectShared &sh, int cur, unsigned long long need, bool count_only) {
     const int lane = threadIdx.x & 63;
-    constexpr int PER = kBins / 64;     // lane owns 4 consecutive digits
+    constexpr int PER = kBins / 64;     // lane owns PER consecutive digits
     unsigned long long loc_m = 0ull;
     unsigned int loc_c = 0u;
     unsigned long long hm[PER];
     unsigned int hc[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
-        hm[i] = sh.hist_m[PER * lane + i];
-        hc[i] = sh.hist_c[PER * lane + i];
+        hm[i] = 0ull;
+        hc[i] = 0u;
+        static_assert(kSub == 2, "two copies are added here");
+        if (!count_only) hm[i] = sh.hist_m[cur][PER * lane + i][0] + sh.hist_m[cur][PER * lane + i][1];
+        hc[i] = sh.hist_c[cur][PER * lane + i][0] + sh.hist_c[cur][PER * lane + i][1];
+        if (count_only) hm[i] = hc[i];
         loc_m += hm[i];
         loc_c += hc[i];
     }
@@ -153,61 +108,84 @@ __device__ __forceinline__ void pick_digit(SelectShared &sh, unsigned long long 
             sh.digit = (unsigned int)(PER * lane + i);
             sh.need_next = need - above_m;
             sh.cabove += above_c;     // exactly one lane and one digit take this branch
+            sh.last_m = hm[i];
+            sh.last_c = hc[i];
         }
         above_m += hm[i];
         above_c += hc[i];
     }
 }
 
-// One round of the slot-order pass over kScanChunks chunks of 1024 slots: numbers the survivors (STABLE)
-// or the holes and the tail survivors (FILL) and writes the slot lists.
-__device__ __forceinline__ void number_round(SelectShared &sh, bool stable, const bool (&tie)[kScanChunks],
-                                             const bool (&keep)[kScanChunks], const bool (&inside)[kScanChunks],
-                                             const int (&slot)[kScanChunks], unsigned long long tie_keep, int n_new,
-                                             int32_t *list_a, int32_t *list_b, int &first_hole) {
-    bool none[kScanChunks];
+// Slot-order numbering of two flags over NCH chunks of NT slots (thread t holds slot NT c + t of
+// chunk c; bit c of f0 / f1 is its flag).  Returns in e0[c] / e1[c] the number of flagged slots before
+// the thread's slot of chunk c within this round (packed: flag 0 in the low, flag 1 in the high 16 bits;
+// a round has fewer than 2^16 slots), and the round totals.  Every wave files its ballots'
+// counts, waves 0 and 1 turn the two NCH x NT/64 tables into exclusive prefixes, every thread adds the lanes below it.
+// Two barriers; the table may be reused after one more barrier.
+template <int NCH, int NT>
+__device__ __forceinline__ void chunk_scan2(SelectShared &sh, uint32_t f0, uint32_t f1, uint32_t (&e)[NCH], int &t0,
+                                            int &t1) {
+    static_assert(NCH * NT < 65536, "packed counts need 16 bits");
+    constexpr int NW = NT / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
-    for (int c = 0; c < kScanChunks; ++c) none[c] = false;
-    int tie_before[kScanChunks], p1[kScanChunks], p2[kScanChunks];
-    if (stable) {
-        // survivors before a slot = sure survivors before it + kept ties before it
-        block_scan3(sh.scan, tie, keep, none, tie_before, p1, p2);
-#pragma unroll
-        for (int c = 0; c < kScanChunks; ++c) {
-            if (!inside[c]) continue;
-            const bool kept = keep[c] || (tie[c] && (unsigned long long)tie_before[c] < tie_keep);
-            const int p = p1[c] + (int)min((unsigned long long)tie_before[c], tie_keep);
-            if (kept) list_a[p] = slot[c];
-            else first_hole = min(first_hole, p);      // folded over the workgroup once, after the last round
-        }
-    } else {
-        block_scan3(sh.scan, tie, none, none, tie_before, p1, p2);
-        bool hole[kScanChunks], tail[kScanChunks];
-#pragma unroll
-        for (int c = 0; c < kScanChunks; ++c) {
-            const bool kept = keep[c] || (tie[c] && (unsigned long long)tie_before[c] < tie_keep);
-            hole[c] = inside[c] && !kept && slot[c] < n_new;
-            tail[c] = inside[c] && kept && slot[c] >= n_new;
-        }
-        int dummy[kScanChunks], hi[kScanChunks], ti[kScanChunks];
-        // a second scan numbers holes and tail survivors (counter 0 keeps counting ties)
-        block_scan3(sh.scan, none, hole, tail, dummy, hi, ti);
-#pragma unroll
-        for (int c = 0; c < kScanChunks; ++c) {
-            if (hole[c]) list_a[hi[c]] = slot[c];
-            if (tail[c]) list_b[ti[c]] = slot[c];
+    for (int c = 0; c < NCH; ++c) {
+        const unsigned long long b0 = __ballot((f0 >> c) & 1u), b1 = __ballot((f1 >> c) & 1u);
+        e[c] = (uint32_t)__popcll(b0 & below) | ((uint32_t)__popcll(b1 & below) << 16);
+        if (lane == 0) {
+            sh.cnt[0][NW * c + wave] = __popcll(b0);
+            sh.cnt[1][NW * c + wave] = __popcll(b1);
         }
     }
+    __syncthreads();
+    if (wave < 2) {
+        // wave k scans table k: lane owns PER consecutive entries
+        constexpr int N = NCH * NW;
+        constexpr int PER = (N + 63) / 64;
+        int *tab = sh.cnt[wave];
+        int v[PER];
+        int sum = 0;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int idx = PER * lane + i;
+            v[i] = idx < N ? tab[idx] : 0;
+            sum += v[i];
+        }
+        int inc = sum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int u = __shfl_up(inc, o);
+            if (lane >= o) inc += u;
+        }
+        int run = inc - sum;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int idx = PER * lane + i;
+            if (idx < N) tab[idx] = run;
+            run += v[i];
+        }
+        if (lane == 63) tab[N] = inc;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        e[c] += (uint32_t)sh.cnt[0][NW * c + wave] | ((uint32_t)sh.cnt[1][NW * c + wave] << 16);
+    }
+    t0 = sh.cnt[0][NCH * NW];
+    t1 = sh.cnt[1][NCH * NW];
 }
 
-// KPT > 0: every thread keeps the keys of its KPT slots (slot = 1024 i + thread) in registers, so the
-// scores are read once, with all loads in flight together; heads longer than 1024 KPT are not accepted
+// NT threads per head.  KPT > 0: every thread keeps the keys of its KPT slots (slot = NT i + thread) in
+// registers, so the scores are read once, with all loads in flight together; heads longer than NT KPT are not accepted
 // by the launch.  KPT == 0: any length, scores re-read from memory in every pass.
-template <int KPT>
-__global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
+template <int KPT, int NT>
+__global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
+    constexpr int NW = NT / 64;
     __shared__ SelectShared sh;
     constexpr int NREG = KPT > 0 ? KPT : 1;
-    constexpr int NROUND = (NREG + kScanChunks - 1) / kScanChunks;
+    constexpr int CH = KPT > 0 ? KPT : 16;       // slots per thread in one round of the slot-order pass
+    static_assert(CH <= kChunkMax, "count table too small");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hg = blockIdx.x;
@@ -215,14 +193,14 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
     const float *score = a.score + base;
     const uint8_t *kind = a.kind + base;
     int L = min(a.len[hg], a.Lmax);
-    if (KPT > 0) L = min(L, 1024 * KPT);
+    if (KPT > 0) L = min(L, NT * KPT);
     const bool budget_mode = a.mode == LVLM_KV_BUDGET;
 
     auto nothing_to_do = [&]() {
         if (tid == 0) {
             if (a.n_evicted) a.n_evicted[hg] = 0;
             a.meta[2 * hg] = L;
-            a.meta[2 * hg + 1] = L;
+            a.meta[2 * hg + 1] = a.fill_external ? 0 : L;
         }
     };
     if ((budget_mode && L <= a.budget) || (!budget_mode && !(a.beta < 1.0)) || L <= 0) {
@@ -234,7 +212,7 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         return budget_mode ? (kd != LVLM_KIND_PROTECTED && slot < recent_lo) : (kd == LVLM_KIND_IMAGE);
     };
 
-    // register-resident keys; bit i of `candm` marks slot 1024 i + tid as a candidate
+    // register-resident keys; bit i of `candm` marks slot NT i + tid as a candidate
     uint32_t key[NREG];
     uint32_t candm = 0u;
     if constexpr (KPT > 0) {
@@ -242,13 +220,13 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         uint8_t kd[NREG];
 #pragma unroll
         for (int i = 0; i < NREG; ++i) {
-            const int sl = min(1024 * i + tid, L - 1);     // clamped: every load is issued, none depends on another
+            const int sl = min(NT * i + tid, L - 1);     // clamped: every load is issued, none depends on another
             sc[i] = score[sl];
             kd[i] = kind[sl];
         }
 #pragma unroll
         for (int i = 0; i < NREG; ++i) {
-            const int slot = 1024 * i + tid;
+            const int slot = NT * i + tid;
             key[i] = score_key(sc[i]);
             if (slot < L && is_cand(slot, kd[i])) candm |= 1u << i;
         }
@@ -268,12 +246,12 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
                 if (candm & (1u << i)) {
                     ++cnt;
                     const unsigned long long c =
-                        ((unsigned long long)key[i] << 32) | (unsigned long long)(0xffffffffu - (uint32_t)(1024 * i + tid));
+                        ((unsigned long long)key[i] << 32) | (unsigned long long)(0xffffffffu - (uint32_t)(NT * i + tid));
                     best = c < best ? c : best;
                 }
             }
         } else {
-            for (int slot = tid; slot < L; slot += 1024) {
+            for (int slot = tid; slot < L; slot += NT) {
                 if (is_cand(slot, kind[slot])) {
                     ++cnt;
                     const unsigned long long c = ((unsigned long long)score_key(score[slot]) << 32) |
@@ -296,7 +274,7 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         best = sh.w_best[0];
         cnt = sh.w_cnt[0];
 #pragma unroll
-        for (int w = 1; w < 16; ++w) {
+        for (int w = 1; w < NW; ++w) {
             best = sh.w_best[w] < best ? sh.w_best[w] : best;
             cnt += sh.w_cnt[w];
         }
@@ -321,7 +299,7 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
             }
             if (tid == 0) {
                 a.meta[2 * hg] = last;
-                a.meta[2 * hg + 1] = last;
+                a.meta[2 * hg + 1] = a.fill_external ? 0 : last;
                 a.len[hg] = last;
                 if (a.n_evicted) a.n_evicted[hg] = 1;
             }
@@ -346,7 +324,7 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
             for (int i = 0; i < NREG; ++i)
                 if (candm & (1u << i)) see(key[i]);
         } else {
-            for (int slot = tid; slot < L; slot += 1024)
+            for (int slot = tid; slot < L; slot += NT)
                 if (is_cand(slot, kind[slot])) see(score_key(score[slot]));
         }
 #pragma unroll
@@ -365,7 +343,10 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         if (tid == 0) {
             sh.cabove = 0u;
             sh.first_hole = L;
-            sh.scan.base[0] = sh.scan.base[1] = sh.scan.base[2] = 0;
+        }
+        for (int i = tid; i < kBins * kSub; i += NT) {
+            (&sh.hist_m[0][0][0])[i] = 0ull;
+            (&sh.hist_c[0][0][0])[i] = 0u;
         }
         __syncthreads();
     }
@@ -373,7 +354,7 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
     int ncand = 0;
     uint32_t kmin = 0xffffffffu, kmax = 0u;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) {
+    for (int w = 0; w < NW; ++w) {
         total += sh.w_mass[w];
         ncand += sh.w_cnt[w];
         kmin = min(kmin, sh.w_min[w]);
@@ -400,39 +381,27 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
     // first (scores of one head share their leading bits, so the digits that are looked at spread over
     // the histogram instead of piling up in a few bins)
     const int hb = 32 - __clz((int)(kmin ^ kmax));     // bits below the common prefix (0: all keys equal)
-    const int n_pass = evict_all_cand ? 0 : (hb + 7) / 8;
+    const int n_pass = evict_all_cand ? 0 : (hb + kDigitBits - 1) / kDigitBits;
     uint32_t prefix = hb >= 32 ? 0u : (kmin >> hb) << hb;
     unsigned long long last_m = total;
     unsigned int last_c = (unsigned int)ncand;
     for (int pass = 0; pass < n_pass; ++pass) {
-        const int top = hb - 8 * pass;                 // bits still undecided
-        const int width = top < 8 ? top : 8;
+        const int top = hb - kDigitBits * pass;        // bits still undecided
+        const int width = top < kDigitBits ? top : kDigitBits;
         const int shift = top - width;
         const uint32_t dmask = (1u << width) - 1u;
-        for (int i = tid; i < kBins; i += 1024) {
-            sh.hist_m[i] = 0ull;
-            sh.hist_c[i] = 0u;
+        const int cur = pass & 1;
+        // the other histogram was last read before the barrier that ended the previous pass
+        for (int i = tid; i < kBins * kSub; i += NT) {
+            (&sh.hist_m[cur ^ 1][0][0])[i] = 0ull;
+            (&sh.hist_c[cur ^ 1][0][0])[i] = 0u;
         }
-        __syncthreads();
         {
-            // a thread first adds up runs of equal digits in registers and only then touches the shared
-            // histogram (fewer colliding LDS atomics)
-            uint32_t run_d = 0xffffffffu;
-            unsigned long long run_m = 0ull;
-            unsigned int run_c = 0u;
+            const int sub = lane & (kSub - 1);
             auto add = [&](uint32_t k) {
                 const uint32_t dgt = (k >> shift) & dmask;
-                if (dgt != run_d) {
-                    if (run_c) {
-                        atomicAdd(&sh.hist_m[run_d], run_m);
-                        atomicAdd(&sh.hist_c[run_d], run_c);
-                    }
-                    run_d = dgt;
-                    run_m = 0ull;
-                    run_c = 0u;
-                }
-                run_m += budget_mode ? 1ull : key_mass(k);
-                ++run_c;
+                if (!budget_mode) atomicAdd(&sh.hist_m[cur][dgt][sub], key_mass(k));   // budget: mass = count
+                atomicAdd(&sh.hist_c[cur][dgt][sub], 1u);
             };
             // keys that agree with the prefix in every bit above the current digit
             auto matches = [&](uint32_t k) { return pass == 0 || ((k ^ prefix) >> top) == 0u; };
@@ -441,27 +410,20 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
                 for (int i = 0; i < NREG; ++i)
                     if ((candm & (1u << i)) && matches(key[i])) add(key[i]);
             } else {
-                for (int slot = tid; slot < L; slot += 1024) {
+                for (int slot = tid; slot < L; slot += NT) {
                     if (!is_cand(slot, kind[slot])) continue;
                     const uint32_t k = score_key(score[slot]);
                     if (matches(k)) add(k);
                 }
             }
-            if (run_c) {
-                atomicAdd(&sh.hist_m[run_d], run_m);
-                atomicAdd(&sh.hist_c[run_d], run_c);
-            }
         }
         __syncthreads();
-        if (wave == 0) pick_digit(sh, need);
+        if (wave == 0) pick_digit(sh, cur, need, budget_mode);
         __syncthreads();
         prefix |= sh.digit << shift;
         need = sh.need_next;
-        if (pass == n_pass - 1) {
-            last_m = sh.hist_m[sh.digit];
-            last_c = sh.hist_c[sh.digit];
-        }
-        __syncthreads();
+        last_m = sh.last_m;
+        last_c = sh.last_c;
     }
     uint32_t kstar = 0xffffffffu;
     unsigned long long tie_keep = 0ull;
@@ -482,56 +444,80 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         return;
     }
 
-    // ---- one pass in slot order: number the survivors (STABLE) or holes / tail survivors (FILL)
+    // ---- one pass in slot order: number the survivors (STABLE) or holes / tail survivors (FILL).
+    // A round covers CH chunks of NT slots (all of them when the keys sit in registers); lanes hold
+    // neighbouring slots, so the list entries they write are neighbours too.
     int32_t *list_a = a.list_a + base;
     int32_t *list_b = a.list_b + base;
     const bool stable = a.order == LVLM_ORDER_STABLE;
     int first_hole = L;                  // lowest new slot whose entry moves (STABLE)
-    if constexpr (KPT > 0) {
+    int base_tie = 0, base_keep = 0, base_hole = 0, base_tail = 0;
+    for (int s0 = 0; s0 < L; s0 += NT * CH) {
+        uint32_t tiem = 0u, keepm = 0u;              // bit c: the thread's slot of chunk c is a tie / a sure survivor
 #pragma unroll
-        for (int r = 0; r < NROUND; ++r) {
-            if (r * kScanChunks * 1024 >= L) break;
-            bool tie[kScanChunks], keep[kScanChunks], inside[kScanChunks];
-            int slot[kScanChunks];
-#pragma unroll
-            for (int c = 0; c < kScanChunks; ++c) {
-                const int i = r * kScanChunks + c;
-                slot[c] = 1024 * i + tid;
-                inside[c] = slot[c] < L;
-                tie[c] = keep[c] = false;
-                if (i < NREG && inside[c]) {
-                    const uint32_t k = key[i < NREG ? i : 0];
-                    if (!(candm & (1u << i))) {
-                        keep[c] = true;
-                    } else {
-                        tie[c] = k == kstar;
-                        keep[c] = k > kstar;
-                    }
+        for (int c = 0; c < CH; ++c) {
+            const int slot = s0 + NT * c + tid;
+            if (slot < L) {
+                uint32_t k;
+                bool cand;
+                if constexpr (KPT > 0) {
+                    k = key[c < NREG ? c : 0];
+                    cand = (candm >> c) & 1u;
+                } else {
+                    cand = is_cand(slot, kind[slot]);
+                    k = score_key(score[slot]);
                 }
+                if (!cand || k > kstar) keepm |= 1u << c;
+                else if (k == kstar) tiem |= 1u << c;
             }
-            number_round(sh, stable, tie, keep, inside, slot, tie_keep, n_new, list_a, list_b, first_hole);
         }
-    } else {
-        for (int s0 = 0; s0 < L; s0 += kScanChunks * 1024) {
-            bool tie[kScanChunks], keep[kScanChunks], inside[kScanChunks];
-            int slot[kScanChunks];
+        uint32_t before[CH];                         // ties (low half) and sure survivors (high half) before the slot
+        int tot_tie, tot_keep;
+        chunk_scan2<CH, NT>(sh, tiem, keepm, before, tot_tie, tot_keep);
+        uint32_t keptm = 0u;
 #pragma unroll
-            for (int c = 0; c < kScanChunks; ++c) {
-                slot[c] = s0 + c * 1024 + tid;
-                inside[c] = slot[c] < L;
-                tie[c] = keep[c] = false;
-                if (inside[c]) {
-                    if (!is_cand(slot[c], kind[slot[c]])) {
-                        keep[c] = true;
-                    } else {
-                        const uint32_t k = score_key(score[slot[c]]);
-                        tie[c] = k == kstar;
-                        keep[c] = k > kstar;
-                    }
-                }
-            }
-            number_round(sh, stable, tie, keep, inside, slot, tie_keep, n_new, list_a, list_b, first_hole);
+        for (int c = 0; c < CH; ++c) {
+            const unsigned long long tb = (unsigned long long)(base_tie + (int)(before[c] & 0xffffu));
+            if (((keepm >> c) & 1u) || (((tiem >> c) & 1u) && tb < tie_keep)) keptm |= 1u << c;
         }
+        if (stable) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int slot = s0 + NT * c + tid;
+                if (slot >= L) continue;
+                // survivors before a slot = sure survivors before it + kept ties before it
+                const unsigned long long tb = (unsigned long long)(base_tie + (int)(before[c] & 0xffffu));
+                const int p = base_keep + (int)(before[c] >> 16) + (int)min(tb, tie_keep);
+                if ((keptm >> c) & 1u) list_a[p] = slot;
+                else first_hole = min(first_hole, p);
+            }
+        } else {
+            // holes (evicted, below the new length) and tail survivors (kept, at or beyond it) are
+            // numbered by a second scan
+            uint32_t holem = 0u, tailm = 0u;
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int slot = s0 + NT * c + tid;
+                if (slot >= L) continue;
+                const bool kept = (keptm >> c) & 1u;
+                if (!kept && slot < n_new) holem |= 1u << c;
+                if (kept && slot >= n_new) tailm |= 1u << c;
+            }
+            __syncthreads();                         // the count table is reused
+            int tot_hole, tot_tail;
+            chunk_scan2<CH, NT>(sh, holem, tailm, before, tot_hole, tot_tail);
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int slot = s0 + NT * c + tid;
+                if ((holem >> c) & 1u) list_a[base_hole + (int)(before[c] & 0xffffu)] = slot;
+                if ((tailm >> c) & 1u) list_b[base_tail + (int)(before[c] >> 16)] = slot;
+            }
+            base_hole += tot_hole;
+            base_tail += tot_tail;
+        }
+        base_tie += tot_tie;
+        base_keep += tot_keep;
+        __syncthreads();                             // the count table is reused by the next round
     }
     if (stable) {
 #pragma unroll
@@ -551,18 +537,27 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
     }
 
     // ---- FILL: sources (>= n_new) and destinations (< n_new) are disjoint
-    const int n_moves = sh.scan.base[1];
+    const int n_moves = base_hole;           // = base_tail: as many holes as tail survivors
+    if (a.fill_external) {
+        if (tid == 0) {
+            a.meta[2 * hg] = n_new;
+            a.meta[2 * hg + 1] = n_moves;
+            a.len[hg] = n_new;
+            if (a.n_evicted) a.n_evicted[hg] = n_evict;
+        }
+        return;
+    }
     const int units = a.row_bytes / 16;
     char *kc = a.k + base * a.row_bytes;
     char *vc = a.v + base * a.row_bytes;
-    for (int idx = tid; idx < n_moves * units; idx += 1024) {
+    for (int idx = tid; idx < n_moves * units; idx += NT) {
         const int i = idx / units, u = idx - i * units;
         const long long src = (long long)list_b[i] * a.row_bytes + 16 * u;
         const long long dst = (long long)list_a[i] * a.row_bytes + 16 * u;
         *reinterpret_cast<uint4 *>(kc + dst) = *reinterpret_cast<const uint4 *>(kc + src);
         *reinterpret_cast<uint4 *>(vc + dst) = *reinterpret_cast<const uint4 *>(vc + src);
     }
-    for (int i = tid; i < n_moves; i += 1024) {
+    for (int i = tid; i < n_moves; i += NT) {
         const int src = list_b[i], dst = list_a[i];
         a.score[base + dst] = a.score[base + src];
         a.kind[base + dst] = a.kind[base + src];
@@ -573,6 +568,54 @@ __global__ __launch_bounds__(1024) void kv_select_kernel(KvArgs a) {
         a.meta[2 * hg + 1] = n_new;
         a.len[hg] = n_new;
         if (a.n_evicted) a.n_evicted[hg] = n_evict;
+    }
+}
+
+constexpr int kFillInKernel = 64;  // most FILL moves per head that the selection kernel performs itself
+constexpr int kFillRows = 32;      // moves per workgroup of kv_fill_kernel (at most 4 row units per thread)
+
+// LVLM_ORDER_FILL with many moves per head: entry list_b[i] (at or beyond the new length) goes to hole
+// list_a[i] (below it).  Sources and destinations are disjoint, so the moves are independent.
+__global__ __launch_bounds__(256) void kv_fill_kernel(KvArgs a) {
+    const int tid = threadIdx.x;
+    const int hg = blockIdx.y;
+    const int n_moves = a.meta[2 * hg + 1];
+    const int i0 = blockIdx.x * kFillRows;
+    if (i0 >= n_moves) return;
+    const int cnt = min(kFillRows, n_moves - i0);
+    const long long base = (long long)hg * a.Lmax;
+    const int32_t *holes = a.list_a + base + i0;
+    const int32_t *tails = a.list_b + base + i0;
+    const int units = a.row_bytes / 16;
+    char *kc = a.k + base * a.row_bytes;
+    char *vc = a.v + base * a.row_bytes;
+    // rows have at most 32 units (fp32, 128 channels): 32 rows are at most 4 units per thread
+    const int n_units = cnt * units;
+    uint4 kv0, kv1, kv2, kv3, vv0, vv1, vv2, vv3;
+    long long d0, d1, d2, d3;
+#define LVLM_FILL_LOAD(x)                                                            \
+    {                                                                                \
+        const int idx = min(256 * x + tid, n_units - 1);                             \
+        const int i = idx / units, u = idx - i * units;                              \
+        const long long src = (long long)tails[i] * a.row_bytes + 16 * u;            \
+        d##x = (long long)holes[i] * a.row_bytes + 16 * u;                           \
+        kv##x = *reinterpret_cast<const uint4 *>(kc + src);                          \
+        vv##x = *reinterpret_cast<const uint4 *>(vc + src);                          \
+    }
+#define LVLM_FILL_STORE(x)                                    \
+    if (256 * x + tid < n_units) {                            \
+        *reinterpret_cast<uint4 *>(kc + d##x) = kv##x;        \
+        *reinterpret_cast<uint4 *>(vc + d##x) = vv##x;        \
+    }
+    LVLM_FILL_LOAD(0) LVLM_FILL_LOAD(1) LVLM_FILL_LOAD(2) LVLM_FILL_LOAD(3)
+    LVLM_FILL_STORE(0) LVLM_FILL_STORE(1) LVLM_FILL_STORE(2) LVLM_FILL_STORE(3)
+#undef LVLM_FILL_LOAD
+#undef LVLM_FILL_STORE
+    if (tid < cnt) {
+        const int src = tails[tid], dst = holes[tid];
+        a.score[base + dst] = a.score[base + src];
+        a.kind[base + dst] = a.kind[base + src];
+        a.pos[base + dst] = a.pos[base + src];
     }
 }
 
@@ -684,13 +727,17 @@ hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvW
     a.row_bytes = d.hd * (d.dtype == LVLM_BF16 ? 2 : 4);
     a.mode = d.mode; a.order = d.order; a.budget = d.budget; a.n_recent = d.n_recent; a.beta = d.beta;
     hipStream_t stream = prof.stream;
-    prof.begin("kv_select");
     const int bound = d.len_bound > 0 ? d.len_bound : d.Lmax;
-    if (bound <= 2048) hipLaunchKernelGGL(kv_select_kernel<2>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
-    else if (bound <= 4096) hipLaunchKernelGGL(kv_select_kernel<4>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
-    else if (bound <= 8192) hipLaunchKernelGGL(kv_select_kernel<8>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
-    else if (bound <= 17408) hipLaunchKernelGGL(kv_select_kernel<17>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
-    else hipLaunchKernelGGL(kv_select_kernel<0>, dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    // FILL moves at most min(new length, evicted entries) entries per head
+    const int max_moves = d.mode == LVLM_KV_BUDGET ? (bound - d.budget < bound / 2 ? bound - d.budget : bound / 2) : bound / 2;
+    a.fill_external = d.order == LVLM_ORDER_FILL && max_moves > kFillInKernel;
+    prof.begin("kv_select");
+    // (smaller workgroups with more keys per thread were measured for short heads: no faster)
+    if (bound <= 2048) hipLaunchKernelGGL((kv_select_kernel<2, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else if (bound <= 4096) hipLaunchKernelGGL((kv_select_kernel<4, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else if (bound <= 8192) hipLaunchKernelGGL((kv_select_kernel<8, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else if (bound <= 17408) hipLaunchKernelGGL((kv_select_kernel<17, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else hipLaunchKernelGGL((kv_select_kernel<0, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
     prof.end();
     if (d.order == LVLM_ORDER_STABLE) {
         prof.begin("kv_move");
@@ -701,6 +748,10 @@ hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvW
             hipLaunchKernelGGL((kv_move_kernel<1024, 64>), dim3(2 * s64 + 1, (unsigned)heads), dim3(1024), 0, stream, a);
         else
             hipLaunchKernelGGL((kv_move_kernel<1024, 32>), dim3(4 * s64 + 1, (unsigned)heads), dim3(1024), 0, stream, a);
+        prof.end();
+    } else if (a.fill_external) {
+        prof.begin("kv_fill");
+        hipLaunchKernelGGL(kv_fill_kernel, dim3((max_moves + kFillRows - 1) / kFillRows, (unsigned)heads), dim3(256), 0, stream, a);
         prof.end();
     }
     return hipGetLastError();
