@@ -12,7 +12,9 @@ Qwen2.5-VL-7B-shaped workload (config 2: 28 layers, 64 system + 2048 image +
       then lvlm_kv_compress (threshold beta = 0.995, stable order) of layer l's
       per-head cache;
   decode, one generated token: per layer lvlm_decode_attn (append + GQA
-      attention over the retained entries + importance update), then
+      attention over the retained entries + importance update) and the
+      fixed-budget eviction: inside the same call when the cache can be
+      exactly one entry over its budget (steady-state decode), else by
       lvlm_kv_compress (fixed budget, fill order).
 
 Inputs are resident in HBM before the timed region.  Every step works on its
@@ -160,10 +162,12 @@ def run_prefill(ctx, lv, w, states, reserve):
 def run_decode(ctx, lv, w, states, reserve, step_pos=0):
     for st in states:
         bound = min(st.Lmax, st.N + 1)
+        # a cache that can be at most one entry over its budget is compressed by the attention call itself
+        fused = w.kv_budget > 0 and bound == w.kv_budget + 1
         ctx.decode_attn(st.q_dec, st.k_dec, st.v_dec, st.k, st.v, st.score, st.kind, st.pos, st.len,
                         score_decay=0.9, new_pos=w.seq_len + step_pos, len_bound=bound, out=st.out_dec,
-                        reserve=reserve)
-        if w.kv_budget > 0:
+                        evict_budget=w.kv_budget if fused else 0, evict_recent=1, reserve=reserve)
+        if w.kv_budget > 0 and not fused:
             ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_BUDGET, budget=w.kv_budget,
                             n_recent=1, order=lv.ORDER_FILL, len_bound=bound, want_evicted=False, reserve=reserve)
 

@@ -285,6 +285,8 @@ typedef struct {
     int32_t new_pos;   /* orig_pos of the appended entry                            */
     float scale;       /* logit scale                                               */
     float score_decay; /* gamma in score <- gamma * score + mean_G(p)               */
+    int32_t evict_budget; /* > 0: per-step compression in the same call (see below)  */
+    int32_t evict_recent; /* the last evict_recent slots are never evicted           */
 } lvlm_attn_desc;
 
 /* Sec. 3.2.2: the current token attends only to the retained entries.
@@ -297,7 +299,17 @@ typedef struct {
  *   score_j <- score_decay * score_j + (1/G) * sum_{h in g} p_j^h,
  * continuing the received-attention definition of Sec. 3.2.1 into decoding.
  * kind / orig_pos may be NULL when nothing is appended.  A head with len 0
- * writes zeros.  Workspace: LVLM_OP_DECODE_ATTN. */
+ * writes zeros.
+ * Per-step cache compression (Sec. 3.2.2 in steady state): with evict_budget > 0
+ * (needs score, kind, orig_pos) a head whose length after the append exceeds
+ * evict_budget then loses ONE entry, chosen on the updated scores exactly as
+ * lvlm_kv_compress would with LVLM_KV_BUDGET, budget = that length - 1,
+ * n_recent = evict_recent, LVLM_ORDER_FILL: the least important entry that is
+ * not LVLM_KIND_PROTECTED and not among the last evict_recent slots (lowest
+ * score, highest slot among equals); the last entry moves into its slot and
+ * len drops by one.  A cache that is more than one entry over its budget
+ * (e.g. right after prefill) is brought down with lvlm_kv_compress first.
+ * Workspace: LVLM_OP_DECODE_ATTN. */
 LVLM_API lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *d,
                              const void *q, const void *k_new, const void *v_new,
                              void *k_cache, void *v_cache, float *score, uint8_t *kind,

@@ -64,7 +64,8 @@ class KvDesc(C.Structure):
 class AttnDesc(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("B", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32),
                 ("hd", C.c_int32), ("Lmax", C.c_int32), ("len_bound", C.c_int32), ("new_kind", C.c_int32),
-                ("new_pos", C.c_int32), ("scale", C.c_float), ("score_decay", C.c_float)]
+                ("new_pos", C.c_int32), ("scale", C.c_float), ("score_decay", C.c_float),
+                ("evict_budget", C.c_int32), ("evict_recent", C.c_int32)]
 
 
 class ProfileEntry(C.Structure):
@@ -287,13 +288,14 @@ class Context:
 
     # ---- step 6 ----
     def decode_attn(self, q, k_new, v_new, k_cache, v_cache, score, kind, orig_pos, length, *, scale=None,
-                    score_decay=1.0, new_kind=KIND_GENERATED, new_pos=0, len_bound=0, out=None, reserve=True):
+                    score_decay=1.0, new_kind=KIND_GENERATED, new_pos=0, len_bound=0, evict_budget=0, evict_recent=0,
+                    out=None, reserve=True):
         """lvlm_decode_attn.  q [B,Hq,d], k_new/v_new [B,Hkv,d] or None -> out [B,Hq,d]."""
         B, Hq, hd = q.shape
         _, Hkv, Lmax, _ = k_cache.shape
         assert q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous()
         d = AttnDesc(_DTYPE[q.dtype], B, Hq, Hkv, hd, Lmax, len_bound, new_kind, new_pos,
-                     float(hd ** -0.5 if scale is None else scale), float(score_decay))
+                     float(hd ** -0.5 if scale is None else scale), float(score_decay), evict_budget, evict_recent)
         if out is None:
             out = torch.empty_like(q)
         if reserve:

@@ -100,6 +100,7 @@ const char *check_attn(const lvlm_attn_desc *d) {
     if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
     if (d->len_bound < 0 || d->len_bound > d->Lmax) return "len_bound must be in [0, Lmax]";
     if (d->new_kind < 0 || d->new_kind > 255) return "new_kind out of range";
+    if (d->evict_budget < 0 || d->evict_recent < 0) return "evict_budget and evict_recent must not be negative";
     return nullptr;
 }
 
@@ -374,6 +375,8 @@ lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *
         return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: k_new and v_new must be given together");
     if (k_new && (!kind || !orig_pos))
         return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: kind and orig_pos are needed to append");
+    if (d->evict_budget > 0 && (!score || !kind || !orig_pos))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: score, kind and orig_pos are needed to evict");
     if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache) ||
         !aligned16(score) || !aligned16(kind) || !aligned16(orig_pos) || !aligned16(len) || !aligned16(out))
         return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: pointers must be 16-byte aligned");

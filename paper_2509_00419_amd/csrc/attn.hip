@@ -40,6 +40,7 @@ struct AttnArgs {
     float *logits;      // [B*Hkv][Lcap][GP]  log2-domain logits of every entry and head
     int32_t *cur_len;   // [B*Hkv]
     int Hq, Hkv, G, Lmax, Lcap, n_split, split_len, append, new_kind, new_pos, update_score;
+    int evict_budget, evict_recent;
     float scale_log2, decay;
 };
 
@@ -515,90 +516,204 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
 
 constexpr int kMaxSplit = 64;   // splits one combine workgroup can fold (checked on the host)
 
-// Workgroup x = 0 folds the splits into the output rows; workgroups x >= 1 each turn 1024 entries' logits
-// into normalised probabilities for the importance update.  All of them first rebuild the per-head
-// normalisers from the splits' (max, sum) pairs.
-template <int DT, int HD, int GP>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
-    __shared__ float s_pm[kMaxSplit][GP], s_pl[kMaxSplit][GP];   // per split: max, then weight exp2(m_s - M)
-    __shared__ float s_m[GP], s_inv[GP];
+template <int GP>
+struct CombineLds {
+    float pm[kMaxSplit][GP];    // per split: running max of each head
+    float pl[kMaxSplit][GP];    // per split: sum, then the split's weight exp2(m_s - M)
+    float m[GP], inv[GP];       // per head: max over the splits, 1 / normaliser
+};
+
+// Rebuilds the per-head normalisers of one (batch, KV head) from the splits' (max, sum) pairs.
+template <int GP, int NT>
+__device__ __forceinline__ void fold_normalisers(const AttnArgs &a, CombineLds<GP> &c, int hg) {
     const int tid = threadIdx.x;
-    const int g = blockIdx.y, b = blockIdx.z;
-    const int hg = b * a.Hkv + g;
-    const int L = a.cur_len[hg];
     const float *pml = a.part_ml + (long long)hg * a.n_split * GP * 2;
-    for (int i = tid; i < a.n_split * GP; i += 256) {
+    for (int i = tid; i < a.n_split * GP; i += NT) {
         const float2 ml = *reinterpret_cast<const float2 *>(pml + 2 * i);
-        s_pm[i / GP][i % GP] = ml.x;
-        s_pl[i / GP][i % GP] = ml.y;
+        c.pm[i / GP][i % GP] = ml.x;
+        c.pl[i / GP][i % GP] = ml.y;
     }
     __syncthreads();
     if (tid < GP) {
         float mx = -INFINITY;
-        for (int s = 0; s < a.n_split; ++s) mx = fmaxf(mx, s_pm[s][tid]);
+        for (int s = 0; s < a.n_split; ++s) mx = fmaxf(mx, c.pm[s][tid]);
         const float ms = (mx == -INFINITY) ? 0.f : mx;
         float l = 0.f;
         for (int s = 0; s < a.n_split; ++s) {
-            const float wgt = exp2f(s_pm[s][tid] - ms);
-            l += s_pl[s][tid] * wgt;
-            s_pl[s][tid] = wgt;                      // reused below as the split's weight
+            const float wgt = exp2f(c.pm[s][tid] - ms);
+            l += c.pl[s][tid] * wgt;
+            c.pl[s][tid] = wgt;                      // reused below as the split's weight
         }
-        s_m[tid] = ms;
-        s_inv[tid] = l > 0.f ? 1.0f / l : 0.f;
+        c.m[tid] = ms;
+        c.inv[tid] = l > 0.f ? 1.0f / l : 0.f;
     }
     __syncthreads();
+}
 
-    if (blockIdx.x == 0) {
-        const float *po = a.part_o + (long long)hg * a.n_split * GP * HD;
-        for (int idx = tid; idx < a.G * HD; idx += 256) {
-            const int h = idx / HD, e = idx % HD;
-            float acc = 0.f;
-            for (int s0 = 0; s0 < a.n_split; s0 += 8) {
-                float v[8];
+// Folds the splits' partial outputs into the output rows of the head group.
+template <int DT, int HD, int GP, int NT>
+__device__ __forceinline__ void write_output(const AttnArgs &a, const CombineLds<GP> &c, int b, int g, int hg) {
+    const int tid = threadIdx.x;
+    const float *po = a.part_o + (long long)hg * a.n_split * GP * HD;
+    for (int idx = tid; idx < a.G * HD; idx += NT) {
+        const int h = idx / HD, e = idx % HD;
+        float acc = 0.f;
+        for (int s0 = 0; s0 < a.n_split; s0 += 8) {
+            float v[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    v[u] = s0 + u < a.n_split ? po[((long long)(s0 + u) * GP + h) * HD + e] : 0.f;
+            for (int u = 0; u < 8; ++u)
+                v[u] = s0 + u < a.n_split ? po[((long long)(s0 + u) * GP + h) * HD + e] : 0.f;
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc += s0 + u < a.n_split ? v[u] * s_pl[s0 + u][h] : 0.f;
-            }
-            acc *= s_inv[h];
-            const long long oi = ((long long)b * a.Hq + g * a.G + h) * HD + e;
-            if constexpr (DT == LVLM_BF16)
-                reinterpret_cast<uint16_t *>(a.out)[oi] = f32_to_bf16(acc);
-            else
-                reinterpret_cast<float *>(a.out)[oi] = acc;
+            for (int u = 0; u < 8; ++u) acc += s0 + u < a.n_split ? v[u] * c.pl[s0 + u][h] : 0.f;
         }
-        if (tid == 0 && a.append) a.len[hg] = L;
-        return;
+        acc *= c.inv[h];
+        const long long oi = ((long long)b * a.Hq + g * a.G + h) * HD + e;
+        if constexpr (DT == LVLM_BF16)
+            reinterpret_cast<uint16_t *>(a.out)[oi] = f32_to_bf16(acc);
+        else
+            reinterpret_cast<float *>(a.out)[oi] = acc;
     }
+}
 
-    const int chunk = blockIdx.x - 1;
+// Importance update of the 1024 entries of one chunk, in two parts so that a caller can have the loads of
+// several chunks in flight before it needs the normalisers.
+template <int GP, int NT>
+struct ChunkRegs {
+    static constexpr int PER = 1024 / NT;     // entries per thread
+    float old[PER];
+    float lv[PER][GP];
+    uint8_t kd[PER];
+};
+
+template <int GP, bool EVICT, int NT>
+__device__ __forceinline__ void load_chunk(const AttnArgs &a, int hg, int L, int chunk, ChunkRegs<GP, NT> &r) {
+    const int tid = threadIdx.x;
+    const long long cbase = (long long)hg * a.Lmax;
+    const float *lg = a.logits + (long long)hg * a.Lcap * GP;
+#pragma unroll
+    for (int i = 0; i < 1024 / NT; ++i) {
+        const int j = chunk * 1024 + NT * i + tid;
+        r.old[i] = 0.f;
+        r.kd[i] = LVLM_KIND_PROTECTED;
+#pragma unroll
+        for (int h = 0; h < GP; ++h) r.lv[i][h] = 0.f;
+        if (j < L) {
+#pragma unroll
+            for (int h = 0; h < GP; ++h) r.lv[i][h] = lg[(long long)j * GP + h];
+            if (!(a.append && j == L - 1)) r.old[i] = a.score[cbase + j];
+            if (EVICT) r.kd[i] = a.kind[cbase + j];
+        }
+    }
+}
+
+// The stored logits become normalised probabilities.  With EVICT the least important evictable entry seen
+// so far is tracked in `best` (importance key in the high half, inverted slot in the low half: the minimum
+// is the lowest score, highest slot among equals).
+template <int GP, bool EVICT, int NT>
+__device__ __forceinline__ void apply_chunk(const AttnArgs &a, const CombineLds<GP> &c, int hg, int L, int chunk,
+                                            const ChunkRegs<GP, NT> &r, int recent_lo, unsigned long long &best) {
+    const int tid = threadIdx.x;
     const long long cbase = (long long)hg * a.Lmax;
     const float inv_g = 1.0f / (float)a.G;
-    const float *lg = a.logits + (long long)hg * a.Lcap * GP;
-    float old[4], pm[4];
-    float lv[4][GP];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int j = chunk * 1024 + 256 * i + tid;
-        old[i] = 0.f;
+    for (int i = 0; i < 1024 / NT; ++i) {
+        const int j = chunk * 1024 + NT * i + tid;
         if (j < L) {
-#pragma unroll
-            for (int h = 0; h < GP; ++h) lv[i][h] = lg[(long long)j * GP + h];
-            if (!(a.append && j == L - 1)) old[i] = a.score[cbase + j];
-        }
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int j = chunk * 1024 + 256 * i + tid;
-        if (j < L) {
-            pm[i] = 0.f;
+            float pm = 0.f;
 #pragma unroll
             for (int h = 0; h < GP; ++h)
-                if (h < a.G) pm[i] += exp2f(lv[i][h] - s_m[h]) * s_inv[h];
-            a.score[cbase + j] = a.decay * old[i] + pm[i] * inv_g;
+                if (h < a.G) pm += exp2f(r.lv[i][h] - c.m[h]) * c.inv[h];
+            const float ns = a.decay * r.old[i] + pm * inv_g;
+            a.score[cbase + j] = ns;
+            if (EVICT && r.kd[i] != LVLM_KIND_PROTECTED && j < recent_lo) {
+                const unsigned long long cand =
+                    ((unsigned long long)score_key(ns) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)j);
+                best = cand < best ? cand : best;
+            }
         }
     }
+}
+
+// Workgroup x = 0 folds the splits into the output rows; workgroups x >= 1 each update the importance of
+// 1024 entries.  All of them first rebuild the per-head normalisers.
+template <int DT, int HD, int GP>
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
+    __shared__ CombineLds<GP> c;
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int hg = b * a.Hkv + g;
+    const int L = a.cur_len[hg];
+    fold_normalisers<GP, 256>(a, c, hg);
+    if (blockIdx.x == 0) {
+        write_output<DT, HD, GP, 256>(a, c, b, g, hg);
+        if (threadIdx.x == 0 && a.append) a.len[hg] = L;
+        return;
+    }
+    unsigned long long unused = ~0ull;
+    ChunkRegs<GP, 256> r;
+    load_chunk<GP, false, 256>(a, hg, L, blockIdx.x - 1, r);
+    apply_chunk<GP, false, 256>(a, c, hg, L, blockIdx.x - 1, r, 0, unused);
+}
+
+// Per-step cache compression in the same launch as the fold (Sec. 3.2.2, steady state): one workgroup per
+// (batch, KV head) writes the output rows, updates every entry's importance, and, if the head is now
+// longer than evict_budget, evicts its least important evictable entry (not protected, not among the last
+// evict_recent slots): the last entry takes its slot, as LVLM_ORDER_FILL does.
+template <int DT, int HD, int GP>
+__global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a) {
+    constexpr int ROWB = HD * esize<DT>();
+    constexpr int NT = 1024;
+    __shared__ CombineLds<GP> c;
+    __shared__ unsigned long long w_best[NT / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int hg = b * a.Hkv + g;
+    const int L = a.cur_len[hg];
+    fold_normalisers<GP, NT>(a, c, hg);
+    write_output<DT, HD, GP, NT>(a, c, b, g, hg);
+    const bool evict = L > a.evict_budget;
+    const int recent_lo = evict ? L - a.evict_recent : 0;      // nothing is a candidate when nothing is evicted
+    unsigned long long best = ~0ull;
+    for (int chunk = 0; chunk * 1024 < L; ++chunk) {
+        ChunkRegs<GP, NT> r;
+        load_chunk<GP, true, NT>(a, hg, L, chunk, r);
+        apply_chunk<GP, true, NT>(a, c, hg, L, chunk, r, recent_lo, best);
+    }
+    int new_len = L;
+    if (evict) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const unsigned long long ob = __shfl_xor(best, o);
+            best = ob < best ? ob : best;
+        }
+        if (lane == 0) w_best[wave] = best;
+        __syncthreads();                                   // also orders the score stores above before the move below
+        best = w_best[0];
+#pragma unroll
+        for (int w = 1; w < NT / 64; ++w) best = w_best[w] < best ? w_best[w] : best;
+        if (best != ~0ull) {
+            const int victim = (int)(0xffffffffu - (uint32_t)(best & 0xffffffffull));
+            const int last = L - 1;
+            new_len = last;
+            if (victim != last) {
+                constexpr int UPR = ROWB / 16;
+                const long long cbase = (long long)hg * a.Lmax;
+                char *kc = a.k + cbase * ROWB;
+                char *vc = a.v + cbase * ROWB;
+                if (tid < UPR)
+                    *reinterpret_cast<uint4 *>(kc + (long long)victim * ROWB + 16 * tid) =
+                        *reinterpret_cast<const uint4 *>(kc + (long long)last * ROWB + 16 * tid);
+                else if (tid < 2 * UPR)
+                    *reinterpret_cast<uint4 *>(vc + (long long)victim * ROWB + 16 * (tid - UPR)) =
+                        *reinterpret_cast<const uint4 *>(vc + (long long)last * ROWB + 16 * (tid - UPR));
+                else if (tid == 2 * UPR) {
+                    a.score[cbase + victim] = a.score[cbase + last];
+                    a.kind[cbase + victim] = a.kind[cbase + last];
+                    a.pos[cbase + victim] = a.pos[cbase + last];
+                }
+            }
+        }
+    }
+    if (tid == 0 && (a.append || new_len != L)) a.len[hg] = new_len;
 }
 
 template <int DT, int HD, int GP>
@@ -610,6 +725,12 @@ void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
     else
         hipLaunchKernelGGL((attn_partial_kernel<DT, HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
     prof.end();
+    if (a.evict_budget > 0) {
+        prof.begin("attn_combine_evict");
+        hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP>), dim3(a.Hkv, B), dim3(1024), 0, stream, a);
+        prof.end();
+        return;
+    }
     const int chunks = a.update_score ? (len_bound + 1023) / 1024 : 0;
     prof.begin("attn_combine");
     hipLaunchKernelGGL((attn_combine_kernel<DT, HD, GP>), dim3(1 + chunks, a.Hkv, B), dim3(256), 0, stream, a);
@@ -678,6 +799,8 @@ hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const A
     a.append = k_new != nullptr;
     a.new_kind = d.new_kind; a.new_pos = d.new_pos;
     a.update_score = score != nullptr;
+    a.evict_budget = d.evict_budget;
+    a.evict_recent = d.evict_recent;
     a.scale_log2 = d.scale * kLog2e;
     a.decay = d.score_decay;
     const int gp = group_pad(G);

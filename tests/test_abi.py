@@ -30,7 +30,7 @@ def test_struct_sizes_match_the_header_layout():
     assert C.sizeof(bd.Plane) == 2 * 8 + 2 * 8 + 4 * 4
     assert C.sizeof(bd.MergeDesc) == 6 * 4
     assert C.sizeof(bd.KvDesc) == 10 * 4 + 8
-    assert C.sizeof(bd.AttnDesc) == 11 * 4
+    assert C.sizeof(bd.AttnDesc) == 13 * 4
 
 
 def test_schedule_helper_matches_oracle():

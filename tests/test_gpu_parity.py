@@ -327,6 +327,67 @@ def test_decode_attn_config4_layer_step(ctx):
                [1024] * (w.batch * w.n_kv_heads), 60, len_bound=1025)
 
 
+def _attn_evict_case(ctx, dtype, B, Hq, Hkv, d, Lmax, lens, budget, n_recent, seed, protected=4):
+    """decode_attn with evict_budget must equal decode_attn followed, for every head now longer than the budget,
+    by the oracle's budget eviction of exactly one entry (budget = length - 1, FILL order) decided on the GPU's
+    updated score bits."""
+    host = _cache(dtype, B, Hkv, Lmax, d, lens, seed, protected=protected)
+    q, kn, vn = _rand((B, Hq, d), dtype, seed + 5), _rand((B, Hkv, d), dtype, seed + 6), _rand((B, Hkv, d), dtype, seed + 7)
+    plain = [t.to(DEV) for t in host]
+    fused = [t.to(DEV) for t in host]
+    out_plain = ctx.decode_attn(q.to(DEV), kn.to(DEV), vn.to(DEV), *plain, score_decay=0.9, new_pos=77)
+    out_fused = ctx.decode_attn(q.to(DEV), kn.to(DEV), vn.to(DEV), *fused, score_decay=0.9, new_pos=77,
+                                evict_budget=budget, evict_recent=n_recent)
+    assert torch.equal(out_plain, out_fused)
+    mid = [t.cpu() for t in plain]
+    got = [t.cpu() for t in fused]
+    for b in range(B):
+        for h in range(Hkv):
+            n = int(mid[5][b, h])
+            one = [f64(mid[0][b:b + 1, h:h + 1]), f64(mid[1][b:b + 1, h:h + 1]), mid[2][b:b + 1, h:h + 1].numpy(),
+                   mid[3][b:b + 1, h:h + 1].numpy(), mid[4][b:b + 1, h:h + 1].numpy(), mid[5][b:b + 1, h:h + 1].numpy()]
+            if n > budget:
+                one = O.kv_compress(*one, mode="budget", budget=n - 1, n_recent=n_recent, order=O.ORDER_FILL)
+            m = int(one[5][0, 0])
+            assert int(got[5][b, h]) == m, (b, h, n, m)
+            assert np.array_equal(f64(got[0][b, h, :m]), one[0][0, 0, :m])
+            assert np.array_equal(f64(got[1][b, h, :m]), one[1][0, 0, :m])
+            assert np.array_equal(got[2][b, h, :m].numpy(), one[2][0, 0, :m])
+            assert np.array_equal(got[3][b, h, :m].numpy(), one[3][0, 0, :m])
+            assert np.array_equal(got[4][b, h, :m].numpy(), one[4][0, 0, :m])
+    return got[5].numpy()
+
+
+def test_decode_attn_with_step_eviction(ctx):
+    # heads at, one over, far over and under the budget; G = 7 and G = 1; fp32; a recent window
+    new_len = _attn_evict_case(ctx, torch.bfloat16, 2, 14, 2, 128, 1100, [1024, 1023, 1060, 300], 1024, 1, 110)
+    assert list(new_len.ravel()) == [1024, 1024, 1060, 301]
+    _attn_evict_case(ctx, torch.float32, 1, 4, 4, 64, 300, [256, 257, 10, 255], 256, 4, 111)
+    _attn_evict_case(ctx, torch.bfloat16, 1, 8, 2, 64, 5000, [4100, 2047], 2048, 0, 112)              # several chunks
+    # every entry protected except the appended one, which the recent window shields: nothing can go
+    new_len = _attn_evict_case(ctx, torch.bfloat16, 1, 2, 2, 128, 64, [40, 41], 8, 1, 113, protected=64)
+    assert list(new_len.ravel()) == [41, 42]
+    # config 4 at its real shape, three steps in a row on the same state
+    w = configs.CFG4
+    host = _cache(torch.bfloat16, w.batch, w.n_kv_heads, w.kv_budget + 8, w.head_dim, [w.kv_budget] * (w.batch * w.n_kv_heads),
+                  114, protected=256, image_only=True)
+    a_state = [t.to(DEV) for t in host]
+    b_state = [t.to(DEV) for t in host]
+    stream = synth.DecodeStream(w)
+    for t in range(3):
+        qt, kt, vt = (x.to(DEV) for x in stream.next())
+        oa = ctx.decode_attn(qt, kt, vt, *a_state, score_decay=0.9, new_pos=1024 + t, len_bound=w.kv_budget + 1)
+        ctx.kv_compress(*a_state, mode=lv.KV_BUDGET, budget=w.kv_budget, n_recent=1, order=lv.ORDER_FILL,
+                        len_bound=w.kv_budget + 1)
+        ob = ctx.decode_attn(qt, kt, vt, *b_state, score_decay=0.9, new_pos=1024 + t, len_bound=w.kv_budget + 1,
+                             evict_budget=w.kv_budget, evict_recent=1)
+        assert torch.equal(oa, ob)
+        assert torch.equal(a_state[5], b_state[5]) and int(b_state[5].max()) == w.kv_budget
+        n = w.kv_budget
+        for x, y in zip(a_state[:5], b_state[:5]):
+            assert torch.equal(x[:, :, :n], y[:, :, :n]), t
+
+
 def test_identity_cases_leave_decode_output_bit_identical(ctx):
     host = _cache(torch.bfloat16, 2, 2, 512, 128, [500, 200, 333, 512], 70)
     q = _rand((2, 14, 128), torch.bfloat16, 71).to(DEV)
