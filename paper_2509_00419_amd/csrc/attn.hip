@@ -637,21 +637,22 @@ __device__ __forceinline__ void apply_chunk(const AttnArgs &a, const CombineLds<
 // Workgroup x = 0 folds the splits into the output rows; workgroups x >= 1 each update the importance of
 // 1024 entries.  All of them first rebuild the per-head normalisers.
 template <int DT, int HD, int GP>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a) {
+__global__ __launch_bounds__(1024) void attn_combine_kernel(AttnArgs a) {
+    constexpr int NT = 1024;      // one entry or output element per thread: the kernel is a chain of latencies
     __shared__ CombineLds<GP> c;
     const int g = blockIdx.y, b = blockIdx.z;
     const int hg = b * a.Hkv + g;
     const int L = a.cur_len[hg];
-    fold_normalisers<GP, 256>(a, c, hg);
+    fold_normalisers<GP, NT>(a, c, hg);
     if (blockIdx.x == 0) {
-        write_output<DT, HD, GP, 256>(a, c, b, g, hg);
+        write_output<DT, HD, GP, NT>(a, c, b, g, hg);
         if (threadIdx.x == 0 && a.append) a.len[hg] = L;
         return;
     }
     unsigned long long unused = ~0ull;
-    ChunkRegs<GP, 256> r;
-    load_chunk<GP, false, 256>(a, hg, L, blockIdx.x - 1, r);
-    apply_chunk<GP, false, 256>(a, c, hg, L, blockIdx.x - 1, r, 0, unused);
+    ChunkRegs<GP, NT> r;
+    load_chunk<GP, false, NT>(a, hg, L, blockIdx.x - 1, r);
+    apply_chunk<GP, false, NT>(a, c, hg, L, blockIdx.x - 1, r, 0, unused);
 }
 
 // Per-step cache compression in the same launch as the fold (Sec. 3.2.2, steady state): one workgroup per
@@ -733,7 +734,7 @@ void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
     }
     const int chunks = a.update_score ? (len_bound + 1023) / 1024 : 0;
     prof.begin("attn_combine");
-    hipLaunchKernelGGL((attn_combine_kernel<DT, HD, GP>), dim3(1 + chunks, a.Hkv, B), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((attn_combine_kernel<DT, HD, GP>), dim3(1 + chunks, a.Hkv, B), dim3(1024), 0, stream, a);
     prof.end();
 }
 
