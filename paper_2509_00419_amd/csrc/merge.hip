@@ -24,6 +24,9 @@
 namespace lvlm {
 namespace {
 
+constexpr int kGatherWgs = 1536;   // workgroups the gather launch aims for (six per compute unit)
+
+
 constexpr int kRankTile = 8192;   // keys staged in LDS per step of the rank kernel (32 KB)
 constexpr int kRankBlock = 64;    // tokens ranked by one workgroup (one per lane; the 16 waves split the keys)
 
@@ -281,7 +284,11 @@ __device__ __forceinline__ void gather_plane(const GatherArgs &a, const PlaneDev
 
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
     const int pi = blockIdx.z / a.B, b = blockIdx.z % a.B;
-    const PlaneDev &p = a.plane[pi];
+    // (selected by comparison: indexing the argument array with a run-time value would copy it to scratch)
+    PlaneDev p = a.plane[0];
+#pragma unroll
+    for (int i = 1; i < LVLM_MAX_PLANES; ++i)
+        if (pi == i) p = a.plane[i];
     if (p.dtype == LVLM_BF16) {
         if (p.unit_bytes == 16) gather_plane<LVLM_BF16, 16>(a, p, pi, b);
         else if (p.unit_bytes == 4) gather_plane<LVLM_BF16, 4>(a, p, pi, b);
@@ -348,8 +355,9 @@ MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes) {
         if (planes[i].row_elems > max_elems) max_elems = planes[i].row_elems;
         units += ((long long)planes[i].row_elems * elem_bytes(planes[i].dtype) + 4095) / 4096;
     }
-    // about three workgroups per CU; longer chunks mean fewer partial sums to write and re-read
-    long long rows = (long long)d.N * d.B * (units ? units : 1) / 768;
+    // about six workgroups per CU (a workgroup waits out the memory latency of every batch of rows, so the
+    // overlap comes from its neighbours); longer chunks would mean fewer partial sums to write and re-read
+    long long rows = (long long)d.N * d.B * (units ? units : 1) / kGatherWgs;
     rows = rows / 4 * 4;
     w.rows_per_chunk = (int)(rows < 8 ? 8 : (rows > 128 ? 128 : rows));
     w.n_chunk = (d.N + w.rows_per_chunk - 1) / w.rows_per_chunk;
