@@ -301,7 +301,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 // bf16 variant on 16x16x32 MFMA tiles: a group has at most 8 query heads, so a 16-wide head axis wastes
 // half as much as a 32-wide one, and the accumulators (32 + 8 registers) leave room for three waves per
 // SIMD.  Lane = (l16, kg): for Q.K^T the A operand row is entry l16 of a 16-entry block and kg selects
-// the quarter of the head vector the lane contracts (the contraction index is free); the result holds
+// which 16 bytes of every 64-byte piece of the head vector the lane contracts (the contraction index is
+// free, and this numbering lets one load instruction read whole 64-byte pieces); the result holds
 // head l16 in column position and entries 4 kg + r in its 4 registers.  Those 8 probabilities per lane
 // (two blocks) are exactly one B operand of the P.V product when the contraction slot i of lane group kg
 // is numbered entry 16 (i/4) + 4 kg + i%4; V^T is read from the wave's LDS tile with the same numbering.
@@ -337,9 +338,11 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
             const int jk = min(j0 + 16 * blk + l16, a.Lmax - 1);
-            const char *ks = kc + (long long)jk * ROWB + kg * (ROWB / 4);
+            // contraction step i of lane group kg covers bytes [64 i + 16 kg, +16) of the row: the four lane
+            // groups of one load instruction read one contiguous 64-byte piece of each row
+            const char *ks = kc + (long long)jk * ROWB + 16 * kg;
 #pragma unroll
-            for (int i = 0; i < QV; ++i) kf[blk][i] = *reinterpret_cast<const uint4 *>(ks + 16 * i);
+            for (int i = 0; i < QV; ++i) kf[blk][i] = *reinterpret_cast<const uint4 *>(ks + 64 * i);
         }
 #pragma unroll
         for (int i = 0; i < VPL; ++i) {
@@ -351,9 +354,9 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
 
     uint4 qf[QV];
     if (l16 < a.G) {
-        const char *src = a.q + ((long long)b * a.Hq + g * a.G + l16) * ROWB + kg * (ROWB / 4);
+        const char *src = a.q + ((long long)b * a.Hq + g * a.G + l16) * ROWB + 16 * kg;
 #pragma unroll
-        for (int i = 0; i < QV; ++i) qf[i] = *reinterpret_cast<const uint4 *>(src + 16 * i);
+        for (int i = 0; i < QV; ++i) qf[i] = *reinterpret_cast<const uint4 *>(src + 64 * i);
     } else {
 #pragma unroll
         for (int i = 0; i < QV; ++i) qf[i] = make_uint4(0, 0, 0, 0);
@@ -391,9 +394,9 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk) {
                 if (j0 + 16 * blk + l16 == new_slot) {
-                    const char *kn = a.k_new + (long long)hg * ROWB + kg * (ROWB / 4);
+                    const char *kn = a.k_new + (long long)hg * ROWB + 16 * kg;
 #pragma unroll
-                    for (int i = 0; i < QV; ++i) kf[blk][i] = *reinterpret_cast<const uint4 *>(kn + 16 * i);
+                    for (int i = 0; i < QV; ++i) kf[blk][i] = *reinterpret_cast<const uint4 *>(kn + 64 * i);
                 }
             }
 #pragma unroll
