@@ -331,10 +331,10 @@ lvlm_status lvlm_merge_similar(lvlm_ctx *ctx, void *stream, const lvlm_merge_des
     if (!aligned16(score_mean) || !aligned16(size_in) || !aligned16(size_out) || !aligned16(keep_idx) ||
         !aligned16(assign))
         return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_similar: pointers must be 16-byte aligned");
-    if (!float_dtype(planes[0].dtype) || (planes[0].row_elems * elem_bytes(planes[0].dtype)) % 64 != 0 ||
+    if (!float_dtype(planes[0].dtype) || (planes[0].row_elems * elem_bytes(planes[0].dtype)) % 16 != 0 ||
         (planes[0].src_stride_b * elem_bytes(planes[0].dtype)) % 16 != 0)
         return fail(ctx, LVLM_ERR_UNSUPPORTED,
-                    "merge_similar: planes[0] must be bf16 or fp32 with rows that are a multiple of 64 bytes");
+                    "merge_similar: planes[0] must be bf16 or fp32 with rows that are a multiple of 16 bytes");
     const SimWs w = sim_ws(*d);
     if (lvlm_status st = need_ws(ctx, w.total)) return st;
     if (lvlm_status st = bind_device(ctx)) return st;

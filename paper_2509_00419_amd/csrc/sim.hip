@@ -109,13 +109,15 @@ __global__ __launch_bounds__(256) void sim_norm_kernel(SimArgs a) {
 
 // ---- dot products dominant x others on the matrix cores, arg-max over the dominant axis ----
 // Workgroup tile: 128 dominant rows x 128 other rows; wave (wn, wm) owns the 64 x 64 quadrant.  Rows are
-// gathered by index; the contraction runs over 64-byte slices of the rows, double buffered in LDS with
-// the next slice's global loads in flight (named scalars: they are carried around the loop).
+// gathered by index; the contraction runs over 128-byte slices of the rows (16 tile products per wave and
+// barrier), double buffered in LDS with the next slice's global loads in flight (named scalars: they are
+// carried around the loop).
 template <int DT>
 __global__ __launch_bounds__(256) void sim_gemm_kernel(SimArgs a) {
     constexpr int ES = esize<DT>();
-    constexpr int HS = 64 / ES;          // elements of one 64-byte slice
-    constexpr int PITCH = 80;            // 64-byte slice + 16 bytes: spreads the rows over the LDS banks
+    constexpr int SB = 128;              // bytes of one slice of a row
+    constexpr int HS = SB / ES;          // its elements
+    constexpr int PITCH = SB + 16;       // slice + 16 bytes: spreads the rows over the LDS banks
     __shared__ __attribute__((aligned(16))) char a_lds[2][128 * PITCH];
     __shared__ __attribute__((aligned(16))) char b_lds[2][128 * PITCH];
     __shared__ float invn[128];
@@ -131,23 +133,34 @@ __global__ __launch_bounds__(256) void sim_gemm_kernel(SimArgs a) {
     const int32_t *rest = a.rest_idx + (long long)b * a.r;
     const int row = tid >> 1, half = tid & 1;
     const char *img = p.src + (long long)b * p.src_stride_b + (long long)a.img_begin * p.row_bytes;
-    const char *pa = img + (long long)keep[min(nb * 128 + row, a.n_keep - 1)] * p.row_bytes + 32 * half;
-    const char *pb = img + (long long)rest[min(mb * 128 + row, a.r - 1)] * p.row_bytes + 32 * half;
+    const char *pa = img + (long long)keep[min(nb * 128 + row, a.n_keep - 1)] * p.row_bytes + 64 * half;
+    const char *pb = img + (long long)rest[min(mb * 128 + row, a.r - 1)] * p.row_bytes + 64 * half;
     if (tid < 128) invn[tid] = a.inv_norm[(long long)b * a.n + keep[min(nb * 128 + tid, a.n_keep - 1)]];
-    const int nk = p.row_bytes / 64;
+    const int nk = (p.row_bytes + SB - 1) / SB;      // the last slice may be partial: zero-filled
 
-    uint4 a0, a1, b0, b1;
+    uint4 a0, a1, a2, a3, b0, b1, b2, b3;
     auto load = [&](int k) {
-        a0 = *reinterpret_cast<const uint4 *>(pa + 64 * k);
-        a1 = *reinterpret_cast<const uint4 *>(pa + 64 * k + 16);
-        b0 = *reinterpret_cast<const uint4 *>(pb + 64 * k);
-        b1 = *reinterpret_cast<const uint4 *>(pb + 64 * k + 16);
+        const int room = p.row_bytes - SB * k - 64 * half;      // bytes of the row at and after this thread's piece
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        a0 = room >= 16 ? *reinterpret_cast<const uint4 *>(pa + SB * k) : z;
+        a1 = room >= 32 ? *reinterpret_cast<const uint4 *>(pa + SB * k + 16) : z;
+        a2 = room >= 48 ? *reinterpret_cast<const uint4 *>(pa + SB * k + 32) : z;
+        a3 = room >= 64 ? *reinterpret_cast<const uint4 *>(pa + SB * k + 48) : z;
+        b0 = room >= 16 ? *reinterpret_cast<const uint4 *>(pb + SB * k) : z;
+        b1 = room >= 32 ? *reinterpret_cast<const uint4 *>(pb + SB * k + 16) : z;
+        b2 = room >= 48 ? *reinterpret_cast<const uint4 *>(pb + SB * k + 32) : z;
+        b3 = room >= 64 ? *reinterpret_cast<const uint4 *>(pb + SB * k + 48) : z;
     };
     auto store = [&](int buf) {
-        *reinterpret_cast<uint4 *>(&a_lds[buf][row * PITCH + 32 * half]) = a0;
-        *reinterpret_cast<uint4 *>(&a_lds[buf][row * PITCH + 32 * half + 16]) = a1;
-        *reinterpret_cast<uint4 *>(&b_lds[buf][row * PITCH + 32 * half]) = b0;
-        *reinterpret_cast<uint4 *>(&b_lds[buf][row * PITCH + 32 * half + 16]) = b1;
+        char *da = &a_lds[buf][row * PITCH + 64 * half], *db = &b_lds[buf][row * PITCH + 64 * half];
+        *reinterpret_cast<uint4 *>(da) = a0;
+        *reinterpret_cast<uint4 *>(da + 16) = a1;
+        *reinterpret_cast<uint4 *>(da + 32) = a2;
+        *reinterpret_cast<uint4 *>(da + 48) = a3;
+        *reinterpret_cast<uint4 *>(db) = b0;
+        *reinterpret_cast<uint4 *>(db + 16) = b1;
+        *reinterpret_cast<uint4 *>(db + 32) = b2;
+        *reinterpret_cast<uint4 *>(db + 48) = b3;
     };
 
     f32x16 acc[2][2];
@@ -170,9 +183,9 @@ __global__ __launch_bounds__(256) void sim_gemm_kernel(SimArgs a) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                fa[t].v[i] = *reinterpret_cast<const uint4 *>(&a_lds[buf][(wn * 64 + t * 32 + l32) * PITCH + 32 * hf + 16 * i]);
-                fb[t].v[i] = *reinterpret_cast<const uint4 *>(&b_lds[buf][(wm * 64 + t * 32 + l32) * PITCH + 32 * hf + 16 * i]);
+            for (int i = 0; i < SB / 32; ++i) {
+                fa[t].v[i] = *reinterpret_cast<const uint4 *>(&a_lds[buf][(wn * 64 + t * 32 + l32) * PITCH + (SB / 2) * hf + 16 * i]);
+                fb[t].v[i] = *reinterpret_cast<const uint4 *>(&b_lds[buf][(wm * 64 + t * 32 + l32) * PITCH + (SB / 2) * hf + 16 * i]);
             }
         }
 #pragma unroll

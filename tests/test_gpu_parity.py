@@ -625,3 +625,4 @@ def test_merge_similar(ctx):
     _similar_case(ctx, torch.float32, 1, 0, 300, 0, 64, 1, 104)                                  # one dominant token
     _similar_case(ctx, torch.float32, 1, 2, 200, 2, 64, 200, 105)                                # nothing removed
     _similar_case(ctx, torch.bfloat16, 1, 1, 500, 1, 128, 130, 106, identical=True)              # all ties
+    _similar_case(ctx, torch.bfloat16, 1, 2, 150, 2, 72, 40, 107, clusters=4)                    # 144-byte rows: partial slice
