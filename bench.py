@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--merge", default="rank", choices=["rank", "similar"],
+                    help="merge rule at the pyramid layers: the paper's rank weights (lvlm_merge_compact) or the "
+                         "similarity merge (lvlm_merge_similar)")
     ap.add_argument("--profile-steps", type=int, default=3, help="eager steps timed per kernel with HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
@@ -104,6 +107,10 @@ class LayerState:
             self.pos_out = torch.empty(B, self.N - r, 3, dtype=torch.int32, device=self.q.device)
             self.keep_idx = torch.empty(B, max(entry["merge_to"] - 1, 1), dtype=torch.int32, device=self.q.device)
             self.merged_idx = torch.empty(B, r + 1, dtype=torch.int32, device=self.q.device)
+            # similarity merge: all n_keep dominant tokens are listed, every image token gets an assignment
+            self.dom_idx = torch.empty(B, entry["merge_to"], dtype=torch.int32, device=self.q.device)
+            self.assign = torch.empty(B, self.n_img, dtype=torch.int32, device=self.q.device)
+            self.size_out = torch.empty(B, entry["merge_to"], dtype=torch.float32, device=self.q.device)
         self.q_dec = m["q_dec"].clone()
         self.k_dec = m["k_dec"].clone()
         self.v_dec = m["v_dec"].clone()
@@ -140,7 +147,7 @@ def build_master(w, layers, torch, synth, dev):
     return master
 
 
-def run_prefill(ctx, lv, w, states, reserve):
+def run_prefill(ctx, lv, w, states, reserve, merge="rank"):
     for st in states:
         e = st.entry
         img0 = w.n_sys
@@ -149,7 +156,12 @@ def run_prefill(ctx, lv, w, states, reserve):
             sh_view = st.score[:, :, img0:img0 + st.n_img]          # scores land in the cache's score array
             ctx.score_tokens(st.q, k_view, q_pos0=img0 + st.n_img, img_begin=img0, n_img=st.n_img,
                              score_head=sh_view, score_mean=st.score_mean, reserve=reserve)
-        if e["merge_to"] is not None:
+        if e["merge_to"] is not None and merge == "similar":
+            ctx.merge_similar([st.hidden, st.pos_ids], st.score_mean, img_begin=img0, n_img=st.n_img,
+                              n_keep=e["merge_to"], rules=[lv.RULE_WEIGHTED, lv.RULE_TOP],
+                              outs=[st.hidden_out, st.pos_out], keep_idx=st.dom_idx, assign=st.assign,
+                              size_out=st.size_out, reserve=reserve)
+        elif e["merge_to"] is not None:
             ctx.merge_compact([st.hidden, st.pos_ids], st.score_mean, img_begin=img0, n_img=st.n_img,
                               n_keep=e["merge_to"], rules=[lv.RULE_WEIGHTED, lv.RULE_TOP],
                               outs=[st.hidden_out, st.pos_out], keep_idx=st.keep_idx, merged_idx=st.merged_idx,
@@ -173,7 +185,7 @@ def run_decode(ctx, lv, w, states, reserve, step_pos=0):
 
 
 # ----------------------------------------------------------------------------- algorithmic work per kernel
-def kernel_work(w, layers, lens_after_prefill):
+def kernel_work(w, layers, lens_after_prefill, merge="rank"):
     """Algorithmic bytes / flops of one launch-set of each kernel in one step (sum over layers)."""
     e = 2 if w.dtype == "bf16" else 4
     B, Hq, H, d, T = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_text
@@ -191,7 +203,10 @@ def kernel_work(w, layers, lens_after_prefill):
             add("score_pass1", "mfma", 2.0 * B * T * en["n_img"] * d * Hq)
         if en["merge_to"] is not None:
             r = en["n_img"] - en["merge_to"]
-            add("merge_gather", "hbm", B * (N + N - r) * (w.hidden * e + 3 * 4))
+            if merge == "similar":
+                add("sim_gemm", "mfma", 2.0 * B * r * en["merge_to"] * w.hidden)
+            else:
+                add("merge_gather", "hbm", B * (N + N - r) * (w.hidden * e + 3 * 4))
         L = float(lens_after_prefill[i].double().mean()) + 1.0 if lens_after_prefill is not None else N + 1
         add("attn_partial", "hbm", 2.0 * B * H * L * d * e)
     return work
@@ -221,7 +236,7 @@ def main():
           file=sys.stderr, flush=True)
 
     # dry run on set 0: sizes the workspace, gives the cache lengths used for the byte counts
-    run_prefill(ctx, lv, w, sets[0], reserve=True)
+    run_prefill(ctx, lv, w, sets[0], reserve=True, merge=args.merge)
     torch.cuda.synchronize()
     lens_after_prefill = [st.len.clone() for st in sets[0]]
     run_decode(ctx, lv, w, sets[0], reserve=True)
@@ -236,7 +251,7 @@ def main():
             gp, gd = torch.cuda.CUDAGraph() if has_prefill else None, torch.cuda.CUDAGraph()
             if has_prefill:
                 with torch.cuda.graph(gp):
-                    run_prefill(ctx, lv, w, sets[s], reserve=False)
+                    run_prefill(ctx, lv, w, sets[s], reserve=False, merge=args.merge)
             with torch.cuda.graph(gd):
                 run_decode(ctx, lv, w, sets[s], reserve=False)
             graphs.append((gp, gd))
@@ -249,7 +264,7 @@ def main():
             ev_mid[i].record()
             graphs[i][1].replay()
         else:
-            run_prefill(ctx, lv, w, sets[1 + i], reserve=False)
+            run_prefill(ctx, lv, w, sets[1 + i], reserve=False, merge=args.merge)
             ev_mid[i].record()
             run_decode(ctx, lv, w, sets[1 + i], reserve=False)
 
@@ -277,7 +292,7 @@ def main():
         ctx.profile(True)
         agg = {}
         for s in range(1 + n_run, n_sets):
-            run_prefill(ctx, lv, w, sets[s], reserve=False)
+            run_prefill(ctx, lv, w, sets[s], reserve=False, merge=args.merge)
             for name, (calls, tot, mn, mx) in ctx.profile_read().items():
                 a = agg.setdefault(name, [0, 0.0])
                 a[0] += calls
@@ -298,7 +313,7 @@ def main():
             dst.copy_(src)           # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
 
-    work = kernel_work(w, layers, lens_after_prefill)
+    work = kernel_work(w, layers, lens_after_prefill, args.merge)
     kernels = {}
     for name, p in sorted(prof.items(), key=lambda kv: -kv[1]["us_per_step"]):
         row = {"avg_us": round(p["avg_us"], 2), "launches_per_step": p["launches_per_step"],
@@ -335,7 +350,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(w, layers, master, torch, lv)
+        cpu = cpu_baseline(w, layers, master, torch, lv, args.merge)
 
     out = {
         "metric": "prefill merge tokens/s + compacted-KV decode steps/s; % HBM roofline",
@@ -347,7 +362,7 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "layers": w.layers, "seq": [w.n_sys, w.n_img, w.n_text],
                    "image_tokens_per_layer": [en["n_img"] for en in layers if en["merge_to"] is not None] +
                                              [layers[-1]["n_img"]],
-                   "kv_beta": w.kv_beta, "kv_budget": w.kv_budget, "graphs": use_graph},
+                   "kv_beta": w.kv_beta, "kv_budget": w.kv_budget, "merge": args.merge, "graphs": use_graph},
         "prefill_ms": round(prefill_ms, 4), "decode_step_ms": round(decode_ms, 4),
         "prefill_image_tokens_per_s": round(w.batch * w.n_img / (prefill_ms * 1e-3), 1),
         "decode_steps_per_s": round(1e3 / decode_ms, 1),
@@ -357,7 +372,7 @@ def main():
 
 
 # ----------------------------------------------------------------------------- oracle leg
-def cpu_baseline(w, layers, master, torch, lv):
+def cpu_baseline(w, layers, master, torch, lv, merge="rank"):
     """The oracle, as it stands, on one full step of the same inputs (host cores)."""
     import numpy as np
 
@@ -383,7 +398,10 @@ def cpu_baseline(w, layers, master, torch, lv):
             k = np.transpose(m["k"][:, :, :N], (0, 2, 1, 3))
             sh, sm = O.score_tokens(m["q"], k, q_pos0=img0 + en["n_img"], img_begin=img0, n_img=en["n_img"])
             m["score"][:, :, img0:img0 + en["n_img"]] = sh
-        if en["merge_to"] is not None:
+        if en["merge_to"] is not None and merge == "similar":
+            O.merge_similar([m["hidden"], m["pos_ids"]], sm, img_begin=img0, n_img=en["n_img"],
+                            n_keep=en["merge_to"], rules=[O.RULE_WEIGHTED, O.RULE_TOP], dtypes=[w.dtype, "f32"])
+        elif en["merge_to"] is not None:
             O.merge_compact([m["hidden"], m["pos_ids"]], sm, img_begin=img0, n_img=en["n_img"],
                             n_keep=en["merge_to"], rules=[O.RULE_WEIGHTED, O.RULE_TOP], dtypes=[w.dtype, "f32"])
         state = [m["k"], m["v"], m["score"].astype(np.float32), m["kind"], m["pos"], m["len"]]
