@@ -276,6 +276,43 @@ def test_kv_compress_every_length_class(ctx, order):
     _kv_case(ctx, torch.bfloat16, 1, 2, 3000, 64, [2999, 2500], 46, mode=lv.KV_BUDGET, budget=1700, order=order, flat=True)
 
 
+@pytest.mark.parametrize("order", [lv.ORDER_STABLE, lv.ORDER_FILL])
+def test_kv_compress_special_scores(ctx, order):
+    # NaN, negative, infinite, zero and tied scores: NaN ranks lowest and weighs nothing, negatives weigh
+    # nothing, +inf is clamped to 2^16 in the mass; both rules must still agree with the oracle bit for bit
+    B, H, Lmax, d = 1, 3, 700, 64
+    host = _cache(torch.bfloat16, B, H, Lmax, d, [700, 650, 333], 120)
+    g = torch.Generator().manual_seed(121)
+    sc = host[2]
+    pick = torch.randint(0, 8, sc.shape, generator=g)
+    sc[pick == 0] = float("nan")
+    sc[pick == 1] = -1.5
+    sc[pick == 2] = 0.0
+    sc[pick == 3] = -0.0
+    sc[pick == 4] = 0.125
+    sc[0, 1, 5] = float("inf")
+    sc[0, 2, 7] = float("-inf")
+    sc[0, 0, 9] = 3.0e5
+    for kw in (dict(mode=lv.KV_BUDGET, budget=400, n_recent=3), dict(mode=lv.KV_BUDGET, budget=300, n_recent=0),
+               dict(mode=lv.KV_THRESHOLD, beta=0.9), dict(mode=lv.KV_THRESHOLD, beta=0.5)):
+        dev = [t.clone().to(DEV) for t in host]
+        nev = ctx.kv_compress(*dev, order=order, **kw)
+        okw = dict(mode="threshold" if kw["mode"] == lv.KV_THRESHOLD else "budget", beta=kw.get("beta", 0.995),
+                   budget=kw.get("budget", 0), n_recent=kw.get("n_recent", 0), order=order)
+        ref = O.kv_compress(f64(host[0]), f64(host[1]), host[2].numpy(), host[3].numpy(), host[4].numpy(),
+                            host[5].numpy(), **okw)
+        new_len = dev[5].cpu().numpy()
+        assert np.array_equal(new_len, ref[5]), kw
+        assert np.array_equal(nev.cpu().numpy(), ref[6])
+        for h in range(H):
+            n = int(new_len[0, h])
+            assert np.array_equal(dev[4][0, h, :n].cpu().numpy(), ref[4][0, h, :n]), (kw, h)      # which entries, in order
+            assert np.array_equal(dev[3][0, h, :n].cpu().numpy(), ref[3][0, h, :n])
+            assert np.array_equal(f64(dev[0][0, h, :n]), ref[0][0, h, :n])
+            got, want = dev[2][0, h, :n].cpu().numpy(), ref[2][0, h, :n]
+            assert np.array_equal(np.isnan(got), np.isnan(want)) and np.array_equal(got[~np.isnan(got)], want[~np.isnan(want)])
+
+
 # --------------------------------------------------------------------------- step 6
 def _attn_case(ctx, dtype, B, Hq, Hkv, d, Lmax, lens, seed, append=True, decay=0.9, track=True, len_bound=0):
     host = _cache(dtype, B, Hkv, Lmax, d, lens, seed)
