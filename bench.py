@@ -9,13 +9,16 @@ Qwen2.5-VL-7B-shaped workload (config 2: 28 layers, 64 system + 2048 image +
       all keys of layer l, written straight into that layer's cache scores);
       at the pyramid layers 5 / 9 / 13: lvlm_merge_compact of the hidden states
       and position ids down to 100 % / 35 % / 3 % of the image tokens;
-      then lvlm_kv_compress (threshold beta = 0.995, stable order) of layer l's
-      per-head cache;
+  after the last layer: ONE lvlm_kv_compress (threshold beta = 0.995, stable
+      order) over the per-head caches of all layers l >= 5 -- the caches of
+      all layers are slices of one tensor, and a layer's cache is not read
+      again before decode, so the compression of 23 layers is one launch pair;
   decode, one generated token: per layer lvlm_decode_attn (append + GQA
       attention over the retained entries + importance update) and the
       fixed-budget eviction: inside the same call when the cache can be
-      exactly one entry over its budget (steady-state decode), else by
-      lvlm_kv_compress (fixed budget, fill order).
+      exactly one entry over its budget (steady-state decode), else by one
+      lvlm_kv_compress (fixed budget, fill order) over all layers' caches
+      after the last layer.
 
 Inputs are resident in HBM before the timed region.  Every step works on its
 own copy of the state (caches are modified in place), so no step re-reads
@@ -81,23 +84,66 @@ def plan(w, lv):
     return layers
 
 
-class LayerState:
-    """Device buffers of one decoder layer for one step."""
+EXTRA_SLOTS = 8     # free cache slots per head beyond the prefill length
 
-    def __init__(self, w, entry, master, torch, extra_slots=8):
+
+def cache_slots(w):
+    """Slots per head of every layer's cache (all layers alike, so that their caches stack into one tensor)."""
+    return w.n_sys + w.n_img + w.n_text + EXTRA_SLOTS
+
+
+class StepState:
+    """Device buffers of one step: the KV caches of all layers live in ONE tensor [layers*B, H, Lmax, d] (and
+    likewise scores, kinds, positions, lengths), so that one lvlm_kv_compress call can serve many layers;
+    every layer works on its own [B, ...] slice."""
+
+    def __init__(self, w, layers, master, torch):
+        B, H, d, L = w.batch, w.n_kv_heads, w.head_dim, cache_slots(w)
+        dev, dt = master[0]["k"].device, master[0]["k"].dtype
+        nl = len(layers)
+        self.k = torch.empty(nl * B, H, L, d, dtype=dt, device=dev)
+        self.v = torch.empty(nl * B, H, L, d, dtype=dt, device=dev)
+        self.score = torch.empty(nl * B, H, L, dtype=torch.float32, device=dev)
+        self.kind = torch.empty(nl * B, H, L, dtype=torch.uint8, device=dev)
+        self.pos = torch.empty(nl * B, H, L, dtype=torch.int32, device=dev)
+        self.len = torch.empty(nl * B, H, dtype=torch.int32, device=dev)
+        self.n_evicted = torch.empty(nl * B, H, dtype=torch.int32, device=dev)
+        self.layers = [LayerState(w, en, master, torch, self, i) for i, en in enumerate(layers)]
+        # the layers whose cache the threshold rule compresses after prefill: a contiguous tail of the stack
+        first = [i for i, en in enumerate(layers) if en["kv_threshold"]]
+        self.kv_from = first[0] * B if first else None
+        assert not first or first == list(range(first[0], nl)), "compressed layers must be the last ones"
+        self.kv_bound = max((st.N for st in self.layers[first[0]:]), default=0) if first else 0
+        self.dec_bound = max(min(L, st.N + 1) for st in self.layers)
+
+    def tail(self, t):
+        return t[self.kv_from:]
+
+    def __iter__(self):
+        return iter(self.layers)
+
+    def __getitem__(self, i):
+        return self.layers[i]
+
+
+class LayerState:
+    """Views and buffers of one decoder layer for one step."""
+
+    def __init__(self, w, entry, master, torch, step, index):
         B, H, d = w.batch, w.n_kv_heads, w.head_dim
         self.entry = entry
         self.n_img = entry["n_img"]
         self.N = w.n_sys + self.n_img + w.n_text
-        self.Lmax = self.N + extra_slots
+        self.Lmax = cache_slots(w)
         m = master[entry["layer"]]
+        sl = slice(index * B, (index + 1) * B)
         self.q = m["q"].clone()                                   # [B,T,Hq,d]
-        self.k = m["k"].clone()                                   # [B,H,Lmax,d] head-major cache
-        self.v = m["v"].clone()
-        self.score = m["score"].clone()
-        self.kind = m["kind"].clone()
-        self.pos = m["pos"].clone()
-        self.len = m["len"].clone()
+        self.k, self.v = step.k[sl], step.v[sl]                   # [B,H,Lmax,d] head-major cache (slice of the stack)
+        self.score, self.kind, self.pos, self.len = step.score[sl], step.kind[sl], step.pos[sl], step.len[sl]
+        self.n_evicted = step.n_evicted[sl]
+        for dst, name in ((self.k, "k"), (self.v, "v"), (self.score, "score"), (self.kind, "kind"), (self.pos, "pos"),
+                          (self.len, "len")):
+            dst.copy_(m[name])
         self.hidden = m["hidden"].clone() if "hidden" in m else None
         self.pos_ids = m["pos_ids"].clone() if "pos_ids" in m else None
         self.score_mean = torch.empty(B, self.n_img, dtype=torch.float32, device=self.q.device)
@@ -115,7 +161,6 @@ class LayerState:
         self.k_dec = m["k_dec"].clone()
         self.v_dec = m["v_dec"].clone()
         self.out_dec = torch.empty_like(self.q_dec)
-        self.n_evicted = torch.empty(B, H, dtype=torch.int32, device=self.q.device)
 
 
 def build_master(w, layers, torch, synth, dev):
@@ -126,7 +171,7 @@ def build_master(w, layers, torch, synth, dev):
         l, n_img = entry["layer"], entry["n_img"]
         x = synth.layer_inputs(w, layer=l, n_img=n_img, device=dev)
         N = x["k"].shape[1]
-        Lmax = N + 8
+        Lmax = cache_slots(w)
         m = {"q": x["q"]}
         for name in ("k", "v"):
             cache = torch.zeros(B, H, Lmax, d, dtype=x[name].dtype, device=dev)
@@ -166,22 +211,27 @@ def run_prefill(ctx, lv, w, states, reserve, merge="rank"):
                               n_keep=e["merge_to"], rules=[lv.RULE_WEIGHTED, lv.RULE_TOP],
                               outs=[st.hidden_out, st.pos_out], keep_idx=st.keep_idx, merged_idx=st.merged_idx,
                               reserve=reserve)
-        if e["kv_threshold"]:
-            ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_THRESHOLD, beta=w.kv_beta,
-                            order=lv.ORDER_STABLE, len_bound=st.N, n_evicted=st.n_evicted, reserve=reserve)
+    if states.kv_from is not None:
+        # the threshold rule on the caches of all compressed layers at once (a cache is only read again in decode)
+        t = states.tail
+        ctx.kv_compress(t(states.k), t(states.v), t(states.score), t(states.kind), t(states.pos), t(states.len),
+                        mode=lv.KV_THRESHOLD, beta=w.kv_beta, order=lv.ORDER_STABLE, len_bound=states.kv_bound,
+                        n_evicted=t(states.n_evicted), reserve=reserve)
 
 
 def run_decode(ctx, lv, w, states, reserve, step_pos=0):
+    # a cache that can be exactly one entry over its budget is compressed by the attention call itself
+    fused = w.kv_budget > 0 and states.dec_bound == w.kv_budget + 1
     for st in states:
         bound = min(st.Lmax, st.N + 1)
-        # a cache that can be at most one entry over its budget is compressed by the attention call itself
-        fused = w.kv_budget > 0 and bound == w.kv_budget + 1
         ctx.decode_attn(st.q_dec, st.k_dec, st.v_dec, st.k, st.v, st.score, st.kind, st.pos, st.len,
                         score_decay=0.9, new_pos=w.seq_len + step_pos, len_bound=bound, out=st.out_dec,
                         evict_budget=w.kv_budget if fused else 0, evict_recent=1, reserve=reserve)
-        if w.kv_budget > 0 and not fused:
-            ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_BUDGET, budget=w.kv_budget,
-                            n_recent=1, order=lv.ORDER_FILL, len_bound=bound, want_evicted=False, reserve=reserve)
+    if w.kv_budget > 0 and not fused:
+        # else one budget eviction over the caches of all layers (a layer's cache is next read in the next step)
+        ctx.kv_compress(states.k, states.v, states.score, states.kind, states.pos, states.len, mode=lv.KV_BUDGET,
+                        budget=w.kv_budget, n_recent=1, order=lv.ORDER_FILL, len_bound=states.dec_bound,
+                        want_evicted=False, reserve=reserve)
 
 
 # ----------------------------------------------------------------------------- algorithmic work per kernel
@@ -230,7 +280,7 @@ def main():
     t_setup = time.time()
     master = build_master(w, layers, torch, synth, dev)
     n_sets = 1 + args.warmup + args.steps + args.profile_steps
-    sets = [[LayerState(w, en, master, torch) for en in layers] for _ in range(n_sets)]
+    sets = [StepState(w, layers, master, torch) for _ in range(n_sets)]
     torch.cuda.synchronize()
     print(f"[bench] {w.name}: {len(layers)} layers, {n_sets} state sets, setup {time.time() - t_setup:.1f}s",
           file=sys.stderr, flush=True)
