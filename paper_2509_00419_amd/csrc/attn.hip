@@ -17,6 +17,8 @@
 //   attn_combine_kernel  folds the splits, writes the output rows, turns the
 //       logits into normalised probabilities for the importance update and
 //       publishes the new length.
+#include <type_traits>
+
 #include "common.h"
 #include "mma.h"
 
@@ -305,18 +307,23 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 // free, and this numbering lets one load instruction read whole 64-byte pieces); the result holds
 // head l16 in column position and entries 4 kg + r in its 4 registers.  Those 8 probabilities per lane
 // (two blocks) are exactly one B operand of the P.V product when the contraction slot i of lane group kg
-// is numbered entry 16 (i/4) + 4 kg + i%4; V^T is read from the wave's LDS tile with the same numbering.
-template <int HD, int GP>
-__global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
+// is numbered entry 16 (i/4) + 4 kg + i%4.  V never passes through LDS: lane (l16, kg) loads, for each of
+// those same 8 entries, the CPL = HD/16 consecutive channels [CPL l16, +CPL) -- 16 lanes read one whole
+// row, so the loads are as coalesced as a row copy -- and turns its 8 x CPL block around in registers
+// (byte permutes) into the CPL operands "8 entries of one channel".  Output block nb, row l16 is then
+// channel CPL l16 + nb.
+// MULTI: a wave may have several tiles (splits longer than 128 entries) and requests the next one while it
+// works on the current one.  With 128 channels the kernel is built for two workgroups per CU: squeezed
+// into the register budget of three it spills and measured slower.
+template <int HD, int GP, bool MULTI>
+__global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kernel(AttnArgs a) {
     constexpr int ROWB = HD * 2;
     constexpr int UPR = ROWB / 16;
-    constexpr int KSUB = 64 / UPR;
-    constexpr int VPL = 32 / KSUB;
     constexpr int QV = HD / 32;           // 16-byte words of a quarter row
-    constexpr int NB = HD / 16;           // 16-channel blocks of the output
-    constexpr int VPITCH = ROWB + 16;
+    constexpr int NB = HD / 16;           // output blocks = channels per lane (CPL)
+    constexpr int VW = NB / 2;            // 32-bit words of V per lane and entry
+    using vrow_t = typename std::conditional<VW == 4, uint4, uint2>::type;
 
-    __shared__ __attribute__((aligned(16))) char v_lds[4][32 * VPITCH];
     __shared__ float wm[4][GP], wl[4][GP];
     __shared__ __attribute__((aligned(16))) float wo[4][GP][HD];
 
@@ -326,13 +333,13 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
     const int hg = b * a.Hkv + g;
     const long long cbase = (long long)hg * a.Lmax;
     const char *kc = a.k + cbase * ROWB;
-    const char *vc = a.v + cbase * ROWB;
-    const int vunit = lane % UPR, vsub = lane / UPR;
+    const char *vc = a.v + cbase * ROWB + 2 * NB * l16;
     const int s_lo = split * a.split_len;
     const int j_first = s_lo + 32 * wave;
+    auto v_entry = [&](int s) { return 16 * (s >> 2) + 4 * kg + (s & 3); };   // entry (within the tile) of slot s
 
     uint4 kf[2][QV];
-    uint4 vv[VPL];
+    vrow_t vv[8];
     // Loads do not wait for the length: any slot below Lmax is readable, stale rows are masked later.
     auto load_tile = [&](int j0) {
 #pragma unroll
@@ -345,9 +352,9 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
             for (int i = 0; i < QV; ++i) kf[blk][i] = *reinterpret_cast<const uint4 *>(ks + 64 * i);
         }
 #pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int jv = min(j0 + vsub + KSUB * i, a.Lmax - 1);
-            vv[i] = *reinterpret_cast<const uint4 *>(vc + (long long)jv * ROWB + 16 * vunit);
+        for (int s = 0; s < 8; ++s) {
+            const int jv = min(j0 + v_entry(s), a.Lmax - 1);
+            vv[s] = *reinterpret_cast<const vrow_t *>(vc + (long long)jv * ROWB);
         }
     };
     if (j_first < a.Lmax) load_tile(j_first);
@@ -383,11 +390,10 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
     }
 
     float m_run = -INFINITY, l_run = 0.f;   // of head l16 (all four lane groups hold the same value)
-    f32x4 oacc[NB];                         // O^T block nb: channels 16 nb + 4 kg + r, head l16
+    f32x4 oacc[NB];                         // O^T block nb: channels NB (4 kg + r) + nb, head l16
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) oacc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    char *vt = &v_lds[wave][0];
     for (int j0 = j_first; j0 < s_hi; j0 += 128) {
         // the appended entry comes from k_new / v_new; rows beyond the range must not reach the MFMA
         if (j0 + 32 > s_hi || (new_slot >= j0 && new_slot < j0 + 32)) {
@@ -400,15 +406,29 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
                 }
             }
 #pragma unroll
-            for (int i = 0; i < VPL; ++i) {
-                const int j = j0 + vsub + KSUB * i;
-                if (j == new_slot) vv[i] = *reinterpret_cast<const uint4 *>(a.v_new + (long long)hg * ROWB + 16 * vunit);
-                if (j >= s_hi) vv[i] = make_uint4(0, 0, 0, 0);
+            for (int s = 0; s < 8; ++s) {
+                const int j = j0 + v_entry(s);
+                if (j == new_slot) vv[s] = *reinterpret_cast<const vrow_t *>(a.v_new + (long long)hg * ROWB + 2 * NB * l16);
+                if (j >= s_hi) vv[s] = vrow_t{};
             }
         }
+        // this tile's V block, turned around: vt[nb][m] = channel nb of entries 2m and 2m+1.  With several
+        // tiles per wave it is done now, before the next tile's loads overwrite vv; with one tile it waits
+        // until the logits are done, which keeps fewer registers alive at the same time.
+        uint32_t vt[NB][4];
+        auto turn = [&]() {
 #pragma unroll
-        for (int i = 0; i < VPL; ++i)
-            *reinterpret_cast<uint4 *>(vt + (vsub + KSUB * i) * VPITCH + 16 * vunit) = vv[i];
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t *ea = reinterpret_cast<const uint32_t *>(&vv[2 * m]);
+                const uint32_t *eb = reinterpret_cast<const uint32_t *>(&vv[2 * m + 1]);
+#pragma unroll
+                for (int w2 = 0; w2 < VW; ++w2) {
+                    vt[2 * w2][m] = __builtin_amdgcn_perm(eb[w2], ea[w2], 0x05040100u);       // low halves
+                    vt[2 * w2 + 1][m] = __builtin_amdgcn_perm(eb[w2], ea[w2], 0x07060302u);   // high halves
+                }
+            }
+        };
+        if (MULTI) turn();
 
         f32x4 acc[2];
 #pragma unroll
@@ -420,7 +440,7 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
                                                                    __builtin_bit_cast(bf16x8, qf[i]), acc[blk], 0, 0, 0);
         }
         // next tile's loads go out while this one is reduced (registers are free again)
-        if (j0 + 128 < s_hi) load_tile(j0 + 128);
+        if (MULTI && j0 + 128 < s_hi) load_tile(j0 + 128);
 
         float t[8];
         float tmax = -INFINITY;
@@ -457,34 +477,23 @@ __global__ __launch_bounds__(256, 3) void attn_partial_bf16_kernel(AttnArgs a) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) oacc[nb] *= alpha;
 
-        // the V tile is private to this wave: order the LDS traffic, no workgroup barrier
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (!MULTI) turn();
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-            uint32_t w[4];
-#pragma unroll
-            for (int i2 = 0; i2 < 4; ++i2) {
-                const int e0 = 16 * (i2 >> 1) + 4 * kg + 2 * (i2 & 1);      // slots 2 i2 and 2 i2 + 1
-                const uint32_t lo = *reinterpret_cast<const uint16_t *>(vt + e0 * VPITCH + 2 * (16 * nb + l16));
-                const uint32_t hi = *reinterpret_cast<const uint16_t *>(vt + (e0 + 1) * VPITCH + 2 * (16 * nb + l16));
-                w[i2] = lo | (hi << 16);
-            }
-            const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(w[0], w[1], w[2], w[3]));
+            const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(vt[nb][0], vt[nb][1], vt[nb][2], vt[nb][3]));
             oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, oacc[nb], 0, 0, 0);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 
     // ---- fold the four waves
     if (l16 < GP) {
+        // register r of block nb is channel NB (4 kg + r) + nb: for one r the NB blocks are neighbours
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-            *reinterpret_cast<float4 *>(&wo[wave][l16][16 * nb + 4 * kg]) =
-                make_float4(oacc[nb][0], oacc[nb][1], oacc[nb][2], oacc[nb][3]);
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int q4 = 0; q4 < NB / 4; ++q4)
+                *reinterpret_cast<float4 *>(&wo[wave][l16][NB * (4 * kg + r) + 4 * q4]) =
+                    make_float4(oacc[4 * q4][r], oacc[4 * q4 + 1][r], oacc[4 * q4 + 2][r], oacc[4 * q4 + 3][r]);
         if (kg == 0) {
             wm[wave][l16] = m_run;
             wl[wave][l16] = l_run;
@@ -725,7 +734,12 @@ void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
     hipStream_t stream = prof.stream;
     prof.begin("attn_partial");
     if constexpr (DT == LVLM_BF16)
-        hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
+    {
+        if (a.split_len > 128)
+            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, true>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
+        else
+            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, false>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
+    }
     else
         hipLaunchKernelGGL((attn_partial_kernel<DT, HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
     prof.end();
