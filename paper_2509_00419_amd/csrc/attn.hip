@@ -773,12 +773,15 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     AttnWs w{};
     const int bound = d.len_bound > 0 ? d.len_bound : d.Lmax;
     const long long heads = (long long)d.B * d.Hkv;
+    // As many splits as fit the chip in one round (two workgroups on each of 256 compute units), each at
+    // least one pass of the four waves (128 entries) and a whole number of 32-entry tiles; measured: a
+    // second, partly filled round costs more than longer splits do.
     const int max_split = (bound + 127) / 128;
-    long long want = (1024 + heads - 1) / heads;
+    long long want = 512 / heads;
     int n_split = (int)(want < 1 ? 1 : (want > max_split ? max_split : want));
     if (n_split > 64) n_split = 64;               // kMaxSplit of the combine kernel
-    if (n_split < 1) n_split = 1;
-    int split_len = ((bound + n_split - 1) / n_split + 127) / 128 * 128;
+    int split_len = ((bound + n_split - 1) / n_split + 31) / 32 * 32;
+    if (split_len < 128) split_len = 128;
     n_split = (bound + split_len - 1) / split_len;
     if (n_split < 1) n_split = 1;
     w.n_split = n_split;
