@@ -235,6 +235,16 @@ def run_decode(ctx, lv, w, states, reserve, step_pos=0):
 
 
 # ----------------------------------------------------------------------------- algorithmic work per kernel
+def score_in_one_launch(w, N):
+    """Whether the library scores a layer of N tokens with its one-launch kernel (short sequences) or with
+    the two-pass kernels.  Restates the library's launch rule, only to credit the flops to the right kernel
+    name; main() checks the launch counts it implies against the ones measured."""
+    e = 2 if w.dtype == "bf16" else 4
+    n_chunks = (w.n_q_heads // w.n_kv_heads * w.n_text + 31) // 32
+    wgs = w.batch * w.n_kv_heads * n_chunks
+    return n_chunks <= 32 and (wgs + 255) // 256 * N * (w.head_dim * e) // 256 <= 1100
+
+
 def kernel_work(w, layers, lens_after_prefill, merge="rank"):
     """Algorithmic bytes / flops of one launch-set of each kernel in one step (sum over layers)."""
     e = 2 if w.dtype == "bf16" else 4
@@ -249,8 +259,11 @@ def kernel_work(w, layers, lens_after_prefill, merge="rank"):
     for i, en in enumerate(layers):
         N = w.n_sys + en["n_img"] + T
         if en["score"]:
-            add("score_pass0", "mfma", 2.0 * B * T * N * d * Hq)
-            add("score_pass1", "mfma", 2.0 * B * T * en["n_img"] * d * Hq)
+            if score_in_one_launch(w, N):
+                add("score_single", "mfma", 2.0 * B * T * (N + en["n_img"]) * d * Hq)
+            else:
+                add("score_pass0", "mfma", 2.0 * B * T * N * d * Hq)
+                add("score_pass1", "mfma", 2.0 * B * T * en["n_img"] * d * Hq)
         if en["merge_to"] is not None:
             r = en["n_img"] - en["merge_to"]
             if merge == "similar":
@@ -370,6 +383,9 @@ def main():
                "us_per_step": round(p["us_per_step"], 1)}
         if name in work and p["us_per_step"] > 0:
             amt = work[name]["amount"]
+            if name.startswith("score_") and abs(p["launches_per_step"] - work[name]["launches"]) > 1e-9:
+                raise SystemExit(f"bench: {name} ran {p['launches_per_step']} times per step, the work model "
+                                 f"expects {work[name]['launches']}: score_in_one_launch() no longer matches the library")
             if work[name]["bound"] == "hbm":
                 row.update(bound="hbm", achieved_GBs=round(amt / p["us_per_step"] / 1e3, 1),
                            frac=round(amt / p["us_per_step"] / 1e3 / HBM_PEAK_GBS, 4))

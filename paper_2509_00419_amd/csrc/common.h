@@ -33,6 +33,7 @@ struct ScoreWs {
     int nkb;       // key blocks of the normaliser pass
     int block_keys;
     int rs, cps;   // row splits per key block, query chunks per split
+    bool single;   // short sequence: both passes in one launch, one part of column sums per query chunk
 };
 ScoreWs score_ws(const lvlm_score_desc &d);
 

@@ -281,6 +281,180 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     }
 }
 
+// ---- short sequences: both passes in one launch ---------------------------------------------------------
+// A workgroup owns ONE chunk of 32 query rows (held in registers as an MFMA operand by all four waves) and
+// sweeps over all keys twice: first for the row normalisers (online max / sum per row, folded over the
+// waves through LDS), then again over the image keys for the column sums.  Nothing but the final column
+// sums of the chunk leaves the workgroup, so the normaliser partials, their fold kernel and the second
+// launch disappear; the price is that every chunk streams the keys from L2 itself, which only pays while
+// the sequence is short (the launch decides by the bytes that re-streaming costs).  Wave w of NW takes the key
+// tiles 32 (w + NW k) .. +32; a tile's rows go straight from global memory into operand registers, the next
+// tile's loads are in flight while the current one is used (two named register sets).  All elements are
+// masked individually: these launches are bound by latency, not by arithmetic.
+#define LVLM_K16(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7) M(8) M(9) M(10) M(11) M(12) M(13) M(14) M(15)
+
+template <int DT, int HD, int NW>
+__global__ __launch_bounds__(64 * NW) void score_small_kernel(ScoreArgs a) {
+    constexpr int ES = esize<DT>();
+    constexpr int ROWB = HD * ES;
+    constexpr int NV = HalfRow<DT, HD>::NV;
+    constexpr int SW = 32 * NW;             // keys all waves take per sweep step
+    static_assert(NV <= 16, "operand registers are written out for up to 16 words");
+    __shared__ float wm[NW][32], wl[NW][32];
+    __shared__ float lse_s[32];
+    __shared__ int pos_s[32];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hf = lane >> 5, l32 = lane & 31;
+    const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int GT = a.G * a.T;
+    const long long rowbase = ((long long)b * a.Hq + (long long)g * a.G) * a.T;
+    auto div_t = [&](int rho) -> int { return a.T == 1 ? rho : (int)__umulhi((unsigned)rho, a.t_magic); };
+
+    // this lane's query row (padding rows repeat the last row and get an infinite LSE)
+    const int rho = c * 32 + l32;
+    const int rc = min(rho, GT - 1);
+    const int hl = div_t(rc), qi = rc - hl * a.T;
+    const int pos = a.causal ? a.q_pos0 + qi : INT_MAX;
+    HalfRow<DT, HD> qa;
+    {
+        const char *src = a.q + ((long long)b * a.qsb + (long long)qi * a.qst + (long long)(g * a.G + hl) * a.qsh) * ES +
+                          hf * (ROWB / 2);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) qa.v[i] = *reinterpret_cast<const uint4 *>(src + 16 * i);
+    }
+    if (tid < 32) pos_s[tid] = pos;
+
+    const char *kbase = a.k + ((long long)b * a.ksb + (long long)g * a.ksh) * ES + hf * (ROWB / 2);
+#define LVLM_DECL(x) uint4 kA##x = make_uint4(0, 0, 0, 0), kB##x = make_uint4(0, 0, 0, 0), kC##x = make_uint4(0, 0, 0, 0);
+    LVLM_K16(LVLM_DECL)
+#undef LVLM_DECL
+#define LVLM_LD(S, x) if (x < NV) S##x = *reinterpret_cast<const uint4 *>(kp_ + 16 * x);
+#define LVLM_LOADK(S, j0, jmax)                                                              \
+    {                                                                                        \
+        const char *kp_ = kbase + (long long)min((j0) + l32, (jmax) - 1) * a.ksn * ES;       \
+        LVLM_LD(S, 0) LVLM_LD(S, 1) LVLM_LD(S, 2) LVLM_LD(S, 3) LVLM_LD(S, 4) LVLM_LD(S, 5) LVLM_LD(S, 6) LVLM_LD(S, 7) \
+        LVLM_LD(S, 8) LVLM_LD(S, 9) LVLM_LD(S, 10) LVLM_LD(S, 11) LVLM_LD(S, 12) LVLM_LD(S, 13) LVLM_LD(S, 14) LVLM_LD(S, 15) \
+    }
+#define LVLM_PACK(S, kf)                                                                     \
+    {                                                                                        \
+        const uint4 w_[16] = {S##0, S##1, S##2, S##3, S##4, S##5, S##6, S##7, S##8, S##9, S##10, S##11, S##12, S##13, S##14, S##15}; \
+        _Pragma("unroll") for (int i = 0; i < NV; ++i) kf.v[i] = w_[i];                      \
+    }
+
+    // the first tile of the second sweep is fetched now: its latency hides behind the first sweep (where
+    // the operand registers allow a third set)
+    constexpr bool kEarly = NV <= 8;
+    const int key_lo = a.img_begin, key_hi = a.img_begin + a.n_img;
+    const int j2_first = key_lo + 32 * wave;
+    if (kEarly && j2_first < key_hi) LVLM_LOADK(kC, j2_first, key_hi)
+
+    // ---- sweep 1: row normalisers over all keys (rows = keys, columns = queries: the row's statistics are
+    // lane-local over 16 registers)
+    if (a.row_lse == nullptr) {
+        float m = -INFINITY, l = 0.f;
+        auto stats = [&](int j0, const HalfRow<DT, HD> &kf) {
+            f32x16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+            mma_tile<DT, HD>(acc, kf, qa);
+            float t[16];
+            float tmax = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = j0 + acc_row(r, hf);
+                t[r] = (j <= pos && j < a.N) ? acc[r] * a.scale_log2 : -INFINITY;
+                tmax = fmaxf(tmax, t[r]);
+            }
+            const float mn = fmaxf(m, tmax);
+            const float ms = (mn == -INFINITY) ? 0.f : mn;
+            float sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(t[r] - ms);   // exp2(-inf) = 0
+            l = l * __builtin_amdgcn_exp2f(m - ms) + sum;
+            m = mn;
+        };
+        const int j_first = 32 * wave;
+        if (j_first < a.N) LVLM_LOADK(kA, j_first, a.N)
+        for (int j0 = j_first; j0 < a.N; j0 += 2 * SW) {
+            HalfRow<DT, HD> kf;
+            if (j0 + SW < a.N) LVLM_LOADK(kB, j0 + SW, a.N)
+            LVLM_PACK(kA, kf)
+            stats(j0, kf);
+            if (j0 + SW >= a.N) break;
+            if (j0 + 2 * SW < a.N) LVLM_LOADK(kA, j0 + 2 * SW, a.N)
+            LVLM_PACK(kB, kf)
+            stats(j0 + SW, kf);
+        }
+        // the two lane halves, then the four waves
+        {
+            const float mo = __shfl_xor(m, 32), lo = __shfl_xor(l, 32);
+            const float mn = fmaxf(m, mo);
+            const float ms = (mn == -INFINITY) ? 0.f : mn;
+            l = l * __builtin_amdgcn_exp2f(m - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
+            m = mn;
+        }
+        if (hf == 0) {
+            wm[wave][l32] = m;
+            wl[wave][l32] = l;
+        }
+        __syncthreads();
+        if (tid < 32) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) mx = fmaxf(mx, wm[w][tid]);
+            const float ms = (mx == -INFINITY) ? 0.f : mx;
+            float tot = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) tot += wl[w][tid] * exp2f(wm[w][tid] - ms);
+            // no visible key, or a padding row: contributes nothing
+            lse_s[tid] = (tot > 0.f && rho < GT) ? mx + log2f(tot) : INFINITY;
+        }
+    } else if (tid < 32) {
+        lse_s[tid] = rho < GT ? a.row_lse[rowbase + rho] * kLog2e : INFINITY;
+    }
+    __syncthreads();
+
+    // ---- sweep 2: column sums over the image keys (rows = queries, columns = keys: a key's sum is lane-local)
+    float *out = a.colpart + (((long long)c * a.B + b) * a.Hkv + g) * a.n_img;
+    auto colsum = [&](int j0, const HalfRow<DT, HD> &kf) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        mma_tile<DT, HD>(acc, qa, kf);
+        const int j = j0 + l32;
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = acc_row(r, hf);
+            const float p = __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_s[row]));
+            sum += (j <= pos_s[row]) ? p : 0.f;
+        }
+        sum += __shfl_xor(sum, 32);
+        if (hf == 0 && j < key_hi) out[j - key_lo] = sum;
+    };
+    if (j2_first < key_hi) {
+        HalfRow<DT, HD> kf;
+        if (!kEarly) LVLM_LOADK(kC, j2_first, key_hi)
+        if (j2_first + SW < key_hi) LVLM_LOADK(kB, j2_first + SW, key_hi)
+        LVLM_PACK(kC, kf)
+        colsum(j2_first, kf);
+        for (int j0 = j2_first + SW; j0 < key_hi; j0 += 2 * SW) {      // tile j0 is in set B
+            if (j0 + SW < key_hi) LVLM_LOADK(kA, j0 + SW, key_hi)
+            LVLM_PACK(kB, kf)
+            colsum(j0, kf);
+            if (j0 + SW >= key_hi) break;
+            if (j0 + 2 * SW < key_hi) LVLM_LOADK(kB, j0 + 2 * SW, key_hi)
+            LVLM_PACK(kA, kf)
+            colsum(j0 + SW, kf);
+        }
+    }
+#undef LVLM_LD
+#undef LVLM_LOADK
+#undef LVLM_PACK
+}
+#undef LVLM_K16
+
 // Fold the per-block, per-wave (max, sum) pairs of each row into a log2-domain LSE.  Eight lanes share a
 // row: each folds every eighth pair online, then the eight partial (max, sum) states are merged.
 __global__ __launch_bounds__(256) void score_lse_kernel(const float *part_m, const float *part_l, float *lse2,
@@ -311,7 +485,8 @@ __global__ __launch_bounds__(256) void score_lse_kernel(const float *part_m, con
 }
 
 // score_head[b][g][j] = (sum over row splits of the column sums) / G;  score_mean[b][j] = mean over g.
-// Four heads x up to eight splits are loaded together so that the loads overlap.
+// Four heads x eight splits are loaded together so that the loads overlap; more splits take more rounds
+// (a fixed summation order either way).
 constexpr int kMaxRowSplit = 8;
 
 __global__ __launch_bounds__(256) void score_finalize_kernel(ScoreArgs a) {
@@ -322,22 +497,30 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(ScoreArgs a) {
     const long long split_stride = (long long)a.B * a.Hkv * a.n_img;
     float mean = 0.f;
     for (int g0 = 0; g0 < a.Hkv; g0 += 4) {
-        float v[4][kMaxRowSplit];
+        float tot[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int r0 = 0; r0 < a.rs; r0 += kMaxRowSplit) {
+            float v[4][kMaxRowSplit];
 #pragma unroll
-        for (int gg = 0; gg < 4; ++gg)
+            for (int gg = 0; gg < 4; ++gg)
 #pragma unroll
-            for (int r = 0; r < kMaxRowSplit; ++r) {
-                const bool on = g0 + gg < a.Hkv && r < a.rs;
-                const int gc = min(g0 + gg, a.Hkv - 1), rc = min(r, a.rs - 1);
-                const float x = a.colpart[rc * split_stride + ((long long)b * a.Hkv + gc) * a.n_img + j];
-                v[gg][r] = on ? x : 0.f;
+                for (int r = 0; r < kMaxRowSplit; ++r) {
+                    const bool on = g0 + gg < a.Hkv && r0 + r < a.rs;
+                    const int gc = min(g0 + gg, a.Hkv - 1), rc = min(r0 + r, a.rs - 1);
+                    const float x = a.colpart[rc * split_stride + ((long long)b * a.Hkv + gc) * a.n_img + j];
+                    v[gg][r] = on ? x : 0.f;
+                }
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+                float s = 0.f;
+#pragma unroll
+                for (int r = 0; r < kMaxRowSplit; ++r) s += v[gg][r];
+                tot[gg] += s;
             }
+        }
 #pragma unroll
         for (int gg = 0; gg < 4; ++gg) {
             if (g0 + gg >= a.Hkv) break;
-            float s = 0.f;
-#pragma unroll
-            for (int r = 0; r < kMaxRowSplit; ++r) s += v[gg][r];
+            float s = tot[gg];
             s *= inv_g;
             a.score_head[(long long)b * a.shb + (long long)(g0 + gg) * a.shh + j] = s;
             mean += s;
@@ -347,9 +530,18 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(ScoreArgs a) {
 }
 
 template <int DT, int HD, int KPW>
-void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse) {
+void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool single) {
     hipStream_t stream = prof.stream;
     constexpr int BN = 4 * KPW * 32;
+    if (single) {
+        prof.begin("score_single");
+        hipLaunchKernelGGL((score_small_kernel<DT, HD, 4>), dim3(a.rs, a.Hkv, a.B), dim3(256), 0, stream, a);
+        prof.end();
+        prof.begin("score_finalize");
+        hipLaunchKernelGGL(score_finalize_kernel, dim3((a.n_img + 255) / 256, a.B), dim3(256), 0, stream, a);
+        prof.end();
+        return;
+    }
     if (need_lse) {
         dim3 grid0(((a.N + BN - 1) / BN + 7) / 8 * 8 * a.rs, a.Hkv, a.B);
         prof.begin("score_pass0");
@@ -372,6 +564,10 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse) {
 
 }  // namespace
 
+constexpr int kSingleMaxChunks = 32;
+constexpr int kSingleMaxRowsPerCu = 1100;      // in 256-byte key rows
+constexpr int kCus = 256;
+
 ScoreWs score_ws(const lvlm_score_desc &d) {
     ScoreWs w{};
     // Wide key blocks (2 tiles per wave) once they still give every CU two workgroups.
@@ -387,6 +583,17 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
     if (rs < 1) rs = 1;
     w.cps = (n_chunks + rs - 1) / rs;
     w.rs = (n_chunks + w.cps - 1) / w.cps;
+    // Short sequences: one launch in which every query chunk streams the keys itself (twice).  Its time
+    // grows with the key rows a CU has to pull through its vector cache -- the workgroups a CU gets times
+    // the sequence length -- and it is taken while that stays below the point where the three launches it
+    // replaces cost more (measured).  The column sums then come in one part per chunk.
+    const long long single_wgs = (long long)d.B * d.Hkv * n_chunks;
+    const long long rows_per_cu = (single_wgs + kCus - 1) / kCus * d.N * (d.hd * (d.dtype == LVLM_BF16 ? 2 : 4)) / 256;
+    w.single = n_chunks <= kSingleMaxChunks && rows_per_cu <= kSingleMaxRowsPerCu;
+    if (w.single) {
+        w.rs = n_chunks;
+        w.cps = 1;
+    }
     const size_t rows = (size_t)d.B * d.Hq * d.T;
     w.part_m = 0;
     w.part_l = align_up(w.part_m + rows * w.nkb * 4 * sizeof(float), 256);
@@ -422,15 +629,15 @@ hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreW
     const bool need_lse = row_lse == nullptr;
     const bool wide = w.block_keys == 256;
     if (d.dtype == LVLM_BF16 && d.hd == 128) {
-        if (wide) launch_passes<LVLM_BF16, 128, 2>(prof, a, need_lse);
-        else launch_passes<LVLM_BF16, 128, 1>(prof, a, need_lse);
+        if (wide) launch_passes<LVLM_BF16, 128, 2>(prof, a, need_lse, w.single);
+        else launch_passes<LVLM_BF16, 128, 1>(prof, a, need_lse, w.single);
     } else if (d.dtype == LVLM_BF16 && d.hd == 64) {
-        if (wide) launch_passes<LVLM_BF16, 64, 2>(prof, a, need_lse);
-        else launch_passes<LVLM_BF16, 64, 1>(prof, a, need_lse);
+        if (wide) launch_passes<LVLM_BF16, 64, 2>(prof, a, need_lse, w.single);
+        else launch_passes<LVLM_BF16, 64, 1>(prof, a, need_lse, w.single);
     } else if (d.dtype == LVLM_F32 && d.hd == 128) {
-        launch_passes<LVLM_F32, 128, 1>(prof, a, need_lse);
+        launch_passes<LVLM_F32, 128, 1>(prof, a, need_lse, w.single);
     } else {
-        launch_passes<LVLM_F32, 64, 1>(prof, a, need_lse);
+        launch_passes<LVLM_F32, 64, 1>(prof, a, need_lse, w.single);
     }
     return hipGetLastError();
 }

@@ -51,6 +51,12 @@ SCORE_CASES = [
     (torch.bfloat16, 2, 9, 6, 2, 128, 5, 333, True),          # G*T = 27 (< one chunk), ragged keys
     (torch.bfloat16, 1, 33, 8, 8, 64, 0, 200, False),         # d=64, no mask, no system prefix
     (torch.bfloat16, 3, 40, 14, 2, 128, 7, 1000, True),       # G=7 with T=40: 280 rows = 8.75 chunks
+    # short sequences take both passes in one launch (one workgroup per 32-row chunk); the cases above with
+    # N <= ~1100 rows of 256 bytes are of that kind, the ones below keep the two-pass kernels on ragged shapes
+    (torch.bfloat16, 1, 64, 28, 4, 128, 64, 717, True),       # config 2 after the first merge: 14 chunks, one launch
+    (torch.bfloat16, 2, 9, 6, 2, 128, 5, 1500, True),         # two-pass, G*T = 27, ragged keys
+    (torch.bfloat16, 1, 33, 8, 8, 64, 0, 2300, False),        # two-pass, d=64, no mask
+    (torch.float32, 2, 5, 4, 2, 128, 3, 700, True),           # two-pass, fp32 d=128
 ]
 
 
@@ -74,10 +80,11 @@ def test_score_tokens(ctx, dtype, B, T, Hq, Hkv, d, n_sys, n_img, causal):
     assert rel_err(sh2.cpu(), osh) < 1e-5 and rel_err(sm2.cpu(), osm) < 1e-5
 
 
-def test_score_tokens_mask_inside_span_and_strided_inputs(ctx):
+@pytest.mark.parametrize("N", [300, 1300])      # one launch for both passes / the two-pass kernels
+def test_score_tokens_mask_inside_span_and_strided_inputs(ctx, N):
     # query rows start INSIDE the scored span (all-rows reading): the causal mask bites in pass 1 too;
     # q and k are views into wider buffers (non-trivial strides)
-    B, T, H, d, N = 2, 48, 4, 128, 300
+    B, T, H, d = 2, 48, 4, 128
     qkv = _rand((B, N, 3, H, d), torch.bfloat16, 3)
     q_all, k_all = qkv[:, :, 0], qkv[:, :, 1]
     q = q_all[:, N - T:]
