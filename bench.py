@@ -5,8 +5,14 @@ One "step" is one pass of the whole hot path over one synthetic batch of the
 Qwen2.5-VL-7B-shaped workload (config 2: 28 layers, 64 system + 2048 image +
 64 instruction tokens, bf16):
 
-  prefill, per decoder layer l >= 5:  lvlm_score_tokens (instruction queries x
-      all keys of layer l, written straight into that layer's cache scores);
+  prefill, decoder layers l >= 5:  lvlm_score_tokens (instruction queries x
+      all keys of a layer, written straight into that layer's cache scores),
+      issued once per run of layers with the same token count -- at the
+      pyramid layer that ends the run, which needs its score for the merge,
+      with the run's layers stacked along the batch axis (layers 5 | 6-9 |
+      10-13 | 14-27: the scores of the other layers of a run feed only the
+      cache compression after prefill; their instruction-token queries and
+      caches are kept until the call);
       at the pyramid layers 5 / 9 / 13: lvlm_merge_compact of the hidden states
       and position ids down to 100 % / 35 % / 3 % of the image tokens;
   after the last layer: ONE lvlm_kv_compress (threshold beta = 0.995, stable
@@ -84,6 +90,25 @@ def plan(w, lv):
     return layers
 
 
+def score_groups(layers):
+    """Runs of consecutive scored layers with the same image-token count, as (first, last) layer indices.  A
+    run ends at a merge layer (which needs its score at once) or with the stack; the layers before it in the
+    run feed only the cache compression after prefill, so one call at the run's end scores them all: their
+    instruction-token queries [T,Hq,d] and their caches are kept until then."""
+    groups, first = [], None
+    for i, en in enumerate(layers):
+        if not en["score"]:
+            assert first is None
+            continue
+        if first is None:
+            first = i
+        if en["merge_to"] is not None or i + 1 == len(layers) or not layers[i + 1]["score"] \
+                or layers[i + 1]["n_img"] != en["n_img"]:
+            groups.append((first, i))
+            first = None
+    return groups
+
+
 EXTRA_SLOTS = 8     # free cache slots per head beyond the prefill length
 
 
@@ -108,6 +133,12 @@ class StepState:
         self.pos = torch.empty(nl * B, H, L, dtype=torch.int32, device=dev)
         self.len = torch.empty(nl * B, H, dtype=torch.int32, device=dev)
         self.n_evicted = torch.empty(nl * B, H, dtype=torch.int32, device=dev)
+        self.q = torch.empty(nl * B, w.n_text, w.n_q_heads, d, dtype=dt, device=dev)     # instruction-token queries
+        self.groups = score_groups(layers)
+        # head-mean scores [g*B, n_img] of each group; the merge reads the last layer's rows
+        self.group_mean = {last: torch.empty((last - first + 1) * B, layers[last]["n_img"], dtype=torch.float32,
+                                             device=dev) for first, last in self.groups}
+        self.group_first = {last: first for first, last in self.groups}
         self.layers = [LayerState(w, en, master, torch, self, i) for i, en in enumerate(layers)]
         # the layers whose cache the threshold rule compresses after prefill: a contiguous tail of the stack
         first = [i for i, en in enumerate(layers) if en["kv_threshold"]]
@@ -137,7 +168,8 @@ class LayerState:
         self.Lmax = cache_slots(w)
         m = master[entry["layer"]]
         sl = slice(index * B, (index + 1) * B)
-        self.q = m["q"].clone()                                   # [B,T,Hq,d]
+        self.q = step.q[sl]                                       # [B,T,Hq,d]
+        self.q.copy_(m["q"])
         self.k, self.v = step.k[sl], step.v[sl]                   # [B,H,Lmax,d] head-major cache (slice of the stack)
         self.score, self.kind, self.pos, self.len = step.score[sl], step.kind[sl], step.pos[sl], step.len[sl]
         self.n_evicted = step.n_evicted[sl]
@@ -146,7 +178,8 @@ class LayerState:
             dst.copy_(m[name])
         self.hidden = m["hidden"].clone() if "hidden" in m else None
         self.pos_ids = m["pos_ids"].clone() if "pos_ids" in m else None
-        self.score_mean = torch.empty(B, self.n_img, dtype=torch.float32, device=self.q.device)
+        # head-mean scores: the last B rows of the group's array when this layer ends a scoring group
+        self.score_mean = step.group_mean[index][-B:] if index in step.group_mean else None
         if entry["merge_to"] is not None:
             r = self.n_img - entry["merge_to"]
             self.hidden_out = torch.empty(B, self.N - r, w.hidden, dtype=self.hidden.dtype, device=self.q.device)
@@ -193,14 +226,17 @@ def build_master(w, layers, torch, synth, dev):
 
 
 def run_prefill(ctx, lv, w, states, reserve, merge="rank"):
-    for st in states:
+    B = w.batch
+    for i, st in enumerate(states):
         e = st.entry
         img0 = w.n_sys
-        if e["score"]:
-            k_view = st.k[:, :, :st.N].permute(0, 2, 1, 3)          # [B,N,H,d] view of the head-major cache
-            sh_view = st.score[:, :, img0:img0 + st.n_img]          # scores land in the cache's score array
-            ctx.score_tokens(st.q, k_view, q_pos0=img0 + st.n_img, img_begin=img0, n_img=st.n_img,
-                             score_head=sh_view, score_mean=st.score_mean, reserve=reserve)
+        if i in states.group_first:
+            # one call scores every layer of the group that ends here (layers stacked along the batch axis)
+            sl = slice(states.group_first[i] * B, (i + 1) * B)
+            k_view = states.k[sl, :, :st.N].permute(0, 2, 1, 3)     # [g*B,N,H,d] view of the head-major caches
+            sh_view = states.score[sl, :, img0:img0 + st.n_img]     # scores land in the caches' score arrays
+            ctx.score_tokens(states.q[sl], k_view, q_pos0=img0 + st.n_img, img_begin=img0, n_img=st.n_img,
+                             score_head=sh_view, score_mean=states.group_mean[i], reserve=reserve)
         if e["merge_to"] is not None and merge == "similar":
             ctx.merge_similar([st.hidden, st.pos_ids], st.score_mean, img_begin=img0, n_img=st.n_img,
                               n_keep=e["merge_to"], rules=[lv.RULE_WEIGHTED, lv.RULE_TOP],
@@ -236,13 +272,12 @@ def run_decode(ctx, lv, w, states, reserve, step_pos=0):
 
 # ----------------------------------------------------------------------------- algorithmic work per kernel
 def score_in_one_launch(w, N):
-    """Whether the library scores a layer of N tokens with its one-launch kernel (short sequences) or with
+    """Whether the library scores sequences of N tokens with its one-launch kernel (short sequences) or with
     the two-pass kernels.  Restates the library's launch rule, only to credit the flops to the right kernel
     name; main() checks the launch counts it implies against the ones measured."""
     e = 2 if w.dtype == "bf16" else 4
     n_chunks = (w.n_q_heads // w.n_kv_heads * w.n_text + 31) // 32
-    wgs = w.batch * w.n_kv_heads * n_chunks
-    return n_chunks <= 32 and (wgs + 255) // 256 * N * (w.head_dim * e) // 256 <= 1100
+    return n_chunks <= 32 and N * (w.head_dim * e) // 256 <= 900
 
 
 def kernel_work(w, layers, lens_after_prefill, merge="rank"):
@@ -256,14 +291,16 @@ def kernel_work(w, layers, lens_after_prefill, merge="rank"):
         a["amount"] += amount
         a["launches"] += launches
 
+    for first, last in score_groups(layers):
+        n_img = layers[last]["n_img"]
+        N, gb = w.n_sys + n_img + T, (last - first + 1) * B
+        if score_in_one_launch(w, N):
+            add("score_single", "mfma", 2.0 * gb * T * (N + n_img) * d * Hq)
+        else:
+            add("score_pass0", "mfma", 2.0 * gb * T * N * d * Hq)
+            add("score_pass1", "mfma", 2.0 * gb * T * n_img * d * Hq)
     for i, en in enumerate(layers):
         N = w.n_sys + en["n_img"] + T
-        if en["score"]:
-            if score_in_one_launch(w, N):
-                add("score_single", "mfma", 2.0 * B * T * (N + en["n_img"]) * d * Hq)
-            else:
-                add("score_pass0", "mfma", 2.0 * B * T * N * d * Hq)
-                add("score_pass1", "mfma", 2.0 * B * T * en["n_img"] * d * Hq)
         if en["merge_to"] is not None:
             r = en["n_img"] - en["merge_to"]
             if merge == "similar":

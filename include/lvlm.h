@@ -12,7 +12,8 @@
  *
  * General rules for every call below
  *   - Every tensor pointer is a DEVICE pointer owned by the caller and must be
- *     16-byte aligned.  Descriptors, plane tables and "host" outputs are HOST
+ *     16-byte aligned (score_mean alone needs only 4 bytes, so that rows of a
+ *     larger array can be passed).  Descriptors, plane tables and "host" outputs are HOST
  *     memory.  Strides are in elements; the innermost dimension is contiguous.
  *   - The four hot-path calls only enqueue kernels on the caller's stream
  *     (a hipStream_t passed as void*; NULL = the default stream).  They do not

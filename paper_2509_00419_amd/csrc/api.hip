@@ -25,6 +25,7 @@ lvlm_status fail(lvlm_ctx *ctx, lvlm_status st, const char *fmt, ...) {
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
 bool float_dtype(int dt) { return dt == LVLM_BF16 || dt == LVLM_F32; }
 int elem_bytes(int dt) { return dt == LVLM_BF16 ? 2 : 4; }
@@ -299,8 +300,8 @@ lvlm_status lvlm_score_tokens(lvlm_ctx *ctx, void *stream, const lvlm_score_desc
     if (!ctx) return LVLM_ERR_INVALID_ARG;
     if (const char *why = check_score(d)) return fail(ctx, LVLM_ERR_INVALID_ARG, "score_tokens: %s", why);
     if (!q || !k || !score_head || !score_mean) return fail(ctx, LVLM_ERR_INVALID_ARG, "score_tokens: null pointer");
-    if (!aligned16(q) || !aligned16(k) || !aligned16(score_head) || !aligned16(score_mean) || !aligned16(row_lse))
-        return fail(ctx, LVLM_ERR_INVALID_ARG, "score_tokens: pointers must be 16-byte aligned");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(score_head) || !aligned4(score_mean) || !aligned16(row_lse))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "score_tokens: pointers must be 16-byte aligned (score_mean: 4)");
     const ScoreWs w = score_ws(*d);
     if (lvlm_status st = need_ws(ctx, w.total)) return st;
     if (lvlm_status st = bind_device(ctx)) return st;
@@ -313,8 +314,8 @@ lvlm_status lvlm_merge_compact(lvlm_ctx *ctx, void *stream, const lvlm_merge_des
     if (!ctx) return LVLM_ERR_INVALID_ARG;
     if (const char *why = check_merge(d, planes)) return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_compact: %s", why);
     if (!score_mean && d->n_keep < d->n_img) return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_compact: null score_mean");
-    if (!aligned16(score_mean) || !aligned16(w) || !aligned16(keep_idx) || !aligned16(merged_idx))
-        return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_compact: pointers must be 16-byte aligned");
+    if (!aligned4(score_mean) || !aligned16(w) || !aligned16(keep_idx) || !aligned16(merged_idx))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_compact: pointers must be 16-byte aligned (score_mean: 4)");
     const MergeWs mw = merge_ws(*d, planes);
     if (lvlm_status st = need_ws(ctx, mw.total)) return st;
     if (lvlm_status st = bind_device(ctx)) return st;
@@ -328,9 +329,9 @@ lvlm_status lvlm_merge_similar(lvlm_ctx *ctx, void *stream, const lvlm_merge_des
     if (!ctx) return LVLM_ERR_INVALID_ARG;
     if (const char *why = check_merge(d, planes)) return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_similar: %s", why);
     if (!score_mean && d->n_keep < d->n_img) return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_similar: null score_mean");
-    if (!aligned16(score_mean) || !aligned16(size_in) || !aligned16(size_out) || !aligned16(keep_idx) ||
+    if (!aligned4(score_mean) || !aligned16(size_in) || !aligned16(size_out) || !aligned16(keep_idx) ||
         !aligned16(assign))
-        return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_similar: pointers must be 16-byte aligned");
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "merge_similar: pointers must be 16-byte aligned (score_mean: 4)");
     if (!float_dtype(planes[0].dtype) || (planes[0].row_elems * elem_bytes(planes[0].dtype)) % 16 != 0 ||
         (planes[0].src_stride_b * elem_bytes(planes[0].dtype)) % 16 != 0)
         return fail(ctx, LVLM_ERR_UNSUPPORTED,

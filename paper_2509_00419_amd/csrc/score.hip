@@ -565,8 +565,7 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool sin
 }  // namespace
 
 constexpr int kSingleMaxChunks = 32;
-constexpr int kSingleMaxRowsPerCu = 1100;      // in 256-byte key rows
-constexpr int kCus = 256;
+constexpr int kSingleMaxRows = 900;      // in 256-byte key rows
 
 ScoreWs score_ws(const lvlm_score_desc &d) {
     ScoreWs w{};
@@ -584,12 +583,11 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
     w.cps = (n_chunks + rs - 1) / rs;
     w.rs = (n_chunks + w.cps - 1) / w.cps;
     // Short sequences: one launch in which every query chunk streams the keys itself (twice).  Its time
-    // grows with the key rows a CU has to pull through its vector cache -- the workgroups a CU gets times
-    // the sequence length -- and it is taken while that stays below the point where the three launches it
-    // replaces cost more (measured).  The column sums then come in one part per chunk.
-    const long long single_wgs = (long long)d.B * d.Hkv * n_chunks;
-    const long long rows_per_cu = (single_wgs + kCus - 1) / kCus * d.N * (d.hd * (d.dtype == LVLM_BF16 ? 2 : 4)) / 256;
-    w.single = n_chunks <= kSingleMaxChunks && rows_per_cu <= kSingleMaxRowsPerCu;
+    // grows with the length of that sweep -- each lane fetches whole key rows, 16 bytes per instruction --
+    // and it is taken up to the length where the three launches it replaces cost the same (measured at
+    // batch sizes from 1 to 64 sequences).  The column sums then come in one part per chunk.
+    const long long sweep_rows = (long long)d.N * (d.hd * (d.dtype == LVLM_BF16 ? 2 : 4)) / 256;
+    w.single = n_chunks <= kSingleMaxChunks && sweep_rows <= kSingleMaxRows;
     if (w.single) {
         w.rs = n_chunks;
         w.cps = 1;
