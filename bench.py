@@ -226,6 +226,12 @@ def build_master(w, layers, torch, synth, dev):
 
 
 def run_prefill(ctx, lv, w, states, reserve, merge="rank"):
+    run_prefill_layers(ctx, lv, w, states, reserve, merge)
+    run_prefill_compress(ctx, lv, w, states, reserve)
+
+
+def run_prefill_layers(ctx, lv, w, states, reserve, merge="rank"):
+    """Scoring and merging, in layer order."""
     B = w.batch
     for i, st in enumerate(states):
         e = st.entry
@@ -247,6 +253,9 @@ def run_prefill(ctx, lv, w, states, reserve, merge="rank"):
                               n_keep=e["merge_to"], rules=[lv.RULE_WEIGHTED, lv.RULE_TOP],
                               outs=[st.hidden_out, st.pos_out], keep_idx=st.keep_idx, merged_idx=st.merged_idx,
                               reserve=reserve)
+
+
+def run_prefill_compress(ctx, lv, w, states, reserve):
     if states.kv_from is not None:
         # the threshold rule on the caches of all compressed layers at once (a cache is only read again in decode)
         t = states.tail
@@ -256,15 +265,27 @@ def run_prefill(ctx, lv, w, states, reserve, merge="rank"):
 
 
 def run_decode(ctx, lv, w, states, reserve, step_pos=0):
-    # a cache that can be exactly one entry over its budget is compressed by the attention call itself
-    fused = w.kv_budget > 0 and states.dec_bound == w.kv_budget + 1
+    run_decode_layers(ctx, lv, w, states, reserve, step_pos)
+    run_decode_compress(ctx, lv, w, states, reserve)
+
+
+def decode_evicts_in_attention(w, states):
+    """A cache that can be exactly one entry over its budget is compressed by the attention call itself."""
+    return w.kv_budget > 0 and states.dec_bound == w.kv_budget + 1
+
+
+def run_decode_layers(ctx, lv, w, states, reserve, step_pos=0):
+    fused = decode_evicts_in_attention(w, states)
     for st in states:
         bound = min(st.Lmax, st.N + 1)
         ctx.decode_attn(st.q_dec, st.k_dec, st.v_dec, st.k, st.v, st.score, st.kind, st.pos, st.len,
                         score_decay=0.9, new_pos=w.seq_len + step_pos, len_bound=bound, out=st.out_dec,
                         evict_budget=w.kv_budget if fused else 0, evict_recent=1, reserve=reserve)
-    if w.kv_budget > 0 and not fused:
-        # else one budget eviction over the caches of all layers (a layer's cache is next read in the next step)
+
+
+def run_decode_compress(ctx, lv, w, states, reserve):
+    if w.kv_budget > 0 and not decode_evicts_in_attention(w, states):
+        # one budget eviction over the caches of all layers (a layer's cache is next read in the next step)
         ctx.kv_compress(states.k, states.v, states.score, states.kind, states.pos, states.len, mode=lv.KV_BUDGET,
                         budget=w.kv_budget, n_recent=1, order=lv.ORDER_FILL, len_bound=states.dec_bound,
                         want_evicted=False, reserve=reserve)

@@ -1,0 +1,186 @@
+"""The step that bench.py times, at full size and in its own launch configuration, against the oracle.
+
+bench.py scores runs of layers in one call (layers stacked on the batch axis, keys read through strided
+views of the stacked head-major caches), compresses the caches of all layers in one call and decodes layer
+by layer.  These tests drive bench.py's own functions on one step's state and check every phase against
+the oracle applied to the state the GPU had just before that phase (so one flipped near-tie cannot
+cascade): scores within 1e-5, index lists and cache moves exact, values within the dtype's tolerance.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import bench  # noqa: E402
+import paper_2509_00419_amd as lv  # noqa: E402
+from oracle import lvlm_oracle as O  # noqa: E402
+from workloads import configs, synth  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def f64(t):
+    return t.detach().double().cpu().numpy()
+
+
+def rel_err(got, ref):
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def snapshot(k, v, score, kind, pos, length):
+    return [f64(k), f64(v), score.cpu().numpy().copy(), kind.cpu().numpy().copy(), pos.cpu().numpy().copy(),
+            length.cpu().numpy().copy()]
+
+
+def same_entries(now, ref, exact_score=True, tol=1e-5):
+    """Caches `now` and `ref` ([k, v, score, kind, pos, len]) hold the same retained entries, slot by slot."""
+    assert np.array_equal(now[5], ref[5])
+    nb, nh = now[5].shape
+    for b in range(nb):
+        for h in range(nh):
+            n = int(now[5][b, h])
+            for i in (0, 1, 3, 4):
+                assert np.array_equal(now[i][b, h, :n], ref[i][b, h, :n]), (b, h, i)
+            if exact_score:
+                assert np.array_equal(now[2][b, h, :n], ref[2][b, h, :n]), (b, h)
+            elif n:
+                assert rel_err(now[2][b, h, :n], ref[2][b, h, :n]) < tol, (b, h)
+
+
+def build(w):
+    layers = bench.plan(w, lv)
+    master = bench.build_master(w, layers, torch, synth, DEV)
+    return layers, master, bench.StepState(w, layers, master, torch)
+
+
+def layer_slices(st, i, B):
+    sl = slice(i * B, (i + 1) * B)
+    return st.k[sl], st.v[sl], st.score[sl], st.kind[sl], st.pos[sl], st.len[sl]
+
+
+@pytest.mark.parametrize("name,every_layer", [("cfg2", True), ("cfg3", False), ("cfg5", False)])
+def test_prefill_and_decode_step_in_bench_configuration(name, every_layer):
+    """Config 2: every layer of the step.  Configs 3 and 5 (B = 8; 16512 tokens): the first and last layer of
+    every scoring run plus one uncompressed layer -- the oracle needs seconds per layer there."""
+    w = configs.ALL[name]
+    ctx = lv.Context(0)
+    layers, master, st = build(w)
+    B, img0, tol = w.batch, w.n_sys, 2e-2
+    if every_layer:
+        assert st.groups == [(5, 5), (6, 9), (10, 13), (14, 27)]
+        sample = list(range(len(layers)))
+    else:
+        sample = sorted({0} | {i for g in st.groups for i in g})
+
+    # ---- prefill, scoring and merging
+    bench.run_prefill_layers(ctx, lv, w, st, reserve=True)
+    torch.cuda.synchronize()
+    for first, last in st.groups:
+        for i in range(first, last + 1):
+            if i not in sample:
+                continue
+            L, m = st[i], master[i]
+            k = m["k"][:, :, :L.N].permute(0, 2, 1, 3)
+            osh, osm = O.score_tokens(f64(m["q"]), f64(k), q_pos0=img0 + L.n_img, img_begin=img0, n_img=L.n_img)
+            assert rel_err(L.score[:, :, img0:img0 + L.n_img].cpu(), osh) < 1e-5, i
+            rows = st.group_mean[last][(i - first) * B:(i - first + 1) * B]
+            assert rel_err(rows.cpu(), osm) < 1e-5, i
+    n_merges = 0
+    for i, L in enumerate(st):
+        e = L.entry
+        if e["merge_to"] is None:
+            continue
+        n_merges += 1
+        m = master[i]
+        oouts, okeep, omerged = O.merge_compact([f64(m["hidden"]), m["pos_ids"].cpu().numpy()],
+                                                L.score_mean.cpu().numpy(), img_begin=img0, n_img=L.n_img,
+                                                n_keep=e["merge_to"], rules=[lv.RULE_WEIGHTED, lv.RULE_TOP],
+                                                dtypes=[w.dtype, "f32"])
+        if e["merge_to"] < L.n_img:
+            assert np.array_equal(L.keep_idx.cpu().numpy(), okeep), i
+            assert np.array_equal(L.merged_idx.cpu().numpy(), omerged), i
+        assert rel_err(f64(L.hidden_out), oouts[0]) < tol, i
+        assert np.array_equal(L.pos_out.cpu().numpy(), oouts[1]), i
+    assert n_merges == 3
+
+    # ---- prefill, threshold compression of the caches of all compressed layers in one call, on the GPU's
+    # score bits
+    compressed = [i for i in sample if layers[i]["kv_threshold"]]
+    before = {i: snapshot(*layer_slices(st, i, B)) for i in compressed}
+    bench.run_prefill_compress(ctx, lv, w, st, reserve=True)
+    torch.cuda.synchronize()
+    shrunk = False
+    for i in compressed:
+        ref = O.kv_compress(*before[i], mode="threshold", beta=w.kv_beta, order=O.ORDER_STABLE)
+        now = snapshot(*layer_slices(st, i, B))
+        same_entries(now, ref[:6])
+        assert np.array_equal(st.n_evicted[i * B:(i + 1) * B].cpu().numpy(), ref[6])
+        shrunk = shrunk or bool((now[5] < before[i][5]).any())
+    assert shrunk
+
+    # ---- one decode step: attention layer by layer, then the budget eviction of all caches in one call
+    assert not bench.decode_evicts_in_attention(w, st)
+    before = {i: snapshot(*layer_slices(st, i, B)) for i in sample}
+    bench.run_decode_layers(ctx, lv, w, st, reserve=True)
+    torch.cuda.synchronize()
+    mid = {i: snapshot(*layer_slices(st, i, B)) for i in sample}
+    for i in sample:
+        m = master[i]
+        ref = O.decode_attn(f64(m["q_dec"]), f64(m["k_dec"]), f64(m["v_dec"]), *before[i], score_decay=0.9,
+                            new_pos=w.seq_len, out_dtype="bf16")
+        assert rel_err(f64(st[i].out_dec), ref[0]) < tol, i
+        same_entries(mid[i], list(ref[1:]), exact_score=False)
+    bench.run_decode_compress(ctx, lv, w, st, reserve=True)
+    torch.cuda.synchronize()
+    for i in sample:
+        now = snapshot(*layer_slices(st, i, B))
+        if w.kv_budget > 0:
+            ref = O.kv_compress(*mid[i], mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
+            same_entries(now, ref[:6])
+            assert int(now[5].max()) <= w.kv_budget
+        else:
+            same_entries(now, mid[i])
+
+
+def test_config4_step_in_bench_configuration():
+    """Decode with the eviction inside the attention call (every cache exactly one entry over its budget)."""
+    w = configs.CFG4
+    ctx = lv.Context(0)
+    layers, master, st = build(w)
+    B = w.batch
+    assert not st.groups and st.dec_bound == w.kv_budget + 1
+    # the same calls without eviction on a second copy of the state give the GPU's updated score bits
+    st2 = bench.StepState(w, layers, master, torch)
+    for L in st2:
+        ctx.decode_attn(L.q_dec, L.k_dec, L.v_dec, L.k, L.v, L.score, L.kind, L.pos, L.len, score_decay=0.9,
+                        new_pos=w.seq_len, len_bound=w.kv_budget + 1, out=L.out_dec)
+    torch.cuda.synchronize()
+    bench.run_decode(ctx, lv, w, st, reserve=True)
+    torch.cuda.synchronize()
+    check = (0, 5, 13, 27)                      # layers compared entry by entry (the oracle is slow at B = 16)
+    for i in check:
+        sl = slice(i * B, (i + 1) * B)
+        mid = snapshot(st2.k[sl], st2.v[sl], st2.score[sl], st2.kind[sl], st2.pos[sl], st2.len[sl])
+        ref = O.kv_compress(*mid, mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
+        now = snapshot(st.k[sl], st.v[sl], st.score[sl], st.kind[sl], st.pos[sl], st.len[sl])
+        same_entries(now, ref[:6])
+        assert int(now[5].min()) == w.kv_budget and int(now[5].max()) == w.kv_budget
+        assert torch.equal(st[i].out_dec, st2[i].out_dec)
+    # and the unfused attention itself against the oracle on one layer
+    i, sl = 13, slice(13 * B, 14 * B)
+    st3 = bench.StepState(w, layers, master, torch)
+    before = snapshot(st3.k[sl], st3.v[sl], st3.score[sl], st3.kind[sl], st3.pos[sl], st3.len[sl])
+    m = master[i]
+    ref = O.decode_attn(f64(m["q_dec"]), f64(m["k_dec"]), f64(m["v_dec"]), *before, score_decay=0.9,
+                        new_pos=w.seq_len, out_dtype="bf16")
+    assert rel_err(f64(st2[i].out_dec), ref[0]) < 2e-2
+    mid = snapshot(st2.k[sl], st2.v[sl], st2.score[sl], st2.kind[sl], st2.pos[sl], st2.len[sl])
+    same_entries(mid, list(ref[1:]), exact_score=False)
