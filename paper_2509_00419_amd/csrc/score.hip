@@ -104,18 +104,50 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     uint4 stB0 = stA0, stB1 = stA0, stB2 = stA0, stB3 = stA0;
     int stA_pos = -1, stB_pos = -1;
     float stA_lse = 0.f, stB_lse = 0.f;
-    auto chunk_src = [&](int c, int x) -> const uint4 * {
-        const int u = tid + 256 * x;
-        const int row = u / UPR, cu = u % UPR;
-        const int rho = min(c * 32 + row, GT - 1);            // padding rows repeat the last row; masked below
-        const int hl = div_t(rho), i = rho - hl * a.T;
-        return reinterpret_cast<const uint4 *>(
-            a.q + ((long long)b * a.qsb + (long long)i * a.qst + (long long)(g * a.G + hl) * a.qsh) * ES + 16 * cu);
+    // A thread stages UPT consecutive 16-byte units of ONE row of every chunk.  Its source address is
+    // carried from load to load (a stage takes every second chunk: 64 rows further down, stepping over to
+    // the next head when the rows of one are used up), so the chunk loop holds no address multiplies.
+    const int srow = tid * UPT / UPR, scu = tid * UPT % UPR;
+    const long long q_step = 64 * a.qst * ES;                            // 64 rows further in the same head
+    const long long q_wrap = (a.qsh - (long long)a.T * a.qst) * ES;      // from row T of a head to row 0 of the next
+    const char *q_grp0 = a.q + ((long long)b * a.qsb + (long long)g * a.G * a.qsh) * ES;    // uniform
+    const char *q_grp = q_grp0 + 16 * scu;
+    // padding rows (beyond the last row of the group, in its last chunk only) repeat the last row; they are
+    // masked in compute.  Its address is formed where it is used, from uniform values: a register pair
+    // held around the loop would push a staging register out to scratch memory.
+    const char *q_last0 = q_grp0 + ((long long)(a.G - 1) * a.qsh + (long long)(a.T - 1) * a.qst) * ES;
+    auto chunk_row = [&](int c, const char *ptr) -> const uint4 * {
+        if (c == n_chunks - 1) {
+            int off = 16 * scu;
+            asm volatile("" : "+v"(off));            // keeps the sum below inside this branch
+            if (c * 32 + srow >= GT) ptr = q_last0 + off;
+        }
+        return reinterpret_cast<const uint4 *>(ptr);
+    };
+    auto row_ptr = [&](int c, int &i) -> const char * {
+        const int rho = c * 32 + srow;
+        const int hl = div_t(rho);
+        i = rho - hl * a.T;
+        return q_grp + ((long long)hl * a.qsh + (long long)i * a.qst) * ES;
+    };
+    int iA = 0, iB = 0;
+    const char *pA = row_ptr(c_lo, iA), *pB = row_ptr(c_lo + 1, iB);
+    auto advance = [&](const char *&ptr, int &i) {
+        i += 64;
+        ptr += q_step;
+        if (a.T >= 64) {
+            const bool over = i >= a.T;
+            i -= over ? a.T : 0;
+            ptr += over ? q_wrap : 0;
+        } else {
+            while (i >= a.T) {
+                i -= a.T;
+                ptr += q_wrap;
+            }
+        }
     };
     auto chunk_dst = [&](int buf, int x) -> uint4 * {
-        const int u = tid + 256 * x;
-        const int row = u / UPR, cu = u % UPR;
-        return reinterpret_cast<uint4 *>(&q_lds[buf][row * PITCH + 16 * cu]);
+        return reinterpret_cast<uint4 *>(&q_lds[buf][srow * PITCH + 16 * (scu + x)]);
     };
     auto row_meta = [&](int c, int &pos, float &lse) {
         pos = -1;             // padding row: sees no key
@@ -129,12 +161,17 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
         }
     };
 #define LVLM_STAGE_FUNCS(S)                                              \
-    auto load_##S = [&](int c) {                                         \
-        st##S##0 = *chunk_src(c, 0);                                     \
-        if constexpr (UPT > 1) st##S##1 = *chunk_src(c, 1);              \
-        if constexpr (UPT > 2) st##S##2 = *chunk_src(c, 2);              \
-        if constexpr (UPT > 3) st##S##3 = *chunk_src(c, 3);              \
-        row_meta(c, st##S##_pos, st##S##_lse);                           \
+    auto load_##S = [&](int kk) {           /* chunk c_lo + kk; nothing to fetch past the last chunk */ \
+        const int c = c_lo + kk;                                         \
+        if (c < c_hi) {                                                  \
+            const uint4 *src = chunk_row(c, p##S);                      \
+            st##S##0 = src[0];                                           \
+            if constexpr (UPT > 1) st##S##1 = src[1];                    \
+            if constexpr (UPT > 2) st##S##2 = src[2];                    \
+            if constexpr (UPT > 3) st##S##3 = src[3];                    \
+            row_meta(c, st##S##_pos, st##S##_lse);                       \
+        }                                                                \
+        advance(p##S, i##S);                                             \
     };                                                                   \
     auto store_##S = [&](int buf) {                                      \
         *chunk_dst(buf, 0) = st##S##0;                                   \
@@ -250,22 +287,21 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     // Pipeline over the chunks k = 0 .. nc-1 of this workgroup: chunk k is loaded from global memory into
     // a register stage two iterations before it is computed (even chunks in A, odd ones in B), copied
     // into one of three LDS buffers one iteration before, and one barrier per chunk publishes the copy.
-    // Loads and copies past the last chunk harmlessly repeat it.
+    // Past the last chunk nothing is loaded; the copies then repeat stale registers that nothing reads.
     const int nc = c_hi - c_lo;
-    auto chunk_at = [&](int k) { return min(c_lo + k, c_hi - 1); };
-    load_A(chunk_at(0));
+    load_A(0);
     store_A(0);
-    load_B(chunk_at(1));
-    load_A(chunk_at(2));
+    load_B(1);
+    load_A(2);
     __syncthreads();
     for (int k = 0; k < nc; k += 2) {
         store_B((k + 1) % NBUF);          // chunk k+1
-        load_B(chunk_at(k + 3));
+        load_B(k + 3);
         compute(c_lo + k, k % NBUF);
         __syncthreads();
         if (k + 1 >= nc) break;
         store_A((k + 2) % NBUF);          // chunk k+2
-        load_A(chunk_at(k + 4));
+        load_A(k + 4);
         compute(c_lo + k + 1, (k + 1) % NBUF);
         __syncthreads();
     }
