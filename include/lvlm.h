@@ -215,7 +215,8 @@ LVLM_API lvlm_status lvlm_merge_compact(lvlm_ctx *ctx, void *stream, const lvlm_
  *   dominant tokens = the n_keep highest-scoring image tokens (order as in
  *   lvlm_merge_compact); every other image token is assigned to the dominant token
  *   with the largest cosine similarity between their rows of planes[0] (bf16 / fp32
- *   plane whose row is a multiple of 16 bytes; ties: lower dominant position; the
+ *   plane whose row is a multiple of 16 bytes and whose image rows span less than
+ *   2 GiB per batch row, else LVLM_ERR_UNSUPPORTED; ties: lower dominant position; the
  *   dot products run in the plane's dtype on the matrix cores with fp32
  *   accumulation); on LVLM_RULE_WEIGHTED planes each dominant token becomes
  *   sum(size * row) / sum(size) over itself and its assigned tokens (fp32, members in

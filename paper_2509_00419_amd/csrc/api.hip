@@ -336,6 +336,8 @@ lvlm_status lvlm_merge_similar(lvlm_ctx *ctx, void *stream, const lvlm_merge_des
         (planes[0].src_stride_b * elem_bytes(planes[0].dtype)) % 16 != 0)
         return fail(ctx, LVLM_ERR_UNSUPPORTED,
                     "merge_similar: planes[0] must be bf16 or fp32 with rows that are a multiple of 16 bytes");
+    if ((long long)d->n_img * planes[0].row_elems * elem_bytes(planes[0].dtype) > 0x7fffffffll)
+        return fail(ctx, LVLM_ERR_UNSUPPORTED, "merge_similar: the image rows of planes[0] must span less than 2 GiB");
     const SimWs w = sim_ws(*d);
     if (lvlm_status st = need_ws(ctx, w.total)) return st;
     if (lvlm_status st = bind_device(ctx)) return st;

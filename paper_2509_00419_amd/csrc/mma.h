@@ -44,6 +44,20 @@ __device__ __forceinline__ void mma_tile(f32x16 &acc, const HalfRow<DT, HD> &a, 
     }
 }
 
+// One matrix instruction of such a product: 16-byte words a, b of the two operands (bf16: the whole word,
+// contraction length 16; fp32: component comp of the word, contraction length 2).
+template <int DT>
+__device__ __forceinline__ void mfma_one(f32x16 &acc, const uint4 &a, const uint4 &b, int comp) {
+    if constexpr (DT == LVLM_BF16) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc,
+                                                      0, 0, 0);
+    } else {
+        const unsigned aw = comp == 0 ? a.x : comp == 1 ? a.y : comp == 2 ? a.z : a.w;
+        const unsigned bw = comp == 0 ? b.x : comp == 1 ? b.y : comp == 2 ? b.z : b.w;
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(aw), __uint_as_float(bw), acc, 0, 0, 0);
+    }
+}
+
 // Row of the 32x32 accumulator held in register r of a lane in half hf (its column is lane % 32).
 __device__ __forceinline__ int acc_row(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
 

@@ -108,66 +108,103 @@ __global__ __launch_bounds__(256) void sim_norm_kernel(SimArgs a) {
 }
 
 // ---- dot products dominant x others on the matrix cores, arg-max over the dominant axis ----
-// Workgroup tile: 128 dominant rows x 128 other rows; wave (wn, wm) owns the 64 x 64 quadrant.  Rows are
-// gathered by index; the contraction runs over 128-byte slices of the rows (16 tile products per wave and
-// barrier), double buffered in LDS with the next slice's global loads in flight (named scalars: they are
-// carried around the loop).
-template <int DT>
-__global__ __launch_bounds__(256) void sim_gemm_kernel(SimArgs a) {
+// Workgroup tile: TM dominant rows x TN other rows, NWN x NWM waves, each owning TR x TC tiles of 32 x 32.
+// Two shapes are built: 256 x 256 with eight waves of 128 x 64 (large problems: per tile product it moves
+// a third less through LDS than the small shape, and half as much from L2) and 128 x 128 with four waves of
+// 64 x 64 (more workgroups when the problem is small).  Rows are gathered by index; the contraction runs
+// over 128-byte slices of the rows, double buffered in LDS with the next slice's global loads in flight
+// (named scalars: they are carried around the loop).  One slice is eight 16-byte units per row and every
+// thread stages four units of the dominant and four of the other rows.
+//
+// Tiles are numbered block by block (blocks of GN x GM tiles, ragged at the edges, batch rows one after the
+// other) and handed out in runs of GN * GM consecutive numbers, run j to XCD j % 8 (workgroups reach the
+// XCDs round-robin by id).  The workgroups resident on an XCD at the same time are then neighbours that
+// sweep the contraction axis together: a row slice fetched into that XCD's L2 serves up to GM (dominant
+// rows) or GN (other rows) of them, and every XCD gets the same number of tiles to within one run.
+constexpr int kSimGN = 8, kSimGM = 4;
+
+template <int DT, int NWN, int NWM, int TR, int TC, bool RAGGED>
+__global__ __launch_bounds__(64 * NWN * NWM) void sim_gemm_kernel(SimArgs a) {
     constexpr int ES = esize<DT>();
+    constexpr int NT = 64 * NWN * NWM;
+    constexpr int TM = NWN * TR * 32, TN = NWM * TC * 32;
     constexpr int SB = 128;              // bytes of one slice of a row
     constexpr int HS = SB / ES;          // its elements
     constexpr int PITCH = SB + 16;       // slice + 16 bytes: spreads the rows over the LDS banks
-    __shared__ __attribute__((aligned(16))) char a_lds[2][128 * PITCH];
-    __shared__ __attribute__((aligned(16))) char b_lds[2][128 * PITCH];
-    __shared__ float invn[128];
-    __shared__ float bv[2][128];
-    __shared__ int bi[2][128];
+    constexpr int RPI = NT / 8;          // rows one load instruction of the workgroup covers
+    constexpr int UA = TM / RPI, UB = TN / RPI;      // staging units per thread: rows srow + RPI j of each operand
+    __shared__ __attribute__((aligned(16))) char a_lds[2][TM * PITCH];
+    __shared__ __attribute__((aligned(16))) char b_lds[2][TN * PITCH];
+    __shared__ float invn[TM];
+    __shared__ float bv[NWN][TN];
+    __shared__ int bi[NWN][TN];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int wn = wave & 1, wm = wave >> 1;
-    const int nb = blockIdx.x, mb = blockIdx.y, b = blockIdx.z;
+    const int wn = wave % NWN, wm = wave / NWN;
+    // tile of this workgroup
+    const int NBt = (a.n_keep + TM - 1) / TM, MBt = (a.r + TN - 1) / TN;
+    constexpr int RUN = kSimGN * kSimGM;
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    int t = ((seq / RUN) * 8 + xcd) * RUN + seq % RUN;
+    if (t >= a.B * NBt * MBt) return;
+    const int b = t / (NBt * MBt);
+    t -= b * NBt * MBt;
+    const int gm = (MBt + kSimGM - 1) / kSimGM, gn = (NBt + kSimGN - 1) / kSimGN;
+    const int bj = min(t / (NBt * kSimGM), gm - 1);              // row of blocks; its height (the last may be lower)
+    t -= bj * NBt * kSimGM;
+    const int bh = min(kSimGM, MBt - bj * kSimGM);
+    const int bi_ = min(t / (kSimGN * bh), gn - 1);              // block in that row; its width
+    t -= bi_ * kSimGN * bh;
+    const int bw = min(kSimGN, NBt - bi_ * kSimGN);
+    const int nb = bi_ * kSimGN + t % bw, mb = bj * kSimGM + t / bw;
+
     const PlaneDev &p = a.plane[0];
     const int32_t *keep = a.keep_idx + (long long)b * a.n_keep;
     const int32_t *rest = a.rest_idx + (long long)b * a.r;
-    const int row = tid >> 1, half = tid & 1;
+    const int srow = tid >> 3, su = tid & 7;        // staging: rows srow + RPI j (j < 4), unit su of the slice
+    // Addresses are a uniform base (batch row, slice) plus a per-thread 32-bit byte offset (row, unit) that
+    // never changes: the slice loop then needs no vector instruction per load -- on this chip matrix and
+    // vector instructions do not overlap, so every one of them is time taken from the matrix cores.  The
+    // offsets fit: the image rows of one batch row span less than 2 GiB (checked on the host).
     const char *img = p.src + (long long)b * p.src_stride_b + (long long)a.img_begin * p.row_bytes;
-    const char *pa = img + (long long)keep[min(nb * 128 + row, a.n_keep - 1)] * p.row_bytes + 64 * half;
-    const char *pb = img + (long long)rest[min(mb * 128 + row, a.r - 1)] * p.row_bytes + 64 * half;
-    if (tid < 128) invn[tid] = a.inv_norm[(long long)b * a.n + keep[min(nb * 128 + tid, a.n_keep - 1)]];
+    // (named scalars below, not arrays: values carried around the slice loop must stay in registers)
+    static_assert(UA <= 8 && UB <= 8, "staging registers are written out for up to eight units");
+#define LVLM_SIM8(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7)
+#define LVLM_DECL(j)                                                                                        \
+    const unsigned oa##j = j < UA ? keep[min(nb * TM + srow + RPI * j, a.n_keep - 1)] * p.row_bytes + 16 * su : 0; \
+    const unsigned ob##j = j < UB ? rest[min(mb * TN + srow + RPI * j, a.r - 1)] * p.row_bytes + 16 * su : 0;      \
+    uint4 sa##j, sb##j;      /* written by load before store reads them */
+    LVLM_SIM8(LVLM_DECL)
+#undef LVLM_DECL
+    for (int i = tid; i < TM; i += NT) invn[i] = a.inv_norm[(long long)b * a.n + keep[min(nb * TM + i, a.n_keep - 1)]];
     const int nk = (p.row_bytes + SB - 1) / SB;      // the last slice may be partial: zero-filled
 
-    uint4 a0, a1, a2, a3, b0, b1, b2, b3;
+    // RAGGED: rows that are not a whole number of slices; units of the last slice beyond the row read as zero
     auto load = [&](int k) {
-        const int room = p.row_bytes - SB * k - 64 * half;      // bytes of the row at and after this thread's piece
+        const char *base = img + SB * k;             // uniform
+        const bool in = !RAGGED || p.row_bytes - SB * k - 16 * su >= 16;
         const uint4 z = make_uint4(0, 0, 0, 0);
-        a0 = room >= 16 ? *reinterpret_cast<const uint4 *>(pa + SB * k) : z;
-        a1 = room >= 32 ? *reinterpret_cast<const uint4 *>(pa + SB * k + 16) : z;
-        a2 = room >= 48 ? *reinterpret_cast<const uint4 *>(pa + SB * k + 32) : z;
-        a3 = room >= 64 ? *reinterpret_cast<const uint4 *>(pa + SB * k + 48) : z;
-        b0 = room >= 16 ? *reinterpret_cast<const uint4 *>(pb + SB * k) : z;
-        b1 = room >= 32 ? *reinterpret_cast<const uint4 *>(pb + SB * k + 16) : z;
-        b2 = room >= 48 ? *reinterpret_cast<const uint4 *>(pb + SB * k + 32) : z;
-        b3 = room >= 64 ? *reinterpret_cast<const uint4 *>(pb + SB * k + 48) : z;
+#define LVLM_LD(j)                                                                              \
+        if constexpr (j < UA) sa##j = in ? *reinterpret_cast<const uint4 *>(base + oa##j) : z;  \
+        if constexpr (j < UB) sb##j = in ? *reinterpret_cast<const uint4 *>(base + ob##j) : z;
+        LVLM_SIM8(LVLM_LD)
+#undef LVLM_LD
     };
     auto store = [&](int buf) {
-        char *da = &a_lds[buf][row * PITCH + 64 * half], *db = &b_lds[buf][row * PITCH + 64 * half];
-        *reinterpret_cast<uint4 *>(da) = a0;
-        *reinterpret_cast<uint4 *>(da + 16) = a1;
-        *reinterpret_cast<uint4 *>(da + 32) = a2;
-        *reinterpret_cast<uint4 *>(da + 48) = a3;
-        *reinterpret_cast<uint4 *>(db) = b0;
-        *reinterpret_cast<uint4 *>(db + 16) = b1;
-        *reinterpret_cast<uint4 *>(db + 32) = b2;
-        *reinterpret_cast<uint4 *>(db + 48) = b3;
+        char *da = &a_lds[buf][srow * PITCH + 16 * su], *db = &b_lds[buf][srow * PITCH + 16 * su];
+#define LVLM_ST(j)                                                                      \
+        if constexpr (j < UA) *reinterpret_cast<uint4 *>(da + j * RPI * PITCH) = sa##j;  \
+        if constexpr (j < UB) *reinterpret_cast<uint4 *>(db + j * RPI * PITCH) = sb##j;
+        LVLM_SIM8(LVLM_ST)
+#undef LVLM_ST
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[TR][TC];
 #pragma unroll
-    for (int nd = 0; nd < 2; ++nd)
+    for (int nd = 0; nd < TR; ++nd)
 #pragma unroll
-        for (int nr = 0; nr < 2; ++nr)
+        for (int nr = 0; nr < TC; ++nr)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[nd][nr][r] = 0.f;
 
@@ -179,34 +216,43 @@ __global__ __launch_bounds__(256) void sim_gemm_kernel(SimArgs a) {
         store((k + 1) & 1);                      // slice k+1 (a harmless repeat after the last one)
         load(min(k + 2, nk - 1));
         const int buf = k & 1;
-        HalfRow<DT, HS> fa[2], fb[2];
+        const char *ar = &a_lds[buf][(wn * TR * 32 + l32) * PITCH + (SB / 2) * hf];
+        const char *br = &b_lds[buf][(wm * TC * 32 + l32) * PITCH + (SB / 2) * hf];
+        // one contraction step (16 bytes per lane and tile row) at a time: TR + TC operand words, TR x TC products
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int i = 0; i < SB / 32; ++i) {
+            uint4 fa[TR], fb[TC];
 #pragma unroll
-            for (int i = 0; i < SB / 32; ++i) {
-                fa[t].v[i] = *reinterpret_cast<const uint4 *>(&a_lds[buf][(wn * 64 + t * 32 + l32) * PITCH + (SB / 2) * hf + 16 * i]);
-                fb[t].v[i] = *reinterpret_cast<const uint4 *>(&b_lds[buf][(wm * 64 + t * 32 + l32) * PITCH + (SB / 2) * hf + 16 * i]);
-            }
+            for (int t = 0; t < TR; ++t) fa[t] = *reinterpret_cast<const uint4 *>(ar + t * 32 * PITCH + 16 * i);
+#pragma unroll
+            for (int t = 0; t < TC; ++t) fb[t] = *reinterpret_cast<const uint4 *>(br + t * 32 * PITCH + 16 * i);
+#pragma unroll
+            for (int nd = 0; nd < TR; ++nd)
+#pragma unroll
+                for (int nr = 0; nr < TC; ++nr) {
+                    if constexpr (DT == LVLM_BF16) {
+                        mfma_one<DT>(acc[nd][nr], fa[nd], fb[nr], 0);      // rows = dominant, cols = others
+                    } else {
+#pragma unroll
+                        for (int cpt = 0; cpt < 4; ++cpt) mfma_one<DT>(acc[nd][nr], fa[nd], fb[nr], cpt);
+                    }
+                }
         }
-#pragma unroll
-        for (int nd = 0; nd < 2; ++nd)
-#pragma unroll
-            for (int nr = 0; nr < 2; ++nr) mma_tile<DT, HS>(acc[nd][nr], fa[nd], fb[nr]);   // rows = dominant, cols = others
         __syncthreads();
     }
 
-    // arg-max over the dominant rows: lane-local over its 32 registers, then the other lane half, then
-    // the two waves that share the columns.  Larger cosine wins; equal cosines go to the lower position.
+    // arg-max over the dominant rows: lane-local over its TR x 16 registers, then the other lane half, then
+    // the NWN waves that share the columns.  Larger cosine wins; equal cosines go to the lower position.
 #pragma unroll
-    for (int nr = 0; nr < 2; ++nr) {
+    for (int nr = 0; nr < TC; ++nr) {
         float best_v = -INFINITY;
         int best_i = INT_MAX;
 #pragma unroll
-        for (int nd = 0; nd < 2; ++nd) {
+        for (int nd = 0; nd < TR; ++nd) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int il = wn * 64 + nd * 32 + acc_row(r, hf);
-                const int gi = nb * 128 + il;
+                const int il = wn * TR * 32 + nd * 32 + acc_row(r, hf);
+                const int gi = nb * TM + il;
                 const float v = acc[nd][nr][r] * invn[il];
                 if (gi < a.n_keep && (v > best_v || (v == best_v && gi < best_i))) {
                     best_v = v;
@@ -221,20 +267,28 @@ __global__ __launch_bounds__(256) void sim_gemm_kernel(SimArgs a) {
             best_i = oi;
         }
         if (hf == 0) {
-            bv[wn][wm * 64 + nr * 32 + l32] = best_v;
-            bi[wn][wm * 64 + nr * 32 + l32] = best_i;
+            bv[wn][wm * TC * 32 + nr * 32 + l32] = best_v;
+            bi[wn][wm * TC * 32 + nr * 32 + l32] = best_i;
         }
     }
     __syncthreads();
-    if (tid < 128) {
-        const int q = mb * 128 + tid;
+    for (int i = tid; i < TN; i += NT) {
+        const int q = mb * TN + i;
         if (q < a.r) {
-            const bool second = bv[1][tid] > bv[0][tid] || (bv[1][tid] == bv[0][tid] && bi[1][tid] < bi[0][tid]);
+            float v = bv[0][i];
+            int ix = bi[0][i];
+#pragma unroll
+            for (int w = 1; w < NWN; ++w)
+                if (bv[w][i] > v || (bv[w][i] == v && bi[w][i] < ix)) {
+                    v = bv[w][i];
+                    ix = bi[w][i];
+                }
             const long long o = ((long long)b * a.NB + nb) * a.r + q;
-            a.pbest_val[o] = second ? bv[1][tid] : bv[0][tid];
-            a.pbest_idx[o] = second ? bi[1][tid] : bi[0][tid];
+            a.pbest_val[o] = v;
+            a.pbest_idx[o] = ix;
         }
     }
+#undef LVLM_SIM8
 }
 
 // ---- fold the dominant blocks; assignment of every token and the key that sorts tokens by it ----
@@ -406,7 +460,9 @@ SimWs sim_ws(const lvlm_merge_desc &d) {
     SimWs w{};
     const size_t n = (size_t)d.B * d.n_img;
     const int r = d.n_img - d.n_keep;
-    w.NB = (d.n_keep + 127) / 128;
+    // the large tile shape once it still gives every CU two workgroups
+    w.tile = ((long long)d.B * ((d.n_keep + 255) / 256) * ((r + 255) / 256) >= 512) ? 256 : 128;
+    w.NB = (d.n_keep + w.tile - 1) / w.tile;
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -486,11 +542,24 @@ hipError_t launch_merge_similar(const Prof &prof, const lvlm_merge_desc &d, cons
         hipLaunchKernelGGL(sim_norm_kernel<LVLM_F32>, dim3((d.n_img + 3) / 4, d.B), dim3(256), 0, stream, a);
     prof.end();
     prof.begin("sim_gemm");
-    const dim3 ggrid(w.NB, (r + 127) / 128, d.B);
-    if (planes[0].dtype == LVLM_BF16)
-        hipLaunchKernelGGL(sim_gemm_kernel<LVLM_BF16>, ggrid, dim3(256), 0, stream, a);
-    else
-        hipLaunchKernelGGL(sim_gemm_kernel<LVLM_F32>, ggrid, dim3(256), 0, stream, a);
+    {
+        const long long tiles = (long long)d.B * w.NB * ((r + w.tile - 1) / w.tile);
+        constexpr int run = kSimGN * kSimGM;
+        const dim3 ggrid((unsigned)(((tiles + run - 1) / run + 7) / 8 * 8 * run));
+        const bool bf = planes[0].dtype == LVLM_BF16;
+        const bool ragged = (planes[0].row_elems * (bf ? 2 : 4)) % 128 != 0;
+#define LVLM_GEMM(DT, NWN, NWM, TR, TC)                                                                              \
+    if (ragged)                                                                                                      \
+        hipLaunchKernelGGL((sim_gemm_kernel<DT, NWN, NWM, TR, TC, true>), ggrid, dim3(64 * NWN * NWM), 0, stream, a);  \
+    else                                                                                                             \
+        hipLaunchKernelGGL((sim_gemm_kernel<DT, NWN, NWM, TR, TC, false>), ggrid, dim3(64 * NWN * NWM), 0, stream, a)
+        if (w.tile == 256) {
+            if (bf) { LVLM_GEMM(LVLM_BF16, 2, 4, 4, 2); } else { LVLM_GEMM(LVLM_F32, 2, 4, 4, 2); }
+        } else {
+            if (bf) { LVLM_GEMM(LVLM_BF16, 2, 2, 2, 2); } else { LVLM_GEMM(LVLM_F32, 2, 2, 2, 2); }
+        }
+#undef LVLM_GEMM
+    }
     prof.end();
     prof.begin("sim_assign");
     hipLaunchKernelGGL(sim_assign_kernel, per_token, dim3(256), 0, stream, a);
