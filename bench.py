@@ -56,6 +56,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--per-layer", action="store_true",
+                    help="one score / compression call per layer instead of one per run of layers / per step "
+                         "(the launch sequence of a caller that batches nothing); default: batched")
     ap.add_argument("--merge", default="rank", choices=["rank", "similar"],
                     help="merge rule at the pyramid layers: the paper's rank weights (lvlm_merge_compact) or the "
                          "similarity merge (lvlm_merge_similar)")
@@ -90,7 +93,7 @@ def plan(w, lv):
     return layers
 
 
-def score_groups(layers):
+def score_groups(layers, per_layer=False):
     """Runs of consecutive scored layers with the same image-token count, as (first, last) layer indices.  A
     run ends at a merge layer (which needs its score at once) or with the stack; the layers before it in the
     run feed only the cache compression after prefill, so one call at the run's end scores them all: their
@@ -102,7 +105,7 @@ def score_groups(layers):
             continue
         if first is None:
             first = i
-        if en["merge_to"] is not None or i + 1 == len(layers) or not layers[i + 1]["score"] \
+        if per_layer or en["merge_to"] is not None or i + 1 == len(layers) or not layers[i + 1]["score"] \
                 or layers[i + 1]["n_img"] != en["n_img"]:
             groups.append((first, i))
             first = None
@@ -122,7 +125,8 @@ class StepState:
     likewise scores, kinds, positions, lengths), so that one lvlm_kv_compress call can serve many layers;
     every layer works on its own [B, ...] slice."""
 
-    def __init__(self, w, layers, master, torch):
+    def __init__(self, w, layers, master, torch, per_layer=False):
+        self.per_layer = per_layer      # one call per layer instead of one per run of layers / per step
         B, H, d, L = w.batch, w.n_kv_heads, w.head_dim, cache_slots(w)
         dev, dt = master[0]["k"].device, master[0]["k"].dtype
         nl = len(layers)
@@ -134,7 +138,7 @@ class StepState:
         self.len = torch.empty(nl * B, H, dtype=torch.int32, device=dev)
         self.n_evicted = torch.empty(nl * B, H, dtype=torch.int32, device=dev)
         self.q = torch.empty(nl * B, w.n_text, w.n_q_heads, d, dtype=dt, device=dev)     # instruction-token queries
-        self.groups = score_groups(layers)
+        self.groups = score_groups(layers, per_layer)
         # head-mean scores [g*B, n_img] of each group; the merge reads the last layer's rows
         self.group_mean = {last: torch.empty((last - first + 1) * B, layers[last]["n_img"], dtype=torch.float32,
                                              device=dev) for first, last in self.groups}
@@ -256,7 +260,11 @@ def run_prefill_layers(ctx, lv, w, states, reserve, merge="rank"):
 
 
 def run_prefill_compress(ctx, lv, w, states, reserve):
-    if states.kv_from is not None:
+    if states.kv_from is not None and states.per_layer:
+        for st in states.layers[states.kv_from // w.batch:]:
+            ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_THRESHOLD, beta=w.kv_beta,
+                            order=lv.ORDER_STABLE, len_bound=st.N, n_evicted=st.n_evicted, reserve=reserve)
+    elif states.kv_from is not None:
         # the threshold rule on the caches of all compressed layers at once (a cache is only read again in decode)
         t = states.tail
         ctx.kv_compress(t(states.k), t(states.v), t(states.score), t(states.kind), t(states.pos), t(states.len),
@@ -284,7 +292,12 @@ def run_decode_layers(ctx, lv, w, states, reserve, step_pos=0):
 
 
 def run_decode_compress(ctx, lv, w, states, reserve):
-    if w.kv_budget > 0 and not decode_evicts_in_attention(w, states):
+    if w.kv_budget > 0 and not decode_evicts_in_attention(w, states) and states.per_layer:
+        for st in states:
+            ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_BUDGET, budget=w.kv_budget,
+                            n_recent=1, order=lv.ORDER_FILL, len_bound=min(st.Lmax, st.N + 1), want_evicted=False,
+                            reserve=reserve)
+    elif w.kv_budget > 0 and not decode_evicts_in_attention(w, states):
         # one budget eviction over the caches of all layers (a layer's cache is next read in the next step)
         ctx.kv_compress(states.k, states.v, states.score, states.kind, states.pos, states.len, mode=lv.KV_BUDGET,
                         budget=w.kv_budget, n_recent=1, order=lv.ORDER_FILL, len_bound=states.dec_bound,
@@ -301,7 +314,7 @@ def score_in_one_launch(w, N):
     return n_chunks <= 32 and N * (w.head_dim * e) // 256 <= 900
 
 
-def kernel_work(w, layers, lens_after_prefill, merge="rank"):
+def kernel_work(w, layers, lens_after_prefill, merge="rank", per_layer=False):
     """Algorithmic bytes / flops of one launch-set of each kernel in one step (sum over layers)."""
     e = 2 if w.dtype == "bf16" else 4
     B, Hq, H, d, T = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_text
@@ -312,7 +325,7 @@ def kernel_work(w, layers, lens_after_prefill, merge="rank"):
         a["amount"] += amount
         a["launches"] += launches
 
-    for first, last in score_groups(layers):
+    for first, last in score_groups(layers, per_layer):
         n_img = layers[last]["n_img"]
         N, gb = w.n_sys + n_img + T, (last - first + 1) * B
         if score_in_one_launch(w, N):
@@ -351,7 +364,7 @@ def main():
     t_setup = time.time()
     master = build_master(w, layers, torch, synth, dev)
     n_sets = 1 + args.warmup + args.steps + args.profile_steps
-    sets = [StepState(w, layers, master, torch) for _ in range(n_sets)]
+    sets = [StepState(w, layers, master, torch, args.per_layer) for _ in range(n_sets)]
     torch.cuda.synchronize()
     print(f"[bench] {w.name}: {len(layers)} layers, {n_sets} state sets, setup {time.time() - t_setup:.1f}s",
           file=sys.stderr, flush=True)
@@ -434,7 +447,7 @@ def main():
             dst.copy_(src)           # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
 
-    work = kernel_work(w, layers, lens_after_prefill, args.merge)
+    work = kernel_work(w, layers, lens_after_prefill, args.merge, args.per_layer)
     kernels = {}
     for name, p in sorted(prof.items(), key=lambda kv: -kv[1]["us_per_step"]):
         row = {"avg_us": round(p["avg_us"], 2), "launches_per_step": p["launches_per_step"],
@@ -486,7 +499,8 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "layers": w.layers, "seq": [w.n_sys, w.n_img, w.n_text],
                    "image_tokens_per_layer": [en["n_img"] for en in layers if en["merge_to"] is not None] +
                                              [layers[-1]["n_img"]],
-                   "kv_beta": w.kv_beta, "kv_budget": w.kv_budget, "merge": args.merge, "graphs": use_graph},
+                   "kv_beta": w.kv_beta, "kv_budget": w.kv_budget, "merge": args.merge, "graphs": use_graph,
+                   "calls": "per layer" if args.per_layer else "batched over layers"},
         "prefill_ms": round(prefill_ms, 4), "decode_step_ms": round(decode_ms, 4),
         "prefill_image_tokens_per_s": round(w.batch * w.n_img / (prefill_ms * 1e-3), 1),
         "decode_steps_per_s": round(1e3 / decode_ms, 1),
