@@ -325,12 +325,11 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
 // launch disappear; the price is that every chunk streams the keys from L2 itself, which only pays while
 // the sequence is short (the launch decides by the bytes that re-streaming costs).  Wave w of NW takes the key
 // tiles 32 (w + NW k) .. +32; a tile's rows go straight from global memory into operand registers, the next
-// tile's loads are in flight while the current one is used (two named register sets).  All elements are
-// masked individually: these launches are bound by latency, not by arithmetic.
+// tile's loads are in flight while the current one is used (two named register sets).
 #define LVLM_K16(M) M(0) M(1) M(2) M(3) M(4) M(5) M(6) M(7) M(8) M(9) M(10) M(11) M(12) M(13) M(14) M(15)
 
 template <int DT, int HD, int NW>
-__global__ __launch_bounds__(64 * NW) void score_small_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(64 * NW, (DT == LVLM_F32 && HD == 128) ? 2 : 3) void score_small_kernel(ScoreArgs a) {
     constexpr int ES = esize<DT>();
     constexpr int ROWB = HD * ES;
     constexpr int NV = HalfRow<DT, HD>::NV;
@@ -342,7 +341,12 @@ __global__ __launch_bounds__(64 * NW) void score_small_kernel(ScoreArgs a) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int hf = lane >> 5, l32 = lane & 31;
-    const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    // Workgroups reach the 8 XCDs round-robin by id: all chunks of one (batch, KV head) pair are given ids
+    // with the same remainder, so that the pair's keys are fetched into one L2 only
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int pair = (seq / a.rs) * 8 + xcd, c = seq % a.rs;
+    if (pair >= a.B * a.Hkv) return;
+    const int b = pair / a.Hkv, g = pair % a.Hkv;
     const int GT = a.G * a.T;
     const long long rowbase = ((long long)b * a.Hq + (long long)g * a.G) * a.T;
     auto div_t = [&](int rho) -> int { return a.T == 1 ? rho : (int)__umulhi((unsigned)rho, a.t_magic); };
@@ -354,18 +358,21 @@ __global__ __launch_bounds__(64 * NW) void score_small_kernel(ScoreArgs a) {
     const int pos = a.causal ? a.q_pos0 + qi : INT_MAX;
     HalfRow<DT, HD> qa;
     {
+        // contraction step i of lane half hf takes bytes [32 i + 16 hf, +16) of the row (the contraction index
+        // is a dummy index: any split works as long as both operands use it): the two halves of one load
+        // instruction then read 32 contiguous bytes of a row, half as many cache lines as with a half row each
         const char *src = a.q + ((long long)b * a.qsb + (long long)qi * a.qst + (long long)(g * a.G + hl) * a.qsh) * ES +
-                          hf * (ROWB / 2);
+                          16 * hf;
 #pragma unroll
-        for (int i = 0; i < NV; ++i) qa.v[i] = *reinterpret_cast<const uint4 *>(src + 16 * i);
+        for (int i = 0; i < NV; ++i) qa.v[i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
     }
     if (tid < 32) pos_s[tid] = pos;
 
-    const char *kbase = a.k + ((long long)b * a.ksb + (long long)g * a.ksh) * ES + hf * (ROWB / 2);
+    const char *kbase = a.k + ((long long)b * a.ksb + (long long)g * a.ksh) * ES + 16 * hf;
 #define LVLM_DECL(x) uint4 kA##x = make_uint4(0, 0, 0, 0), kB##x = make_uint4(0, 0, 0, 0), kC##x = make_uint4(0, 0, 0, 0);
     LVLM_K16(LVLM_DECL)
 #undef LVLM_DECL
-#define LVLM_LD(S, x) if (x < NV) S##x = *reinterpret_cast<const uint4 *>(kp_ + 16 * x);
+#define LVLM_LD(S, x) if (x < NV) S##x = *reinterpret_cast<const uint4 *>(kp_ + 32 * x);
 #define LVLM_LOADK(S, j0, jmax)                                                              \
     {                                                                                        \
         const char *kp_ = kbase + (long long)min((j0) + l32, (jmax) - 1) * a.ksn * ES;       \
@@ -385,6 +392,12 @@ __global__ __launch_bounds__(64 * NW) void score_small_kernel(ScoreArgs a) {
     const int j2_first = key_lo + 32 * wave;
     if (kEarly && j2_first < key_hi) LVLM_LOADK(kC, j2_first, key_hi)
 
+    // A tile whose keys all lie in range and at or before the earliest query position of the chunk needs no
+    // per-element mask (uniform test): that is every image key for instruction rows.
+    const int rho_last = min(c * 32 + 31, GT - 1);
+    const int hc0 = div_t(c * 32), hc1 = div_t(rho_last);
+    const int pos_min = a.causal ? a.q_pos0 + ((hc0 != hc1) ? 0 : c * 32 - hc0 * a.T) : INT_MAX;
+
     // ---- sweep 1: row normalisers over all keys (rows = keys, columns = queries: the row's statistics are
     // lane-local over 16 registers)
     if (a.row_lse == nullptr) {
@@ -394,6 +407,18 @@ __global__ __launch_bounds__(64 * NW) void score_small_kernel(ScoreArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = 0.f;
             mma_tile<DT, HD>(acc, kf, qa);
+            if (j0 + 32 <= a.N && j0 + 31 <= pos_min) {
+                float tmax = acc[0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, acc[r]);
+                const float mn = fmaxf(m, tmax * a.scale_log2);      // finite; scale >= 0 (checked on the host)
+                float sum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -mn));
+                l = l * __builtin_amdgcn_exp2f(m - mn) + sum;
+                m = mn;
+                return;
+            }
             float t[16];
             float tmax = -INFINITY;
 #pragma unroll
@@ -460,11 +485,17 @@ __global__ __launch_bounds__(64 * NW) void score_small_kernel(ScoreArgs a) {
         mma_tile<DT, HD>(acc, qa, kf);
         const int j = j0 + l32;
         float sum = 0.f;
+        if (j0 + 31 <= pos_min) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = acc_row(r, hf);
-            const float p = __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_s[row]));
-            sum += (j <= pos_s[row]) ? p : 0.f;
+            for (int r = 0; r < 16; ++r)
+                sum += __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_s[acc_row(r, hf)]));
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = acc_row(r, hf);
+                const float p = __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_s[row]));
+                sum += (j <= pos_s[row]) ? p : 0.f;
+            }
         }
         sum += __shfl_xor(sum, 32);
         if (hf == 0 && j < key_hi) out[j - key_lo] = sum;
@@ -571,7 +602,8 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool sin
     constexpr int BN = 4 * KPW * 32;
     if (single) {
         prof.begin("score_single");
-        hipLaunchKernelGGL((score_small_kernel<DT, HD, 4>), dim3(a.rs, a.Hkv, a.B), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((score_small_kernel<DT, HD, 4>), dim3((a.B * a.Hkv + 7) / 8 * 8 * a.rs), dim3(256), 0, stream,
+                           a);
         prof.end();
         prof.begin("score_finalize");
         hipLaunchKernelGGL(score_finalize_kernel, dim3((a.n_img + 255) / 256, a.B), dim3(256), 0, stream, a);
