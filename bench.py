@@ -311,7 +311,7 @@ def score_in_one_launch(w, N):
     name; main() checks the launch counts it implies against the ones measured."""
     e = 2 if w.dtype == "bf16" else 4
     n_chunks = (w.n_q_heads // w.n_kv_heads * w.n_text + 31) // 32
-    return n_chunks <= 32 and N * (w.head_dim * e) // 256 <= 900
+    return n_chunks <= 32 and N * (w.head_dim * e) // 256 <= 1100
 
 
 def kernel_work(w, layers, lens_after_prefill, merge="rank", per_layer=False):

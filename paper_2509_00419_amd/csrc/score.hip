@@ -368,21 +368,29 @@ __global__ __launch_bounds__(64 * NW, (DT == LVLM_F32 && HD == 128) ? 2 : 3) voi
     }
     if (tid < 32) pos_s[tid] = pos;
 
-    const char *kbase = a.k + ((long long)b * a.ksb + (long long)g * a.ksh) * ES + 16 * hf;
+    // loads: lane pair (2 r, 2 r + 1) reads 32 contiguous bytes of row r (half as many memory requests as one
+    // row per lane); LVLM_PACK moves each piece to the lane (row l32, half hf) the MFMA wants it in
+    const char *kbase = a.k + ((long long)b * a.ksb + (long long)g * a.ksh) * ES + 16 * (lane & 1);
+    const int k_src = 4 * (2 * l32 + hf);
 #define LVLM_DECL(x) uint4 kA##x = make_uint4(0, 0, 0, 0), kB##x = make_uint4(0, 0, 0, 0), kC##x = make_uint4(0, 0, 0, 0);
     LVLM_K16(LVLM_DECL)
 #undef LVLM_DECL
 #define LVLM_LD(S, x) if (x < NV) S##x = *reinterpret_cast<const uint4 *>(kp_ + 32 * x);
 #define LVLM_LOADK(S, j0, jmax)                                                              \
     {                                                                                        \
-        const char *kp_ = kbase + (long long)min((j0) + l32, (jmax) - 1) * a.ksn * ES;       \
+        const char *kp_ = kbase + (long long)min((j0) + (lane >> 1), (jmax) - 1) * a.ksn * ES; \
         LVLM_LD(S, 0) LVLM_LD(S, 1) LVLM_LD(S, 2) LVLM_LD(S, 3) LVLM_LD(S, 4) LVLM_LD(S, 5) LVLM_LD(S, 6) LVLM_LD(S, 7) \
         LVLM_LD(S, 8) LVLM_LD(S, 9) LVLM_LD(S, 10) LVLM_LD(S, 11) LVLM_LD(S, 12) LVLM_LD(S, 13) LVLM_LD(S, 14) LVLM_LD(S, 15) \
     }
 #define LVLM_PACK(S, kf)                                                                     \
     {                                                                                        \
         const uint4 w_[16] = {S##0, S##1, S##2, S##3, S##4, S##5, S##6, S##7, S##8, S##9, S##10, S##11, S##12, S##13, S##14, S##15}; \
-        _Pragma("unroll") for (int i = 0; i < NV; ++i) kf.v[i] = w_[i];                      \
+        _Pragma("unroll") for (int i = 0; i < NV; ++i) {                                     \
+            kf.v[i].x = __builtin_amdgcn_ds_bpermute(k_src, w_[i].x);                         \
+            kf.v[i].y = __builtin_amdgcn_ds_bpermute(k_src, w_[i].y);                         \
+            kf.v[i].z = __builtin_amdgcn_ds_bpermute(k_src, w_[i].z);                         \
+            kf.v[i].w = __builtin_amdgcn_ds_bpermute(k_src, w_[i].w);                         \
+        }                                                                                    \
     }
 
     // the first tile of the second sweep is fetched now: its latency hides behind the first sweep (where
@@ -633,7 +641,7 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool sin
 }  // namespace
 
 constexpr int kSingleMaxChunks = 32;
-constexpr int kSingleMaxRows = 900;      // in 256-byte key rows
+constexpr int kSingleMaxRows = 1100;      // in 256-byte key rows
 
 ScoreWs score_ws(const lvlm_score_desc &d) {
     ScoreWs w{};

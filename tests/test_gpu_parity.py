@@ -52,7 +52,7 @@ SCORE_CASES = [
     (torch.bfloat16, 1, 33, 8, 8, 64, 0, 200, False),         # d=64, no mask, no system prefix
     (torch.bfloat16, 3, 40, 14, 2, 128, 7, 1000, True),       # G=7 with T=40: 280 rows = 8.75 chunks
     # short sequences take both passes in one launch (one workgroup per 32-row chunk); the cases above with
-    # N <= ~1100 rows of 256 bytes are of that kind, the ones below keep the two-pass kernels on ragged shapes
+    # N <= 1100 rows of 256 bytes are of that kind, the ones below keep the two-pass kernels on ragged shapes
     (torch.bfloat16, 1, 64, 28, 4, 128, 64, 717, True),       # config 2 after the first merge: 14 chunks, one launch
     (torch.bfloat16, 2, 9, 6, 2, 128, 5, 1500, True),         # two-pass, G*T = 27, ragged keys
     (torch.bfloat16, 1, 33, 8, 8, 64, 0, 2300, False),        # two-pass, d=64, no mask
