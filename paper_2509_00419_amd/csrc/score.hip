@@ -104,10 +104,11 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     uint4 stB0 = stA0, stB1 = stA0, stB2 = stA0, stB3 = stA0;
     int stA_pos = -1, stB_pos = -1;
     float stA_lse = 0.f, stB_lse = 0.f;
-    // A thread stages UPT consecutive 16-byte units of ONE row of every chunk.  Its source address is
+    // A thread stages UPT 16-byte units of ONE row of every chunk.  Its source address is
     // carried from load to load (a stage takes every second chunk: 64 rows further down, stepping over to
     // the next head when the rows of one are used up), so the chunk loop holds no address multiplies.
-    const int srow = tid * UPT / UPR, scu = tid * UPT % UPR;
+    constexpr int TPR = UPR / UPT;       // threads per row: neighbouring lanes read neighbouring 16-byte units
+    const int srow = tid / TPR, scu = tid % TPR;       // units scu + TPR x, x < UPT
     const long long q_step = 64 * a.qst * ES;                            // 64 rows further in the same head
     const long long q_wrap = (a.qsh - (long long)a.T * a.qst) * ES;      // from row T of a head to row 0 of the next
     const char *q_grp0 = a.q + ((long long)b * a.qsb + (long long)g * a.G * a.qsh) * ES;    // uniform
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
         }
     };
     auto chunk_dst = [&](int buf, int x) -> uint4 * {
-        return reinterpret_cast<uint4 *>(&q_lds[buf][srow * PITCH + 16 * (scu + x)]);
+        return reinterpret_cast<uint4 *>(&q_lds[buf][srow * PITCH + 16 * (scu + TPR * x)]);
     };
     auto row_meta = [&](int c, int &pos, float &lse) {
         pos = -1;             // padding row: sees no key
@@ -166,9 +167,9 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
         if (c < c_hi) {                                                  \
             const uint4 *src = chunk_row(c, p##S);                      \
             st##S##0 = src[0];                                           \
-            if constexpr (UPT > 1) st##S##1 = src[1];                    \
-            if constexpr (UPT > 2) st##S##2 = src[2];                    \
-            if constexpr (UPT > 3) st##S##3 = src[3];                    \
+            if constexpr (UPT > 1) st##S##1 = src[TPR];                  \
+            if constexpr (UPT > 2) st##S##2 = src[2 * TPR];              \
+            if constexpr (UPT > 3) st##S##3 = src[3 * TPR];              \
             row_meta(c, st##S##_pos, st##S##_lse);                       \
         }                                                                \
         advance(p##S, i##S);                                             \
