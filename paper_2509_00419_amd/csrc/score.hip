@@ -14,9 +14,9 @@
 // Tiling (wave64, MFMA 32x32): a workgroup of 4 waves owns 4*KPW*32 keys; each
 // wave keeps its KPW 32-key operand tiles in registers for the whole kernel and
 // streams 32-row query chunks through LDS (double buffered, one barrier per
-// chunk).  The reduction index of the MFMA is a dummy index, so each lane feeds
-// one contiguous half of a head vector (lane/32 selects the half) -- global and
-// LDS reads are then plain 16-byte vectors.
+// chunk).  The reduction index of the MFMA is a dummy index, so step i of lane
+// half lane/32 simply takes bytes [32 i + 16 (lane/32), +16) of a head vector --
+// global and LDS reads are then plain 16-byte vectors.
 #include <limits.h>
 
 #include "common.h"
@@ -86,14 +86,27 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     HalfRow<DT, HD> kf[KPW];
 #pragma unroll
     for (int s = 0; s < KPW; ++s) {
-        const int j = jbase + 32 * s + l32;
+        // Contraction step i of lane half hf takes bytes [32 i + 16 hf, +16) of a row (both operands).  The
+        // load puts a lane PAIR on 32 contiguous bytes of one row -- the memory pipeline serves one request
+        // per lane when every lane of a quad reads another row -- and a lane permute then moves each piece
+        // to the lane (row l32, half hf) the MFMA wants it in.
+        const int j = jbase + 32 * s + (lane >> 1);
+        uint4 raw[NV];
 #pragma unroll
-        for (int i = 0; i < NV; ++i) kf[s].v[i] = make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < NV; ++i) raw[i] = make_uint4(0, 0, 0, 0);
         if (j < key_hi) {
             const char *src = a.k + ((long long)b * a.ksb + (long long)j * a.ksn + (long long)g * a.ksh) * ES +
-                              hf * (ROWB / 2);
+                              16 * (lane & 1);
 #pragma unroll
-            for (int i = 0; i < NV; ++i) kf[s].v[i] = *reinterpret_cast<const uint4 *>(src + 16 * i);
+            for (int i = 0; i < NV; ++i) raw[i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
+        }
+        const int from = 4 * (2 * l32 + hf);
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            kf[s].v[i].x = __builtin_amdgcn_ds_bpermute(from, raw[i].x);
+            kf[s].v[i].y = __builtin_amdgcn_ds_bpermute(from, raw[i].y);
+            kf[s].v[i].z = __builtin_amdgcn_ds_bpermute(from, raw[i].z);
+            kf[s].v[i].w = __builtin_amdgcn_ds_bpermute(from, raw[i].w);
         }
     }
 
@@ -195,9 +208,9 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     auto compute = [&](int c, int buf) {
         HalfRow<DT, HD> qa;
         {
-            const char *src = &q_lds[buf][l32 * PITCH + hf * (ROWB / 2)];
+            const char *src = &q_lds[buf][l32 * PITCH + 16 * hf];
 #pragma unroll
-            for (int i = 0; i < NV; ++i) qa.v[i] = *reinterpret_cast<const uint4 *>(src + 16 * i);
+            for (int i = 0; i < NV; ++i) qa.v[i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
         }
         f32x16 acc[KPW];
 #pragma unroll
