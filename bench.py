@@ -56,6 +56,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--prefill-order", default="stable", choices=["stable", "fill"],
+                    help="slot order after the threshold compression of the caches: survivors in ascending slot "
+                         "order (stable, default) or holes filled from the tail (fill)")
     ap.add_argument("--per-layer", action="store_true",
                     help="one score / compression call per layer instead of one per run of layers / per step "
                          "(the launch sequence of a caller that batches nothing); default: batched")
@@ -125,8 +128,9 @@ class StepState:
     likewise scores, kinds, positions, lengths), so that one lvlm_kv_compress call can serve many layers;
     every layer works on its own [B, ...] slice."""
 
-    def __init__(self, w, layers, master, torch, per_layer=False):
+    def __init__(self, w, layers, master, torch, per_layer=False, prefill_order="stable"):
         self.per_layer = per_layer      # one call per layer instead of one per run of layers / per step
+        self.prefill_order = prefill_order
         B, H, d, L = w.batch, w.n_kv_heads, w.head_dim, cache_slots(w)
         dev, dt = master[0]["k"].device, master[0]["k"].dtype
         nl = len(layers)
@@ -260,15 +264,18 @@ def run_prefill_layers(ctx, lv, w, states, reserve, merge="rank"):
 
 
 def run_prefill_compress(ctx, lv, w, states, reserve):
+    # survivors keep their slot order (stable) or the holes are filled from the tail (fill: moves only as many
+    # entries as were evicted)
+    order = lv.ORDER_FILL if states.prefill_order == "fill" else lv.ORDER_STABLE
     if states.kv_from is not None and states.per_layer:
         for st in states.layers[states.kv_from // w.batch:]:
             ctx.kv_compress(st.k, st.v, st.score, st.kind, st.pos, st.len, mode=lv.KV_THRESHOLD, beta=w.kv_beta,
-                            order=lv.ORDER_STABLE, len_bound=st.N, n_evicted=st.n_evicted, reserve=reserve)
+                            order=order, len_bound=st.N, n_evicted=st.n_evicted, reserve=reserve)
     elif states.kv_from is not None:
         # the threshold rule on the caches of all compressed layers at once (a cache is only read again in decode)
         t = states.tail
         ctx.kv_compress(t(states.k), t(states.v), t(states.score), t(states.kind), t(states.pos), t(states.len),
-                        mode=lv.KV_THRESHOLD, beta=w.kv_beta, order=lv.ORDER_STABLE, len_bound=states.kv_bound,
+                        mode=lv.KV_THRESHOLD, beta=w.kv_beta, order=order, len_bound=states.kv_bound,
                         n_evicted=t(states.n_evicted), reserve=reserve)
 
 
@@ -364,7 +371,7 @@ def main():
     t_setup = time.time()
     master = build_master(w, layers, torch, synth, dev)
     n_sets = 1 + args.warmup + args.steps + args.profile_steps
-    sets = [StepState(w, layers, master, torch, args.per_layer) for _ in range(n_sets)]
+    sets = [StepState(w, layers, master, torch, args.per_layer, args.prefill_order) for _ in range(n_sets)]
     torch.cuda.synchronize()
     print(f"[bench] {w.name}: {len(layers)} layers, {n_sets} state sets, setup {time.time() - t_setup:.1f}s",
           file=sys.stderr, flush=True)
@@ -500,7 +507,8 @@ def main():
                    "image_tokens_per_layer": [en["n_img"] for en in layers if en["merge_to"] is not None] +
                                              [layers[-1]["n_img"]],
                    "kv_beta": w.kv_beta, "kv_budget": w.kv_budget, "merge": args.merge, "graphs": use_graph,
-                   "calls": "per layer" if args.per_layer else "batched over layers"},
+                   "calls": "per layer" if args.per_layer else "batched over layers",
+                   "prefill_order": args.prefill_order},
         "prefill_ms": round(prefill_ms, 4), "decode_step_ms": round(decode_ms, 4),
         "prefill_image_tokens_per_s": round(w.batch * w.n_img / (prefill_ms * 1e-3), 1),
         "decode_steps_per_s": round(1e3 / decode_ms, 1),
