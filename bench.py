@@ -56,6 +56,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--row-lse", default="computed", choices=["computed", "given"],
+                    help="row normalisers of the scoring step: computed by the library (default: one more pass over "
+                         "the keys) or given, as a prefill attention kernel that emits its log-sum-exp would (Sec. "
+                         "3.2.1: the scores then cost one pass over the image keys)")
     ap.add_argument("--prefill-order", default="stable", choices=["stable", "fill"],
                     help="slot order after the threshold compression of the caches: survivors in ascending slot "
                          "order (stable, default) or holes filled from the tail (fill)")
@@ -128,7 +132,7 @@ class StepState:
     likewise scores, kinds, positions, lengths), so that one lvlm_kv_compress call can serve many layers;
     every layer works on its own [B, ...] slice."""
 
-    def __init__(self, w, layers, master, torch, per_layer=False, prefill_order="stable"):
+    def __init__(self, w, layers, master, torch, per_layer=False, prefill_order="stable", given_lse=False):
         self.per_layer = per_layer      # one call per layer instead of one per run of layers / per step
         self.prefill_order = prefill_order
         B, H, d, L = w.batch, w.n_kv_heads, w.head_dim, cache_slots(w)
@@ -142,6 +146,13 @@ class StepState:
         self.len = torch.empty(nl * B, H, dtype=torch.int32, device=dev)
         self.n_evicted = torch.empty(nl * B, H, dtype=torch.int32, device=dev)
         self.q = torch.empty(nl * B, w.n_text, w.n_q_heads, d, dtype=dt, device=dev)     # instruction-token queries
+        # natural-log sum-exp of every instruction row's scaled logits, as an attention kernel would leave it
+        self.row_lse = None
+        if given_lse:
+            self.row_lse = torch.zeros(nl * B, w.n_q_heads, w.n_text, dtype=torch.float32, device=dev)
+            for i, m in enumerate(master):
+                if "row_lse" in m:
+                    self.row_lse[i * B:(i + 1) * B] = m["row_lse"]
         self.groups = score_groups(layers, per_layer)
         # head-mean scores [g*B, n_img] of each group; the merge reads the last layer's rows
         self.group_mean = {last: torch.empty((last - first + 1) * B, layers[last]["n_img"], dtype=torch.float32,
@@ -204,7 +215,19 @@ class LayerState:
         self.out_dec = torch.empty_like(self.q_dec)
 
 
-def build_master(w, layers, torch, synth, dev):
+def row_lse_of(q, k, q_pos0, torch):
+    """[B,Hq,T] natural-log sum-exp over the causally visible keys of q.k / sqrt(d) (fp32, plain torch: set-up)."""
+    B, T, Hq, d = q.shape
+    N, Hkv = k.shape[1], k.shape[2]
+    out = torch.empty(B, Hq, T, dtype=torch.float32, device=q.device)
+    vis = torch.arange(N, device=q.device)[None, :] <= (q_pos0 + torch.arange(T, device=q.device))[:, None]
+    for h in range(Hq):
+        s = torch.einsum("btd,bnd->btn", q[:, :, h].float(), k[:, :, h // (Hq // Hkv)].float()) / math.sqrt(d)
+        out[:, h] = torch.logsumexp(s.masked_fill(~vis, float("-inf")), dim=-1)
+    return out
+
+
+def build_master(w, layers, torch, synth, dev, given_lse=False):
     """One set of inputs per layer, generated on the GPU (seeded)."""
     master = []
     B, H, d = w.batch, w.n_kv_heads, w.head_dim
@@ -214,6 +237,8 @@ def build_master(w, layers, torch, synth, dev):
         N = x["k"].shape[1]
         Lmax = cache_slots(w)
         m = {"q": x["q"]}
+        if given_lse and entry["score"]:
+            m["row_lse"] = row_lse_of(x["q"], x["k"], w.n_sys + n_img, torch)
         for name in ("k", "v"):
             cache = torch.zeros(B, H, Lmax, d, dtype=x[name].dtype, device=dev)
             cache[:, :, :N] = x[name].permute(0, 2, 1, 3)
@@ -250,6 +275,7 @@ def run_prefill_layers(ctx, lv, w, states, reserve, merge="rank"):
             k_view = states.k[sl, :, :st.N].permute(0, 2, 1, 3)     # [g*B,N,H,d] view of the head-major caches
             sh_view = states.score[sl, :, img0:img0 + st.n_img]     # scores land in the caches' score arrays
             ctx.score_tokens(states.q[sl], k_view, q_pos0=img0 + st.n_img, img_begin=img0, n_img=st.n_img,
+                             row_lse=None if states.row_lse is None else states.row_lse[sl],
                              score_head=sh_view, score_mean=states.group_mean[i], reserve=reserve)
         if e["merge_to"] is not None and merge == "similar":
             ctx.merge_similar([st.hidden, st.pos_ids], st.score_mean, img_begin=img0, n_img=st.n_img,
@@ -321,7 +347,7 @@ def score_in_one_launch(w, N):
     return n_chunks <= 32 and N * (w.head_dim * e) // 256 <= 1100
 
 
-def kernel_work(w, layers, lens_after_prefill, merge="rank", per_layer=False):
+def kernel_work(w, layers, lens_after_prefill, merge="rank", per_layer=False, given_lse=False):
     """Algorithmic bytes / flops of one launch-set of each kernel in one step (sum over layers)."""
     e = 2 if w.dtype == "bf16" else 4
     B, Hq, H, d, T = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_text
@@ -336,9 +362,10 @@ def kernel_work(w, layers, lens_after_prefill, merge="rank", per_layer=False):
         n_img = layers[last]["n_img"]
         N, gb = w.n_sys + n_img + T, (last - first + 1) * B
         if score_in_one_launch(w, N):
-            add("score_single", "mfma", 2.0 * gb * T * (N + n_img) * d * Hq)
+            add("score_single", "mfma", 2.0 * gb * T * ((0 if given_lse else N) + n_img) * d * Hq)
         else:
-            add("score_pass0", "mfma", 2.0 * gb * T * N * d * Hq)
+            if not given_lse:
+                add("score_pass0", "mfma", 2.0 * gb * T * N * d * Hq)
             add("score_pass1", "mfma", 2.0 * gb * T * n_img * d * Hq)
     for i, en in enumerate(layers):
         N = w.n_sys + en["n_img"] + T
@@ -369,9 +396,10 @@ def main():
     layers = plan(w, lv)
     ctx = lv.Context(0)
     t_setup = time.time()
-    master = build_master(w, layers, torch, synth, dev)
+    master = build_master(w, layers, torch, synth, dev, args.row_lse == "given")
     n_sets = 1 + args.warmup + args.steps + args.profile_steps
-    sets = [StepState(w, layers, master, torch, args.per_layer, args.prefill_order) for _ in range(n_sets)]
+    sets = [StepState(w, layers, master, torch, args.per_layer, args.prefill_order, args.row_lse == "given")
+            for _ in range(n_sets)]
     torch.cuda.synchronize()
     print(f"[bench] {w.name}: {len(layers)} layers, {n_sets} state sets, setup {time.time() - t_setup:.1f}s",
           file=sys.stderr, flush=True)
@@ -454,7 +482,7 @@ def main():
             dst.copy_(src)           # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
 
-    work = kernel_work(w, layers, lens_after_prefill, args.merge, args.per_layer)
+    work = kernel_work(w, layers, lens_after_prefill, args.merge, args.per_layer, args.row_lse == "given")
     kernels = {}
     for name, p in sorted(prof.items(), key=lambda kv: -kv[1]["us_per_step"]):
         row = {"avg_us": round(p["avg_us"], 2), "launches_per_step": p["launches_per_step"],
@@ -508,7 +536,7 @@ def main():
                                              [layers[-1]["n_img"]],
                    "kv_beta": w.kv_beta, "kv_budget": w.kv_budget, "merge": args.merge, "graphs": use_graph,
                    "calls": "per layer" if args.per_layer else "batched over layers",
-                   "prefill_order": args.prefill_order},
+                   "prefill_order": args.prefill_order, "row_lse": args.row_lse},
         "prefill_ms": round(prefill_ms, 4), "decode_step_ms": round(decode_ms, 4),
         "prefill_image_tokens_per_s": round(w.batch * w.n_img / (prefill_ms * 1e-3), 1),
         "decode_steps_per_s": round(1e3 / decode_ms, 1),

@@ -55,10 +55,10 @@ def same_entries(now, ref, exact_score=True, tol=1e-5):
                 assert rel_err(now[2][b, h, :n], ref[2][b, h, :n]) < tol, (b, h)
 
 
-def build(w):
+def build(w, given_lse=False):
     layers = bench.plan(w, lv)
-    master = bench.build_master(w, layers, torch, synth, DEV)
-    return layers, master, bench.StepState(w, layers, master, torch)
+    master = bench.build_master(w, layers, torch, synth, DEV, given_lse)
+    return layers, master, bench.StepState(w, layers, master, torch, given_lse=given_lse)
 
 
 def layer_slices(st, i, B):
@@ -66,13 +66,15 @@ def layer_slices(st, i, B):
     return st.k[sl], st.v[sl], st.score[sl], st.kind[sl], st.pos[sl], st.len[sl]
 
 
-@pytest.mark.parametrize("name,every_layer", [("cfg2", True), ("cfg3", False), ("cfg5", False)])
-def test_prefill_and_decode_step_in_bench_configuration(name, every_layer):
+@pytest.mark.parametrize("name,every_layer,given_lse", [("cfg2", True, False), ("cfg3", False, False),
+                                                        ("cfg5", False, False), ("cfg2", True, True)])
+def test_prefill_and_decode_step_in_bench_configuration(name, every_layer, given_lse):
     """Config 2: every layer of the step.  Configs 3 and 5 (B = 8; 16512 tokens): the first and last layer of
-    every scoring run plus one uncompressed layer -- the oracle needs seconds per layer there."""
+    every scoring run plus one uncompressed layer -- the oracle needs seconds per layer there.  given_lse: the
+    bench's --row-lse given mode (row normalisers from plain torch, as an attention kernel would leave them)."""
     w = configs.ALL[name]
     ctx = lv.Context(0)
-    layers, master, st = build(w)
+    layers, master, st = build(w, given_lse)
     B, img0, tol = w.batch, w.n_sys, 2e-2
     if every_layer:
         assert st.groups == [(5, 5), (6, 9), (10, 13), (14, 27)]
