@@ -801,7 +801,6 @@ hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const A
                               const void *k_new, const void *v_new, void *k_cache, void *v_cache, float *score,
                               uint8_t *kind, int32_t *orig_pos, int32_t *len, void *out) {
     const int bound = d.len_bound > 0 ? d.len_bound : d.Lmax;
-    const long long heads = (long long)d.B * d.Hkv;
     const int G = d.Hq / d.Hkv;
     AttnArgs a{};
     a.q = static_cast<const char *>(q);

@@ -345,7 +345,6 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
 template <int DT, int HD, int NW>
 __global__ __launch_bounds__(64 * NW, (DT == LVLM_F32 && HD == 128) ? 2 : 3) void score_small_kernel(ScoreArgs a) {
     constexpr int ES = esize<DT>();
-    constexpr int ROWB = HD * ES;
     constexpr int NV = HalfRow<DT, HD>::NV;
     constexpr int SW = 32 * NW;             // keys all waves take per sweep step
     static_assert(NV <= 16, "operand registers are written out for up to 16 words");

@@ -125,11 +125,9 @@ constexpr int kSimGN = 8, kSimGM = 4;
 
 template <int DT, int NWN, int NWM, int TR, int TC, bool RAGGED>
 __global__ __launch_bounds__(64 * NWN * NWM) void sim_gemm_kernel(SimArgs a) {
-    constexpr int ES = esize<DT>();
     constexpr int NT = 64 * NWN * NWM;
     constexpr int TM = NWN * TR * 32, TN = NWM * TC * 32;
     constexpr int SB = 128;              // bytes of one slice of a row
-    constexpr int HS = SB / ES;          // its elements
     constexpr int PITCH = SB + 16;       // slice + 16 bytes: spreads the rows over the LDS banks
     constexpr int RPI = NT / 8;          // rows one load instruction of the workgroup covers
     constexpr int UA = TM / RPI, UB = TN / RPI;      // staging units per thread: rows srow + RPI j of each operand
