@@ -206,6 +206,25 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     for (int s = 0; s < KPW; ++s) colsum[s] = 0.f;
 
     auto compute = [&](int c, int buf) {
+        // Positions of the chunk's rows (uniform): a chunk inside one head covers rows i0 .. i0 + 31 of it, one
+        // that straddles two heads anything from 0 to T - 1.
+        const int rho0 = c * 32, rho1 = min(rho0 + 31, GT - 1);
+        const int h0 = div_t(rho0), h1 = div_t(rho1);
+        const int min_i = (h0 != h1) ? 0 : rho0 - h0 * a.T;
+        const int max_i = (h0 != h1) ? a.T - 1 : rho1 - h1 * a.T;
+        // Every key of this wave lies ahead of every row of the chunk (query rows inside the key range, as when
+        // all rows of the sequence are scored): nothing to multiply.
+        if (a.causal && jbase > a.q_pos0 + max_i) {
+            if (PASS == 0) {
+                const int rho = rho0 + l32;
+                if (hf == 0 && rho < GT) {
+                    const long long pidx = ((long long)kb * 4 + wave) * rows_total + rowbase + rho;
+                    a.part_m[pidx] = -INFINITY;
+                    a.part_l[pidx] = 0.f;
+                }
+            }
+            return;
+        }
         HalfRow<DT, HD> qa;
         {
             const char *src = &q_lds[buf][l32 * PITCH + 16 * hf];
@@ -224,9 +243,6 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
         }
         // Is any element of this 32 x (KPW*32) block masked?  Uniform over the workgroup's wave:
         // keys beyond the range, padding rows, or a key ahead of the earliest query position of the chunk.
-        const int rho0 = c * 32, rho1 = min(rho0 + 31, GT - 1);
-        const int h0 = div_t(rho0), h1 = div_t(rho1);
-        const int min_i = (h0 != h1) ? 0 : rho0 - h0 * a.T;
         const bool masked = jbase + KPW * 32 > key_hi || rho0 + 32 > GT ||
                             (a.causal && jbase + KPW * 32 - 1 > a.q_pos0 + min_i);
 

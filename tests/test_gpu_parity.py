@@ -98,6 +98,20 @@ def test_score_tokens_mask_inside_span_and_strided_inputs(ctx, N):
     assert float(sm[:, -1].max()) < 1.0                            # last key is seen by one row only
 
 
+def test_score_all_rows_reading_long_sequence(ctx):
+    # every row of the sequence is a query row (the all-rows reading of Sec. 3.2.1) under the causal mask: half
+    # of the (key block, row chunk) pairs lie wholly above the diagonal and are skipped, the ones on it are
+    # masked element by element; 2176 tokens, G = 4
+    B, N, Hq, Hkv, d, n_sys, n_img = 1, 2176, 8, 2, 128, 64, 2048
+    q, k = _rand((B, N, Hq, d), torch.bfloat16, 5), _rand((B, N, Hkv, d), torch.bfloat16, 6)
+    kw = dict(q_pos0=0, img_begin=n_sys, n_img=n_img, causal=True)
+    sh, sm = ctx.score_tokens(q.to(DEV), k.to(DEV), **kw)
+    osh, osm = O.score_tokens(f64(q), f64(k), **kw)
+    assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
+    # an early image key is seen by almost every row, the last one by the text rows only
+    assert float(sm[0, 0]) > float(sm[0, -1])
+
+
 def test_score_wide_blocks_config3_shape(ctx):
     # B=8, 8 KV heads, N=1888: enough workgroups for the 256-key blocks (2 tiles per wave)
     w = configs.CFG3
