@@ -53,7 +53,8 @@ typedef enum {
     LVLM_OP_MERGE = 1,
     LVLM_OP_KV_COMPRESS = 2,
     LVLM_OP_DECODE_ATTN = 3,
-    LVLM_OP_MERGE_SIMILAR = 4
+    LVLM_OP_MERGE_SIMILAR = 4,
+    LVLM_OP_SCORE_PROBS = 5
 } lvlm_op;
 
 /* Rank -> weight tables for the merged token (Sec. 3.2.1, par. 4). */
@@ -159,6 +160,29 @@ typedef struct {
 LVLM_API lvlm_status lvlm_score_tokens(lvlm_ctx *ctx, void *stream, const lvlm_score_desc *d,
                               const void *q, const void *k, const float *row_lse,
                               float *score_head, float *score_mean);
+
+/* The same scores from attention probabilities the caller already holds -- a
+ * plain attention that materialises its matrix (Sec. 3.2.2 names both sources:
+ * the full attention matrix or the cumulative score).  probs[b][h][i][j] is the
+ * softmax probability of query row i (of the T rows to be summed, e.g. the
+ * instruction rows) on key j, dtype bf16 or fp32, innermost axis contiguous,
+ * strides in elements.  score_head[b][g][j] = (1/G)
+ * sum over the G heads of group g and the T rows of probs[..][img_begin + j];
+ * score_mean as in lvlm_score_tokens.  Sums are fp32 in a fixed order. */
+typedef struct {
+    int32_t dtype;     /* LVLM_BF16 or LVLM_F32: element type of probs            */
+    int32_t B, N, T;   /* batch, keys per row, query rows                         */
+    int32_t Hq, Hkv;   /* query heads, KV heads (Hq % Hkv == 0)                   */
+    int32_t img_begin; /* first image key                                         */
+    int32_t n_img;     /* number of image keys; img_begin + n_img <= N            */
+    int64_t p_stride_b, p_stride_h, p_stride_t; /* probs[b][h][i][0..N)           */
+    int64_t sh_stride_b, sh_stride_h; /* score_head strides; both 0 = dense       */
+} lvlm_probs_desc;
+
+/* probs: device.  score_head [B,Hkv,n_img] fp32, score_mean [B,n_img] fp32 (4-byte
+ * aligned suffices), both written in full.  Workspace: LVLM_OP_SCORE_PROBS. */
+LVLM_API lvlm_status lvlm_score_from_probs(lvlm_ctx *ctx, void *stream, const lvlm_probs_desc *d,
+                                           const void *probs, float *score_head, float *score_mean);
 
 /* ---- steps 2-4: partition, merge, compact -------------------------------- */
 

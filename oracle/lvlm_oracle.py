@@ -125,6 +125,21 @@ def score_tokens(q, k, *, q_pos0: int, img_begin: int, n_img: int,
     return score_head.astype(np.float32), score_mean.astype(np.float32)
 
 
+def score_from_probs(probs, *, n_kv_heads: int, img_begin: int, n_img: int):
+    """The same scores when the attention probabilities are already there (Sec. 3.2.2 takes them from "the
+    full attention matrix" of a plain attention just as well): probs [B, Hq, T, N], the softmax rows of the T
+    query rows to be summed.  Column sums over the rows, mean over the G heads of a KV group, mean over the
+    groups.  Returns (score_head [B,Hkv,n_img] f32, score_mean [B,n_img] f32)."""
+    p = np.asarray(probs, dtype=np.float64)
+    B, Hq, T, N = p.shape
+    assert Hq % n_kv_heads == 0 and 0 <= img_begin and img_begin + n_img <= N
+    G = Hq // n_kv_heads
+    a = p[:, :, :, img_begin:img_begin + n_img].sum(axis=2)            # [B, Hq, n_img]: attention received
+    score_head = a.reshape(B, n_kv_heads, G, n_img).sum(axis=2) / G
+    score_mean = score_head.sum(axis=1) / n_kv_heads
+    return score_head.astype(np.float32), score_mean.astype(np.float32)
+
+
 # --------------------------------------------------------------------------
 # step 2: order by importance   (Sec. 3.2.1, par. 4: "reorder ... by importance")
 # --------------------------------------------------------------------------

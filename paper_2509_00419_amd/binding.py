@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "liblvlm.so")
 
 # ---- enums (include/lvlm.h) ----
 BF16, F32, I32 = 0, 1, 2
-OP_SCORE, OP_MERGE, OP_KV_COMPRESS, OP_DECODE_ATTN, OP_MERGE_SIMILAR = 0, 1, 2, 3, 4
+OP_SCORE, OP_MERGE, OP_KV_COMPRESS, OP_DECODE_ATTN, OP_MERGE_SIMILAR, OP_SCORE_PROBS = 0, 1, 2, 3, 4, 5
 MERGE_LINEAR_RANK, MERGE_PAIRWISE, MERGE_LINEAR_RAW = 0, 1, 2
 RULE_WEIGHTED, RULE_TOP = 0, 1
 KV_THRESHOLD, KV_BUDGET = 0, 1
@@ -37,6 +37,13 @@ class ScoreDesc(C.Structure):
                 ("img_begin", C.c_int32), ("n_img", C.c_int32), ("causal", C.c_int32), ("scale", C.c_float),
                 ("q_stride_b", C.c_int64), ("q_stride_t", C.c_int64), ("q_stride_h", C.c_int64),
                 ("k_stride_b", C.c_int64), ("k_stride_n", C.c_int64), ("k_stride_h", C.c_int64),
+                ("sh_stride_b", C.c_int64), ("sh_stride_h", C.c_int64)]
+
+
+class ProbsDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("B", C.c_int32), ("N", C.c_int32), ("T", C.c_int32),
+                ("Hq", C.c_int32), ("Hkv", C.c_int32), ("img_begin", C.c_int32), ("n_img", C.c_int32),
+                ("p_stride_b", C.c_int64), ("p_stride_h", C.c_int64), ("p_stride_t", C.c_int64),
                 ("sh_stride_b", C.c_int64), ("sh_stride_h", C.c_int64)]
 
 
@@ -94,6 +101,7 @@ def _load():
     lib.lvlm_schedule.argtypes = [C.c_int, C.c_double, C.c_int, C.POINTER(C.c_int)]
     lib.lvlm_merge_weights.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_float)]
     lib.lvlm_score_tokens.argtypes = [vp, vp, C.POINTER(ScoreDesc), vp, vp, f32p, f32p, f32p]
+    lib.lvlm_score_from_probs.argtypes = [vp, vp, C.POINTER(ProbsDesc), vp, f32p, f32p]
     lib.lvlm_merge_compact.argtypes = [vp, vp, C.POINTER(MergeDesc), f32p, f32p, C.POINTER(Plane), i32p, i32p]
     lib.lvlm_merge_similar.argtypes = [vp, vp, C.POINTER(MergeDesc), f32p, C.POINTER(Plane), f32p, f32p, i32p, i32p]
     lib.lvlm_kv_compress.argtypes = [vp, vp, C.POINTER(KvDesc), vp, vp, f32p, vp, i32p, i32p, i32p]
@@ -101,7 +109,8 @@ def _load():
     lib.lvlm_profile.argtypes = [C.c_void_p, C.c_int]
     lib.lvlm_profile_read.argtypes = [C.c_void_p, C.POINTER(ProfileEntry), C.c_int, C.POINTER(C.c_int)]
     for name in ("lvlm_profile", "lvlm_profile_read", "lvlm_create", "lvlm_destroy", "lvlm_workspace_bytes", "lvlm_set_workspace", "lvlm_schedule",
-                 "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_merge_compact", "lvlm_merge_similar",
+                 "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_score_from_probs", "lvlm_merge_compact",
+                 "lvlm_merge_similar",
                  "lvlm_kv_compress",
                  "lvlm_decode_attn"):
         getattr(lib, name).restype = C.c_int
@@ -212,6 +221,25 @@ class Context:
             self.reserve(self.workspace_bytes(OP_SCORE, d))
         self._check(lib.lvlm_score_tokens(self._h, _stream(), C.byref(d), _ptr(q), _ptr(k), _ptr(row_lse),
                                           _ptr(score_head), _ptr(score_mean)))
+        return score_head, score_mean
+
+    def score_from_probs(self, probs, *, n_kv_heads, img_begin, n_img, score_head=None, score_mean=None, reserve=True):
+        """lvlm_score_from_probs.  probs [B,Hq,T,N] (softmax rows of the query rows to be summed) ->
+        (score_head [B,Hkv,n_img], score_mean [B,n_img])."""
+        B, Hq, T, N = probs.shape
+        assert probs.stride(3) == 1, "the key axis must be contiguous"
+        d = ProbsDesc(_DTYPE[probs.dtype], B, N, T, Hq, n_kv_heads, img_begin, n_img,
+                      probs.stride(0), probs.stride(1), probs.stride(2),
+                      0 if score_head is None else score_head.stride(0),
+                      0 if score_head is None else score_head.stride(1))
+        if score_head is None:
+            score_head = torch.empty(B, n_kv_heads, n_img, dtype=torch.float32, device=probs.device)
+        if score_mean is None:
+            score_mean = torch.empty(B, n_img, dtype=torch.float32, device=probs.device)
+        if reserve:
+            self.reserve(self.workspace_bytes(OP_SCORE_PROBS, d))
+        self._check(lib.lvlm_score_from_probs(self._h, _stream(), C.byref(d), _ptr(probs), _ptr(score_head),
+                                              _ptr(score_mean)))
         return score_head, score_mean
 
     # ---- steps 2-4 ----

@@ -51,6 +51,21 @@ const char *check_score(const lvlm_score_desc *d) {
     return nullptr;
 }
 
+const char *check_probs(const lvlm_probs_desc *d) {
+    if (!d) return "null descriptor";
+    if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
+    if (d->B < 1 || d->N < 1 || d->T < 1 || d->Hq < 1 || d->Hkv < 1) return "sizes must be positive";
+    if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
+    if ((long long)(d->Hq / d->Hkv) * d->T >= 65536) return "query rows per KV head (Hq/Hkv * T) must be below 65536";
+    if (d->img_begin < 0 || d->n_img < 1 || (long long)d->img_begin + d->n_img > d->N) return "image span outside [0, N)";
+    if (d->p_stride_t < d->N || d->p_stride_h < d->p_stride_t || d->p_stride_b < d->p_stride_h)
+        return "probs strides smaller than the rows they separate";
+    if ((d->sh_stride_b == 0) != (d->sh_stride_h == 0)) return "score_head strides must be both zero or both set";
+    if (d->sh_stride_h != 0 && (d->sh_stride_h < d->n_img || d->sh_stride_b < d->sh_stride_h))
+        return "score_head strides smaller than the rows they separate";
+    return nullptr;
+}
+
 const char *check_merge(const lvlm_merge_desc *d, const lvlm_plane *planes) {
     if (!d) return "null descriptor";
     if (d->B < 1 || d->N < 1) return "sizes must be positive";
@@ -218,6 +233,12 @@ lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const void *de
             *bytes = score_ws(*d).total;
             return LVLM_OK;
         }
+        case LVLM_OP_SCORE_PROBS: {
+            const auto *d = static_cast<const lvlm_probs_desc *>(desc);
+            if ((why = check_probs(d))) break;
+            *bytes = probs_ws(*d).total;
+            return LVLM_OK;
+        }
         case LVLM_OP_MERGE:
         case LVLM_OP_MERGE_SIMILAR: {
             // only shapes matter for the size: plane pointers are not inspected
@@ -307,6 +328,20 @@ lvlm_status lvlm_score_tokens(lvlm_ctx *ctx, void *stream, const lvlm_score_desc
     if (lvlm_status st = bind_device(ctx)) return st;
     return after_launch(ctx, launch_score(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w, static_cast<char *>(ctx->ws), q, k,
                                           row_lse, score_head, score_mean));
+}
+
+lvlm_status lvlm_score_from_probs(lvlm_ctx *ctx, void *stream, const lvlm_probs_desc *d, const void *probs,
+                                  float *score_head, float *score_mean) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (const char *why = check_probs(d)) return fail(ctx, LVLM_ERR_INVALID_ARG, "score_from_probs: %s", why);
+    if (!probs || !score_head || !score_mean) return fail(ctx, LVLM_ERR_INVALID_ARG, "score_from_probs: null pointer");
+    if (!aligned16(probs) || !aligned16(score_head) || !aligned4(score_mean))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "score_from_probs: pointers must be 16-byte aligned (score_mean: 4)");
+    const ProbsWs w = probs_ws(*d);
+    if (lvlm_status st = need_ws(ctx, w.total)) return st;
+    if (lvlm_status st = bind_device(ctx)) return st;
+    return after_launch(ctx, launch_score_probs(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w,
+                                                static_cast<char *>(ctx->ws), probs, score_head, score_mean));
 }
 
 lvlm_status lvlm_merge_compact(lvlm_ctx *ctx, void *stream, const lvlm_merge_desc *d, const float *score_mean,

@@ -37,6 +37,12 @@ struct ScoreWs {
 };
 ScoreWs score_ws(const lvlm_score_desc &d);
 
+struct ProbsWs {
+    size_t colpart, total;
+    int rs;        // row groups of 32 rows (heads of a group x query rows) that are summed separately
+};
+ProbsWs probs_ws(const lvlm_probs_desc &d);
+
 struct MergeWs {
     size_t rank_part, dst_of, wgt, partial, total;
     int n_split;   // always 1: the rank kernel leaves complete ranks
@@ -85,6 +91,8 @@ void launch_rank(hipStream_t stream, const float *score, int32_t *rank, int n, i
 hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreWs &w, char *ws,
                         const void *q, const void *k, const float *row_lse, float *score_head,
                         float *score_mean);
+hipError_t launch_score_probs(const Prof &prof, const lvlm_probs_desc &d, const ProbsWs &w, char *ws, const void *probs,
+                              float *score_head, float *score_mean);
 hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeWs &w, char *ws,
                         const float *score_mean, const float *wtab, const lvlm_plane *planes,
                         int32_t *keep_idx, int32_t *merged_idx);

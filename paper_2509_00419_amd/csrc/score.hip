@@ -633,6 +633,97 @@ __global__ __launch_bounds__(256) void score_finalize_kernel(ScoreArgs a) {
     a.score_mean[(long long)b * a.n_img + j] = mean / (float)a.Hkv;
 }
 
+// ---- scores from probabilities the caller already holds ---------------------------------------------
+// Workgroup (column block, row group c): thread j sums probs[b][g*G + hl][i][img_begin + j] over the 32
+// rows rho = hl*T + i of group c (neighbouring threads read neighbouring columns), all 32 loads in flight;
+// the per-group sums go through the same finalize kernel as the column sums of the passes.
+struct ProbsArgs {
+    const char *p;
+    float *colpart;
+    int B, T, Hkv, G, img_begin, n_img;
+    unsigned t_magic;
+    long long psb, psh, pst;
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void probs_colsum_kernel(ProbsArgs a, int n_col_blocks) {
+    constexpr int ES = esize<DT>();
+    const int cb = blockIdx.x % n_col_blocks, c = blockIdx.x / n_col_blocks;
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int j = cb * 256 + threadIdx.x;
+    if (j >= a.n_img) return;
+    const int GT = a.G * a.T;
+    const int r0 = c * 32, r1 = min(GT, r0 + 32);
+    const char *base = a.p + ((long long)b * a.psb + (long long)g * a.G * a.psh + a.img_begin + j) * ES;
+    auto at = [&](int rho) -> float {
+        const int hl = a.T == 1 ? rho : (int)__umulhi((unsigned)rho, a.t_magic), i = rho - hl * a.T;
+        const char *q = base + ((long long)hl * a.psh + (long long)i * a.pst) * ES;
+        if constexpr (DT == LVLM_BF16) return bf16_to_f32(*reinterpret_cast<const uint16_t *>(q));
+        else return *reinterpret_cast<const float *>(q);
+    };
+    // all 32 loads of the group are issued before the first is used
+    float v[32];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) v[u] = r0 + u < r1 ? at(r0 + u) : 0.f;
+    float sum = 0.f;
+#pragma unroll
+    for (int u = 0; u < 32; ++u) sum += v[u];
+    a.colpart[(((long long)c * a.B + b) * a.Hkv + g) * a.n_img + j] = sum;
+}
+
+// The same with 16-byte loads, for probabilities whose rows and image span start on 16-byte boundaries and
+// whose image span is a whole number of 16-byte words: thread (sub, cj) sums 8 rows (group c, rows 8 sub ..)
+// of the 16 / ES columns of word cj; the four row subsets are folded through LDS.
+template <int DT>
+__global__ __launch_bounds__(256) void probs_colsum_vec_kernel(ProbsArgs a, int n_col_blocks) {
+    constexpr int ES = esize<DT>();
+    constexpr int CPT = 16 / ES;              // columns per thread
+    constexpr int WC = 64 * CPT;              // columns per workgroup
+    __shared__ float part[4][WC];
+    const int cb = blockIdx.x % n_col_blocks, c = blockIdx.x / n_col_blocks;
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int sub = threadIdx.x >> 6, cj = threadIdx.x & 63;
+    const int j0 = cb * WC + cj * CPT;
+    const int GT = a.G * a.T;
+    const int r0 = c * 32 + 8 * sub, r1 = min(GT, r0 + 8);
+    float acc[CPT];
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) acc[e] = 0.f;
+    if (j0 < a.n_img) {
+        const char *base = a.p + ((long long)b * a.psb + (long long)g * a.G * a.psh + a.img_begin + j0) * ES;
+        uint4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int rho = min(r0 + u, GT - 1);
+            const int hl = a.T == 1 ? rho : (int)__umulhi((unsigned)rho, a.t_magic), i = rho - hl * a.T;
+            v[u] = *reinterpret_cast<const uint4 *>(base + ((long long)hl * a.psh + (long long)i * a.pst) * ES);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (r0 + u >= r1) continue;
+            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if constexpr (DT == LVLM_BF16) {
+                    acc[2 * q] += __uint_as_float(w[q] << 16);
+                    acc[2 * q + 1] += __uint_as_float(w[q] & 0xffff0000u);
+                } else {
+                    acc[q] += __uint_as_float(w[q]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < CPT; ++e) part[sub][cj * CPT + e] = acc[e];
+    __syncthreads();
+    for (int x = threadIdx.x; x < WC; x += 256) {
+        const int j = cb * WC + x;
+        if (j < a.n_img)
+            a.colpart[(((long long)c * a.B + b) * a.Hkv + g) * a.n_img + j] =
+                (part[0][x] + part[1][x]) + (part[2][x] + part[3][x]);
+    }
+}
+
 template <int DT, int HD, int KPW>
 void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool single) {
     hipStream_t stream = prof.stream;
@@ -671,6 +762,57 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool sin
 
 constexpr int kSingleMaxChunks = 32;
 constexpr int kSingleMaxRows = 1100;      // in 256-byte key rows
+
+ProbsWs probs_ws(const lvlm_probs_desc &d) {
+    ProbsWs w{};
+    w.rs = (d.Hq / d.Hkv * d.T + 31) / 32;
+    w.colpart = 0;
+    w.total = align_up((size_t)w.rs * d.B * d.Hkv * d.n_img * sizeof(float), 256);
+    return w;
+}
+
+hipError_t launch_score_probs(const Prof &prof, const lvlm_probs_desc &d, const ProbsWs &w, char *ws, const void *probs,
+                              float *score_head, float *score_mean) {
+    ProbsArgs pa{};
+    pa.p = static_cast<const char *>(probs);
+    pa.colpart = reinterpret_cast<float *>(ws + w.colpart);
+    pa.B = d.B; pa.T = d.T; pa.Hkv = d.Hkv; pa.G = d.Hq / d.Hkv; pa.img_begin = d.img_begin; pa.n_img = d.n_img;
+    pa.t_magic = (unsigned)(0x100000000ull / (unsigned long long)d.T) + 1u;
+    pa.psb = d.p_stride_b; pa.psh = d.p_stride_h; pa.pst = d.p_stride_t;
+    const int es = d.dtype == LVLM_BF16 ? 2 : 4, cpt = 16 / es;
+    const bool vec = (d.p_stride_b * es) % 16 == 0 && (d.p_stride_h * es) % 16 == 0 && (d.p_stride_t * es) % 16 == 0 &&
+                     (d.img_begin * es) % 16 == 0 && d.n_img % cpt == 0;      // the base pointer is 16-byte aligned
+    prof.begin("score_probs");
+    if (vec) {
+        const int ncb = (d.n_img + 64 * cpt - 1) / (64 * cpt);
+        const dim3 grid(ncb * w.rs, d.Hkv, d.B);
+        if (d.dtype == LVLM_BF16)
+            hipLaunchKernelGGL(probs_colsum_vec_kernel<LVLM_BF16>, grid, dim3(256), 0, prof.stream, pa, ncb);
+        else
+            hipLaunchKernelGGL(probs_colsum_vec_kernel<LVLM_F32>, grid, dim3(256), 0, prof.stream, pa, ncb);
+    } else {
+        const int ncb = (d.n_img + 255) / 256;
+        const dim3 grid(ncb * w.rs, d.Hkv, d.B);
+        if (d.dtype == LVLM_BF16)
+            hipLaunchKernelGGL(probs_colsum_kernel<LVLM_BF16>, grid, dim3(256), 0, prof.stream, pa, ncb);
+        else
+            hipLaunchKernelGGL(probs_colsum_kernel<LVLM_F32>, grid, dim3(256), 0, prof.stream, pa, ncb);
+    }
+    prof.end();
+    ScoreArgs a{};
+    a.colpart = pa.colpart;
+    a.rs = w.rs;
+    a.score_head = score_head;
+    a.score_mean = score_mean;
+    a.B = d.B; a.Hkv = d.Hkv; a.G = pa.G; a.n_img = d.n_img;
+    const bool dense = d.sh_stride_b == 0 && d.sh_stride_h == 0;
+    a.shh = dense ? d.n_img : d.sh_stride_h;
+    a.shb = dense ? (long long)d.Hkv * d.n_img : d.sh_stride_b;
+    prof.begin("score_finalize");
+    hipLaunchKernelGGL(score_finalize_kernel, dim3((d.n_img + 255) / 256, d.B), dim3(256), 0, prof.stream, a);
+    prof.end();
+    return hipGetLastError();
+}
 
 ScoreWs score_ws(const lvlm_score_desc &d) {
     ScoreWs w{};

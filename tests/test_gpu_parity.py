@@ -112,6 +112,31 @@ def test_score_all_rows_reading_long_sequence(ctx):
     assert float(sm[0, 0]) > float(sm[0, -1])
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_score_from_probs(ctx, dtype):
+    # attention probabilities handed in (a plain attention's matrix): ragged sizes, G = 3, a strided view of a
+    # wider buffer; and the config-2 shape (28/4 heads, 64 rows, 2176 keys)
+    for B, T, Hq, Hkv, N, img0, n_img, seed in ((2, 37, 6, 2, 301, 5, 290, 7), (1, 64, 28, 4, 2176, 64, 2048, 8)):
+        g = torch.Generator().manual_seed(seed)
+        wide = torch.softmax(3.0 * torch.randn(B, Hq, T + 3, (N + 47) // 32 * 32, generator=g), dim=-1).to(dtype)
+        p = wide[:, :, 2:2 + T, 8:8 + N]                      # rows and columns cut out of a larger array
+        p_d = wide.to(DEV)[:, :, 2:2 + T, 8:8 + N]
+        assert not p_d.is_contiguous()
+        sh, sm = ctx.score_from_probs(p_d, n_kv_heads=Hkv, img_begin=img0, n_img=n_img)
+        osh, osm = O.score_from_probs(f64(p), n_kv_heads=Hkv, img_begin=img0, n_img=n_img)
+        assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
+    # the two sources of Sec. 3.2.2 agree: probabilities computed here give what lvlm_score_tokens computes itself
+    B, T, Hq, Hkv, d, n_sys, n_img = 1, 32, 8, 4, 64, 16, 400
+    N = n_sys + n_img + T
+    q, k = _rand((B, T, Hq, d), dtype, 9), _rand((B, N, Hkv, d), dtype, 10)
+    s = torch.einsum("bthd,bnhd->bhtn", q.double(), k.double().repeat_interleave(Hq // Hkv, dim=2)) / math.sqrt(d)
+    mask = torch.arange(N)[None, :] > (n_sys + n_img + torch.arange(T))[:, None]
+    probs = torch.softmax(s.masked_fill(mask, float("-inf")), dim=-1).float().contiguous()
+    a_h, a_m = ctx.score_from_probs(probs.to(DEV), n_kv_heads=Hkv, img_begin=n_sys, n_img=n_img)
+    b_h, b_m = ctx.score_tokens(q.to(DEV), k.to(DEV), q_pos0=n_sys + n_img, img_begin=n_sys, n_img=n_img)
+    assert rel_err(a_h.cpu(), b_h.cpu()) < 1e-5 and rel_err(a_m.cpu(), b_m.cpu()) < 1e-5
+
+
 def test_score_wide_blocks_config3_shape(ctx):
     # B=8, 8 KV heads, N=1888: enough workgroups for the 256-key blocks (2 tiles per wave)
     w = configs.CFG3

@@ -173,3 +173,29 @@ def test_row_lse_path_matches():
     b = O.score_tokens(q, k, q_pos0=q_pos0, img_begin=2, n_img=8, row_lse=lse)
     np.testing.assert_allclose(a[0], b[0], rtol=1e-6)
     np.testing.assert_allclose(a[1], b[1], rtol=1e-6)
+
+
+def test_score_from_probs_agrees_with_the_pinned_path_and_closed_forms():
+    # (1) probabilities built here with a library softmax give the scores of score_tokens (pinned above)
+    rng = np.random.default_rng(41)
+    B, T, Hq, Hkv, d, N, img0, n_img, q_pos0 = 2, 5, 6, 2, 8, 23, 3, 13, 18
+    q, k = rng.standard_normal((B, T, Hq, d)), rng.standard_normal((B, N, Hkv, d))
+    G = Hq // Hkv
+    s = np.einsum("bthd,bnhd->bhtn", q, np.repeat(k, G, axis=2)) / math.sqrt(d)
+    mask = np.arange(N)[None, :] > (q_pos0 + np.arange(T))[:, None]
+    p = torch.softmax(torch.from_numpy(np.where(mask, -np.inf, s)), dim=-1).numpy()
+    sh, sm = O.score_from_probs(p, n_kv_heads=Hkv, img_begin=img0, n_img=n_img)
+    rh, rm = O.score_tokens(q, k, q_pos0=q_pos0, img_begin=img0, n_img=n_img)
+    assert np.allclose(sh, rh, rtol=1e-6, atol=1e-7) and np.allclose(sm, rm, rtol=1e-6, atol=1e-7)
+    # (2) one probability at a time
+    for b, g, j in ((0, 0, 0), (1, 1, 12), (0, 1, 5)):
+        want = sum(p[b, g * G + h, i, img0 + j] for h in range(G) for i in range(T)) / G
+        assert abs(sh[b, g, j] - want) < 1e-6
+    # (3) uniform rows: every key receives T / N from every head; one-hot rows: the hit column counts the rows
+    u = np.full((1, 4, 7, 10), 0.1)
+    sh, sm = O.score_from_probs(u, n_kv_heads=2, img_begin=2, n_img=6)
+    assert np.allclose(sh, 0.7) and np.allclose(sm, 0.7)
+    e = np.zeros((1, 4, 7, 10))
+    e[..., 4] = 1.0
+    sh, sm = O.score_from_probs(e, n_kv_heads=4, img_begin=2, n_img=6)
+    assert np.allclose(sh[0, :, 2], 7.0) and np.allclose(np.delete(sh, 2, axis=2), 0.0) and sm[0, 2] == 7.0
