@@ -9,8 +9,8 @@ Qwen2.5-VL-7B-shaped workload (config 2: 28 layers, 64 system + 2048 image +
       all keys of a layer, written straight into that layer's cache scores),
       issued once per run of layers with the same token count -- at the
       pyramid layer that ends the run, which needs its score for the merge,
-      with the run's layers stacked along the batch axis (layers 5 | 6-9 |
-      10-13 | 14-27: the scores of the other layers of a run feed only the
+      with the run's layers stacked along the batch axis (layers 5-9 |
+      10-13 | 14-27; the 100 % stage at layer 5 merges nothing: the scores of the other layers of a run feed only the
       cache compression after prefill; their instruction-token queries and
       caches are kept until the call);
       at the pyramid layers 5 / 9 / 13: lvlm_merge_compact of the hidden states
@@ -102,8 +102,8 @@ def plan(w, lv):
 
 def score_groups(layers, per_layer=False):
     """Runs of consecutive scored layers with the same image-token count, as (first, last) layer indices.  A
-    run ends at a merge layer (which needs its score at once) or with the stack; the layers before it in the
-    run feed only the cache compression after prefill, so one call at the run's end scores them all: their
+    run ends at a layer that really merges (it needs its score at once) or with the stack; the layers before it
+    in the run feed only the cache compression after prefill, so one call at the run's end scores them all: their
     instruction-token queries [T,Hq,d] and their caches are kept until then."""
     groups, first = [], None
     for i, en in enumerate(layers):
@@ -112,7 +112,8 @@ def score_groups(layers, per_layer=False):
             continue
         if first is None:
             first = i
-        if per_layer or en["merge_to"] is not None or i + 1 == len(layers) or not layers[i + 1]["score"] \
+        merges = en["merge_to"] is not None and en["merge_to"] < en["n_img"]      # a 100 % stage merges nothing
+        if per_layer or merges or i + 1 == len(layers) or not layers[i + 1]["score"] \
                 or layers[i + 1]["n_img"] != en["n_img"]:
             groups.append((first, i))
             first = None
