@@ -339,13 +339,15 @@ def run_decode_compress(ctx, lv, w, states, reserve):
 
 
 # ----------------------------------------------------------------------------- algorithmic work per kernel
-def score_in_one_launch(w, N):
-    """Whether the library scores sequences of N tokens with its one-launch kernel (short sequences) or with
+def score_in_one_launch(w, N, batch):
+    """Whether the library scores `batch` sequences of N tokens with a one-launch kernel (short sequences) or with
     the two-pass kernels.  Restates the library's launch rule, only to credit the flops to the right kernel
     name; main() checks the launch counts it implies against the ones measured."""
     e = 2 if w.dtype == "bf16" else 4
     n_chunks = (w.n_q_heads // w.n_kv_heads * w.n_text + 31) // 32
-    return n_chunks <= 32 and N * (w.head_dim * e) // 256 <= 1100
+    rows = N * (w.head_dim * e) // 256
+    shared = 3 <= n_chunks <= 32 and batch * w.n_kv_heads * ((n_chunks + 3) // 4) >= 256 and rows <= 8192
+    return shared or (n_chunks <= 32 and rows <= 1100)
 
 
 def kernel_work(w, layers, lens_after_prefill, merge="rank", per_layer=False, given_lse=False):
@@ -362,7 +364,7 @@ def kernel_work(w, layers, lens_after_prefill, merge="rank", per_layer=False, gi
     for first, last in score_groups(layers, per_layer):
         n_img = layers[last]["n_img"]
         N, gb = w.n_sys + n_img + T, (last - first + 1) * B
-        if score_in_one_launch(w, N):
+        if score_in_one_launch(w, N, gb):
             add("score_single", "mfma", 2.0 * gb * T * ((0 if given_lse else N) + n_img) * d * Hq)
         else:
             if not given_lse:

@@ -34,6 +34,7 @@ struct ScoreWs {
     int block_keys;
     int rs, cps;   // row splits per key block, query chunks per split
     bool single;   // short sequence: both passes in one launch, one part of column sums per query chunk
+    bool shared_tiles;   // ... with four query chunks per workgroup sharing the key tiles through LDS
 };
 ScoreWs score_ws(const lvlm_score_desc &d);
 

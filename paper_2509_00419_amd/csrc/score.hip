@@ -559,6 +559,185 @@ __global__ __launch_bounds__(64 * NW, (DT == LVLM_F32 && HD == 128) ? 2 : 3) voi
 }
 #undef LVLM_K16
 
+// ---- short sequences, several query chunks per KV head: one launch, key tiles shared through LDS -------
+// A workgroup owns FOUR chunks of 32 query rows of one (batch, KV head) pair, one per wave, each held in
+// registers as an MFMA operand.  The keys are swept twice, tile by tile (32 keys): the 256 threads fetch a
+// tile with fully coalesced 16-byte loads (16 lanes per row) two tiles ahead, copy it into one of two LDS
+// buffers one tile ahead, and after one barrier per tile every wave reads it as its other operand -- the
+// keys cross the memory pipeline once per workgroup instead of once per wave, and in whole 64-byte requests.
+// Sweep 1 (rows = keys, columns = queries) leaves each lane the online (max, sum) of its own query row: no
+// fold across waves; sweep 2 (rows = queries, columns = keys) over the image keys leaves each lane the
+// column sum of its key for this wave's chunk, which is that chunk's part of the result.
+template <int DT, int HD>
+__global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void score_chunks_kernel(ScoreArgs a) {
+    constexpr int ES = esize<DT>();
+    constexpr int ROWB = HD * ES;
+    constexpr int PITCH = ROWB + 16;
+    constexpr int NV = HalfRow<DT, HD>::NV;
+    constexpr int UPR = ROWB / 16;          // 16-byte units per row
+    constexpr int UPT = 32 * UPR / 256;     // units each thread stages per tile
+    constexpr int TPR = UPR / UPT;          // threads per row
+    static_assert(UPT >= 1 && UPT <= 4, "staging covers 1..4 units per thread");
+    __shared__ __attribute__((aligned(16))) char k_lds[2][32 * PITCH];
+    __shared__ float lse_s[4][32];
+    __shared__ int pos_s[4][32];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hf = lane >> 5, l32 = lane & 31;
+    // all workgroups of one (batch, KV head) pair on one XCD (ids with the same remainder modulo 8)
+    const int wpp = (a.rs + 3) >> 2;                      // workgroups per pair
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int pair = (seq / wpp) * 8 + xcd;
+    if (pair >= a.B * a.Hkv) return;
+    const int b = pair / a.Hkv, g = pair % a.Hkv;
+    const int c = (seq % wpp) * 4 + wave;                 // this wave's chunk
+    const bool live = c < a.rs;                           // a wave without a chunk only helps to move tiles
+    const int GT = a.G * a.T;
+    const long long rowbase = ((long long)b * a.Hq + (long long)g * a.G) * a.T;
+    auto div_t = [&](int rho) -> int { return a.T == 1 ? rho : (int)__umulhi((unsigned)rho, a.t_magic); };
+
+    // this lane's query row (padding rows repeat the last row and get an infinite LSE)
+    const int rho = c * 32 + l32;
+    const int rc = min(rho, GT - 1);
+    const int hl = div_t(rc), qi = rc - hl * a.T;
+    const int pos = a.causal ? a.q_pos0 + qi : INT_MAX;
+    HalfRow<DT, HD> qa;
+    {
+        const char *src = a.q + ((long long)b * a.qsb + (long long)qi * a.qst + (long long)(g * a.G + hl) * a.qsh) * ES +
+                          16 * hf;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) qa.v[i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
+    }
+    if (hf == 0) pos_s[wave][l32] = pos;
+    // earliest position of the chunk's rows (uniform per wave): tiles at or before it need no mask
+    const int rho_last = min(c * 32 + 31, GT - 1);
+    const int hc0 = div_t(min(c * 32, GT - 1)), hc1 = div_t(rho_last);
+    const int pos_min = a.causal ? a.q_pos0 + ((hc0 != hc1) ? 0 : min(c * 32, GT - 1) - hc0 * a.T) : INT_MAX;
+
+    // staging: thread -> row srow of the tile, units scu + TPR x
+    const int srow = tid / TPR, scu = tid % TPR;
+    const char *kbase = a.k + ((long long)b * a.ksb + (long long)g * a.ksh) * ES + 16 * scu;
+    uint4 st0 = make_uint4(0, 0, 0, 0), st1 = st0, st2 = st0, st3 = st0;
+    auto fetch = [&](int j0, int j_end) {                 // tile rows j0 .. j0+31, clamped to the range
+        const uint4 *src = reinterpret_cast<const uint4 *>(kbase + (long long)min(j0 + srow, j_end - 1) * a.ksn * ES);
+        st0 = src[0];
+        if constexpr (UPT > 1) st1 = src[TPR];
+        if constexpr (UPT > 2) st2 = src[2 * TPR];
+        if constexpr (UPT > 3) st3 = src[3 * TPR];
+    };
+    auto stash = [&](int buf) {
+        uint4 *dst = reinterpret_cast<uint4 *>(&k_lds[buf][srow * PITCH + 16 * scu]);
+        dst[0] = st0;
+        if constexpr (UPT > 1) dst[TPR] = st1;
+        if constexpr (UPT > 2) dst[2 * TPR] = st2;
+        if constexpr (UPT > 3) dst[3 * TPR] = st3;
+    };
+    auto tile_operand = [&](int buf, HalfRow<DT, HD> &kf) {
+        const char *src = &k_lds[buf][l32 * PITCH + 16 * hf];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) kf.v[i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
+    };
+
+    // ---- sweep 1: this lane's row normaliser over all keys
+    float m = -INFINITY, l = 0.f;
+    auto stats = [&](int j0, const HalfRow<DT, HD> &kf) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        mma_tile<DT, HD>(acc, kf, qa);                    // rows = keys, columns = queries
+        if (j0 + 32 <= a.N && j0 + 31 <= pos_min) {
+            float tmax = acc[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, acc[r]);
+            const float mn = fmaxf(m, tmax * a.scale_log2);      // finite; scale >= 0 (checked on the host)
+            float sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -mn));
+            l = l * __builtin_amdgcn_exp2f(m - mn) + sum;
+            m = mn;
+            return;
+        }
+        float t[16];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int j = j0 + acc_row(r, hf);
+            t[r] = (j <= pos && j < a.N) ? acc[r] * a.scale_log2 : -INFINITY;
+            tmax = fmaxf(tmax, t[r]);
+        }
+        const float mn = fmaxf(m, tmax);
+        const float ms = (mn == -INFINITY) ? 0.f : mn;
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(t[r] - ms);   // exp2(-inf) = 0
+        l = l * __builtin_amdgcn_exp2f(m - ms) + sum;
+        m = mn;
+    };
+    // ---- sweep 2: column sums of the image keys for this wave's chunk
+    const int key_lo = a.img_begin, key_hi = a.img_begin + a.n_img;
+    float *out = a.colpart + (((long long)min(c, a.rs - 1) * a.B + b) * a.Hkv + g) * a.n_img;
+    auto colsum = [&](int j0, const HalfRow<DT, HD> &kf) {
+        f32x16 acc;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        mma_tile<DT, HD>(acc, qa, kf);                    // rows = queries, columns = keys
+        const int j = j0 + l32;
+        float sum = 0.f;
+        if (j0 + 31 <= pos_min) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                sum += __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_s[wave][acc_row(r, hf)]));
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = acc_row(r, hf);
+                const float p = __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_s[wave][row]));
+                sum += (j <= pos_s[wave][row]) ? p : 0.f;
+            }
+        }
+        sum += __shfl_xor(sum, 32);
+        if (hf == 0 && j < key_hi) out[j - key_lo] = sum;
+    };
+
+    // One sweep: tile t is fetched in iteration t-2, copied to LDS in iteration t-1 and used in iteration t
+    // (one barrier per tile publishes the copy; fetches past the last tile repeat its last row).
+    auto sweep = [&](int j_begin, int j_end, bool second) {
+        const int nt = (j_end - j_begin + 31) >> 5;
+        fetch(j_begin, j_end);
+        stash(0);
+        fetch(j_begin + 32, j_end);
+        __syncthreads();
+        for (int t = 0; t < nt; ++t) {
+            stash((t + 1) & 1);                           // tile t+1
+            fetch(j_begin + 32 * (t + 2), j_end);
+            if (live) {
+                HalfRow<DT, HD> kf;
+                tile_operand(t & 1, kf);
+                if (second) colsum(j_begin + 32 * t, kf);
+                else stats(j_begin + 32 * t, kf);
+            }
+            __syncthreads();
+        }
+    };
+
+    if (a.row_lse == nullptr) {
+        sweep(0, a.N, false);
+        {
+            const float mo = __shfl_xor(m, 32), lo = __shfl_xor(l, 32);
+            const float mn = fmaxf(m, mo);
+            const float ms = (mn == -INFINITY) ? 0.f : mn;
+            l = l * __builtin_amdgcn_exp2f(m - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
+            m = mn;
+        }
+        // no visible key, or a padding row: contributes nothing
+        if (hf == 0) lse_s[wave][l32] = (l > 0.f && rho < GT) ? m + log2f(l) : INFINITY;
+    } else if (hf == 0) {
+        lse_s[wave][l32] = (live && rho < GT) ? a.row_lse[rowbase + rho] * kLog2e : INFINITY;
+    }
+    __syncthreads();
+    sweep(key_lo, key_hi, true);
+}
+
 // Fold the per-block, per-wave (max, sum) pairs of each row into a log2-domain LSE.  Eight lanes share a
 // row: each folds every eighth pair online, then the eight partial (max, sum) states are merged.
 __global__ __launch_bounds__(256) void score_lse_kernel(const float *part_m, const float *part_l, float *lse2,
@@ -725,13 +904,17 @@ __global__ __launch_bounds__(256) void probs_colsum_vec_kernel(ProbsArgs a, int 
 }
 
 template <int DT, int HD, int KPW>
-void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool single) {
+void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool single, bool shared_tiles) {
     hipStream_t stream = prof.stream;
     constexpr int BN = 4 * KPW * 32;
     if (single) {
         prof.begin("score_single");
-        hipLaunchKernelGGL((score_small_kernel<DT, HD, 4>), dim3((a.B * a.Hkv + 7) / 8 * 8 * a.rs), dim3(256), 0, stream,
-                           a);
+        if (shared_tiles)
+            hipLaunchKernelGGL((score_chunks_kernel<DT, HD>), dim3((a.B * a.Hkv + 7) / 8 * 8 * ((a.rs + 3) / 4)), dim3(256), 0,
+                               stream, a);
+        else
+            hipLaunchKernelGGL((score_small_kernel<DT, HD, 4>), dim3((a.B * a.Hkv + 7) / 8 * 8 * a.rs), dim3(256), 0, stream,
+                               a);
         prof.end();
         prof.begin("score_finalize");
         hipLaunchKernelGGL(score_finalize_kernel, dim3((a.n_img + 255) / 256, a.B), dim3(256), 0, stream, a);
@@ -761,7 +944,8 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool sin
 }  // namespace
 
 constexpr int kSingleMaxChunks = 32;
-constexpr int kSingleMaxRows = 1100;      // in 256-byte key rows
+constexpr int kSingleMaxRows = 1100;      // in 256-byte key rows, one chunk per workgroup
+constexpr int kSharedMaxRows = 8192;      // ... four chunks per workgroup sharing the key tiles
 
 ProbsWs probs_ws(const lvlm_probs_desc &d) {
     ProbsWs w{};
@@ -829,12 +1013,15 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
     if (rs < 1) rs = 1;
     w.cps = (n_chunks + rs - 1) / rs;
     w.rs = (n_chunks + w.cps - 1) / w.cps;
-    // Short sequences: one launch in which every query chunk streams the keys itself (twice).  Its time
-    // grows with the length of that sweep -- each lane fetches whole key rows, 16 bytes per instruction --
-    // and it is taken up to the length where the three launches it replaces cost the same (measured at
-    // batch sizes from 1 to 64 sequences).  The column sums then come in one part per chunk.
+    // Short sequences: both passes in ONE launch (the column sums then come in one part per chunk).  Two
+    // shapes: four chunks per workgroup that share the key tiles through LDS, when that still fills the
+    // chip -- measured faster than the two-pass kernels up to several thousand keys (it saves the partials,
+    // their fold and a launch) -- else one chunk per workgroup whose waves split the keys and fetch them
+    // themselves, which pays up to the length where the three launches it replaces cost the same.
     const long long sweep_rows = (long long)d.N * (d.hd * (d.dtype == LVLM_BF16 ? 2 : 4)) / 256;
-    w.single = n_chunks <= kSingleMaxChunks && sweep_rows <= kSingleMaxRows;
+    w.shared_tiles = n_chunks >= 3 && n_chunks <= kSingleMaxChunks && (long long)d.B * d.Hkv * ((n_chunks + 3) / 4) >= 256 &&
+                     sweep_rows <= kSharedMaxRows;
+    w.single = w.shared_tiles || (n_chunks <= kSingleMaxChunks && sweep_rows <= kSingleMaxRows);
     if (w.single) {
         w.rs = n_chunks;
         w.cps = 1;
@@ -874,15 +1061,15 @@ hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreW
     const bool need_lse = row_lse == nullptr;
     const bool wide = w.block_keys == 256;
     if (d.dtype == LVLM_BF16 && d.hd == 128) {
-        if (wide) launch_passes<LVLM_BF16, 128, 2>(prof, a, need_lse, w.single);
-        else launch_passes<LVLM_BF16, 128, 1>(prof, a, need_lse, w.single);
+        if (wide) launch_passes<LVLM_BF16, 128, 2>(prof, a, need_lse, w.single, w.shared_tiles);
+        else launch_passes<LVLM_BF16, 128, 1>(prof, a, need_lse, w.single, w.shared_tiles);
     } else if (d.dtype == LVLM_BF16 && d.hd == 64) {
-        if (wide) launch_passes<LVLM_BF16, 64, 2>(prof, a, need_lse, w.single);
-        else launch_passes<LVLM_BF16, 64, 1>(prof, a, need_lse, w.single);
+        if (wide) launch_passes<LVLM_BF16, 64, 2>(prof, a, need_lse, w.single, w.shared_tiles);
+        else launch_passes<LVLM_BF16, 64, 1>(prof, a, need_lse, w.single, w.shared_tiles);
     } else if (d.dtype == LVLM_F32 && d.hd == 128) {
-        launch_passes<LVLM_F32, 128, 1>(prof, a, need_lse, w.single);
+        launch_passes<LVLM_F32, 128, 1>(prof, a, need_lse, w.single, w.shared_tiles);
     } else {
-        launch_passes<LVLM_F32, 64, 1>(prof, a, need_lse, w.single);
+        launch_passes<LVLM_F32, 64, 1>(prof, a, need_lse, w.single, w.shared_tiles);
     }
     return hipGetLastError();
 }
