@@ -140,6 +140,45 @@ def score_from_probs(probs, *, n_kv_heads: int, img_begin: int, n_img: int):
     return score_head.astype(np.float32), score_mean.astype(np.float32)
 
 
+def prefill_attn(q, k, v, *, scale: float | None = None, causal: bool = True, dtype: str = "f32"):
+    """Prefill self-attention of one layer, with the row normalisers it leaves behind.
+
+    q: [B, N, Hq, d], k, v: [B, N, Hkv, d] (row i of q sits at position i).  Head h reads KV head h // G.
+    out[b,i,h,:] = sum_j softmax_j(scale * q[b,i,h].k[b,j,g]) v[b,j,g,:] over the keys row i may see (j <= i
+    when causal, else all N) -- the attention the paper's scores are a by-product of (Sec. 3.2.1: the
+    scores come "from the attention" of the layer, Sec. 3.2.2: from its kernel's statistics).
+    lse[b,h,i] is the natural-log sum-exp of row i's scaled logits over those keys: with it,
+    score_tokens(..., row_lse=lse[:, :, N-T:]) gives the scores of the last T rows without a second
+    normaliser pass.
+
+    Returns (out [B,N,Hq,d] rounded to `dtype`, lse [B,Hq,N] f32).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    B, N, Hq, d = q.shape
+    Hkv = k.shape[2]
+    assert k.shape == (B, N, Hkv, d) and v.shape == (B, N, Hkv, d) and Hq % Hkv == 0
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    scale = float(scale)
+    out = np.zeros((B, N, Hq, d), dtype=np.float64)
+    lse = np.zeros((B, Hq, N), dtype=np.float64)
+    visible = (np.arange(N)[None, :] <= np.arange(N)[:, None]) if causal else np.ones((N, N), bool)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            s = scale * (q[b, :, h, :] @ k[b, :, g, :].T)          # [N, N]
+            s = np.where(visible, s, -np.inf)
+            m = s.max(axis=1, keepdims=True)
+            e = np.exp(s - m)
+            den = e.sum(axis=1, keepdims=True)
+            out[b, :, h, :] = (e / den) @ v[b, :, g, :]
+            lse[b, h, :] = (m + np.log(den))[:, 0]
+    return round_out(out, dtype), lse.astype(np.float32)
+
+
 # --------------------------------------------------------------------------
 # step 2: order by importance   (Sec. 3.2.1, par. 4: "reorder ... by importance")
 # --------------------------------------------------------------------------
