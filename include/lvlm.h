@@ -54,7 +54,8 @@ typedef enum {
     LVLM_OP_KV_COMPRESS = 2,
     LVLM_OP_DECODE_ATTN = 3,
     LVLM_OP_MERGE_SIMILAR = 4,
-    LVLM_OP_SCORE_PROBS = 5
+    LVLM_OP_SCORE_PROBS = 5,
+    LVLM_OP_PREFILL_ATTN = 6
 } lvlm_op;
 
 /* Rank -> weight tables for the merged token (Sec. 3.2.1, par. 4). */
@@ -183,6 +184,45 @@ typedef struct {
  * aligned suffices), both written in full.  Workspace: LVLM_OP_SCORE_PROBS. */
 LVLM_API lvlm_status lvlm_score_from_probs(lvlm_ctx *ctx, void *stream, const lvlm_probs_desc *d,
                                            const void *probs, float *score_head, float *score_mean);
+
+/* The layer's own prefill attention with the scores as its by-product (Sec.
+ * 3.2.1: the importance of a token is read off the attention of the layer, at
+ * no cost of its own; Sec. 3.2.2: off the statistics its kernel keeps).  Row i
+ * of q sits at position i; head h reads KV head h / (Hq/Hkv):
+ *   out[b][i][h][:] = sum_j softmax_j(scale q[b][i][h] . k[b][j][g]) v[b][j][g][:]
+ * over the keys the row may see (j <= i if causal, else all N), softmax and
+ * sums in fp32; row_lse[b][h][i] = natural-log sum-exp of the row's scaled
+ * logits.  With T > 0 the last T rows are the instruction rows: their scores
+ * over the image keys are computed from these normalisers with the one
+ * column-sum pass of lvlm_score_tokens (no normaliser pass), as
+ * lvlm_score_tokens(q rows N-T.., q_pos0 = N-T, row_lse = these) would give. */
+typedef struct {
+    int32_t dtype;     /* LVLM_BF16 or LVLM_F32: element type of q, k, v, out     */
+    int32_t B, N;      /* batch, tokens per sequence (query rows = keys)          */
+    int32_t Hq, Hkv;   /* query heads, KV heads (Hq % Hkv == 0)                   */
+    int32_t hd;        /* head dimension: 64 or 128                               */
+    int32_t causal;    /* 0 / 1                                                   */
+    float scale;       /* logit scale > 0, usually 1/sqrt(hd)                     */
+    int32_t T;         /* instruction rows (the last T); 0 = attention only       */
+    int32_t img_begin; /* first image key        (read only when T > 0)           */
+    int32_t n_img;     /* number of image keys; img_begin + n_img <= N            */
+    int64_t q_stride_b, q_stride_n, q_stride_h; /* q[b][i][h][0..hd), elements    */
+    int64_t k_stride_b, k_stride_n, k_stride_h; /* k[b][j][g][0..hd)              */
+    int64_t v_stride_b, v_stride_n, v_stride_h; /* v[b][j][g][0..hd)              */
+    int64_t o_stride_b, o_stride_n, o_stride_h; /* out[b][i][h][0..hd)            */
+    int64_t sh_stride_b, sh_stride_h; /* score_head strides; both 0 = dense       */
+} lvlm_prefill_desc;
+
+/* q, k, v: device, read only.  out: device, dtype above, must not overlap the
+ * inputs.  row_lse: device fp32 [B,Hq,N], written in full.  score_head
+ * [B,Hkv,n_img] and score_mean [B,n_img] fp32: written in full when T > 0 (then
+ * both required), untouched when T == 0 (may be NULL).  All pointers 16-byte
+ * aligned (score_mean: 4), strides multiples of 16 bytes.  Errors: invalid
+ * descriptor or pointer -> LVLM_ERR_INVALID_ARG, nothing launched.
+ * Workspace: LVLM_OP_PREFILL_ATTN. */
+LVLM_API lvlm_status lvlm_prefill_attn(lvlm_ctx *ctx, void *stream, const lvlm_prefill_desc *d, const void *q,
+                                       const void *k, const void *v, void *out, float *row_lse,
+                                       float *score_head, float *score_mean);
 
 /* ---- steps 2-4: partition, merge, compact -------------------------------- */
 

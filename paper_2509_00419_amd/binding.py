@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(HERE, "liblvlm.so")
 
 # ---- enums (include/lvlm.h) ----
 BF16, F32, I32 = 0, 1, 2
-OP_SCORE, OP_MERGE, OP_KV_COMPRESS, OP_DECODE_ATTN, OP_MERGE_SIMILAR, OP_SCORE_PROBS = 0, 1, 2, 3, 4, 5
+OP_SCORE, OP_MERGE, OP_KV_COMPRESS, OP_DECODE_ATTN, OP_MERGE_SIMILAR, OP_SCORE_PROBS, OP_PREFILL_ATTN = 0, 1, 2, 3, 4, 5, 6
 MERGE_LINEAR_RANK, MERGE_PAIRWISE, MERGE_LINEAR_RAW = 0, 1, 2
 RULE_WEIGHTED, RULE_TOP = 0, 1
 KV_THRESHOLD, KV_BUDGET = 0, 1
@@ -44,6 +44,17 @@ class ProbsDesc(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("B", C.c_int32), ("N", C.c_int32), ("T", C.c_int32),
                 ("Hq", C.c_int32), ("Hkv", C.c_int32), ("img_begin", C.c_int32), ("n_img", C.c_int32),
                 ("p_stride_b", C.c_int64), ("p_stride_h", C.c_int64), ("p_stride_t", C.c_int64),
+                ("sh_stride_b", C.c_int64), ("sh_stride_h", C.c_int64)]
+
+
+class PrefillDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("B", C.c_int32), ("N", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32),
+                ("hd", C.c_int32), ("causal", C.c_int32), ("scale", C.c_float), ("T", C.c_int32),
+                ("img_begin", C.c_int32), ("n_img", C.c_int32),
+                ("q_stride_b", C.c_int64), ("q_stride_n", C.c_int64), ("q_stride_h", C.c_int64),
+                ("k_stride_b", C.c_int64), ("k_stride_n", C.c_int64), ("k_stride_h", C.c_int64),
+                ("v_stride_b", C.c_int64), ("v_stride_n", C.c_int64), ("v_stride_h", C.c_int64),
+                ("o_stride_b", C.c_int64), ("o_stride_n", C.c_int64), ("o_stride_h", C.c_int64),
                 ("sh_stride_b", C.c_int64), ("sh_stride_h", C.c_int64)]
 
 
@@ -102,6 +113,7 @@ def _load():
     lib.lvlm_merge_weights.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_float)]
     lib.lvlm_score_tokens.argtypes = [vp, vp, C.POINTER(ScoreDesc), vp, vp, f32p, f32p, f32p]
     lib.lvlm_score_from_probs.argtypes = [vp, vp, C.POINTER(ProbsDesc), vp, f32p, f32p]
+    lib.lvlm_prefill_attn.argtypes = [vp, vp, C.POINTER(PrefillDesc), vp, vp, vp, vp, f32p, f32p, f32p]
     lib.lvlm_merge_compact.argtypes = [vp, vp, C.POINTER(MergeDesc), f32p, f32p, C.POINTER(Plane), i32p, i32p]
     lib.lvlm_merge_similar.argtypes = [vp, vp, C.POINTER(MergeDesc), f32p, C.POINTER(Plane), f32p, f32p, i32p, i32p]
     lib.lvlm_kv_compress.argtypes = [vp, vp, C.POINTER(KvDesc), vp, vp, f32p, vp, i32p, i32p, i32p]
@@ -109,7 +121,7 @@ def _load():
     lib.lvlm_profile.argtypes = [C.c_void_p, C.c_int]
     lib.lvlm_profile_read.argtypes = [C.c_void_p, C.POINTER(ProfileEntry), C.c_int, C.POINTER(C.c_int)]
     for name in ("lvlm_profile", "lvlm_profile_read", "lvlm_create", "lvlm_destroy", "lvlm_workspace_bytes", "lvlm_set_workspace", "lvlm_schedule",
-                 "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_score_from_probs", "lvlm_merge_compact",
+                 "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_score_from_probs", "lvlm_prefill_attn", "lvlm_merge_compact",
                  "lvlm_merge_similar",
                  "lvlm_kv_compress",
                  "lvlm_decode_attn"):
@@ -241,6 +253,36 @@ class Context:
         self._check(lib.lvlm_score_from_probs(self._h, _stream(), C.byref(d), _ptr(probs), _ptr(score_head),
                                               _ptr(score_mean)))
         return score_head, score_mean
+
+    def prefill_attn(self, q, k, v, *, scale=None, causal=True, n_text=0, img_begin=0, n_img=0, out=None, row_lse=None,
+                     score_head=None, score_mean=None, reserve=True):
+        """lvlm_prefill_attn.  q [B,N,Hq,d], k, v [B,N,Hkv,d] (any strides with a contiguous head vector) ->
+        (out [B,N,Hq,d], row_lse [B,Hq,N], score_head, score_mean); the scores (of the last n_text rows over
+        the image keys) only when n_text > 0, else None."""
+        B, N, Hq, hd = q.shape
+        Hkv = k.shape[2]
+        assert k.shape == (B, N, Hkv, hd) and v.shape == (B, N, Hkv, hd)
+        assert q.stride(3) == 1 and k.stride(3) == 1 and v.stride(3) == 1
+        if out is None:
+            out = torch.empty(B, N, Hq, hd, dtype=q.dtype, device=q.device)
+        if row_lse is None:
+            row_lse = torch.empty(B, Hq, N, dtype=torch.float32, device=q.device)
+        assert out.stride(3) == 1 and row_lse.is_contiguous()
+        if n_text > 0:
+            if score_head is None:
+                score_head = torch.empty(B, Hkv, n_img, dtype=torch.float32, device=q.device)
+            if score_mean is None:
+                score_mean = torch.empty(B, n_img, dtype=torch.float32, device=q.device)
+        dense = score_head is None or score_head.is_contiguous()
+        d = PrefillDesc(_DTYPE[q.dtype], B, N, Hq, Hkv, hd, int(causal), float(scale if scale is not None else hd ** -0.5),
+                        n_text, img_begin, n_img, q.stride(0), q.stride(1), q.stride(2), k.stride(0), k.stride(1),
+                        k.stride(2), v.stride(0), v.stride(1), v.stride(2), out.stride(0), out.stride(1), out.stride(2),
+                        0 if dense else score_head.stride(0), 0 if dense else score_head.stride(1))
+        if reserve:
+            self.reserve(self.workspace_bytes(OP_PREFILL_ATTN, d))
+        self._check(lib.lvlm_prefill_attn(self._h, _stream(), C.byref(d), _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(row_lse),
+                                          _ptr(score_head), _ptr(score_mean)))
+        return out, row_lse, score_head, score_mean
 
     # ---- steps 2-4 ----
     @staticmethod

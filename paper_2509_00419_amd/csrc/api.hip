@@ -51,6 +51,30 @@ const char *check_score(const lvlm_score_desc *d) {
     return nullptr;
 }
 
+const char *check_prefill(const lvlm_prefill_desc *d) {
+    if (!d) return "null descriptor";
+    if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
+    if (d->hd != 64 && d->hd != 128) return "head dimension must be 64 or 128";
+    if (d->B < 1 || d->N < 1 || d->Hq < 1 || d->Hkv < 1) return "sizes must be positive";
+    if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
+    if (d->T < 0 || d->T > d->N) return "T must be in [0, N]";
+    if (!(d->scale > 0.0f)) return "scale must be positive";
+    const int vec = 16 / elem_bytes(d->dtype);
+    const long long s[12] = {d->q_stride_b, d->q_stride_n, d->q_stride_h, d->k_stride_b, d->k_stride_n, d->k_stride_h,
+                             d->v_stride_b, d->v_stride_n, d->v_stride_h, d->o_stride_b, d->o_stride_n, d->o_stride_h};
+    for (long long x : s)
+        if (x < 0 || x % vec != 0) return "strides must be non-negative multiples of 16 bytes";
+    if (d->q_stride_h < d->hd || d->k_stride_h < d->hd || d->v_stride_h < d->hd || d->o_stride_h < d->hd)
+        return "head stride smaller than the head dimension";
+    if ((long long)d->B * d->Hq * ((d->N + 127) / 128) >= (1ll << 28) || (long long)d->B * d->Hq * d->N >= (1ll << 33))
+        return "too many query blocks for one launch";
+    if (d->T > 0) {
+        const lvlm_score_desc sd = prefill_score_desc(*d);
+        return check_score(&sd);
+    }
+    return nullptr;
+}
+
 const char *check_probs(const lvlm_probs_desc *d) {
     if (!d) return "null descriptor";
     if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
@@ -239,6 +263,12 @@ lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const void *de
             *bytes = probs_ws(*d).total;
             return LVLM_OK;
         }
+        case LVLM_OP_PREFILL_ATTN: {
+            const auto *d = static_cast<const lvlm_prefill_desc *>(desc);
+            if ((why = check_prefill(d))) break;
+            *bytes = prefill_ws(*d).total;
+            return LVLM_OK;
+        }
         case LVLM_OP_MERGE:
         case LVLM_OP_MERGE_SIMILAR: {
             // only shapes matter for the size: plane pointers are not inspected
@@ -342,6 +372,23 @@ lvlm_status lvlm_score_from_probs(lvlm_ctx *ctx, void *stream, const lvlm_probs_
     if (lvlm_status st = bind_device(ctx)) return st;
     return after_launch(ctx, launch_score_probs(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w,
                                                 static_cast<char *>(ctx->ws), probs, score_head, score_mean));
+}
+
+lvlm_status lvlm_prefill_attn(lvlm_ctx *ctx, void *stream, const lvlm_prefill_desc *d, const void *q, const void *k,
+                              const void *v, void *out, float *row_lse, float *score_head, float *score_mean) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (const char *why = check_prefill(d)) return fail(ctx, LVLM_ERR_INVALID_ARG, "prefill_attn: %s", why);
+    if (!q || !k || !v || !out || !row_lse) return fail(ctx, LVLM_ERR_INVALID_ARG, "prefill_attn: null pointer");
+    if (d->T > 0 && (!score_head || !score_mean))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "prefill_attn: T > 0 needs score_head and score_mean");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(row_lse) || !aligned16(score_head) ||
+        !aligned4(score_mean))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "prefill_attn: pointers must be 16-byte aligned (score_mean: 4)");
+    const PrefillWs w = prefill_ws(*d);
+    if (lvlm_status st = need_ws(ctx, w.total)) return st;
+    if (lvlm_status st = bind_device(ctx)) return st;
+    return after_launch(ctx, launch_prefill_attn(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w, static_cast<char *>(ctx->ws),
+                                                 q, k, v, out, row_lse, score_head, score_mean));
 }
 
 lvlm_status lvlm_merge_compact(lvlm_ctx *ctx, void *stream, const lvlm_merge_desc *d, const float *score_mean,

@@ -44,6 +44,12 @@ struct ProbsWs {
 };
 ProbsWs probs_ws(const lvlm_probs_desc &d);
 
+struct PrefillWs {
+    size_t lse_t, score, total;   // normalisers of the last T rows, then the score pass's own workspace
+};
+PrefillWs prefill_ws(const lvlm_prefill_desc &d);
+lvlm_score_desc prefill_score_desc(const lvlm_prefill_desc &d);   // the score call the last T rows amount to
+
 struct MergeWs {
     size_t rank_part, dst_of, wgt, partial, total;
     int n_split;   // always 1: the rank kernel leaves complete ranks
@@ -94,6 +100,9 @@ hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreW
                         float *score_mean);
 hipError_t launch_score_probs(const Prof &prof, const lvlm_probs_desc &d, const ProbsWs &w, char *ws, const void *probs,
                               float *score_head, float *score_mean);
+hipError_t launch_prefill_attn(const Prof &prof, const lvlm_prefill_desc &d, const PrefillWs &w, char *ws, const void *q,
+                               const void *k, const void *v, void *out, float *row_lse, float *score_head,
+                               float *score_mean);
 hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeWs &w, char *ws,
                         const float *score_mean, const float *wtab, const lvlm_plane *planes,
                         int32_t *keep_idx, int32_t *merged_idx);

@@ -1,0 +1,389 @@
+// The layer's own prefill attention, leaving the row normalisers the token scores are computed from
+// (Sec. 3.2.1: the scores are a by-product of the attention of the layer; Sec. 3.2.2: of its statistics).
+//
+// out[b,i,h,:] = sum_j softmax_j(scale q[b,i,h].k[b,j,g]) v[b,j,g,:], g = h / G, over the keys row i may
+// see; row_lse[b,h,i] = natural-log sum-exp of the row's scaled logits.  The last T rows' normalisers are
+// also left densely packed for the column-sum pass of the score kernels, which then needs no normaliser
+// pass of its own.
+#include "mma.h"
+
+#include <climits>
+
+namespace lvlm {
+namespace {
+
+struct PrefillArgs {
+    const char *q, *k, *v;
+    char *out;
+    float *row_lse;     // [B][Hq][N]
+    float *lse_t;       // [B][Hq][T] or null: the last T rows again
+    int B, N, Hq, Hkv, G, causal, T;
+    int nqb;            // query blocks per head
+    int pair_groups;    // ceil(B * Hkv / 8)
+    float scale, scale_log2;
+    long long qsb, qsn, qsh, ksb, ksn, ksh, vsb, vsn, vsh, osb, osn, osh;   // bytes
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    const bf2 r = __builtin_convertvector(f2{lo, hi}, bf2);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// bf16, matrix cores.  A workgroup of two waves owns 128 query rows of one head, 64 per wave as two 32-row
+// blocks held in registers as MFMA operands.  Keys and values go by in tiles of 32: the 128 threads fetch
+// the next tile while the current one is multiplied, K into LDS as it is (rows = keys), V turned around
+// (rows = channels, 32 keys each) in registers on the way in; one barrier per tile.  Per tile and block:
+// S^T = K Q^T (rows = keys, columns = queries), so a lane owns ONE query row and 16 of its logits -- the
+// online max and sum are lane-local but for one exchange with the other half-wave -- and the 16
+// probabilities, rounded to bf16, are already laid out as the second operand of O^T += V^T P^T when the
+// keys inside V^T's rows are stored in the order the accumulator registers hold them.  Both blocks of a wave
+// use each K and V^T fragment read from LDS, which is what keeps LDS bandwidth (about 64 bytes a clock per
+// CU, measured) from bounding the kernel: one fragment read feeds two matrix instructions.
+template <int HD>
+__global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a) {
+    constexpr int ROWB = HD * 2;
+    constexpr int KP = ROWB + 16;           // K tile pitch: odd multiple of 16 bytes
+    constexpr int VP = 80;                  // V^T row: 32 keys x 2 bytes + 16
+    constexpr int NV = HD / 16;             // 16-byte words a lane holds of a row half
+    constexpr int NCB = HD / 32;            // blocks of 32 channels
+    constexpr int UPR = ROWB / 16;          // 16-byte units per row
+    constexpr int KUPT = 32 * UPR / 128;    // K units per thread and tile
+    constexpr int KTPR = UPR / KUPT;        // threads per K row
+    __shared__ __attribute__((aligned(16))) char k_lds[2][32 * KP];
+    __shared__ __attribute__((aligned(16))) char v_lds[2][HD * VP];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int hf = lane >> 5, l32 = lane & 31;
+    // Workgroup id -> (batch, head, query block).  Ids with the same remainder modulo 8 run on one XCD: all
+    // heads of a (batch, KV head) pair go there, they read the same keys and values.  Within an XCD the
+    // longest blocks (latest rows) come first.
+    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int per_blk = a.pair_groups * a.G;
+    const int qb = a.nqb - 1 - seq / per_blk;
+    const int rem = seq % per_blk;
+    const int pair = (rem / a.G) * 8 + xcd;
+    if (pair >= a.B * a.Hkv) return;
+    const int b = pair / a.Hkv, g = pair % a.Hkv, h = g * a.G + rem % a.G;
+    const int q0 = qb * 128;
+    const int wrow0 = q0 + 64 * wave;                 // this wave's first row
+    const int kmax = a.causal ? min(a.N, q0 + 128) : a.N;
+    const int n_tiles = (kmax + 31) >> 5;
+
+    // query operands: lane (row l32 of block x, half hf) holds bytes 16 hf + 32 i of its row
+    uint4 qf[2][NV];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+        const int row = wrow0 + 32 * x + l32;
+        const char *src = a.q + (long long)b * a.qsb + (long long)min(row, a.N - 1) * a.qsn + (long long)h * a.qsh + 16 * hf;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) qf[x][i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
+    }
+
+    // staging.  K: thread -> row krow, units kcu + KTPR x.  V: thread -> four keys 4 vkg .. 4 vkg + 3 of one
+    // 16-byte unit vcu (8 channels); HD = 64 needs only half the threads for V.
+    const int krow = tid / KTPR, kcu = tid % KTPR;
+    const char *kbase = a.k + (long long)b * a.ksb + (long long)g * a.ksh + 16 * kcu;
+    const int vkg = tid & 7, vcu = tid >> 3;
+    const bool v_on = vcu < UPR;
+    const char *vbase = a.v + (long long)b * a.vsb + (long long)g * a.vsh + 16 * (v_on ? vcu : 0);
+    // named registers, not arrays: what a loop carries from its top to its bottom must not be indexed
+    uint4 ks0 = make_uint4(0, 0, 0, 0), ks1 = ks0, ks2 = ks0, ks3 = ks0, vs0 = ks0, vs1 = ks0, vs2 = ks0, vs3 = ks0;
+    auto fetch = [&](int j0) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(kbase + (long long)min(j0 + krow, a.N - 1) * a.ksn);
+        ks0 = src[0];
+        if constexpr (KUPT > 1) ks1 = src[KTPR];
+        if constexpr (KUPT > 2) ks2 = src[2 * KTPR];
+        if constexpr (KUPT > 3) ks3 = src[3 * KTPR];
+        if (v_on) {
+            const int jv = j0 + 4 * vkg;
+            vs0 = *reinterpret_cast<const uint4 *>(vbase + (long long)min(jv + 0, a.N - 1) * a.vsn);
+            vs1 = *reinterpret_cast<const uint4 *>(vbase + (long long)min(jv + 1, a.N - 1) * a.vsn);
+            vs2 = *reinterpret_cast<const uint4 *>(vbase + (long long)min(jv + 2, a.N - 1) * a.vsn);
+            vs3 = *reinterpret_cast<const uint4 *>(vbase + (long long)min(jv + 3, a.N - 1) * a.vsn);
+        }
+    };
+    // Position of key kk of a tile inside a V^T row: accumulator register r of half hf holds key
+    // 8 (r / 4) + 4 hf + r % 4 of a 32-key tile, and the second product wants the 8 keys of registers
+    // 8 t .. 8 t + 7 in one 16-byte word: word index 2 t + hf, inside it 4 (r / 4 % 2) + r % 4.  Four keys
+    // 4 vkg .. 4 vkg + 3 stay together: they go to byte 32 (vkg / 4) + 16 (vkg % 2) + 8 (vkg / 2 % 2).
+    const int v_off = 32 * (vkg >> 2) + 16 * (vkg & 1) + 8 * ((vkg >> 1) & 1);
+    // channels 2m (low halves of word m) and 2m + 1 (high halves) of the unit, four keys each
+#define LVLM_VT(m, c)                                                                    \
+    {                                                                                    \
+        uint2 lo, hi;                                                                    \
+        lo.x = __builtin_amdgcn_perm(vs1.c, vs0.c, 0x05040100u);                         \
+        lo.y = __builtin_amdgcn_perm(vs3.c, vs2.c, 0x05040100u);                         \
+        hi.x = __builtin_amdgcn_perm(vs1.c, vs0.c, 0x07060302u);                         \
+        hi.y = __builtin_amdgcn_perm(vs3.c, vs2.c, 0x07060302u);                         \
+        *reinterpret_cast<uint2 *>(vd + (2 * m) * VP) = lo;                              \
+        *reinterpret_cast<uint2 *>(vd + (2 * m + 1) * VP) = hi;                          \
+    }
+    auto stash = [&](int buf) {
+        uint4 *dst = reinterpret_cast<uint4 *>(&k_lds[buf][krow * KP + 16 * kcu]);
+        dst[0] = ks0;
+        if constexpr (KUPT > 1) dst[KTPR] = ks1;
+        if constexpr (KUPT > 2) dst[2 * KTPR] = ks2;
+        if constexpr (KUPT > 3) dst[3 * KTPR] = ks3;
+        if (v_on) {
+            char *vd = &v_lds[buf][(8 * vcu) * VP + v_off];
+            LVLM_VT(0, x) LVLM_VT(1, y) LVLM_VT(2, z) LVLM_VT(3, w)
+        }
+    };
+#undef LVLM_VT
+
+    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    f32x16 oacc[2][NCB];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[x][cb][r] = 0.f;
+
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int t = 0; t < n_tiles; ++t) {
+        const int j0 = t << 5, buf = t & 1;
+        if (t + 1 < n_tiles) fetch(j0 + 32);
+        // the wave's rows end at wrow0 + 63: later tiles are all masked for it (it still moves tiles)
+        if (!a.causal || j0 <= wrow0 + 63) {
+            const bool on1 = !a.causal || j0 <= wrow0 + 32 + 31;    // block 1 (rows wrow0 + 32 ..)
+            const bool on0 = !a.causal || j0 <= wrow0 + 31;
+            f32x16 s0, s1;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s0[r] = 0.f, s1[r] = 0.f;
+            {
+                const char *src = &k_lds[buf][l32 * KP + 16 * hf];
+#pragma unroll
+                for (int i = 0; i < NV; ++i) {
+                    const uint4 kf = *reinterpret_cast<const uint4 *>(src + 32 * i);
+                    const bf16x8 kb = __builtin_bit_cast(bf16x8, kf);
+                    if (on0) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb, __builtin_bit_cast(bf16x8, qf[0][i]), s0, 0, 0, 0);
+                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb, __builtin_bit_cast(bf16x8, qf[1][i]), s1, 0, 0, 0);
+                }
+            }
+            uint4 pf[2][2];
+            auto softmax = [&](int x, f32x16 &s) {
+                const int row = wrow0 + 32 * x + l32;
+                // a mask is needed where the tile reaches past the block's first row or past the last key
+                if ((a.causal && j0 + 31 > wrow0 + 32 * x) || j0 + 32 > a.N) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int j = j0 + acc_row(r, hf);
+                        if ((a.causal && j > row) || j >= a.N) s[r] = -INFINITY;
+                    }
+                }
+                float mx = s[0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                // key j0 is visible to every row of an active block (j0 <= the block's first row), so the
+                // running maximum is finite from the first tile on
+                const float m_new = fmaxf(m_run[x], mx);
+                const float mb = m_new * a.scale_log2;
+                float sum = 0.f;
+                float p[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2, -mb));
+                    sum += p[r];
+                }
+                if (__builtin_amdgcn_ballot_w64(m_new != m_run[x]) != 0ull) {
+                    const float alpha = __builtin_amdgcn_exp2f((m_run[x] - m_new) * a.scale_log2);   // first tile: 0
+                    l_run[x] *= alpha;
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) oacc[x][cb][r] *= alpha;
+                    m_run[x] = m_new;
+                }
+                l_run[x] += sum;
+#pragma unroll
+                for (int t2 = 0; t2 < 2; ++t2) {
+                    pf[x][t2].x = pack_bf16(p[8 * t2 + 0], p[8 * t2 + 1]);
+                    pf[x][t2].y = pack_bf16(p[8 * t2 + 2], p[8 * t2 + 3]);
+                    pf[x][t2].z = pack_bf16(p[8 * t2 + 4], p[8 * t2 + 5]);
+                    pf[x][t2].w = pack_bf16(p[8 * t2 + 6], p[8 * t2 + 7]);
+                }
+            };
+            if (on0) softmax(0, s0);
+            softmax(1, s1);
+            (void)on1;
+            {
+                const char *src = &v_lds[buf][l32 * VP + 16 * hf];
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; ++t2) {
+                        const uint4 vf = *reinterpret_cast<const uint4 *>(src + (32 * cb) * VP + 32 * t2);
+                        const bf16x8 vb = __builtin_bit_cast(bf16x8, vf);
+                        if (on0)
+                            oacc[0][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, __builtin_bit_cast(bf16x8, pf[0][t2]),
+                                                                                 oacc[0][cb], 0, 0, 0);
+                        oacc[1][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, __builtin_bit_cast(bf16x8, pf[1][t2]),
+                                                                             oacc[1][cb], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        if (t + 1 < n_tiles) stash(buf ^ 1);
+        __syncthreads();
+    }
+
+    // normalise and write: lane (query l32, half hf) holds channels 32 cb + 8 (r / 4) + 4 hf + r % 4
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+        const int row = wrow0 + 32 * x + l32;
+        const float l_tot = l_run[x] + __shfl_xor(l_run[x], 32);
+        if (row >= a.N) continue;
+        const float inv = 1.f / l_tot;
+        char *dst = a.out + (long long)b * a.osb + (long long)row * a.osn + (long long)h * a.osh + 8 * hf;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                uint2 w;
+                w.x = pack_bf16(oacc[x][cb][4 * r4 + 0] * inv, oacc[x][cb][4 * r4 + 1] * inv);
+                w.y = pack_bf16(oacc[x][cb][4 * r4 + 2] * inv, oacc[x][cb][4 * r4 + 3] * inv);
+                *reinterpret_cast<uint2 *>(dst + 64 * cb + 16 * r4) = w;
+            }
+        if (hf == 0) {
+            const float lse = m_run[x] * a.scale + __logf(l_tot);
+            a.row_lse[((long long)b * a.Hq + h) * a.N + row] = lse;
+            if (a.lse_t && row >= a.N - a.T) a.lse_t[((long long)b * a.Hq + h) * a.T + (row - (a.N - a.T))] = lse;
+        }
+    }
+}
+
+// fp32 (the small fp32 configuration; plain vector arithmetic, no matrix cores): one wave per query row, its
+// lanes take every 64th visible key with an online (max, sum, weighted value sum) each, folded at the end.
+template <int HD>
+__global__ __launch_bounds__(256) void prefill_attn_f32_kernel(PrefillArgs a) {
+    __shared__ __attribute__((aligned(16))) float q_s[4][HD];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const long long total = (long long)a.B * a.Hq * a.N;
+    const long long rid = (long long)blockIdx.x * 4 + wave;
+    const bool live = rid < total;
+    const long long rc = live ? rid : total - 1;
+    const int i = (int)(rc % a.N), h = (int)((rc / a.N) % a.Hq), b = (int)(rc / ((long long)a.N * a.Hq));
+    const int g = h / a.G;
+    {
+        const float *qr = reinterpret_cast<const float *>(a.q + (long long)b * a.qsb + (long long)i * a.qsn + (long long)h * a.qsh);
+        for (int c = lane; c < HD; c += 64) q_s[wave][c] = qr[c];
+    }
+    __syncthreads();
+    const int last = a.causal ? i : a.N - 1;
+    float m = -INFINITY, l = 0.f;
+    float o[HD];
+#pragma unroll
+    for (int c = 0; c < HD; ++c) o[c] = 0.f;
+    const char *kb = a.k + (long long)b * a.ksb + (long long)g * a.ksh;
+    const char *vb = a.v + (long long)b * a.vsb + (long long)g * a.vsh;
+    for (int j = lane; j <= last; j += 64) {
+        const float4 *kr = reinterpret_cast<const float4 *>(kb + (long long)j * a.ksn);
+        const float4 *vr = reinterpret_cast<const float4 *>(vb + (long long)j * a.vsn);
+        float s = 0.f;
+#pragma unroll
+        for (int c4 = 0; c4 < HD / 4; ++c4) {
+            const float4 kk = kr[c4];
+            const float4 qq = *reinterpret_cast<const float4 *>(&q_s[wave][4 * c4]);
+            s = fmaf(qq.x, kk.x, s); s = fmaf(qq.y, kk.y, s); s = fmaf(qq.z, kk.z, s); s = fmaf(qq.w, kk.w, s);
+        }
+        s *= a.scale_log2;
+        const float m_new = fmaxf(m, s);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);     // first key: exp2(-inf) = 0
+        const float p = __builtin_amdgcn_exp2f(s - m_new);
+        l = l * alpha + p;
+#pragma unroll
+        for (int c4 = 0; c4 < HD / 4; ++c4) {
+            const float4 vv = vr[c4];
+            o[4 * c4 + 0] = fmaf(o[4 * c4 + 0], alpha, p * vv.x);
+            o[4 * c4 + 1] = fmaf(o[4 * c4 + 1], alpha, p * vv.y);
+            o[4 * c4 + 2] = fmaf(o[4 * c4 + 2], alpha, p * vv.z);
+            o[4 * c4 + 3] = fmaf(o[4 * c4 + 3], alpha, p * vv.w);
+        }
+        m = m_new;
+    }
+    const float M = wave_max(m);                                    // lane 0 always has key 0: finite
+    const float f = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - M);
+    const float L = wave_sum(l * f);
+    const float inv = 1.f / L;
+    float mine = 0.f, mine2 = 0.f;                                  // lane c keeps channels c and c + 64
+#pragma unroll
+    for (int c = 0; c < HD; ++c) {
+        const float tot = wave_sum(o[c] * f);
+        if ((c & 63) == lane) { if (c < 64) mine = tot; else mine2 = tot; }
+    }
+    if (!live) return;
+    float *dst = reinterpret_cast<float *>(a.out + (long long)b * a.osb + (long long)i * a.osn + (long long)h * a.osh);
+    dst[lane] = mine * inv;
+    if (HD > 64) dst[64 + lane] = mine2 * inv;
+    if (lane == 0) {
+        const float lse = (M + __log2f(L)) * 0.6931471805599453f;
+        a.row_lse[((long long)b * a.Hq + h) * a.N + i] = lse;
+        if (a.lse_t && i >= a.N - a.T) a.lse_t[((long long)b * a.Hq + h) * a.T + (i - (a.N - a.T))] = lse;
+    }
+}
+
+}  // namespace
+
+PrefillWs prefill_ws(const lvlm_prefill_desc &d) {
+    PrefillWs w{};
+    w.lse_t = 0;
+    w.score = align_up((size_t)d.B * d.Hq * (d.T > 0 ? d.T : 0) * sizeof(float), 256);
+    w.total = w.score;
+    if (d.T > 0) w.total += align_up(score_ws(prefill_score_desc(d)).total, 256);
+    return w;
+}
+
+lvlm_score_desc prefill_score_desc(const lvlm_prefill_desc &d) {
+    lvlm_score_desc s{};
+    s.dtype = d.dtype; s.B = d.B; s.N = d.N; s.T = d.T; s.q_pos0 = d.N - d.T; s.Hq = d.Hq; s.Hkv = d.Hkv; s.hd = d.hd;
+    s.img_begin = d.img_begin; s.n_img = d.n_img; s.causal = d.causal; s.scale = d.scale;
+    s.q_stride_b = d.q_stride_b; s.q_stride_t = d.q_stride_n; s.q_stride_h = d.q_stride_h;
+    s.k_stride_b = d.k_stride_b; s.k_stride_n = d.k_stride_n; s.k_stride_h = d.k_stride_h;
+    s.sh_stride_b = d.sh_stride_b; s.sh_stride_h = d.sh_stride_h;
+    return s;
+}
+
+hipError_t launch_prefill_attn(const Prof &prof, const lvlm_prefill_desc &d, const PrefillWs &w, char *ws, const void *q,
+                               const void *k, const void *v, void *out, float *row_lse, float *score_head,
+                               float *score_mean) {
+    hipStream_t stream = prof.stream;
+    const int es = d.dtype == LVLM_BF16 ? 2 : 4;
+    PrefillArgs a{};
+    a.q = static_cast<const char *>(q); a.k = static_cast<const char *>(k); a.v = static_cast<const char *>(v);
+    a.out = static_cast<char *>(out);
+    a.row_lse = row_lse;
+    a.lse_t = d.T > 0 ? reinterpret_cast<float *>(ws + w.lse_t) : nullptr;
+    a.B = d.B; a.N = d.N; a.Hq = d.Hq; a.Hkv = d.Hkv; a.G = d.Hq / d.Hkv; a.causal = d.causal; a.T = d.T;
+    a.nqb = (d.N + 127) / 128;
+    a.pair_groups = (d.B * d.Hkv + 7) / 8;
+    a.scale = d.scale; a.scale_log2 = d.scale * kLog2e;
+    a.qsb = d.q_stride_b * es; a.qsn = d.q_stride_n * es; a.qsh = d.q_stride_h * es;
+    a.ksb = d.k_stride_b * es; a.ksn = d.k_stride_n * es; a.ksh = d.k_stride_h * es;
+    a.vsb = d.v_stride_b * es; a.vsn = d.v_stride_n * es; a.vsh = d.v_stride_h * es;
+    a.osb = d.o_stride_b * es; a.osn = d.o_stride_n * es; a.osh = d.o_stride_h * es;
+    prof.begin("prefill_attn");
+    if (d.dtype == LVLM_BF16) {
+        const long long grid = (long long)a.pair_groups * 8 * a.G * a.nqb;
+        if (d.hd == 128) hipLaunchKernelGGL((prefill_attn_bf16_kernel<128>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+        else hipLaunchKernelGGL((prefill_attn_bf16_kernel<64>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+    } else {
+        const long long grid = ((long long)d.B * d.Hq * d.N + 3) / 4;
+        if (d.hd == 128) hipLaunchKernelGGL((prefill_attn_f32_kernel<128>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((prefill_attn_f32_kernel<64>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+    }
+    prof.end();
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || d.T <= 0) return e;
+    // the scores of the last T rows from the normalisers just written: the column-sum pass alone
+    const lvlm_score_desc sd = prefill_score_desc(d);
+    const char *q_t = static_cast<const char *>(q) + (long long)(d.N - d.T) * d.q_stride_n * es;
+    return launch_score(prof, sd, score_ws(sd), ws + w.score, q_t, k, a.lse_t, score_head, score_mean);
+}
+
+}  // namespace lvlm

@@ -1,0 +1,125 @@
+"""GPU parity of lvlm_prefill_attn (the layer's attention with the scores as its by-product) against the CPU
+oracle, through the C ABI.
+
+Tolerances (max |gpu - oracle| / max |oracle|): outputs 2e-2 (bf16) / 1e-5 (fp32); the row normalisers and
+the scores are fp32 whatever the input dtype: 1e-5.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2509_00419_amd as lv
+from oracle import lvlm_oracle as O
+from workloads import configs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+TOL = {torch.float32: 1e-5, torch.bfloat16: 2e-2}
+
+
+def f64(t):
+    return t.detach().double().cpu().numpy()
+
+
+def rel_err(got, ref):
+    got, ref = np.asarray(got, dtype=np.float64), np.asarray(ref, dtype=np.float64)
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    return lv.Context(0)
+
+
+def _qkv(B, N, Hq, Hkv, d, dtype, seed, q_gain=1.0):
+    """q, k, v as views of one fused projection output [B, N, Hq + 2 Hkv, d], as a model lays them out."""
+    g = torch.Generator().manual_seed(seed)
+    fused = torch.randn(B, N, Hq + 2 * Hkv, d, generator=g)
+    fused[:, :, :Hq] *= q_gain
+    fused = fused.to(dtype)
+    return fused, (lambda t: (t[:, :, :Hq], t[:, :, Hq:Hq + Hkv], t[:, :, Hq + Hkv:]))
+
+
+CASES = [
+    # dtype, B, N, Hq, Hkv, d, causal, T, img_begin, n_img, q_gain        what it covers
+    (torch.float32, 1, 640, 4, 4, 64, True, 32, 32, 576, 1.0),            # config 1
+    (torch.float32, 2, 77, 4, 2, 128, True, 5, 3, 60, 2.0),               # fp32, d = 128, ragged
+    (torch.float32, 1, 130, 2, 1, 64, False, 0, 0, 0, 1.0),               # fp32, no mask, attention only
+    (torch.bfloat16, 2, 333, 6, 2, 128, True, 9, 5, 300, 1.0),            # ragged rows and keys, G = 3
+    (torch.bfloat16, 1, 233, 8, 8, 64, False, 0, 0, 0, 1.0),              # d = 64, no mask, attention only
+    (torch.bfloat16, 1, 257, 4, 2, 64, True, 40, 10, 200, 3.0),           # d = 64 causal, peaky rows, one row past a block
+    (torch.bfloat16, 3, 500, 8, 4, 128, True, 64, 20, 400, 1.0),          # 12 (batch, KV head) pairs: 8 + 4 over the XCDs
+    (torch.bfloat16, 1, 31, 2, 2, 128, True, 31, 0, 20, 1.0),             # shorter than one tile, every row an instruction row
+    (torch.bfloat16, 1, 2176, 28, 4, 128, True, 64, 64, 2048, 1.0),       # config 2 layer
+]
+
+
+@pytest.mark.parametrize("dtype,B,N,Hq,Hkv,d,causal,T,img0,n_img,gain", CASES)
+def test_prefill_attn_matches_oracle(ctx, dtype, B, N, Hq, Hkv, d, causal, T, img0, n_img, gain):
+    fused, split = _qkv(B, N, Hq, Hkv, d, dtype, 100 + N, gain)
+    q, k, v = split(fused)
+    qd, kd, vd = split(fused.to(DEV))
+    out, lse, sh, sm = ctx.prefill_attn(qd, kd, vd, causal=causal, n_text=T, img_begin=img0, n_img=n_img)
+    torch.cuda.synchronize()
+    o_out, o_lse = O.prefill_attn(f64(q), f64(k), f64(v), causal=causal, dtype="bf16" if dtype == torch.bfloat16 else "f32")
+    assert rel_err(out.float().cpu(), o_out) < TOL[dtype]
+    assert np.abs(lse.cpu().numpy() - o_lse).max() < 1e-5 * max(1.0, np.abs(o_lse).max())
+    if T > 0:
+        osh, osm = O.score_tokens(f64(q[:, N - T:]), f64(k), q_pos0=N - T, img_begin=img0, n_img=n_img, causal=causal)
+        assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
+        # and exactly what lvlm_score_tokens gives from the same normalisers
+        sh2, sm2 = ctx.score_tokens(qd[:, N - T:], kd, q_pos0=N - T, img_begin=img0, n_img=n_img, causal=causal,
+                                    row_lse=lse[:, :, N - T:].contiguous())
+        assert torch.equal(sh, sh2) and torch.equal(sm, sm2)
+    else:
+        assert sh is None and sm is None
+
+
+def test_prefill_attn_config3_shape_two_sequences(ctx):
+    # InternVL2.5-8B-shaped layer (32 / 8 heads, 1792 image + 96 text tokens), two of the eight sequences for the oracle
+    w = configs.CFG3
+    B, N = 2, w.seq_len
+    fused, split = _qkv(B, N, w.n_q_heads, w.n_kv_heads, w.head_dim, torch.bfloat16, 7)
+    q, k, v = split(fused)
+    qd, kd, vd = split(fused.to(DEV))
+    out, lse, sh, sm = ctx.prefill_attn(qd, kd, vd, n_text=w.n_text, img_begin=w.n_sys, n_img=w.n_img)
+    o_out, o_lse = O.prefill_attn(f64(q), f64(k), f64(v), dtype="bf16")
+    assert rel_err(out.float().cpu(), o_out) < 2e-2
+    assert np.abs(lse.cpu().numpy() - o_lse).max() < 1e-5 * np.abs(o_lse).max()
+    osh, osm = O.score_tokens(f64(q[:, N - w.n_text:]), f64(k), q_pos0=N - w.n_text, img_begin=w.n_sys, n_img=w.n_img)
+    assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
+
+
+def test_prefill_attn_config5_shape_sampled_group(ctx):
+    # 16512 tokens, 48 / 8 heads on the GPU; the oracle checks one KV group (its 6 query heads), every row
+    w = configs.CFG5
+    N, Hq, Hkv, d = w.seq_len, w.n_q_heads, w.n_kv_heads, w.head_dim
+    fused, split = _qkv(1, N, Hq, Hkv, d, torch.bfloat16, 11)
+    q, k, v = split(fused)
+    qd, kd, vd = split(fused.to(DEV))
+    out, lse, sh, sm = ctx.prefill_attn(qd, kd, vd, n_text=w.n_text, img_begin=w.n_sys, n_img=w.n_img)
+    torch.cuda.synchronize()
+    g, G = Hkv - 1, Hq // Hkv
+    heads = slice(g * G, (g + 1) * G)
+    o_out, o_lse = O.prefill_attn(f64(q[:, :, heads]), f64(k[:, :, g:g + 1]), f64(v[:, :, g:g + 1]), dtype="bf16")
+    assert rel_err(out[:, :, heads].float().cpu(), o_out) < 2e-2
+    assert np.abs(lse[:, heads].cpu().numpy() - o_lse).max() < 1e-5 * np.abs(o_lse).max()
+    osh, _ = O.score_tokens(f64(q[:, N - w.n_text:, heads]), f64(k[:, :, g:g + 1]), q_pos0=N - w.n_text,
+                            img_begin=w.n_sys, n_img=w.n_img)
+    assert rel_err(sh[:, g:g + 1].cpu(), osh) < 1e-5
+    # properties that hold for every head: rows are convex combinations of the values they see
+    vmax = vd.float().abs().amax()
+    assert float(out.float().abs().amax()) <= float(vmax) * (1 + 2 ** -7)
+    assert torch.isfinite(lse).all()
+
+
+def test_prefill_attn_rejects_bad_arguments(ctx):
+    fused, split = _qkv(1, 64, 4, 2, 64, torch.bfloat16, 1)
+    qd, kd, vd = split(fused.to(DEV))
+    with pytest.raises(lv.LvlmError):
+        ctx.prefill_attn(qd, kd, vd, scale=0.0)                     # scale must be positive
+    with pytest.raises(lv.LvlmError):
+        ctx.prefill_attn(qd, kd, vd, n_text=65, img_begin=0, n_img=10)      # more instruction rows than rows
+    with pytest.raises(lv.LvlmError):
+        ctx.prefill_attn(qd, kd, vd, n_text=8, img_begin=60, n_img=10)      # image span outside the sequence
