@@ -24,6 +24,8 @@ struct PrefillArgs {
     long long qsb, qsn, qsh, ksb, ksn, ksh, vsb, vsn, vsh, osb, osn, osh;   // bytes
 };
 
+constexpr float kLazy = 8.f;   // log2 of how far the true row maximum may run ahead of the reference one
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
     typedef float f2 __attribute__((ext_vector_type(2)));
@@ -54,7 +56,8 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     __shared__ __attribute__((aligned(16))) char k_lds[2][32 * KP];
     __shared__ __attribute__((aligned(16))) char v_lds[2][HD * VP];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform: conditions on it are scalar branches
     const int hf = lane >> 5, l32 = lane & 31;
     // Workgroup id -> (batch, head, query block).  Ids with the same remainder modulo 8 run on one XCD: all
     // heads of a (batch, KV head) pair go there, they read the same keys and values.  Within an XCD the
@@ -90,7 +93,25 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     const char *vbase = a.v + (long long)b * a.vsb + (long long)g * a.vsh + 16 * (v_on ? vcu : 0);
     // named registers, not arrays: what a loop carries from its top to its bottom must not be indexed
     uint4 ks0 = make_uint4(0, 0, 0, 0), ks1 = ks0, ks2 = ks0, ks3 = ks0, vs0 = ks0, vs1 = ks0, vs2 = ks0, vs3 = ks0;
+    const char *kthr = kbase + (long long)krow * a.ksn;           // this thread's row of tile 0
+    const char *vthr = vbase + (long long)(4 * vkg) * a.vsn;
     auto fetch = [&](int j0) {
+        if (j0 + 32 <= a.N) {                                     // whole tile: uniform offsets only
+            const uint4 *src = reinterpret_cast<const uint4 *>(kthr + (long long)j0 * a.ksn);
+            ks0 = src[0];
+            if constexpr (KUPT > 1) ks1 = src[KTPR];
+            if constexpr (KUPT > 2) ks2 = src[2 * KTPR];
+            if constexpr (KUPT > 3) ks3 = src[3 * KTPR];
+            if (v_on) {
+                const char *vp = vthr + (long long)j0 * a.vsn;
+                vs0 = *reinterpret_cast<const uint4 *>(vp);
+                vs1 = *reinterpret_cast<const uint4 *>(vp + a.vsn);
+                vs2 = *reinterpret_cast<const uint4 *>(vp + 2 * a.vsn);
+                vs3 = *reinterpret_cast<const uint4 *>(vp + 3 * a.vsn);
+            }
+            return;
+        }
+        // the ragged last tile: rows past the end repeat the last row (masked later)
         const uint4 *src = reinterpret_cast<const uint4 *>(kbase + (long long)min(j0 + krow, a.N - 1) * a.ksn);
         ks0 = src[0];
         if constexpr (KUPT > 1) ks1 = src[KTPR];
@@ -148,10 +169,9 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     for (int t = 0; t < n_tiles; ++t) {
         const int j0 = t << 5, buf = t & 1;
         if (t + 1 < n_tiles) fetch(j0 + 32);
-        // the wave's rows end at wrow0 + 63: later tiles are all masked for it (it still moves tiles)
+        // the wave's rows end at wrow0 + 63: later tiles are all masked for it (it still moves tiles).  Both
+        // blocks take every tile up to there: the one tile block 0 does not need is masked whole and adds zeros.
         if (!a.causal || j0 <= wrow0 + 63) {
-            const bool on1 = !a.causal || j0 <= wrow0 + 32 + 31;    // block 1 (rows wrow0 + 32 ..)
-            const bool on0 = !a.causal || j0 <= wrow0 + 31;
             f32x16 s0, s1;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s0[r] = 0.f, s1[r] = 0.f;
@@ -161,7 +181,7 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
                 for (int i = 0; i < NV; ++i) {
                     const uint4 kf = *reinterpret_cast<const uint4 *>(src + 32 * i);
                     const bf16x8 kb = __builtin_bit_cast(bf16x8, kf);
-                    if (on0) s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb, __builtin_bit_cast(bf16x8, qf[0][i]), s0, 0, 0, 0);
+                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb, __builtin_bit_cast(bf16x8, qf[0][i]), s0, 0, 0, 0);
                     s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb, __builtin_bit_cast(bf16x8, qf[1][i]), s1, 0, 0, 0);
                 }
             }
@@ -180,18 +200,13 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
 #pragma unroll
                 for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // key j0 is visible to every row of an active block (j0 <= the block's first row), so the
-                // running maximum is finite from the first tile on
-                const float m_new = fmaxf(m_run[x], mx);
-                const float mb = m_new * a.scale_log2;
-                float sum = 0.f;
-                float p[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2, -mb));
-                    sum += p[r];
-                }
-                if (__builtin_amdgcn_ballot_w64(m_new != m_run[x]) != 0ull) {
+                // The reference maximum m_run only follows the true one when that has run ahead by more than
+                // 2^kLazy: until then the probabilities are at most 2^kLazy instead of 1 (harmless in fp32 sums
+                // and bf16 operands: the final division takes it out) and the accumulators need no rescaling.
+                // Key j0 is visible to every row of a block the tile really reaches, so the first tile sets a
+                // finite reference; a tile masked whole (-inf everywhere) changes nothing and adds zeros.
+                if (__builtin_amdgcn_ballot_w64((mx - m_run[x]) * a.scale_log2 > kLazy) != 0ull) {
+                    const float m_new = fmaxf(m_run[x], mx);
                     const float alpha = __builtin_amdgcn_exp2f((m_run[x] - m_new) * a.scale_log2);   // first tile: 0
                     l_run[x] *= alpha;
 #pragma unroll
@@ -199,6 +214,14 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
 #pragma unroll
                         for (int r = 0; r < 16; ++r) oacc[x][cb][r] *= alpha;
                     m_run[x] = m_new;
+                }
+                const float mb = m_run[x] * a.scale_log2;
+                float sum = 0.f;
+                float p[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2, -mb));
+                    sum += p[r];
                 }
                 l_run[x] += sum;
 #pragma unroll
@@ -209,9 +232,8 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
                     pf[x][t2].w = pack_bf16(p[8 * t2 + 6], p[8 * t2 + 7]);
                 }
             };
-            if (on0) softmax(0, s0);
+            softmax(0, s0);
             softmax(1, s1);
-            (void)on1;
             {
                 const char *src = &v_lds[buf][l32 * VP + 16 * hf];
 #pragma unroll
@@ -220,9 +242,8 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
                     for (int t2 = 0; t2 < 2; ++t2) {
                         const uint4 vf = *reinterpret_cast<const uint4 *>(src + (32 * cb) * VP + 32 * t2);
                         const bf16x8 vb = __builtin_bit_cast(bf16x8, vf);
-                        if (on0)
-                            oacc[0][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, __builtin_bit_cast(bf16x8, pf[0][t2]),
-                                                                                 oacc[0][cb], 0, 0, 0);
+                        oacc[0][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, __builtin_bit_cast(bf16x8, pf[0][t2]),
+                                                                             oacc[0][cb], 0, 0, 0);
                         oacc[1][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, __builtin_bit_cast(bf16x8, pf[1][t2]),
                                                                              oacc[1][cb], 0, 0, 0);
                     }
