@@ -45,7 +45,7 @@ struct ProbsWs {
 ProbsWs probs_ws(const lvlm_probs_desc &d);
 
 struct PrefillWs {
-    size_t lse_t, score, total;   // normalisers of the last T rows, then the score pass's own workspace
+    size_t lse_t, redo, score, total;   // normalisers of the last T rows, redo marks per workgroup, the score pass's workspace
 };
 PrefillWs prefill_ws(const lvlm_prefill_desc &d);
 lvlm_score_desc prefill_score_desc(const lvlm_prefill_desc &d);   // the score call the last T rows amount to

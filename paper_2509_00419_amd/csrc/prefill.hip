@@ -17,6 +17,7 @@ struct PrefillArgs {
     char *out;
     float *row_lse;     // [B][Hq][N]
     float *lse_t;       // [B][Hq][T] or null: the last T rows again
+    int *redo;          // [grid]: workgroups the FAST kernel gave up, for the SAFE kernel
     int B, N, Hq, Hkv, G, causal, T;
     int nqb;            // query blocks per head
     int pair_groups;    // ceil(B * Hkv / 8)
@@ -24,7 +25,17 @@ struct PrefillArgs {
     long long qsb, qsn, qsh, ksb, ksn, ksh, vsb, vsn, vsh, osb, osn, osh;   // bytes
 };
 
-constexpr float kLazy = 8.f;   // log2 of how far the true row maximum may run ahead of the reference one
+constexpr float kLazy = 8.f;    // SAFE sweep: log2 of how far the row maximum may run ahead of the reference before a rescale
+constexpr float kRisk = 64.f;   // FAST sweep: ... before the workgroup falls back to the SAFE sweep
+
+// max of a value and the one held by the lane 32 places away (the other half-wave): one lane-swap instruction
+// instead of a trip through the LDS permute unit.  The swap exchanges lanes 32..63 of its first operand with
+// lanes 0..31 of its second; with the same value in both, every lane ends up with the two halves' values.
+__device__ __forceinline__ float half_max(float x) {
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
@@ -43,7 +54,18 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // keys inside V^T's rows are stored in the order the accumulator registers hold them.  Both blocks of a wave
 // use each K and V^T fragment read from LDS, which is what keeps LDS bandwidth (about 64 bytes a clock per
 // CU, measured) from bounding the kernel: one fragment read feeds two matrix instructions.
-template <int HD>
+//
+// The kernel exists twice.  The FAST one fixes each row's reference maximum at the first tile (every row sees
+// key 0 there) and never rescales: probabilities are exp2 of the distance to that reference, possibly far
+// above 1, which fp32 sums and bf16 operands carry at unchanged relative precision, and no vector instruction
+// touches the output accumulators inside the loop, so they stay in the accumulation registers (with the
+// rescaling branch in the loop the compiler copied all of them to vector registers and back on every tile).
+// Should a logit rise more than 2^kRisk above its row's reference, the wave writes nothing and the workgroup
+// marks itself in `redo`; the SAFE
+// kernel, launched right after over the same grid, does the marked workgroups again with the textbook online
+// softmax, whose reference follows the running maximum (lazily, in steps of 2^kLazy) and rescales sums and
+// accumulators when it moves.  Unmarked workgroups of the SAFE launch exit at once.
+template <int HD, bool SAFE>
 __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a) {
     constexpr int ROWB = HD * 2;
     constexpr int KP = ROWB + 16;           // K tile pitch: odd multiple of 16 bytes
@@ -68,6 +90,9 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     const int rem = seq % per_blk;
     const int pair = (rem / a.G) * 8 + xcd;
     if (pair >= a.B * a.Hkv) return;
+    if constexpr (SAFE) {
+        if (a.redo[blockIdx.x] == 0) return;
+    }
     const int b = pair / a.Hkv, g = pair % a.Hkv, h = g * a.G + rem % a.G;
     const int q0 = qb * 128;
     const int wrow0 = q0 + 64 * wave;                 // this wave's first row
@@ -91,7 +116,9 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     const int vkg = tid & 7, vcu = tid >> 3;
     const bool v_on = vcu < UPR;
     const char *vbase = a.v + (long long)b * a.vsb + (long long)g * a.vsh + 16 * (v_on ? vcu : 0);
-    // named registers, not arrays: what a loop carries from its top to its bottom must not be indexed
+    // Named registers, not arrays (an indexed array that lives across the tile's arithmetic goes to scratch), and
+    // written on EVERY tile (the last one fetches itself again): a value that may survive from the previous
+    // tile is carried around the loop, and the compiler parks it in accumulation registers and copies it back.
     uint4 ks0 = make_uint4(0, 0, 0, 0), ks1 = ks0, ks2 = ks0, ks3 = ks0, vs0 = ks0, vs1 = ks0, vs2 = ks0, vs3 = ks0;
     const char *kthr = kbase + (long long)krow * a.ksn;           // this thread's row of tile 0
     const char *vthr = vbase + (long long)(4 * vkg) * a.vsn;
@@ -154,24 +181,34 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     };
 #undef LVLM_VT
 
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    __shared__ int bail_s[2];
+    float m_run[2], l_run[2];
     f32x16 oacc[2][NCB];
+    bool risky = false;                     // FAST: some logit ran too far ahead of its row's reference (uniform per wave)
 #pragma unroll
-    for (int x = 0; x < 2; ++x)
+    for (int x = 0; x < 2; ++x) {
+        m_run[x] = -INFINITY;
+        l_run[x] = 0.f;
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[x][cb][r] = 0.f;
-
+    }
     fetch(0);
     stash(0);
     __syncthreads();
     for (int t = 0; t < n_tiles; ++t) {
         const int j0 = t << 5, buf = t & 1;
-        if (t + 1 < n_tiles) fetch(j0 + 32);
-        // the wave's rows end at wrow0 + 63: later tiles are all masked for it (it still moves tiles).  Both
-        // blocks take every tile up to there: the one tile block 0 does not need is masked whole and adds zeros.
-        if (!a.causal || j0 <= wrow0 + 63) {
+        fetch(min(j0 + 32, (n_tiles - 1) << 5));
+        // the output accumulators stay where the matrix instructions keep them
+#pragma unroll
+        for (int x = 0; x < 2; ++x)
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) asm volatile("" : "+a"(oacc[x][cb]));
+        // Both blocks of both waves take every tile of the workgroup: the up to three last ones a block does not
+        // need are masked whole and add zeros.  The wave would wait at the barrier for the other one anyway, and
+        // a loop body without a skipping branch keeps the accumulators in place (no copies where paths join).
+        {
             f32x16 s0, s1;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s0[r] = 0.f, s1[r] = 0.f;
@@ -199,13 +236,16 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
                 float mx = s[0];
 #pragma unroll
                 for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                // The reference maximum m_run only follows the true one when that has run ahead by more than
-                // 2^kLazy: until then the probabilities are at most 2^kLazy instead of 1 (harmless in fp32 sums
-                // and bf16 operands: the final division takes it out) and the accumulators need no rescaling.
+                mx = half_max(mx);
                 // Key j0 is visible to every row of a block the tile really reaches, so the first tile sets a
                 // finite reference; a tile masked whole (-inf everywhere) changes nothing and adds zeros.
-                if (__builtin_amdgcn_ballot_w64((mx - m_run[x]) * a.scale_log2 > kLazy) != 0ull) {
+                if constexpr (!SAFE) {
+                    if (t == 0) {
+                        m_run[x] = mx;
+                    } else {
+                        risky |= __builtin_amdgcn_ballot_w64((mx - m_run[x]) * a.scale_log2 > kRisk) != 0ull;
+                    }
+                } else if (__builtin_amdgcn_ballot_w64((mx - m_run[x]) * a.scale_log2 > kLazy) != 0ull) {
                     const float m_new = fmaxf(m_run[x], mx);
                     const float alpha = __builtin_amdgcn_exp2f((m_run[x] - m_new) * a.scale_log2);   // first tile: 0
                     l_run[x] *= alpha;
@@ -252,6 +292,15 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
         }
         if (t + 1 < n_tiles) stash(buf ^ 1);
         __syncthreads();
+    }
+    // The FAST sweep runs to its end even when it has become useless (an exit from inside the loop makes the
+    // compiler copy the accumulators on every tile); a wave that saw the risk writes nothing, and the mark
+    // makes the SAFE kernel do the whole workgroup again.
+    if constexpr (!SAFE) {
+        if (lane == 0) bail_s[wave] = risky;
+        __syncthreads();
+        if (tid == 0) a.redo[blockIdx.x] = bail_s[0] | bail_s[1];
+        if (risky) return;
     }
 
     // normalise and write: lane (query l32, half hf) holds channels 32 cb + 8 (r / 4) + 4 hf + r % 4
@@ -354,7 +403,9 @@ __global__ __launch_bounds__(256) void prefill_attn_f32_kernel(PrefillArgs a) {
 PrefillWs prefill_ws(const lvlm_prefill_desc &d) {
     PrefillWs w{};
     w.lse_t = 0;
-    w.score = align_up((size_t)d.B * d.Hq * (d.T > 0 ? d.T : 0) * sizeof(float), 256);
+    w.redo = align_up((size_t)d.B * d.Hq * (d.T > 0 ? d.T : 0) * sizeof(float), 256);
+    const size_t grid = (size_t)((d.B * d.Hkv + 7) / 8) * 8 * (d.Hq / d.Hkv) * ((d.N + 127) / 128);
+    w.score = align_up(w.redo + grid * sizeof(int), 256);
     w.total = w.score;
     if (d.T > 0) w.total += align_up(score_ws(prefill_score_desc(d)).total, 256);
     return w;
@@ -380,6 +431,7 @@ hipError_t launch_prefill_attn(const Prof &prof, const lvlm_prefill_desc &d, con
     a.out = static_cast<char *>(out);
     a.row_lse = row_lse;
     a.lse_t = d.T > 0 ? reinterpret_cast<float *>(ws + w.lse_t) : nullptr;
+    a.redo = reinterpret_cast<int *>(ws + w.redo);
     a.B = d.B; a.N = d.N; a.Hq = d.Hq; a.Hkv = d.Hkv; a.G = d.Hq / d.Hkv; a.causal = d.causal; a.T = d.T;
     a.nqb = (d.N + 127) / 128;
     a.pair_groups = (d.B * d.Hkv + 7) / 8;
@@ -391,8 +443,13 @@ hipError_t launch_prefill_attn(const Prof &prof, const lvlm_prefill_desc &d, con
     prof.begin("prefill_attn");
     if (d.dtype == LVLM_BF16) {
         const long long grid = (long long)a.pair_groups * 8 * a.G * a.nqb;
-        if (d.hd == 128) hipLaunchKernelGGL((prefill_attn_bf16_kernel<128>), dim3((unsigned)grid), dim3(128), 0, stream, a);
-        else hipLaunchKernelGGL((prefill_attn_bf16_kernel<64>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+        if (d.hd == 128) {
+            hipLaunchKernelGGL((prefill_attn_bf16_kernel<128, false>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+            hipLaunchKernelGGL((prefill_attn_bf16_kernel<128, true>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+        } else {
+            hipLaunchKernelGGL((prefill_attn_bf16_kernel<64, false>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+            hipLaunchKernelGGL((prefill_attn_bf16_kernel<64, true>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+        }
     } else {
         const long long grid = ((long long)d.B * d.Hq * d.N + 3) / 4;
         if (d.hd == 128) hipLaunchKernelGGL((prefill_attn_f32_kernel<128>), dim3((unsigned)grid), dim3(256), 0, stream, a);
