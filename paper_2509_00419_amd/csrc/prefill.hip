@@ -20,7 +20,7 @@ struct PrefillArgs {
     int *redo;          // [grid]: workgroups the FAST kernel gave up, for the SAFE kernel
     int B, N, Hq, Hkv, G, causal, T;
     int nqb;            // query blocks per head
-    int pair_groups;    // ceil(B * Hkv / 8)
+    int heads_per_xcd;  // ceil(B * Hq / 8)
     float scale, scale_log2;
     long long qsb, qsn, qsh, ksb, ksn, ksh, vsb, vsn, vsh, osb, osn, osh;   // bytes
 };
@@ -81,19 +81,21 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform: conditions on it are scalar branches
     const int hf = lane >> 5, l32 = lane & 31;
-    // Workgroup id -> (batch, head, query block).  Ids with the same remainder modulo 8 run on one XCD: all
-    // heads of a (batch, KV head) pair go there, they read the same keys and values.  Within an XCD the
-    // longest blocks (latest rows) come first.
+    // Workgroup id -> (batch, head, query block).  Ids with the same remainder modulo 8 run on one XCD.  The
+    // B * Hq heads, in memory order (heads of one KV head next to each other), are dealt to the 8 XCDs in
+    // contiguous runs of equal length (+-1): heads that read the same keys and values mostly share an L2, and
+    // every XCD gets the same load whatever the head counts.  Within an XCD the longest blocks (latest rows)
+    // come first.
     const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
-    const int per_blk = a.pair_groups * a.G;
-    const int qb = a.nqb - 1 - seq / per_blk;
-    const int rem = seq % per_blk;
-    const int pair = (rem / a.G) * 8 + xcd;
-    if (pair >= a.B * a.Hkv) return;
+    const int NH = a.B * a.Hq;
+    const int qb = a.nqb - 1 - seq / a.heads_per_xcd;
+    const int head_first = (xcd * NH + 7) >> 3, head_end = ((xcd + 1) * NH + 7) >> 3;
+    const int bh = head_first + seq % a.heads_per_xcd;
+    if (bh >= head_end) return;
     if constexpr (SAFE) {
         if (a.redo[blockIdx.x] == 0) return;
     }
-    const int b = pair / a.Hkv, g = pair % a.Hkv, h = g * a.G + rem % a.G;
+    const int b = bh / a.Hq, h = bh % a.Hq, g = h / a.G;
     const int q0 = qb * 128;
     const int wrow0 = q0 + 64 * wave;                 // this wave's first row
     const int kmax = a.causal ? min(a.N, q0 + 128) : a.N;
@@ -404,7 +406,7 @@ PrefillWs prefill_ws(const lvlm_prefill_desc &d) {
     PrefillWs w{};
     w.lse_t = 0;
     w.redo = align_up((size_t)d.B * d.Hq * (d.T > 0 ? d.T : 0) * sizeof(float), 256);
-    const size_t grid = (size_t)((d.B * d.Hkv + 7) / 8) * 8 * (d.Hq / d.Hkv) * ((d.N + 127) / 128);
+    const size_t grid = (size_t)((d.B * d.Hq + 7) / 8) * 8 * ((d.N + 127) / 128);
     w.score = align_up(w.redo + grid * sizeof(int), 256);
     w.total = w.score;
     if (d.T > 0) w.total += align_up(score_ws(prefill_score_desc(d)).total, 256);
@@ -434,7 +436,7 @@ hipError_t launch_prefill_attn(const Prof &prof, const lvlm_prefill_desc &d, con
     a.redo = reinterpret_cast<int *>(ws + w.redo);
     a.B = d.B; a.N = d.N; a.Hq = d.Hq; a.Hkv = d.Hkv; a.G = d.Hq / d.Hkv; a.causal = d.causal; a.T = d.T;
     a.nqb = (d.N + 127) / 128;
-    a.pair_groups = (d.B * d.Hkv + 7) / 8;
+    a.heads_per_xcd = (d.B * d.Hq + 7) / 8;
     a.scale = d.scale; a.scale_log2 = d.scale * kLog2e;
     a.qsb = d.q_stride_b * es; a.qsn = d.q_stride_n * es; a.qsh = d.q_stride_h * es;
     a.ksb = d.k_stride_b * es; a.ksn = d.k_stride_n * es; a.ksh = d.k_stride_h * es;
@@ -442,7 +444,7 @@ hipError_t launch_prefill_attn(const Prof &prof, const lvlm_prefill_desc &d, con
     a.osb = d.o_stride_b * es; a.osn = d.o_stride_n * es; a.osh = d.o_stride_h * es;
     prof.begin("prefill_attn");
     if (d.dtype == LVLM_BF16) {
-        const long long grid = (long long)a.pair_groups * 8 * a.G * a.nqb;
+        const long long grid = (long long)a.heads_per_xcd * 8 * a.nqb;
         if (d.hd == 128) {
             hipLaunchKernelGGL((prefill_attn_bf16_kernel<128, false>), dim3((unsigned)grid), dim3(128), 0, stream, a);
             hipLaunchKernelGGL((prefill_attn_bf16_kernel<128, true>), dim3((unsigned)grid), dim3(128), 0, stream, a);
