@@ -69,6 +69,10 @@ def parse():
     ap.add_argument("--merge", default="rank", choices=["rank", "similar"],
                     help="merge rule at the pyramid layers: the paper's rank weights (lvlm_merge_compact) or the "
                          "similarity merge (lvlm_merge_similar)")
+    ap.add_argument("--op", default="step", choices=["step", "prefill_attn"],
+                    help="step: the token-reduction path (the default, the headline metric); prefill_attn: "
+                         "lvlm_prefill_attn alone over the layer stack -- the layers' own attention at the token "
+                         "counts the pyramid leaves, with the scores as its by-product where the path scores")
     ap.add_argument("--profile-steps", type=int, default=3, help="eager steps timed per kernel with HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
@@ -398,6 +402,8 @@ def main():
     w = configs.ALL[args.workload]
     layers = plan(w, lv)
     ctx = lv.Context(0)
+    if args.op == "prefill_attn":
+        return main_prefill_attn(args, w, layers, ctx, lv, torch, dev)
     t_setup = time.time()
     master = build_master(w, layers, torch, synth, dev, args.row_lse == "given")
     n_sets = 1 + args.warmup + args.steps + args.profile_steps
@@ -546,6 +552,104 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
     }
     print(json.dumps(out))
+
+
+# ----------------------------------------------------------------------------- the layers' own attention
+def main_prefill_attn(args, w, layers, ctx, lv, torch, dev):
+    """--op prefill_attn: one step = lvlm_prefill_attn for every layer of the stack, layer l on the
+    n_sys + n_img(l) + n_text tokens the pyramid has left at its input, with the scores of the instruction rows
+    as by-product at the layers the path scores.  The same stack without merging (every layer at the full
+    sequence) is timed beside it: the ratio is the attention share of the paper's prefill saving.
+    q, k, v are views of one fused projection output [B, N, Hq + 2 Hkv, d] (four buffers taken in turn)."""
+    Hq, Hkv, d, B, T = w.n_q_heads, w.n_kv_heads, w.head_dim, w.batch, w.n_text
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    Nmax = w.seq_len
+    g = torch.Generator(device=dev).manual_seed(w.seed)
+    fused = [torch.randn(B, Nmax, Hq + 2 * Hkv, d, generator=g, device=dev).to(dt) for _ in range(4)]
+    out = torch.empty(B, Nmax, Hq, d, dtype=dt, device=dev)
+    lse = torch.empty(B * Hq * Nmax, dtype=torch.float32, device=dev)
+    sizes = sorted({en["n_img"] for en in layers} | {w.n_img})
+    sh = {n: torch.empty(B, Hkv, n, dtype=torch.float32, device=dev) for n in sizes}
+    sm = {n: torch.empty(B, n, dtype=torch.float32, device=dev) for n in sizes}
+
+    def run(merged, reserve=False):
+        for li, en in enumerate(layers):
+            n_img = en["n_img"] if merged else w.n_img
+            N = w.n_sys + n_img + T
+            f = fused[li % 4][:, :N]
+            scored = en["score"] and n_img > 0
+            ctx.prefill_attn(f[:, :, :Hq], f[:, :, Hq:Hq + Hkv], f[:, :, Hq + Hkv:], n_text=T if scored else 0,
+                             img_begin=w.n_sys, n_img=n_img, out=out[:, :N], row_lse=lse[:B * Hq * N].view(B, Hq, N),
+                             score_head=sh[n_img] if scored else None, score_mean=sm[n_img] if scored else None,
+                             reserve=reserve)
+
+    def timed(merged, steps, warmup):
+        for _ in range(warmup):
+            run(merged)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run(merged)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    run(False, reserve=True)
+    run(True, reserve=True)
+    torch.cuda.synchronize()
+    ms_per_step = timed(True, args.steps, args.warmup)
+    ms_unmerged = timed(False, max(1, args.steps // 4), 1)
+
+    # per-kernel durations: HIP events on the launch stream around every launch
+    prof = {}
+    if args.profile_steps > 0:
+        ctx.profile(True)
+        for _ in range(args.profile_steps):
+            run(True)
+        torch.cuda.synchronize()
+        prof = {k: {"launches_per_step": v[0] / args.profile_steps, "us_per_step": v[1] * 1e3 / args.profile_steps,
+                    "avg_us": v[1] * 1e3 / max(v[0], 1)} for k, v in ctx.profile_read().items()}
+        ctx.profile(False)
+    counts = [w.n_sys + en["n_img"] + T for en in layers]
+    flops = sum(4.0 * B * Hq * d * n * (n + 1) / 2 for n in counts)        # causal: row i multiplies i + 1 keys, twice
+    kernels = {k: {"avg_us": round(v["avg_us"], 2), "launches_per_step": v["launches_per_step"],
+                   "us_per_step": round(v["us_per_step"], 1)} for k, v in sorted(prof.items(), key=lambda kv: -kv[1]["us_per_step"])}
+    roofline = None
+    if "prefill_attn" in prof:
+        p = prof["prefill_attn"]
+        tf = flops / p["us_per_step"] / 1e6
+        peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 157.3
+        kernels["prefill_attn"].update(bound="mfma" if w.dtype == "bf16" else "alu", achieved_TFLOPs=round(tf, 1),
+                                       frac=round(tf / peak, 4))
+        roofline = {"kernel": "prefill_attn", "bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": round(tf, 1),
+                    "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4), "traffic": None,
+                    "algorithmic_flops_per_launch": flops / len(layers), "avg_launch_us": round(p["avg_us"], 2)}
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import lvlm_oracle as O
+        # the oracle on one sequence of one layer of the stack (the longest of at most 6000 tokens) and as many KV
+        # groups as keep the sample near ten seconds, scaled by causal flops to the whole stack
+        fit = [n for n in counts if n <= 6000]
+        N = max(fit) if fit else min(counts)
+        li = counts.index(N)
+        G = Hq // Hkv
+        ng = max(1, min(Hkv, int(2e8 / (float(N) * N * G))))
+        f = fused[li % 4][:1, :N].double().cpu().numpy()
+        t0 = time.perf_counter()
+        O.prefill_attn(f[:, :, :ng * G], f[:, :, Hq:Hq + ng], f[:, :, Hq + Hkv:Hq + Hkv + ng], dtype=w.dtype)
+        t = time.perf_counter() - t0
+        sample_flops = 4.0 * ng * G * d * N * (N + 1) / 2
+        cpu = {"value": round(B * w.n_img / (t * flops / sample_flops), 2), "unit": "image tokens/s", "cores": os.cpu_count(),
+               "kind": "oracle", "sample": f"oracle.prefill_attn on one sequence of layer {li} ({N} tokens), {ng} KV "
+               f"group(s) = {ng * G} query heads: {t:.2f} s, scaled by causal flops to the whole stack"}
+    print(json.dumps({
+        "metric": "prefill attention with scores as by-product, over the layer stack",
+        "value": round(B * w.n_img / (ms_per_step * 1e-3), 1), "unit": "image tokens/s (attention of all layers)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "op": "prefill_attn", "batch": B, "layers": w.layers, "seq": [w.n_sys, w.n_img, T],
+                   "tokens_per_layer": counts},
+        "ms_per_step_without_merging": round(ms_unmerged, 4), "attention_speedup_from_merging": round(ms_unmerged / ms_per_step, 3),
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels}))
 
 
 # ----------------------------------------------------------------------------- oracle leg
