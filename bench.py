@@ -55,7 +55,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
     ap.add_argument("--row-lse", default="computed", choices=["computed", "given"],
                     help="row normalisers of the scoring step: computed by the library (default: one more pass over "
                          "the keys) or given, as a prefill attention kernel that emits its log-sum-exp would (Sec. "

@@ -67,10 +67,12 @@ def layer_slices(st, i, B):
 
 
 @pytest.mark.parametrize("name,every_layer,given_lse", [("cfg2", True, False), ("cfg3", False, False),
-                                                        ("cfg5", False, False), ("cfg2", True, True)])
+                                                        ("cfg5", False, False), ("cfg2", True, True),
+                                                        ("cfg6", False, False)])
 def test_prefill_and_decode_step_in_bench_configuration(name, every_layer, given_lse):
-    """Config 2: every layer of the step.  Configs 3 and 5 (B = 8; 16512 tokens): the first and last layer of
-    every scoring run plus one uncompressed layer -- the oracle needs seconds per layer there.  given_lse: the
+    """Config 2: every layer of the step.  Configs 3, 5 and 6 (B = 8; 16512 tokens; the 38B shape with a
+    video-like input, G = 5): the first and last layer of every scoring run plus one uncompressed layer -- the
+    oracle needs seconds per layer there.  given_lse: the
     bench's --row-lse given mode (row normalisers from plain torch, as an attention kernel would leave them)."""
     w = configs.ALL[name]
     ctx = lv.Context(0)

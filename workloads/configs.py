@@ -1,4 +1,4 @@
-"""The five benchmark configurations, as shapes only.
+"""The five benchmark configurations (and one more shape beyond them), as shapes only.
 
 These describe the layer shapes, token counts and schedules of the workloads
 the build measures; they hold no arithmetic of the method.  Image-token keep
@@ -77,4 +77,13 @@ CFG5 = Workload(
     merge_layers=(12, 24, 36), final_keep=(0.03,), kv_first_layer=12, kv_budget=2048, decode_steps=2048,
     notes="16384 image tokens down to 3 %, then 2048 decode steps with a 2048-entry budget")
 
-ALL = {w.name.split("_")[0]: w for w in (CFG1, CFG2, CFG3, CFG4, CFG5)}
+# Beyond the five benchmark configurations: a video-shaped input (64 frames of 256 tokens, clusters per frame) on
+# the 38B model's language-model shape (64 layers, 40 query / 8 KV heads: a group of 5, padded to 8 by the kernels).
+CFG6 = Workload(
+    name="cfg6_internvl25_38b_video_bf16", dtype="bf16", batch=1, layers=64, hidden=5120, n_q_heads=40,
+    n_kv_heads=8, head_dim=128, n_sys=0, n_img=16384, n_text=128, n_clusters=16, cluster_tile=256,
+    merge_layers=(16, 32, 48), final_keep=(0.03,), kv_first_layer=16, kv_budget=2048, decode_steps=2048, seed=6,
+    notes="64 frames x 256 image tokens (16 clusters per frame) down to 3 %, quarter-depth merge layers, then decode "
+          "with a 2048-entry budget")
+
+ALL = {w.name.split("_")[0]: w for w in (CFG1, CFG2, CFG3, CFG4, CFG5, CFG6)}
