@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 
     const int L = min(a.len[hg] + (a.append ? 1 : 0), a.Lmax);
     const int new_slot = a.append ? L - 1 : -1;
-    const int s_hi = min(L, s_lo + a.split_len);
+    const int s_hi = split == a.n_split - 1 ? L : min(L, s_lo + a.split_len);   // the last split takes the remainder
     if (split == 0) {
         if (a.append) {
             if (tid < UPR)
@@ -371,7 +371,8 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
 
     const int L = min(a.len[hg] + (a.append ? 1 : 0), a.Lmax);
     const int new_slot = a.append ? L - 1 : -1;
-    const int s_hi = min(L, s_lo + a.split_len);
+    // the last split takes the remainder (only the form whose waves fetch a second tile can)
+    const int s_hi = (MULTI && split == a.n_split - 1) ? L : min(L, s_lo + a.split_len);
     if (split == 0) {
         // the appended entry goes into the cache here; every reader below takes it from k_new / v_new
         if (a.append) {
@@ -735,7 +736,7 @@ void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
     prof.begin("attn_partial");
     if constexpr (DT == LVLM_BF16)
     {
-        if (a.split_len > 128)
+        if (a.split_len > 128 || a.n_split * a.split_len < len_bound)      // some wave has a second tile
             hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, true>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
         else
             hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, false>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
@@ -783,6 +784,13 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     int split_len = ((bound + n_split - 1) / n_split + 31) / 32 * 32;
     if (split_len < 128) split_len = 128;
     n_split = (bound + split_len - 1) / split_len;
+    // A remainder of at most one tile beyond whole 128-entry splits (steady-state decode: budget + 1 entries)
+    // goes to the last split as one extra tile of one wave, instead of lengthening every split by a tile.
+    const int full = bound / 128;
+    if (full >= 1 && want >= full && bound - 128 * full <= 32 && full <= 64) {
+        n_split = full;
+        split_len = 128;
+    }
     if (n_split < 1) n_split = 1;
     w.n_split = n_split;
     w.split_len = split_len;
