@@ -187,6 +187,7 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     float m_run[2], l_run[2];
     f32x16 oacc[2][NCB];
     bool risky = false;                     // FAST: some logit ran too far ahead of its row's reference (uniform per wave)
+    (void)risky;
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
         m_run[x] = -INFINITY;
@@ -235,19 +236,19 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
                         if ((a.causal && j > row) || j >= a.N) s[r] = -INFINITY;
                     }
                 }
-                float mx = s[0];
-#pragma unroll
-                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-                mx = half_max(mx);
                 // Key j0 is visible to every row of a block the tile really reaches, so the first tile sets a
                 // finite reference; a tile masked whole (-inf everywhere) changes nothing and adds zeros.
+                auto row_max = [&]() {
+                    float mx = s[0];
+#pragma unroll
+                    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+                    return half_max(mx);
+                };
                 if constexpr (!SAFE) {
-                    if (t == 0) {
-                        m_run[x] = mx;
-                    } else {
-                        risky |= __builtin_amdgcn_ballot_w64((mx - m_run[x]) * a.scale_log2 > kRisk) != 0ull;
-                    }
-                } else if (__builtin_amdgcn_ballot_w64((mx - m_run[x]) * a.scale_log2 > kLazy) != 0ull) {
+                    // the reference is the first tile's maximum; later tiles need no maximum at all: a logit
+                    // far above the reference shows in the row sum (checked once, after the sweep)
+                    if (t == 0) m_run[x] = row_max();
+                } else if (const float mx = row_max(); __builtin_amdgcn_ballot_w64((mx - m_run[x]) * a.scale_log2 > kLazy) != 0ull) {
                     const float m_new = fmaxf(m_run[x], mx);
                     const float alpha = __builtin_amdgcn_exp2f((m_run[x] - m_new) * a.scale_log2);   // first tile: 0
                     l_run[x] *= alpha;
@@ -299,6 +300,9 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     // compiler copy the accumulators on every tile); a wave that saw the risk writes nothing, and the mark
     // makes the SAFE kernel do the whole workgroup again.
     if constexpr (!SAFE) {
+        // sums stay below 2^kRisk times the row length unless some probability went beyond 2^kRisk (or to inf / NaN)
+        const float limit = __builtin_amdgcn_exp2f(kRisk) * 65536.f;
+        risky = __builtin_amdgcn_ballot_w64(!(l_run[0] < limit) || !(l_run[1] < limit)) != 0ull;
         if (lane == 0) bail_s[wave] = risky;
         __syncthreads();
         if (tid == 0) a.redo[blockIdx.x] = bail_s[0] | bail_s[1];

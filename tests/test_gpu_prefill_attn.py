@@ -114,6 +114,34 @@ def test_prefill_attn_config5_shape_sampled_group(ctx):
     assert torch.isfinite(lse).all()
 
 
+def test_prefill_attn_logits_far_above_the_first_tile(ctx):
+    """Rows whose later logits exceed everything in the first 32 keys by far more than fp32 can hold as a
+    probability ratio (natural-log distance 120): the kernel that fixes its reference at the first tile must
+    give these workgroups to the one that follows the running maximum.  Also the reverse (a dominant first key)
+    and ordinary rows in the same launch."""
+    B, N, Hq, Hkv, d = 1, 420, 4, 2, 64
+    g = torch.Generator().manual_seed(3)
+    q = 0.05 * torch.randn(B, N, Hq, d, generator=g)
+    k = 0.05 * torch.randn(B, N, Hkv, d, generator=g)
+    v = torch.randn(B, N, Hkv, d, generator=g)
+    q[:, :, 0:2, 0] = 22.0                       # heads 0, 1 (KV head 0): logit = 22 * k0 / 8
+    k[:, :32, 0, 0] = -22.0                      # first tile: -60.5
+    k[:, 32:, 0, 0] = 22.0                       # later keys: +60.5
+    k[:, 200, 0, 0] = 30.0                       # and one at +82.5
+    q[:, :, 2, 0] = 22.0                         # head 2 (KV head 1): a dominant first key, the rest far below
+    k[:, 0, 1, 0] = 22.0
+    k[:, 1:, 1, 0] = -22.0
+    q, k, v = q.bfloat16(), k.bfloat16(), v.bfloat16()
+    out, lse, sh, sm = ctx.prefill_attn(q.to(DEV), k.to(DEV), v.to(DEV), n_text=20, img_begin=8, n_img=380)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    o_out, o_lse = O.prefill_attn(f64(q), f64(k), f64(v), dtype="bf16")
+    assert rel_err(out.float().cpu(), o_out) < 2e-2
+    assert np.abs(lse.cpu().numpy() - o_lse).max() < 1e-5 * np.abs(o_lse).max()
+    osh, osm = O.score_tokens(f64(q[:, N - 20:]), f64(k), q_pos0=N - 20, img_begin=8, n_img=380)
+    assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
+
+
 def test_prefill_attn_rejects_bad_arguments(ctx):
     fused, split = _qkv(1, 64, 4, 2, 64, torch.bfloat16, 1)
     qd, kd, vd = split(fused.to(DEV))
