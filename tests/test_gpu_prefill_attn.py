@@ -51,6 +51,10 @@ CASES = [
     (torch.bfloat16, 1, 257, 4, 2, 64, True, 40, 10, 200, 3.0),           # d = 64 causal, peaky rows, one row past a block
     (torch.bfloat16, 3, 500, 8, 4, 128, True, 64, 20, 400, 1.0),          # 12 (batch, KV head) pairs: 8 + 4 over the XCDs
     (torch.bfloat16, 1, 31, 2, 2, 128, True, 31, 0, 20, 1.0),             # shorter than one tile, every row an instruction row
+    (torch.bfloat16, 1, 1, 2, 1, 128, True, 1, 0, 1, 1.0),                # one token
+    (torch.float32, 1, 1, 2, 2, 64, True, 1, 0, 1, 1.0),                  # one token, fp32
+    (torch.bfloat16, 2, 150, 4, 2, 128, False, 10, 5, 100, 1.0),          # scores without a causal mask
+    (torch.bfloat16, 1, 128, 2, 1, 128, True, 3, 0, 125, 1.0),            # exactly one full query block
     (torch.bfloat16, 1, 2176, 28, 4, 128, True, 64, 64, 2048, 1.0),       # config 2 layer
 ]
 
