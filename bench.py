@@ -31,7 +31,8 @@ own copy of the state (caches are modified in place), so no step re-reads
 buffers a previous step left in cache.  Each step is a pair of HIP graphs
 (prefill, decode) captured beforehand; the timed region replays them.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (image tokens/s over the whole step), ms_per_step, the roofline of the dominant
+kernel (algorithmic bytes or flops over its measured launch time), the CPU oracle timed beside it, and per-kernel rows.
 """
 from __future__ import annotations
 
