@@ -8,6 +8,7 @@
 #include "mma.h"
 
 #include <climits>
+#include <type_traits>
 
 namespace lvlm {
 namespace {
@@ -200,7 +201,15 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     fetch(0);
     stash(0);
     __syncthreads();
-    for (int t = 0; t < n_tiles; ++t) {
+    // One tile.  EDGE = false: every row of the workgroup sees the whole tile -- no masks, both blocks.  EDGE = true
+    // (the up to four tiles around the diagonal, and a ragged last tile): per block the tile is seen whole, cut by
+    // the diagonal (one fixed lane pattern, blocks and tiles being aligned alike), cut by the end of the sequence,
+    // or not seen at all; a block that does not see it skips the logits and the softmax and multiplies zeros
+    // into its accumulators (no branch around the instructions that update them: such a branch makes the
+    // compiler copy all accumulators where its paths join).
+    const int diag_lim = l32 - 4 * hf;       // register r of this lane holds a key past the diagonal iff 8 (r / 4) + r % 4 > diag_lim
+    auto step = [&](int t, auto edge_tag) {
+        constexpr bool EDGE = decltype(edge_tag)::value;
         const int j0 = t << 5, buf = t & 1;
         fetch(min(j0 + 32, (n_tiles - 1) << 5));
         // the output accumulators stay where the matrix instructions keep them
@@ -208,94 +217,114 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
         for (int x = 0; x < 2; ++x)
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) asm volatile("" : "+a"(oacc[x][cb]));
-        // Both blocks of both waves take every tile of the workgroup: the up to three last ones a block does not
-        // need are masked whole and add zeros.  The wave would wait at the barrier for the other one anyway, and
-        // a loop body without a skipping branch keeps the accumulators in place (no copies where paths join).
-        {
+        uint4 pf[2][2];
+        auto softmax = [&](int x, f32x16 &s) {
+            // Key j0 is visible to every row of a block the tile reaches, so the first tile sets a finite reference.
+            auto row_max = [&]() {
+                float mx = s[0];
+#pragma unroll
+                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+                return half_max(mx);
+            };
+            if constexpr (!SAFE) {
+                // the reference is the first tile's maximum; later tiles need no maximum at all: a logit
+                // far above the reference shows in the row sum (checked once, after the sweep)
+                if (t == 0) m_run[x] = row_max();
+            } else if (const float mx = row_max(); __builtin_amdgcn_ballot_w64((mx - m_run[x]) * a.scale_log2 > kLazy) != 0ull) {
+                const float m_new = fmaxf(m_run[x], mx);
+                const float alpha = __builtin_amdgcn_exp2f((m_run[x] - m_new) * a.scale_log2);   // first tile: 0
+                l_run[x] *= alpha;
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[x][cb][r] *= alpha;
+                m_run[x] = m_new;
+            }
+            const float mb = m_run[x] * a.scale_log2;
+            float sum = 0.f;
+            float p[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2, -mb));
+                sum += p[r];
+            }
+            l_run[x] += sum;
+#pragma unroll
+            for (int t2 = 0; t2 < 2; ++t2) {
+                pf[x][t2].x = pack_bf16(p[8 * t2 + 0], p[8 * t2 + 1]);
+                pf[x][t2].y = pack_bf16(p[8 * t2 + 2], p[8 * t2 + 3]);
+                pf[x][t2].z = pack_bf16(p[8 * t2 + 4], p[8 * t2 + 5]);
+                pf[x][t2].w = pack_bf16(p[8 * t2 + 6], p[8 * t2 + 7]);
+            }
+        };
+        const char *ksrc = &k_lds[buf][l32 * KP + 16 * hf];
+        if constexpr (!EDGE) {
             f32x16 s0, s1;
 #pragma unroll
             for (int r = 0; r < 16; ++r) s0[r] = 0.f, s1[r] = 0.f;
-            {
-                const char *src = &k_lds[buf][l32 * KP + 16 * hf];
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const uint4 kf = *reinterpret_cast<const uint4 *>(ksrc + 32 * i);
+                const bf16x8 kb = __builtin_bit_cast(bf16x8, kf);
+                s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb, __builtin_bit_cast(bf16x8, qf[0][i]), s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb, __builtin_bit_cast(bf16x8, qf[1][i]), s1, 0, 0, 0);
+            }
+            softmax(0, s0);
+            softmax(1, s1);
+        } else {
+#pragma unroll
+            for (int x = 0; x < 2; ++x) {
+                const int blk0 = wrow0 + 32 * x;             // first row of the block
+                if (a.causal && j0 > blk0) {                 // not seen at all
+                    pf[x][0] = pf[x][1] = make_uint4(0, 0, 0, 0);
+                    continue;
+                }
+                f32x16 s;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
                 for (int i = 0; i < NV; ++i) {
-                    const uint4 kf = *reinterpret_cast<const uint4 *>(src + 32 * i);
-                    const bf16x8 kb = __builtin_bit_cast(bf16x8, kf);
-                    s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb, __builtin_bit_cast(bf16x8, qf[0][i]), s0, 0, 0, 0);
-                    s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb, __builtin_bit_cast(bf16x8, qf[1][i]), s1, 0, 0, 0);
+                    const uint4 kf = *reinterpret_cast<const uint4 *>(ksrc + 32 * i);
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf),
+                                                                __builtin_bit_cast(bf16x8, qf[x][i]), s, 0, 0, 0);
                 }
-            }
-            uint4 pf[2][2];
-            auto softmax = [&](int x, f32x16 &s) {
-                const int row = wrow0 + 32 * x + l32;
-                // a mask is needed where the tile reaches past the block's first row or past the last key
-                if ((a.causal && j0 + 31 > wrow0 + 32 * x) || j0 + 32 > a.N) {
+                if (j0 + 32 > a.N) {                         // the ragged last tile: by key index
+                    const int row = blk0 + l32;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int j = j0 + acc_row(r, hf);
                         if ((a.causal && j > row) || j >= a.N) s[r] = -INFINITY;
                     }
+                } else if (a.causal && j0 == blk0) {         // the diagonal tile: a fixed pattern
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        if (8 * (r >> 2) + (r & 3) > diag_lim) s[r] = -INFINITY;
                 }
-                // Key j0 is visible to every row of a block the tile really reaches, so the first tile sets a
-                // finite reference; a tile masked whole (-inf everywhere) changes nothing and adds zeros.
-                auto row_max = [&]() {
-                    float mx = s[0];
+                softmax(x, s);
+            }
+        }
+        {
+            const char *src = &v_lds[buf][l32 * VP + 16 * hf];
 #pragma unroll
-                    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-                    return half_max(mx);
-                };
-                if constexpr (!SAFE) {
-                    // the reference is the first tile's maximum; later tiles need no maximum at all: a logit
-                    // far above the reference shows in the row sum (checked once, after the sweep)
-                    if (t == 0) m_run[x] = row_max();
-                } else if (const float mx = row_max(); __builtin_amdgcn_ballot_w64((mx - m_run[x]) * a.scale_log2 > kLazy) != 0ull) {
-                    const float m_new = fmaxf(m_run[x], mx);
-                    const float alpha = __builtin_amdgcn_exp2f((m_run[x] - m_new) * a.scale_log2);   // first tile: 0
-                    l_run[x] *= alpha;
-#pragma unroll
-                    for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[x][cb][r] *= alpha;
-                    m_run[x] = m_new;
-                }
-                const float mb = m_run[x] * a.scale_log2;
-                float sum = 0.f;
-                float p[16];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2, -mb));
-                    sum += p[r];
-                }
-                l_run[x] += sum;
+            for (int cb = 0; cb < NCB; ++cb) {
 #pragma unroll
                 for (int t2 = 0; t2 < 2; ++t2) {
-                    pf[x][t2].x = pack_bf16(p[8 * t2 + 0], p[8 * t2 + 1]);
-                    pf[x][t2].y = pack_bf16(p[8 * t2 + 2], p[8 * t2 + 3]);
-                    pf[x][t2].z = pack_bf16(p[8 * t2 + 4], p[8 * t2 + 5]);
-                    pf[x][t2].w = pack_bf16(p[8 * t2 + 6], p[8 * t2 + 7]);
-                }
-            };
-            softmax(0, s0);
-            softmax(1, s1);
-            {
-                const char *src = &v_lds[buf][l32 * VP + 16 * hf];
-#pragma unroll
-                for (int cb = 0; cb < NCB; ++cb) {
-#pragma unroll
-                    for (int t2 = 0; t2 < 2; ++t2) {
-                        const uint4 vf = *reinterpret_cast<const uint4 *>(src + (32 * cb) * VP + 32 * t2);
-                        const bf16x8 vb = __builtin_bit_cast(bf16x8, vf);
-                        oacc[0][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, __builtin_bit_cast(bf16x8, pf[0][t2]),
-                                                                             oacc[0][cb], 0, 0, 0);
-                        oacc[1][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, __builtin_bit_cast(bf16x8, pf[1][t2]),
-                                                                             oacc[1][cb], 0, 0, 0);
-                    }
+                    const uint4 vf = *reinterpret_cast<const uint4 *>(src + (32 * cb) * VP + 32 * t2);
+                    const bf16x8 vb = __builtin_bit_cast(bf16x8, vf);
+                    oacc[0][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, __builtin_bit_cast(bf16x8, pf[0][t2]),
+                                                                         oacc[0][cb], 0, 0, 0);
+                    oacc[1][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb, __builtin_bit_cast(bf16x8, pf[1][t2]),
+                                                                         oacc[1][cb], 0, 0, 0);
                 }
             }
         }
         if (t + 1 < n_tiles) stash(buf ^ 1);
         __syncthreads();
-    }
+    };
+    // tiles [0, t_whole) are seen whole by every row of the workgroup
+    const int t_whole = a.causal ? min(q0, a.N) >> 5 : a.N >> 5;
+    for (int t = 0; t < t_whole; ++t) step(t, std::false_type{});
+    for (int t = t_whole; t < n_tiles; ++t) step(t, std::true_type{});
     // The FAST sweep runs to its end even when it has become useless (an exit from inside the loop makes the
     // compiler copy the accumulators on every tile); a wave that saw the risk writes nothing, and the mark
     // makes the SAFE kernel do the whole workgroup again.
