@@ -547,18 +547,36 @@ __device__ __forceinline__ void fold_normalisers(const AttnArgs &a, CombineLds<G
         c.pl[i / GP][i % GP] = ml.y;
     }
     __syncthreads();
-    if (tid < GP) {
-        float mx = -INFINITY;
-        for (int s = 0; s < a.n_split; ++s) mx = fmaxf(mx, c.pm[s][tid]);
-        const float ms = (mx == -INFINITY) ? 0.f : mx;
-        float l = 0.f;
-        for (int s = 0; s < a.n_split; ++s) {
-            const float wgt = exp2f(c.pm[s][tid] - ms);
-            l += c.pl[s][tid] * wgt;
-            c.pl[s][tid] = wgt;                      // reused below as the split's weight
+    // Few splits: one thread per head walks them.  Many (up to 64): one wave per head, one lane per split, two wave
+    // reductions instead of two serial loops (measured: config 5's 16 splits gain 0.9 us per launch, 8 splits lose).
+    static_assert(NT >= 64 * GP, "one wave per head");
+    const int wave = tid >> 6, lane = tid & 63;
+    if (a.n_split <= 8) {
+        if (tid < GP) {
+            float mx = -INFINITY;
+            for (int s = 0; s < a.n_split; ++s) mx = fmaxf(mx, c.pm[s][tid]);
+            const float ms = (mx == -INFINITY) ? 0.f : mx;
+            float l = 0.f;
+            for (int s = 0; s < a.n_split; ++s) {
+                const float wgt = exp2f(c.pm[s][tid] - ms);
+                l += c.pl[s][tid] * wgt;
+                c.pl[s][tid] = wgt;                      // reused below as the split's weight
+            }
+            c.m[tid] = ms;
+            c.inv[tid] = l > 0.f ? 1.0f / l : 0.f;
         }
-        c.m[tid] = ms;
-        c.inv[tid] = l > 0.f ? 1.0f / l : 0.f;
+    } else if (wave < GP) {
+        const bool on = lane < a.n_split;
+        const float m_s = on ? c.pm[lane][wave] : -INFINITY;
+        const float mx = wave_max(m_s);
+        const float ms = (mx == -INFINITY) ? 0.f : mx;
+        const float wgt = on ? exp2f(m_s - ms) : 0.f;
+        const float l = wave_sum(on ? c.pl[lane][wave] * wgt : 0.f);
+        if (on) c.pl[lane][wave] = wgt;              // reused below as the split's weight
+        if (lane == 0) {
+            c.m[wave] = ms;
+            c.inv[wave] = l > 0.f ? 1.0f / l : 0.f;
+        }
     }
     __syncthreads();
 }
@@ -571,14 +589,19 @@ __device__ __forceinline__ void write_output(const AttnArgs &a, const CombineLds
     for (int idx = tid; idx < a.G * HD; idx += NT) {
         const int h = idx / HD, e = idx % HD;
         float acc = 0.f;
-        for (int s0 = 0; s0 < a.n_split; s0 += 8) {
-            float v[8];
+        auto rounds = [&](auto width) {                    // W loads in flight per round
+            constexpr int W = decltype(width)::value;
+            for (int s0 = 0; s0 < a.n_split; s0 += W) {
+                float v[W];
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                v[u] = s0 + u < a.n_split ? po[((long long)(s0 + u) * GP + h) * HD + e] : 0.f;
+                for (int u = 0; u < W; ++u)
+                    v[u] = s0 + u < a.n_split ? po[((long long)(s0 + u) * GP + h) * HD + e] : 0.f;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) acc += s0 + u < a.n_split ? v[u] * c.pl[s0 + u][h] : 0.f;
-        }
+                for (int u = 0; u < W; ++u) acc += s0 + u < a.n_split ? v[u] * c.pl[s0 + u][h] : 0.f;
+            }
+        };
+        if (a.n_split <= 8) rounds(std::integral_constant<int, 8>{});
+        else rounds(std::integral_constant<int, 16>{});     // one round for up to 16 splits
         acc *= c.inv[h];
         const long long oi = ((long long)b * a.Hq + g * a.G + h) * HD + e;
         if constexpr (DT == LVLM_BF16)
