@@ -146,6 +146,30 @@ def test_prefill_attn_logits_far_above_the_first_tile(ctx):
     assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
 
 
+def test_prefill_attn_far_logits_in_the_middle_of_a_long_row(ctx):
+    """One sequence of nine query blocks with few heads; logits that jump far above everything before them in the
+    middle of the rows (natural-log distance 120 and more), so that only the workgroups whose rows reach those keys
+    take the fallback kernel, the others the plain one, in the same launch."""
+    B, N, Hq, Hkv, d = 1, 1100, 4, 2, 128
+    g = torch.Generator().manual_seed(5)
+    q = 0.05 * torch.randn(B, N, Hq, d, generator=g)
+    k = 0.05 * torch.randn(B, N, Hkv, d, generator=g)
+    v = torch.randn(B, N, Hkv, d, generator=g)
+    q[:, :, 0:2, 0] = 26.0                       # heads 0, 1: logit = 26 * k0 / sqrt(128)
+    k[:, :, 0, 0] = -26.0                        # -59.8 everywhere ...
+    k[:, 300:330, 0, 0] = 26.0                   # ... but +59.8 on 30 keys inside a later part
+    k[:, 700, 0, 0] = 30.0
+    q, k, v = q.bfloat16(), k.bfloat16(), v.bfloat16()
+    out, lse, sh, sm = ctx.prefill_attn(q.to(DEV), k.to(DEV), v.to(DEV), n_text=40, img_begin=16, n_img=1000)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    o_out, o_lse = O.prefill_attn(f64(q), f64(k), f64(v), dtype="bf16")
+    assert rel_err(out.float().cpu(), o_out) < 2e-2
+    assert np.abs(lse.cpu().numpy() - o_lse).max() < 1e-5 * np.abs(o_lse).max()
+    osh, osm = O.score_tokens(f64(q[:, N - 40:]), f64(k), q_pos0=N - 40, img_begin=16, n_img=1000)
+    assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
+
+
 def test_prefill_attn_rejects_bad_arguments(ctx):
     fused, split = _qkv(1, 64, 4, 2, 64, torch.bfloat16, 1)
     qd, kd, vd = split(fused.to(DEV))
