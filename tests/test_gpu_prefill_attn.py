@@ -170,6 +170,40 @@ def test_prefill_attn_far_logits_in_the_middle_of_a_long_row(ctx):
     assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
 
 
+def test_prefill_attn_random_shapes(ctx):
+    """Seeded sweep over small shapes: lengths around the tile and block edges, head counts and groups (G = 1 ... 7),
+    both head dimensions and dtypes, with and without the mask, any number of instruction rows, any image span,
+    flat and peaky rows."""
+    rng = np.random.default_rng(20250901)
+    for it in range(24):
+        dtype = torch.bfloat16 if rng.random() < 0.8 else torch.float32
+        d = int(rng.choice([64, 128]))
+        Hkv, G = int(rng.choice([1, 2, 3, 4, 8])), int(rng.choice([1, 2, 4, 5, 7]))
+        Hq = Hkv * G
+        B = int(rng.choice([1, 1, 2, 3, 9]))
+        N = int(rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 255, 256, 257, 300, 511, 513, 640]))
+        if dtype == torch.float32:
+            N = min(N, 300)
+        if B * Hq * N * N > 4e7:
+            B = 1
+        causal = bool(rng.random() < 0.8)
+        T = int(rng.integers(0, min(N, 70) + 1))
+        n_img = int(rng.integers(1, N + 1)) if T > 0 else 0
+        img0 = int(rng.integers(0, N - n_img + 1)) if T > 0 else 0
+        fused, split = _qkv(B, N, Hq, Hkv, d, dtype, 3000 + it, float(rng.choice([1.0, 1.0, 3.0, 6.0])))
+        q, k, v = split(fused)
+        qd, kd, vd = split(fused.to(DEV))
+        out, lse, sh, sm = ctx.prefill_attn(qd, kd, vd, causal=causal, n_text=T, img_begin=img0, n_img=n_img)
+        torch.cuda.synchronize()
+        case = (it, dtype, B, N, Hq, Hkv, d, causal, T, img0, n_img)
+        o_out, o_lse = O.prefill_attn(f64(q), f64(k), f64(v), causal=causal, dtype="bf16" if dtype == torch.bfloat16 else "f32")
+        assert rel_err(out.float().cpu(), o_out) < TOL[dtype], case
+        assert np.abs(lse.cpu().numpy() - o_lse).max() < 1e-5 * max(1.0, np.abs(o_lse).max()), case
+        if T > 0:
+            osh, osm = O.score_tokens(f64(q[:, N - T:]), f64(k), q_pos0=N - T, img_begin=img0, n_img=n_img, causal=causal)
+            assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5, case
+
+
 def test_prefill_attn_rejects_bad_arguments(ctx):
     fused, split = _qkv(1, 64, 4, 2, 64, torch.bfloat16, 1)
     qd, kd, vd = split(fused.to(DEV))
