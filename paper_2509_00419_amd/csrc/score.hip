@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
                 for (int s = 0; s < KPW; ++s)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) m = fmaxf(m, acc[s][r]);
-                m = fmaxf(m, __shfl_xor(m, 32)) * a.scale_log2;      // scale >= 0 (checked on the host)
+                m = fmaxf(m, other_half(m)) * a.scale_log2;      // scale >= 0 (checked on the host)
 #pragma unroll
                 for (int s = 0; s < KPW; ++s)
 #pragma unroll
@@ -271,14 +271,14 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
                         m = fmaxf(m, t);
                     }
                 }
-                m = fmaxf(m, __shfl_xor(m, 32));
+                m = fmaxf(m, other_half(m));
                 const float ms = (m == -INFINITY) ? 0.f : m;
 #pragma unroll
                 for (int s = 0; s < KPW; ++s)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) l += __builtin_amdgcn_exp2f(acc[s][r] - ms);   // exp2(-inf) = 0
             }
-            l += __shfl_xor(l, 32);
+            l += other_half(l);
             const int rho = rho0 + l32;
             if (hf == 0 && rho < GT) {
                 const long long pidx = ((long long)kb * 4 + wave) * rows_total + rowbase + rho;
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     if (PASS == 1) {
 #pragma unroll
         for (int s = 0; s < KPW; ++s) {
-            const float tot = colsum[s] + __shfl_xor(colsum[s], 32);
+            const float tot = colsum[s] + other_half(colsum[s]);
             const int j = jbase + 32 * s + l32;
             if (hf == 0 && j < key_hi)
                 a.colpart[(((long long)rs * a.B + b) * a.Hkv + g) * a.n_img + (j - a.img_begin)] = tot;
@@ -486,7 +486,7 @@ __global__ __launch_bounds__(64 * NW, (DT == LVLM_F32 && HD == 128) ? 2 : 3) voi
         }
         // the two lane halves, then the four waves
         {
-            const float mo = __shfl_xor(m, 32), lo = __shfl_xor(l, 32);
+            const float mo = other_half(m), lo = other_half(l);
             const float mn = fmaxf(m, mo);
             const float ms = (mn == -INFINITY) ? 0.f : mn;
             l = l * __builtin_amdgcn_exp2f(m - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
@@ -534,7 +534,7 @@ __global__ __launch_bounds__(64 * NW, (DT == LVLM_F32 && HD == 128) ? 2 : 3) voi
                 sum += (j <= pos_s[row]) ? p : 0.f;
             }
         }
-        sum += __shfl_xor(sum, 32);
+        sum += other_half(sum);
         if (hf == 0 && j < key_hi) out[j - key_lo] = sum;
     };
     if (j2_first < key_hi) {
@@ -695,7 +695,7 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
                 sum += (j <= pos_s[wave][row]) ? p : 0.f;
             }
         }
-        sum += __shfl_xor(sum, 32);
+        sum += other_half(sum);
         if (hf == 0 && j < key_hi) out[j - key_lo] = sum;
     };
 
@@ -723,7 +723,7 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
     if (a.row_lse == nullptr) {
         sweep(0, a.N, false);
         {
-            const float mo = __shfl_xor(m, 32), lo = __shfl_xor(l, 32);
+            const float mo = other_half(m), lo = other_half(l);
             const float mn = fmaxf(m, mo);
             const float ms = (mn == -INFINITY) ? 0.f : mn;
             l = l * __builtin_amdgcn_exp2f(m - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
