@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
             acc[r] = t;
             tmax = fmaxf(tmax, t);
         }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        tmax = fmaxf(tmax, other_half(tmax));
         const float m_new = fmaxf(m_run, tmax);          // finite: the tile holds at least one entry
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         if (a.update_score && l32 < a.G) {
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
             p[r] = __builtin_amdgcn_exp2f(acc[r] - m_new);
             psum += p[r];
         }
-        psum += __shfl_xor(psum, 32);
+        psum += other_half(psum);
         l_run = l_run * alpha + psum;
         m_run = m_new;
 #pragma unroll
@@ -451,8 +451,8 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
             t[i] = (j < s_hi) ? acc[i >> 2][i & 3] * a.scale_log2 : -INFINITY;
             tmax = fmaxf(tmax, t[i]);
         }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        tmax = fmaxf(tmax, other_row(tmax));
+        tmax = fmaxf(tmax, other_half(tmax));
         const float m_new = fmaxf(m_run, tmax);          // finite: the tile holds at least one entry
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
         if (a.update_score && l16 < a.G) {
@@ -470,8 +470,8 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
             p[i] = __builtin_amdgcn_exp2f(t[i] - m_new);
             psum += p[i];
         }
-        psum += __shfl_xor(psum, 16);
-        psum += __shfl_xor(psum, 32);
+        psum += other_row(psum);
+        psum += other_half(psum);
         l_run = l_run * alpha + psum;
         m_run = m_new;
         const bf16x8 pb = pack_bf16x8(p);
