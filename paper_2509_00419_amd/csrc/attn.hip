@@ -717,11 +717,7 @@ __global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a) {
     }
     int new_len = L;
     if (evict) {
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const unsigned long long ob = __shfl_xor(best, o);
-            best = ob < best ? ob : best;
-        }
+        best = wave_min_u64(best);
         if (lane == 0) w_best[wave] = best;
         __syncthreads();                                   // also orders the score stores above before the move below
         best = w_best[0];

@@ -150,14 +150,55 @@ __device__ __forceinline__ unsigned long long score_fixed(float s) {
     return ((unsigned long long)hi << 32) | lo;
 }
 
+// Wave reductions that leave the result in every lane, without the LDS permute unit: inside a row of 16 lanes by
+// data-parallel-primitive moves (swap neighbours, swap pairs, mirror the halves of 8, mirror the row), across the
+// rows and the two half-waves by the lane-swap instructions.
+__device__ __forceinline__ float dpp_quad1(float v) { return __int_as_float(__hip_move_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true)); }   // lanes 1,0,3,2
+__device__ __forceinline__ float dpp_quad2(float v) { return __int_as_float(__hip_move_dpp(__float_as_int(v), 0x4E, 0xF, 0xF, true)); }   // lanes 2,3,0,1
+__device__ __forceinline__ float dpp_half_mirror(float v) { return __int_as_float(__hip_move_dpp(__float_as_int(v), 0x141, 0xF, 0xF, true)); }
+__device__ __forceinline__ float dpp_row_mirror(float v) { return __int_as_float(__hip_move_dpp(__float_as_int(v), 0x140, 0xF, 0xF, true)); }
+__device__ __forceinline__ float swap_rows(float x) {          // the value of the lane 16 places away
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float((threadIdx.x & 16) ? r.x : r.y);
+}
+__device__ __forceinline__ float swap_halves(float x) {        // the value of the lane 32 places away
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float((threadIdx.x & 32) ? r.x : r.y);
+}
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-    return v;
+    v = fmaxf(v, dpp_quad1(v));
+    v = fmaxf(v, dpp_quad2(v));
+    v = fmaxf(v, dpp_half_mirror(v));
+    v = fmaxf(v, dpp_row_mirror(v));
+    v = fmaxf(v, swap_rows(v));
+    return fmaxf(v, swap_halves(v));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    v += dpp_quad1(v);
+    v += dpp_quad2(v);
+    v += dpp_half_mirror(v);
+    v += dpp_row_mirror(v);
+    v += swap_rows(v);
+    return v + swap_halves(v);
+}
+// Minimum of a 64-bit key over the wave, in every lane (the moves are bitwise: the halves travel as floats).
+__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
+#define LVLM_MIN_STEP(MOVE)                                                                          \
+    {                                                                                                \
+        const unsigned ph = __float_as_uint(MOVE(__uint_as_float((unsigned)(v >> 32))));             \
+        const unsigned pl = __float_as_uint(MOVE(__uint_as_float((unsigned)v)));                     \
+        const unsigned long long o = ((unsigned long long)ph << 32) | pl;                            \
+        v = o < v ? o : v;                                                                           \
+    }
+    LVLM_MIN_STEP(dpp_quad1)
+    LVLM_MIN_STEP(dpp_quad2)
+    LVLM_MIN_STEP(dpp_half_mirror)
+    LVLM_MIN_STEP(dpp_row_mirror)
+    LVLM_MIN_STEP(swap_rows)
+    LVLM_MIN_STEP(swap_halves)
+#undef LVLM_MIN_STEP
     return v;
 }
 #endif

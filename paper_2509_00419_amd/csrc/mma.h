@@ -58,22 +58,9 @@ __device__ __forceinline__ void mfma_one(f32x16 &acc, const uint4 &a, const uint
     }
 }
 
-// The value the lane 32 places away (the other half-wave) holds, by one lane-swap instruction instead of a trip
-// through the LDS permute unit: the swap exchanges lanes 32..63 of its first operand with lanes 0..31 of its
-// second, so with the same value in both every lane ends up with both halves' values (.x: the low half's).
-__device__ __forceinline__ float other_half(float x) {
-    typedef unsigned u2 __attribute__((ext_vector_type(2)));
-    const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float((threadIdx.x & 32) ? r.x : r.y);
-}
-
-// The same across 16-lane rows: the value of the lane 16 places away (rows 0 <-> 1, 2 <-> 3).  That swap exchanges
-// the odd rows of its first operand with the even rows of its second.
-__device__ __forceinline__ float other_row(float x) {
-    typedef unsigned u2 __attribute__((ext_vector_type(2)));
-    const u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return __uint_as_float((threadIdx.x & 16) ? r.x : r.y);
-}
+// Exchanges with the other half-wave and with the neighbouring 16-lane row (common.h: lane-swap instructions).
+__device__ __forceinline__ float other_half(float x) { return swap_halves(x); }
+__device__ __forceinline__ float other_row(float x) { return swap_rows(x); }
 
 // Row of the 32x32 accumulator held in register r of a lane in half hf (its column is lane % 32).
 __device__ __forceinline__ int acc_row(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
