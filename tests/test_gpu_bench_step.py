@@ -189,3 +189,21 @@ def test_config4_step_in_bench_configuration():
     assert rel_err(f64(st2[i].out_dec), ref[0]) < 2e-2
     mid = snapshot(st2.k[sl], st2.v[sl], st2.score[sl], st2.kind[sl], st2.pos[sl], st2.len[sl])
     same_entries(mid, list(ref[1:]), exact_score=False)
+
+
+def test_prefill_attention_bench_mode_prints_its_line(capsys):
+    """bench.py --op prefill_attn on the small fp32 configuration: the mode runs, and its JSON line carries the
+    contract's fields with a roofline for the attention kernel."""
+    import json
+    import types
+    w = configs.CFG1
+    args = types.SimpleNamespace(steps=2, warmup=1, profile_steps=1, no_cpu_baseline=False)
+    bench.main_prefill_attn(args, w, bench.plan(w, lv), lv.Context(0), lv, torch, DEV)
+    line = [l for l in capsys.readouterr().out.splitlines() if l.startswith("{")][-1]
+    out = json.loads(line)
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in out, key
+    assert out["config"]["op"] == "prefill_attn" and out["config"]["tokens_per_layer"] == [w.seq_len]
+    assert out["roofline"]["kernel"] == "prefill_attn" and out["roofline"]["achieved"] > 0
+    assert out["cpu_baseline"]["kind"] == "oracle" and out["value"] > 0
