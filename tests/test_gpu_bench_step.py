@@ -207,3 +207,46 @@ def test_prefill_attention_bench_mode_prints_its_line(capsys):
     assert out["config"]["op"] == "prefill_attn" and out["config"]["tokens_per_layer"] == [w.seq_len]
     assert out["roofline"]["kernel"] == "prefill_attn" and out["roofline"]["achieved"] > 0
     assert out["cpu_baseline"]["kind"] == "oracle" and out["value"] > 0
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg4"])
+def test_graph_replays_equal_the_eager_step(name):
+    """The bench times HIP-graph replays of the step.  A captured (prefill, decode) pair is replayed three times on
+    restored state, with eager copies and synchronisation between the replays, and every replay must leave exactly
+    what the eager step leaves: caches, scores, lengths, merged hidden states, attention outputs."""
+    w = configs.ALL[name]
+    ctx = lv.Context(0)
+    layers = bench.plan(w, lv)
+    master = bench.build_master(w, layers, torch, synth, DEV)
+    eager = bench.StepState(w, layers, master, torch)
+    bench.run_prefill(ctx, lv, w, eager, reserve=True)
+    bench.run_decode(ctx, lv, w, eager, reserve=True)
+    torch.cuda.synchronize()
+
+    st = bench.StepState(w, layers, master, torch)
+    mutable = ("k", "v", "score", "kind", "pos", "len")
+    saved = {n: getattr(st, n).clone() for n in mutable}
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        bench.run_prefill(ctx, lv, w, st, reserve=False)
+        bench.run_decode(ctx, lv, w, st, reserve=False)
+    for rep in range(3):
+        for n in mutable:                                # eager work between the replays: the state goes back
+            getattr(st, n).copy_(saved[n])
+        for L in st:
+            L.out_dec.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(st.len, eager.len), rep
+        for i, (a, b) in enumerate(zip(st, eager)):
+            assert torch.equal(a.out_dec, b.out_dec), (rep, i)
+            if a.entry["merge_to"] is not None:
+                assert torch.equal(a.hidden_out, b.hidden_out) and torch.equal(a.pos_out, b.pos_out), (rep, i)
+        lens = st.len.cpu()
+        for n in ("k", "v", "score", "kind", "pos"):
+            x, y = getattr(st, n), getattr(eager, n)
+            for row in range(0, lens.shape[0], max(1, lens.shape[0] // 7)):      # a sample of layers: whole heads
+                for h in range(lens.shape[1]):
+                    m = int(lens[row, h])
+                    assert torch.equal(x[row, h, :m], y[row, h, :m]), (rep, n, row, h)
