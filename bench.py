@@ -619,9 +619,9 @@ def main_prefill_attn(args, w, layers, ctx, lv, torch, dev):
         p = prof["prefill_attn"]
         tf = flops / p["us_per_step"] / 1e6
         peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else 157.3
-        kernels["prefill_attn"].update(bound="mfma" if w.dtype == "bf16" else "alu", achieved_TFLOPs=round(tf, 1),
+        kernels["prefill_attn"].update(bound="mfma", achieved_TFLOPs=round(tf, 1),
                                        frac=round(tf / peak, 4))
-        roofline = {"kernel": "prefill_attn", "bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": round(tf, 1),
+        roofline = {"kernel": "prefill_attn", "bound": "mfma", "achieved": round(tf, 1),
                     "peak": peak, "unit": "TFLOP/s", "frac": round(tf / peak, 4), "traffic": None,
                     "algorithmic_flops_per_launch": flops / len(layers), "avg_launch_us": round(p["avg_us"], 2)}
     cpu = None

@@ -68,6 +68,7 @@ const char *check_prefill(const lvlm_prefill_desc *d) {
         return "head stride smaller than the head dimension";
     if ((long long)d->B * d->Hq * ((d->N + 127) / 128) >= (1ll << 28) || (long long)d->B * d->Hq * d->N >= (1ll << 33))
         return "too many query blocks for one launch";
+    if (d->dtype == LVLM_F32 && (d->B > 65535 || d->Hq > 65535)) return "fp32: B and Hq must be below 65536";
     if (d->T > 0) {
         const lvlm_score_desc sd = prefill_score_desc(*d);
         return check_score(&sd);

@@ -363,73 +363,148 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     }
 }
 
-// fp32 (the small fp32 configuration; plain vector arithmetic, no matrix cores): one wave per query row, its
-// lanes take every 64th visible key with an online (max, sum, weighted value sum) each, folded at the end.
+// fp32 (the small fp32 configuration), on the fp32 matrix instruction (32 x 32 x 2, exact fp32 products, fp32 sums).
+// A workgroup of four waves owns 128 query rows of one head, one 32-row block per wave, its rows held as an MFMA
+// operand.  K and V tiles of 32 keys go through LDS as they are (rows = keys), fetched one tile ahead by the 256
+// threads, one barrier per tile.  S^T = K Q^T (rows = keys, columns = queries): a lane owns one query row and 16
+// of its logits; the textbook online softmax (the reference follows the running maximum, sums and accumulators
+// are rescaled when it moves).  For O^T += V^T P^T the contraction of one instruction is two keys, one per
+// half-wave: exactly the two keys the two halves hold in the same accumulator register, so register r of the
+// probabilities is the second operand as it stands and the first is V[that key][channel] read from the tile.
 template <int HD>
-__global__ __launch_bounds__(256) void prefill_attn_f32_kernel(PrefillArgs a) {
-    __shared__ __attribute__((aligned(16))) float q_s[4][HD];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const long long total = (long long)a.B * a.Hq * a.N;
-    const long long rid = (long long)blockIdx.x * 4 + wave;
-    const bool live = rid < total;
-    const long long rc = live ? rid : total - 1;
-    const int i = (int)(rc % a.N), h = (int)((rc / a.N) % a.Hq), b = (int)(rc / ((long long)a.N * a.Hq));
+__global__ __launch_bounds__(256, 1) void prefill_attn_f32_kernel(PrefillArgs a) {
+    constexpr int ROWB = HD * 4;
+    constexpr int KP = ROWB + 16;           // tile pitch: odd multiple of 16 bytes
+    constexpr int NV = HalfRow<LVLM_F32, HD>::NV;
+    constexpr int NCB = HD / 32;
+    constexpr int UPR = ROWB / 16;          // 16-byte units per row
+    constexpr int UPT = 32 * UPR / 256;     // units per thread and tile (2 or 4)
+    constexpr int TPR = UPR / UPT;          // threads per row
+    __shared__ __attribute__((aligned(16))) char k_lds[2][32 * KP];
+    __shared__ __attribute__((aligned(16))) char v_lds[2][32 * KP];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hf = lane >> 5, l32 = lane & 31;
+    const int qb = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;      // longest blocks first
     const int g = h / a.G;
+    const int q0 = qb * 128, blk0 = q0 + 32 * wave;
+    const int row = blk0 + l32;
+    const int kmax = a.causal ? min(a.N, q0 + 128) : a.N;
+    const int n_tiles = (kmax + 31) >> 5;
+
+    HalfRow<LVLM_F32, HD> qa;               // lane (row l32, half hf): bytes 16 hf + 32 i of its row
     {
-        const float *qr = reinterpret_cast<const float *>(a.q + (long long)b * a.qsb + (long long)i * a.qsn + (long long)h * a.qsh);
-        for (int c = lane; c < HD; c += 64) q_s[wave][c] = qr[c];
+        const char *src = a.q + (long long)b * a.qsb + (long long)min(row, a.N - 1) * a.qsn + (long long)h * a.qsh + 16 * hf;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) qa.v[i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
     }
+    const int srow = tid / TPR, scu = tid % TPR;
+    const char *kbase = a.k + (long long)b * a.ksb + (long long)g * a.ksh + 16 * scu;
+    const char *vbase = a.v + (long long)b * a.vsb + (long long)g * a.vsh + 16 * scu;
+    uint4 ks0 = make_uint4(0, 0, 0, 0), ks1 = ks0, ks2 = ks0, ks3 = ks0, vs0 = ks0, vs1 = ks0, vs2 = ks0, vs3 = ks0;
+    auto fetch = [&](int j0) {              // rows past the end repeat the last row (masked later)
+        const long long r = min(j0 + srow, a.N - 1);
+        const uint4 *ksrc = reinterpret_cast<const uint4 *>(kbase + r * a.ksn);
+        const uint4 *vsrc = reinterpret_cast<const uint4 *>(vbase + r * a.vsn);
+        ks0 = ksrc[0], vs0 = vsrc[0];
+        ks1 = ksrc[TPR], vs1 = vsrc[TPR];
+        if constexpr (UPT > 2) {
+            ks2 = ksrc[2 * TPR], vs2 = vsrc[2 * TPR];
+            ks3 = ksrc[3 * TPR], vs3 = vsrc[3 * TPR];
+        }
+    };
+    auto stash = [&](int buf) {
+        uint4 *kd = reinterpret_cast<uint4 *>(&k_lds[buf][srow * KP + 16 * scu]);
+        uint4 *vd = reinterpret_cast<uint4 *>(&v_lds[buf][srow * KP + 16 * scu]);
+        kd[0] = ks0, vd[0] = vs0;
+        kd[TPR] = ks1, vd[TPR] = vs1;
+        if constexpr (UPT > 2) {
+            kd[2 * TPR] = ks2, vd[2 * TPR] = vs2;
+            kd[3 * TPR] = ks3, vd[3 * TPR] = vs3;
+        }
+    };
+
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x16 oacc[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
+
+    fetch(0);
+    stash(0);
     __syncthreads();
-    const int last = a.causal ? i : a.N - 1;
-    float m = -INFINITY, l = 0.f;
-    float o[HD];
+    for (int t = 0; t < n_tiles; ++t) {
+        const int j0 = t << 5, buf = t & 1;
+        fetch(min(j0 + 32, (n_tiles - 1) << 5));
+        if (!a.causal || j0 <= blk0 + 31) {                       // the block sees some key of the tile
+            HalfRow<LVLM_F32, HD> kf;
+            {
+                const char *src = &k_lds[buf][l32 * KP + 16 * hf];
 #pragma unroll
-    for (int c = 0; c < HD; ++c) o[c] = 0.f;
-    const char *kb = a.k + (long long)b * a.ksb + (long long)g * a.ksh;
-    const char *vb = a.v + (long long)b * a.vsb + (long long)g * a.vsh;
-    for (int j = lane; j <= last; j += 64) {
-        const float4 *kr = reinterpret_cast<const float4 *>(kb + (long long)j * a.ksn);
-        const float4 *vr = reinterpret_cast<const float4 *>(vb + (long long)j * a.vsn);
-        float s = 0.f;
+                for (int i = 0; i < NV; ++i) kf.v[i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
+            }
+            f32x16 s;
 #pragma unroll
-        for (int c4 = 0; c4 < HD / 4; ++c4) {
-            const float4 kk = kr[c4];
-            const float4 qq = *reinterpret_cast<const float4 *>(&q_s[wave][4 * c4]);
-            s = fmaf(qq.x, kk.x, s); s = fmaf(qq.y, kk.y, s); s = fmaf(qq.z, kk.z, s); s = fmaf(qq.w, kk.w, s);
+            for (int r = 0; r < 16; ++r) s[r] = 0.f;
+            mma_tile<LVLM_F32, HD>(s, kf, qa);                    // rows = keys, columns = queries
+            if ((a.causal && j0 + 31 > blk0) || j0 + 32 > a.N) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int j = j0 + acc_row(r, hf);
+                    if ((a.causal && j > row) || j >= a.N) s[r] = -INFINITY;
+                }
+            }
+            float mx = s[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+            mx = fmaxf(mx, other_half(mx));                       // finite: key j0 <= blk0 is visible to every row
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * a.scale_log2);   // first tile: 0
+            const float mb = m_new * a.scale_log2;
+            float p[16], sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], a.scale_log2, -mb));
+                sum += p[r];
+            }
+            l_run = l_run * alpha + sum;
+            m_run = m_new;
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[cb][r] *= alpha;
+                // register r of the two half-waves: keys acc_row(r, 0) and acc_row(r, 1) -- the two keys one
+                // instruction contracts
+                const char *vsrc = &v_lds[buf][4 * (32 * cb + l32)];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float vv = *reinterpret_cast<const float *>(vsrc + acc_row(r, hf) * KP);
+                    oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x2f32(vv, p[r], oacc[cb], 0, 0, 0);
+                }
+            }
         }
-        s *= a.scale_log2;
-        const float m_new = fmaxf(m, s);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);     // first key: exp2(-inf) = 0
-        const float p = __builtin_amdgcn_exp2f(s - m_new);
-        l = l * alpha + p;
-#pragma unroll
-        for (int c4 = 0; c4 < HD / 4; ++c4) {
-            const float4 vv = vr[c4];
-            o[4 * c4 + 0] = fmaf(o[4 * c4 + 0], alpha, p * vv.x);
-            o[4 * c4 + 1] = fmaf(o[4 * c4 + 1], alpha, p * vv.y);
-            o[4 * c4 + 2] = fmaf(o[4 * c4 + 2], alpha, p * vv.z);
-            o[4 * c4 + 3] = fmaf(o[4 * c4 + 3], alpha, p * vv.w);
-        }
-        m = m_new;
+        if (t + 1 < n_tiles) stash(buf ^ 1);
+        __syncthreads();
     }
-    const float M = wave_max(m);                                    // lane 0 always has key 0: finite
-    const float f = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - M);
-    const float L = wave_sum(l * f);
-    const float inv = 1.f / L;
-    float mine = 0.f, mine2 = 0.f;                                  // lane c keeps channels c and c + 64
+
+    const float l_tot = l_run + other_half(l_run);
+    if (row >= a.N) return;
+    const float inv = 1.f / l_tot;
+    // lane (query l32, half hf) holds channels 32 cb + 8 (r / 4) + 4 hf + r % 4
+    float *dst = reinterpret_cast<float *>(a.out + (long long)b * a.osb + (long long)row * a.osn + (long long)h * a.osh) + 4 * hf;
 #pragma unroll
-    for (int c = 0; c < HD; ++c) {
-        const float tot = wave_sum(o[c] * f);
-        if ((c & 63) == lane) { if (c < 64) mine = tot; else mine2 = tot; }
-    }
-    if (!live) return;
-    float *dst = reinterpret_cast<float *>(a.out + (long long)b * a.osb + (long long)i * a.osn + (long long)h * a.osh);
-    dst[lane] = mine * inv;
-    if (HD > 64) dst[64 + lane] = mine2 * inv;
-    if (lane == 0) {
-        const float lse = (M + __log2f(L)) * 0.6931471805599453f;
-        a.row_lse[((long long)b * a.Hq + h) * a.N + i] = lse;
-        if (a.lse_t && i >= a.N - a.T) a.lse_t[((long long)b * a.Hq + h) * a.T + (i - (a.N - a.T))] = lse;
+    for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4)
+            *reinterpret_cast<float4 *>(dst + 32 * cb + 8 * r4) =
+                make_float4(oacc[cb][4 * r4 + 0] * inv, oacc[cb][4 * r4 + 1] * inv, oacc[cb][4 * r4 + 2] * inv,
+                            oacc[cb][4 * r4 + 3] * inv);
+    if (hf == 0) {
+        const float lse = m_run * a.scale + __logf(l_tot);
+        a.row_lse[((long long)b * a.Hq + h) * a.N + row] = lse;
+        if (a.lse_t && row >= a.N - a.T) a.lse_t[((long long)b * a.Hq + h) * a.T + (row - (a.N - a.T))] = lse;
     }
 }
 
@@ -486,9 +561,9 @@ hipError_t launch_prefill_attn(const Prof &prof, const lvlm_prefill_desc &d, con
             hipLaunchKernelGGL((prefill_attn_bf16_kernel<64, true>), dim3((unsigned)grid), dim3(128), 0, stream, a);
         }
     } else {
-        const long long grid = ((long long)d.B * d.Hq * d.N + 3) / 4;
-        if (d.hd == 128) hipLaunchKernelGGL((prefill_attn_f32_kernel<128>), dim3((unsigned)grid), dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((prefill_attn_f32_kernel<64>), dim3((unsigned)grid), dim3(256), 0, stream, a);
+        const dim3 grid((unsigned)a.nqb, (unsigned)d.Hq, (unsigned)d.B);
+        if (d.hd == 128) hipLaunchKernelGGL((prefill_attn_f32_kernel<128>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((prefill_attn_f32_kernel<64>), grid, dim3(256), 0, stream, a);
     }
     prof.end();
     hipError_t e = hipGetLastError();
