@@ -22,6 +22,8 @@
 #include "common.h"
 #include "mma.h"
 
+#include <type_traits>
+
 namespace lvlm {
 namespace {
 
@@ -640,12 +642,23 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
 
     // ---- sweep 1: this lane's row normaliser over all keys
     float m = -INFINITY, l = 0.f;
-    auto stats = [&](int j0, const HalfRow<DT, HD> &kf) {
+    // SAFE = false: after the first whole tile has set a finite reference m, later whole tiles take it as it is --
+    // no maximum, no rescaling; a logit far above it shows as an overflowing sum, checked after the sweep, and the
+    // workgroup then repeats the sweep with SAFE = true (the reference follows the running maximum on every tile).
+    auto stats = [&](int j0, const HalfRow<DT, HD> &kf, auto safe_tag) {
+        constexpr bool SAFE = decltype(safe_tag)::value;
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
         mma_tile<DT, HD>(acc, kf, qa);                    // rows = keys, columns = queries
         if (j0 + 32 <= a.N && j0 + 31 <= pos_min) {
+            if (!SAFE && j0 > 0) {                        // tile 0 was whole too (tiles ascend): m is finite
+                float sum = 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -m));
+                l += sum;
+                return;
+            }
             float tmax = acc[0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, acc[r]);
@@ -701,7 +714,7 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
 
     // One sweep: tile t is fetched in iteration t-2, copied to LDS in iteration t-1 and used in iteration t
     // (one barrier per tile publishes the copy; fetches past the last tile repeat its last row).
-    auto sweep = [&](int j_begin, int j_end, bool second) {
+    auto sweep = [&](int j_begin, int j_end, bool second, auto safe_tag) {
         const int nt = (j_end - j_begin + 31) >> 5;
         fetch(j_begin, j_end);
         stash(0);
@@ -714,14 +727,18 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
                 HalfRow<DT, HD> kf;
                 tile_operand(t & 1, kf);
                 if (second) colsum(j_begin + 32 * t, kf);
-                else stats(j_begin + 32 * t, kf);
+                else stats(j_begin + 32 * t, kf, safe_tag);
             }
             __syncthreads();
         }
     };
 
     if (a.row_lse == nullptr) {
-        sweep(0, a.N, false);
+        sweep(0, a.N, false, std::false_type{});
+        if (__syncthreads_or(!(l < 1.0e30f))) {           // some sum ran away (or is not a number): the careful sweep
+            m = -INFINITY, l = 0.f;
+            sweep(0, a.N, false, std::true_type{});
+        }
         {
             const float mo = other_half(m), lo = other_half(l);
             const float mn = fmaxf(m, mo);
@@ -735,7 +752,7 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
         lse_s[wave][l32] = (live && rho < GT) ? a.row_lse[rowbase + rho] * kLog2e : INFINITY;
     }
     __syncthreads();
-    sweep(key_lo, key_hi, true);
+    sweep(key_lo, key_hi, true, std::true_type{});
 }
 
 // Fold the per-block, per-wave (max, sum) pairs of each row into a log2-domain LSE.  Eight lanes share a

@@ -137,6 +137,27 @@ def test_score_from_probs(ctx, dtype):
     assert rel_err(a_h.cpu(), b_h.cpu()) < 1e-5 and rel_err(a_m.cpu(), b_m.cpu()) < 1e-5
 
 
+def test_score_batched_form_with_logits_far_above_the_first_tile(ctx):
+    # 32 sequences x 8 KV heads, three query chunks each: the one-launch form whose workgroups share the key tiles.
+    # Its first sweep keeps the first tile's reference; keys whose logits lie far above everything before them
+    # (natural-log distance 120) must send the workgroup through the careful sweep, others not.
+    B, T, Hq, Hkv, d, n_sys, n_img = 32, 96, 8, 8, 64, 8, 280
+    N = n_sys + n_img + T
+    g = torch.Generator().manual_seed(21)
+    q = 0.05 * torch.randn(B, T, Hq, d, generator=g)
+    k = 0.05 * torch.randn(B, N, Hkv, d, generator=g)
+    q[:, :, 0:3, 0] = 22.0
+    k[:, :, 0:3, 0] = -22.0
+    k[:, 100:130, 0:3, 0] = 22.0
+    k[:, 200, 1, 0] = 30.0
+    q, k = q.bfloat16(), k.bfloat16()
+    kw = dict(q_pos0=n_sys + n_img, img_begin=n_sys, n_img=n_img)
+    sh, sm = ctx.score_tokens(q.to(DEV), k.to(DEV), **kw)
+    osh, osm = O.score_tokens(f64(q), f64(k), **kw)
+    assert torch.isfinite(sh).all()
+    assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5
+
+
 def test_score_wide_blocks_config3_shape(ctx):
     # B=8, 8 KV heads, N=1888: enough workgroups for the 256-key blocks (2 tiles per wave)
     w = configs.CFG3
