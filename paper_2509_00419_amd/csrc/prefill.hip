@@ -102,16 +102,6 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
     const int kmax = a.causal ? min(a.N, q0 + 128) : a.N;
     const int n_tiles = (kmax + 31) >> 5;
 
-    // query operands: lane (row l32 of block x, half hf) holds bytes 16 hf + 32 i of its row
-    uint4 qf[2][NV];
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-        const int row = wrow0 + 32 * x + l32;
-        const char *src = a.q + (long long)b * a.qsb + (long long)min(row, a.N - 1) * a.qsn + (long long)h * a.qsh + 16 * hf;
-#pragma unroll
-        for (int i = 0; i < NV; ++i) qf[x][i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
-    }
-
     // staging.  K: thread -> row krow, units kcu + KTPR x.  V: thread -> four keys 4 vkg .. 4 vkg + 3 of one
     // 16-byte unit vcu (8 channels); HD = 64 needs only half the threads for V.
     const int krow = tid / KTPR, kcu = tid % KTPR;
@@ -199,6 +189,18 @@ __global__ __launch_bounds__(128, 1) void prefill_attn_bf16_kernel(PrefillArgs a
             for (int r = 0; r < 16; ++r) oacc[x][cb][r] = 0.f;
     }
     fetch(0);
+    // The operand loads go out after the first tile's: loads return in order, and the tile (mostly in L2) would
+    // otherwise wait behind the operand rows (from memory) before it can go to LDS.
+    // Query operands: lane (row l32 of block x, half hf) holds bytes 16 hf + 32 i of its row
+    uint4 qf[2][NV];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+        const int row = wrow0 + 32 * x + l32;
+        const char *src = a.q + (long long)b * a.qsb + (long long)min(row, a.N - 1) * a.qsn + (long long)h * a.qsh + 16 * hf;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) qf[x][i] = *reinterpret_cast<const uint4 *>(src + 32 * i);
+    }
+
     stash(0);
     __syncthreads();
     // One tile.  EDGE = false: every row of the workgroup sees the whole tile -- no masks, both blocks.  EDGE = true
