@@ -351,7 +351,7 @@ def score_in_one_launch(w, N, batch):
     e = 2 if w.dtype == "bf16" else 4
     n_chunks = (w.n_q_heads // w.n_kv_heads * w.n_text + 31) // 32
     rows = N * (w.head_dim * e) // 256
-    shared = 3 <= n_chunks <= 32 and batch * w.n_kv_heads * ((n_chunks + 3) // 4) >= 256 and rows <= 8192
+    shared = 3 <= n_chunks <= 32 and batch * w.n_kv_heads * ((n_chunks + 3) // 4) >= 192 and rows <= 8192
     return shared or (n_chunks <= 32 and rows <= 1100)
 
 

@@ -961,6 +961,7 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool sin
 }  // namespace
 
 constexpr int kSingleMaxChunks = 32;
+constexpr int kSharedMinWgs = 192;       // workgroups of four chunks from which the shared-tile form is taken
 constexpr int kSingleMaxRows = 1100;      // in 256-byte key rows, one chunk per workgroup
 constexpr int kSharedMaxRows = 8192;      // ... four chunks per workgroup sharing the key tiles
 
@@ -1036,7 +1037,7 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
     // their fold and a launch) -- else one chunk per workgroup whose waves split the keys and fetch them
     // themselves, which pays up to the length where the three launches it replaces cost the same.
     const long long sweep_rows = (long long)d.N * (d.hd * (d.dtype == LVLM_BF16 ? 2 : 4)) / 256;
-    w.shared_tiles = n_chunks >= 3 && n_chunks <= kSingleMaxChunks && (long long)d.B * d.Hkv * ((n_chunks + 3) / 4) >= 256 &&
+    w.shared_tiles = n_chunks >= 3 && n_chunks <= kSingleMaxChunks && (long long)d.B * d.Hkv * ((n_chunks + 3) / 4) >= kSharedMinWgs &&
                      sweep_rows <= kSharedMaxRows;
     w.single = w.shared_tiles || (n_chunks <= kSingleMaxChunks && sweep_rows <= kSingleMaxRows);
     if (w.single) {
