@@ -730,3 +730,77 @@ def test_merge_similar(ctx):
     _similar_case(ctx, torch.float32, 1, 2, 200, 2, 64, 200, 105)                                # nothing removed
     _similar_case(ctx, torch.bfloat16, 1, 1, 500, 1, 128, 130, 106, identical=True)              # all ties
     _similar_case(ctx, torch.bfloat16, 1, 2, 150, 2, 72, 40, 107, clusters=4)                    # 144-byte rows: partial slice
+
+
+# --------------------------------------------------------------------------- seeded random shapes, every entry point
+def _random_lens(rng, n, Lmax, lo=0):
+    edges = [127, 128, 129, 159, 160, 161, 255, 256, 257, 1023, 1024, 1025]
+    out = []
+    for _ in range(n):
+        r = rng.random()
+        if r < 0.1:
+            out.append(lo)
+        elif r < 0.2:
+            out.append(Lmax - 1)
+        elif r < 0.4:
+            out.append(min(Lmax - 1, rng.choice(edges)))
+        else:
+            out.append(rng.randint(lo, Lmax - 1))
+    return out
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_shapes_every_entry_point(ctx, seed):
+    """Shapes drawn at random inside the documented limits (group sizes 1-8, both head sizes and dtypes, ragged and
+    empty heads, lengths around the tile edges), each checked like the hand-picked cases above."""
+    import random
+    rng = random.Random(seed)
+    combos = [(torch.bfloat16, 128), (torch.bfloat16, 64), (torch.float32, 64), (torch.float32, 128)]
+
+    def heads():
+        hkv = rng.choice([1, 2, 3, 4, 8])
+        return hkv * rng.randint(1, 8), hkv
+
+    for _ in range(40):
+        # score
+        (dtype, d), (Hq, Hkv) = rng.choice(combos), heads()
+        n_img = rng.choice([1, 2, 31, 33, 200, 717, rng.randint(1, 2600)])
+        if dtype == torch.float32:
+            n_img = min(n_img, 900)
+        test_score_tokens(ctx, dtype, rng.randint(1, 3), rng.choice([1, 5, 31, 32, 33, 64, 96, rng.randint(1, 100)]), Hq,
+                          Hkv, d, rng.choice([0, 3, 64, rng.randint(0, 70)]), n_img, rng.random() < 0.8)
+        # merge
+        n_img = rng.choice([1, 2, 3, 64, 65, 576, rng.randint(1, 3000)])
+        _merge_case(ctx, rng.choice([torch.bfloat16, torch.float32]), rng.randint(1, 3), rng.randint(0, 9), n_img,
+                    rng.randint(0, 9), rng.choice([1, 7, 64, 100, 256, 257, 520, 1024, rng.randint(1, 1200)]),
+                    rng.choice([1, n_img, max(1, n_img - 1), rng.randint(1, n_img)]),
+                    w_mode=rng.choice([None, None, lv.MERGE_PAIRWISE, lv.MERGE_LINEAR_RAW]),
+                    extra_planes=rng.random() < 0.5, seed=rng.randint(0, 10000))
+        # cache compression
+        (dtype, d), B, H = rng.choice(combos), rng.randint(1, 2), rng.randint(1, 3)
+        Lmax = rng.choice([8, 65, 700, 2048, 2049, 4100, rng.randint(5, 9000)])
+        order = rng.choice([lv.ORDER_STABLE, lv.ORDER_FILL])
+        if rng.random() < 0.5:
+            kw = dict(mode=lv.KV_THRESHOLD, beta=rng.choice([0.3, 0.9, 0.995, 0.9999, 1.0]), order=order)
+        else:
+            kw = dict(mode=lv.KV_BUDGET, budget=rng.choice([1, 2, Lmax // 2 + 1, Lmax, rng.randint(1, Lmax)]),
+                      n_recent=rng.choice([0, 1, 7]), order=order)
+        _kv_case(ctx, dtype, B, H, Lmax, d, _random_lens(rng, B * H, Lmax + 1), rng.randint(0, 10000),
+                 dyadic=rng.random() < 0.3, image_only=rng.random() < 0.3, protected=rng.choice([0, 4, min(Lmax, 64)]), **kw)
+        # decode attention
+        (dtype, d), (Hq, Hkv), B = rng.choice(combos), heads(), rng.randint(1, 3)
+        Lmax = rng.choice([2, 33, 129, 161, 300, 1100, 2200, rng.randint(2, 5000)])
+        append = rng.random() < 0.8
+        lens = _random_lens(rng, B * Hkv, Lmax, lo=0 if append else 1)
+        lb = 0
+        if rng.random() < 0.4:
+            lb = min(Lmax, max(lens) + int(append) + rng.choice([0, 1, 31, 200]))
+        _attn_case(ctx, dtype, B, Hq, Hkv, d, Lmax, lens, rng.randint(0, 10000), append=append,
+                   decay=rng.choice([0.9, 1.0, 0.0]), track=rng.random() < 0.8, len_bound=lb)
+        # decode attention with the per-step eviction
+        (dtype, d), (Hq, Hkv), B = rng.choice(combos), heads(), rng.randint(1, 2)
+        Lmax = rng.choice([64, 300, 1100, 2500, rng.randint(16, 3000)])
+        budget = rng.randint(1, Lmax - 1)
+        lens = [min(Lmax - 1, max(0, budget + rng.choice([-5, -1, 0, 0, 1, 3, 40]))) for _ in range(B * Hkv)]
+        _attn_evict_case(ctx, dtype, B, Hq, Hkv, d, Lmax, lens, budget, rng.choice([0, 1, 4]), rng.randint(0, 10000),
+                         protected=rng.choice([0, 4]))
