@@ -647,7 +647,8 @@ __device__ __forceinline__ void load_chunk(const AttnArgs &a, int hg, int L, int
 // is the lowest score, highest slot among equals).
 template <int GP, bool EVICT, int NT>
 __device__ __forceinline__ void apply_chunk(const AttnArgs &a, const CombineLds<GP> &c, int hg, int L, int chunk,
-                                            const ChunkRegs<GP, NT> &r, int recent_lo, unsigned long long &best) {
+                                            const ChunkRegs<GP, NT> &r, int recent_lo, unsigned long long &best,
+                                            float *last_ns = nullptr) {
     const int tid = threadIdx.x;
     const long long cbase = (long long)hg * a.Lmax;
     const float inv_g = 1.0f / (float)a.G;
@@ -661,6 +662,7 @@ __device__ __forceinline__ void apply_chunk(const AttnArgs &a, const CombineLds<
                 if (h < a.G) pm += exp2f(r.lv[i][h] - c.m[h]) * c.inv[h];
             const float ns = a.decay * r.old[i] + pm * inv_g;
             a.score[cbase + j] = ns;
+            if (EVICT && j == L - 1) *last_ns = ns;          // the entry that fills the victim's slot
             if (EVICT && r.kd[i] != LVLM_KIND_PROTECTED && j < recent_lo) {
                 const unsigned long long cand =
                     ((unsigned long long)score_key(ns) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)j);
@@ -701,19 +703,37 @@ __global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a) {
     constexpr int NT = 1024;
     __shared__ CombineLds<GP> c;
     __shared__ unsigned long long w_best[NT / 64];
+    __shared__ float last_ns;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x, b = blockIdx.y;
     const int hg = b * a.Hkv + g;
     const int L = a.cur_len[hg];
+    const bool evict = L > a.evict_budget;
+    // The entry that will fill the victim's slot is known before the victim is: its K and V rows, kind and
+    // position are fetched now (nothing in this kernel changes them), its new importance comes through LDS,
+    // so the move at the end is stores only.
+    constexpr int UPR = ROWB / 16;
+    const long long cbase = (long long)hg * a.Lmax;
+    uint4 last_row = make_uint4(0, 0, 0, 0);
+    uint8_t last_kind = 0;
+    int32_t last_pos = 0;
+    if (evict) {
+        const long long last = cbase + L - 1;
+        if (tid < UPR) last_row = *reinterpret_cast<const uint4 *>(a.k + last * ROWB + 16 * tid);
+        else if (tid < 2 * UPR) last_row = *reinterpret_cast<const uint4 *>(a.v + last * ROWB + 16 * (tid - UPR));
+        else if (tid == 2 * UPR) {
+            last_kind = a.kind[last];
+            last_pos = a.pos[last];
+        }
+    }
     fold_normalisers<GP, NT>(a, c, hg);
     write_output<DT, HD, GP, NT>(a, c, b, g, hg);
-    const bool evict = L > a.evict_budget;
     const int recent_lo = evict ? L - a.evict_recent : 0;      // nothing is a candidate when nothing is evicted
     unsigned long long best = ~0ull;
     for (int chunk = 0; chunk * 1024 < L; ++chunk) {
         ChunkRegs<GP, NT> r;
         load_chunk<GP, true, NT>(a, hg, L, chunk, r);
-        apply_chunk<GP, true, NT>(a, c, hg, L, chunk, r, recent_lo, best);
+        apply_chunk<GP, true, NT>(a, c, hg, L, chunk, r, recent_lo, best, &last_ns);
     }
     int new_len = L;
     if (evict) {
@@ -728,20 +748,14 @@ __global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a) {
             const int last = L - 1;
             new_len = last;
             if (victim != last) {
-                constexpr int UPR = ROWB / 16;
-                const long long cbase = (long long)hg * a.Lmax;
-                char *kc = a.k + cbase * ROWB;
-                char *vc = a.v + cbase * ROWB;
                 if (tid < UPR)
-                    *reinterpret_cast<uint4 *>(kc + (long long)victim * ROWB + 16 * tid) =
-                        *reinterpret_cast<const uint4 *>(kc + (long long)last * ROWB + 16 * tid);
+                    *reinterpret_cast<uint4 *>(a.k + (cbase + victim) * ROWB + 16 * tid) = last_row;
                 else if (tid < 2 * UPR)
-                    *reinterpret_cast<uint4 *>(vc + (long long)victim * ROWB + 16 * (tid - UPR)) =
-                        *reinterpret_cast<const uint4 *>(vc + (long long)last * ROWB + 16 * (tid - UPR));
+                    *reinterpret_cast<uint4 *>(a.v + (cbase + victim) * ROWB + 16 * (tid - UPR)) = last_row;
                 else if (tid == 2 * UPR) {
-                    a.score[cbase + victim] = a.score[cbase + last];
-                    a.kind[cbase + victim] = a.kind[cbase + last];
-                    a.pos[cbase + victim] = a.pos[cbase + last];
+                    a.score[cbase + victim] = last_ns;
+                    a.kind[cbase + victim] = last_kind;
+                    a.pos[cbase + victim] = last_pos;
                 }
             }
         }
