@@ -105,3 +105,17 @@ def test_argument_errors_are_reported_before_any_launch():
     ad = bd.AttnDesc(bd.BF16, 1, 4, 2, 128, 64, 0, 2, 0, 1.0, 1.0)
     st = bd.lib.lvlm_decode_attn(ctx._h, None, C.byref(ad), 256, 512, None, 512, 768, None, None, None, 1024, 2048)
     assert st == 1 and b"together" in bd.lib.lvlm_last_error(ctx._h)
+
+
+def test_bench_launch_model_uses_the_library_constants():
+    """bench.py restates the library's rule for scoring in one launch (only to credit flops to the right kernel
+    name); its numbers must be the ones in the source of that rule."""
+    import inspect
+    import bench
+    src = open(os.path.join(os.path.dirname(bd.__file__), "csrc", "score.hip")).read()
+    const = {k: int(v) for k, v in re.findall(r"constexpr int (kSingleMaxChunks|kSharedMinWgs|kSingleMaxRows|kSharedMaxRows) = (\d+);", src)}
+    assert len(const) == 4
+    model = inspect.getsource(bench.score_in_one_launch)
+    assert f">= {const['kSharedMinWgs']} and rows <= {const['kSharedMaxRows']}" in model
+    assert f"n_chunks <= {const['kSingleMaxChunks']} and rows <= {const['kSingleMaxRows']}" in model
+    assert f"3 <= n_chunks <= {const['kSingleMaxChunks']}" in model
