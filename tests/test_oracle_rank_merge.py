@@ -253,3 +253,29 @@ def test_schedule_golden_and_properties():
     assert O.schedule(10, 1e-9, 3) == [1, 1, 1]
     assert gold["merge_layers_qwen25vl_7b"] == [5, 9, 13] and gold["kv_beta"] == 0.995
     assert gold["keep_budgets"] == [0.35, 0.15, 0.03]
+
+
+def _stage_count_exact(n, f_num, f_den, s, S=3):
+    """floor(n * (f_num/f_den)^(s/S) + 1/2) without floating point: k is that value exactly when
+    (2k-1)^S * f_den^s <= (2n)^S * f_num^s < (2k+1)^S * f_den^s."""
+    rhs = (2 * n) ** S * f_num ** s
+    k = 0
+    while (2 * k + 1) ** S * f_den ** s <= rhs:
+        k += 1
+    return k
+
+
+def test_schedule_every_stage_is_rounded_half_up_from_the_original_count():
+    """App. A.2: a constant reduction ratio per merge layer, fixed by the budget.  The counts of every stage (not
+    only the last) are round-half-up of n * f^(s/3) taken from the ORIGINAL count: the printed table below was
+    evaluated by hand for the benchmark shapes, and the integer-cube bracket gives the same values with no
+    floating point at all, so a floor instead of a round, or a ratio applied to the previous stage's rounded
+    count, fails here (1792 * 0.35^(2/3) = 889.97 must give 890; 636 * 0.3107 = 197.6 -> 198 only from 2048)."""
+    table = {(2048, 3, 100): [636, 198, 61], (2048, 35, 100): [1443, 1017, 717], (1792, 35, 100): [1263, 890, 627],
+             (16384, 3, 100): [5091, 1582, 492]}
+    for (n, a, b), want in table.items():
+        assert O.schedule(n, a / b, 3) == want
+        assert [_stage_count_exact(n, a, b, s) for s in (1, 2, 3)] == want
+    for n, a, b in [(2048, 15, 100), (1476, 3, 100), (4096, 1, 8), (999, 1, 2), (7, 1, 3)]:
+        assert O.schedule(n, a / b, 3) == [max(1, _stage_count_exact(n, a, b, s)) for s in (1, 2, 3)]
+    assert O.schedule(576, 0.5, 1) == [288]
