@@ -98,7 +98,9 @@ LVLM_API const char *lvlm_last_error(const lvlm_ctx *ctx);
 /* Bytes of scratch the given call needs.  `desc` points to the lvlm_*_desc of
  * that op; for LVLM_OP_MERGE / LVLM_OP_MERGE_SIMILAR to an lvlm_merge_query (descriptor plus
  * plane table: only row_elems and dtype of each plane are read).  Pure host
- * arithmetic; the size never depends on pointer values or on n_keep. */
+ * arithmetic; the size never depends on pointer values.  It does not depend on
+ * n_keep either, except for LVLM_OP_MERGE_SIMILAR (whose scratch holds one entry
+ * per dominant token: there n_keep must already be the value of the call). */
 LVLM_API lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const void *desc, size_t *bytes);
 /* Attaches caller-owned device scratch (256-byte aligned).  May be replaced at
  * any time between calls; the library never frees it. */
@@ -161,6 +163,12 @@ typedef struct {
 LVLM_API lvlm_status lvlm_score_tokens(lvlm_ctx *ctx, void *stream, const lvlm_score_desc *d,
                               const void *q, const void *k, const float *row_lse,
                               float *score_head, float *score_mean);
+
+/* Which kernels lvlm_score_tokens takes for a shape (host arithmetic; for benchmarks that credit work to
+ * kernels by name): *form = 0 two passes over the keys in separate launches (normalisers, then column
+ * sums), 1 both sweeps in one launch with one query chunk per workgroup, 2 both sweeps in one launch with
+ * four query chunks per workgroup sharing the key tiles. */
+LVLM_API lvlm_status lvlm_score_plan(const lvlm_ctx *ctx, const lvlm_score_desc *d, int32_t *form);
 
 /* The same scores from attention probabilities the caller already holds -- a
  * plain attention that materialises its matrix (Sec. 3.2.2 names both sources:
@@ -262,8 +270,8 @@ typedef struct {
  *    evaluated on the device.
  * planes: HOST array of n_planes entries.
  * keep_idx [B, n_keep-1] i32 ascending, merged_idx [B, r+1] i32 in rank order:
- *    device outputs, indices relative to img_begin (for r == 0 keep_idx is not
- *    written).  Either may be NULL.
+ *    device outputs, indices relative to img_begin (for r == 0 neither list is
+ *    written: nothing was partitioned).  Either may be NULL.
  * Accumulation is fp32 in a fixed order; the result is rounded to the plane
  * dtype with round-to-nearest-even.  Workspace: LVLM_OP_MERGE. */
 LVLM_API lvlm_status lvlm_merge_compact(lvlm_ctx *ctx, void *stream, const lvlm_merge_desc *d,
@@ -333,6 +341,8 @@ typedef struct {
  * Survivors are then compacted in place in the chosen order, all five arrays
  * together, and len is updated.  n_evicted [B,Hkv] i32 (device, optional)
  * receives old len - new len.  Slots at or beyond the new len keep stale data.
+ * len_bound is a promise the launch is sized by; a head that breaks it (len >
+ * len_bound) is left exactly as it is, with n_evicted = 0.
  * A call that evicts nothing changes nothing; LVLM_KV_BUDGET with len_bound (or
  * Lmax) <= budget and no n_evicted launches nothing.  Workspace: LVLM_OP_KV_COMPRESS. */
 LVLM_API lvlm_status lvlm_kv_compress(lvlm_ctx *ctx, void *stream, const lvlm_kv_desc *d,
@@ -357,8 +367,14 @@ typedef struct {
 
 /* Sec. 3.2.2: the current token attends only to the retained entries.
  * If k_new / v_new [B,Hkv,hd] are given, the entry is first appended at slot
- * len[b][g] (score 0, kind new_kind, orig_pos new_pos) and len += 1; the
- * caller guarantees len + 1 <= Lmax.  Then for every query head h of KV head g:
+ * len[b][g] (score 0, kind new_kind, orig_pos new_pos) and len += 1.  The
+ * caller keeps len + 1 <= len_bound (<= Lmax); the lengths live on the device, so
+ * a head that breaks this is handled there, without touching memory beyond the
+ * bound: a head with len == len_bound is full -- the new entry is dropped
+ * (nothing is overwritten, len stays) and the head attends to what it holds; a
+ * head with len > len_bound attends to its first len_bound entries only, its
+ * len is left alone and nothing is evicted from it.  A caller that cannot rule
+ * this out compares len before and after.  Then for every query head h of KV head g:
  *   out[b][h] = sum_j softmax_j(scale * q[b][h] . k_j) * v_j,  j in [0, len[b][g])
  * with fp32 online softmax and accumulation, split over the entries and
  * recombined.  If `score` is not NULL every entry's importance is updated as

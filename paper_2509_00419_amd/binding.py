@@ -112,6 +112,7 @@ def _load():
     lib.lvlm_schedule.argtypes = [C.c_int, C.c_double, C.c_int, C.POINTER(C.c_int)]
     lib.lvlm_merge_weights.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_float)]
     lib.lvlm_score_tokens.argtypes = [vp, vp, C.POINTER(ScoreDesc), vp, vp, f32p, f32p, f32p]
+    lib.lvlm_score_plan.argtypes = [vp, C.POINTER(ScoreDesc), C.POINTER(C.c_int32)]
     lib.lvlm_score_from_probs.argtypes = [vp, vp, C.POINTER(ProbsDesc), vp, f32p, f32p]
     lib.lvlm_prefill_attn.argtypes = [vp, vp, C.POINTER(PrefillDesc), vp, vp, vp, vp, f32p, f32p, f32p]
     lib.lvlm_merge_compact.argtypes = [vp, vp, C.POINTER(MergeDesc), f32p, f32p, C.POINTER(Plane), i32p, i32p]
@@ -121,7 +122,7 @@ def _load():
     lib.lvlm_profile.argtypes = [C.c_void_p, C.c_int]
     lib.lvlm_profile_read.argtypes = [C.c_void_p, C.POINTER(ProfileEntry), C.c_int, C.POINTER(C.c_int)]
     for name in ("lvlm_profile", "lvlm_profile_read", "lvlm_create", "lvlm_destroy", "lvlm_workspace_bytes", "lvlm_set_workspace", "lvlm_schedule",
-                 "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_score_from_probs", "lvlm_prefill_attn", "lvlm_merge_compact",
+                 "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_score_plan", "lvlm_score_from_probs", "lvlm_prefill_attn", "lvlm_merge_compact",
                  "lvlm_merge_similar",
                  "lvlm_kv_compress",
                  "lvlm_decode_attn"):
@@ -219,6 +220,12 @@ class Context:
                          q.stride(0), q.stride(1), q.stride(2), k.stride(0), k.stride(1), k.stride(2),
                          0 if score_head is None else score_head.stride(0),
                          0 if score_head is None else score_head.stride(1))
+
+    def score_plan(self, desc: ScoreDesc) -> int:
+        """lvlm_score_plan: 0 = two-pass kernels, 1 = one launch (a chunk per workgroup), 2 = one launch (shared tiles)."""
+        form = C.c_int32()
+        self._check(lib.lvlm_score_plan(self._h, C.byref(desc), C.byref(form)))
+        return form.value
 
     def score_tokens(self, q, k, *, q_pos0, img_begin, n_img, scale=None, causal=True, row_lse=None,
                      score_head=None, score_mean=None, reserve=True):

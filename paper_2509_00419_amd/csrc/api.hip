@@ -347,6 +347,15 @@ lvlm_status lvlm_merge_weights(lvlm_merge_mode mode, int m, float *w) {
     return LVLM_ERR_INVALID_ARG;
 }
 
+lvlm_status lvlm_score_plan(const lvlm_ctx *ctx, const lvlm_score_desc *d, int32_t *form) {
+    lvlm_ctx *c = const_cast<lvlm_ctx *>(ctx);
+    if (!ctx || !form) return fail(c, LVLM_ERR_INVALID_ARG, "score_plan: null argument");
+    if (const char *why = check_score(d)) return fail(c, LVLM_ERR_INVALID_ARG, "score_plan: %s", why);
+    const ScoreWs w = score_ws(*d);
+    *form = w.shared_tiles ? 2 : (w.single ? 1 : 0);
+    return LVLM_OK;
+}
+
 lvlm_status lvlm_score_tokens(lvlm_ctx *ctx, void *stream, const lvlm_score_desc *d, const void *q, const void *k,
                               const float *row_lse, float *score_head, float *score_mean) {
     if (!ctx) return LVLM_ERR_INVALID_ARG;

@@ -26,6 +26,27 @@ namespace lvlm {
 namespace {
 
 
+// What a head's first workgroup tells the fold kernel besides the attended length.
+constexpr int kAppended = 1;    // the new entry went into the cache: the length is to be published
+constexpr int kTruncated = 2;   // the head is longer than the caller's bound: only its first `bound` entries were
+                                // attended to; its length is left alone and nothing is evicted
+
+// The entries a head attends to.  A head with room below the caller's bound (len_bound, at most Lmax) takes the new
+// entry; a full head does not (the entry is dropped, nothing is overwritten); a head already longer than the bound
+// is read up to the bound only.  Every index derived from L therefore stays below the bound the workspace and the
+// grids were sized for.
+struct HeadLen {
+    int L, new_slot, flags;
+};
+__device__ __forceinline__ HeadLen head_len(int len0, int bound, int append) {
+    HeadLen h;
+    const bool app = append && len0 < bound;
+    h.L = min(len0, bound) + (app ? 1 : 0);
+    h.new_slot = app ? h.L - 1 : -1;
+    h.flags = (app ? kAppended : 0) | (len0 > bound ? kTruncated : 0);
+    return h;
+}
+
 struct AttnArgs {
     const char *q;
     const char *k_new;
@@ -40,8 +61,8 @@ struct AttnArgs {
     float *part_ml;     // [B*Hkv][n_split][GP][2]
     float *part_o;      // [B*Hkv][n_split][GP][HD]
     float *logits;      // [B*Hkv][Lcap][GP]  log2-domain logits of every entry and head
-    int32_t *cur_len;   // [B*Hkv]
-    int Hq, Hkv, G, Lmax, Lcap, n_split, split_len, append, new_kind, new_pos, update_score;
+    int32_t *cur_len;   // [B*Hkv][2]  entries attended to; flags (kAppended, kTruncated)
+    int Hq, Hkv, G, Lmax, Lcap, bound, n_split, split_len, append, new_kind, new_pos, update_score;
     int evict_budget, evict_recent;
     float scale_log2, decay;
 };
@@ -130,11 +151,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         vn_u = *reinterpret_cast<const uint4 *>(vn + 16 * vunit);
     }
 
-    const int L = min(a.len[hg] + (a.append ? 1 : 0), a.Lmax);
-    const int new_slot = a.append ? L - 1 : -1;
+    const HeadLen hl = head_len(a.len[hg], a.bound, a.append);
+    const int L = hl.L, new_slot = hl.new_slot;
     const int s_hi = split == a.n_split - 1 ? L : min(L, s_lo + a.split_len);   // the last split takes the remainder
     if (split == 0) {
-        if (a.append) {
+        if (new_slot >= 0) {
             if (tid < UPR)
                 *reinterpret_cast<uint4 *>(a.k + (cbase + new_slot) * ROWB + 16 * tid) =
                     *reinterpret_cast<const uint4 *>(a.k_new + (long long)hg * ROWB + 16 * tid);
@@ -146,7 +167,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
                 a.pos[cbase + new_slot] = a.new_pos;
             }
         }
-        if (tid == 0) a.cur_len[hg] = L;
+        if (tid == 0) {
+            a.cur_len[2 * hg] = L;
+            a.cur_len[2 * hg + 1] = hl.flags;
+        }
     }
 
     float m_run = -INFINITY, l_run = 0.f;   // of head l32 (both lane halves hold the same value)
@@ -369,13 +393,13 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
         for (int i = 0; i < QV; ++i) qf[i] = make_uint4(0, 0, 0, 0);
     }
 
-    const int L = min(a.len[hg] + (a.append ? 1 : 0), a.Lmax);
-    const int new_slot = a.append ? L - 1 : -1;
+    const HeadLen hl = head_len(a.len[hg], a.bound, a.append);
+    const int L = hl.L, new_slot = hl.new_slot;
     // the last split takes the remainder (only the form whose waves fetch a second tile can)
     const int s_hi = (MULTI && split == a.n_split - 1) ? L : min(L, s_lo + a.split_len);
     if (split == 0) {
         // the appended entry goes into the cache here; every reader below takes it from k_new / v_new
-        if (a.append) {
+        if (new_slot >= 0) {
             if (tid < UPR)
                 *reinterpret_cast<uint4 *>(a.k + (cbase + new_slot) * ROWB + 16 * tid) =
                     *reinterpret_cast<const uint4 *>(a.k_new + (long long)hg * ROWB + 16 * tid);
@@ -387,7 +411,10 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
                 a.pos[cbase + new_slot] = a.new_pos;
             }
         }
-        if (tid == 0) a.cur_len[hg] = L;
+        if (tid == 0) {
+            a.cur_len[2 * hg] = L;
+            a.cur_len[2 * hg + 1] = hl.flags;
+        }
     }
 
     float m_run = -INFINITY, l_run = 0.f;   // of head l16 (all four lane groups hold the same value)
@@ -622,7 +649,8 @@ struct ChunkRegs {
 };
 
 template <int GP, bool EVICT, int NT>
-__device__ __forceinline__ void load_chunk(const AttnArgs &a, int hg, int L, int chunk, ChunkRegs<GP, NT> &r) {
+__device__ __forceinline__ void load_chunk(const AttnArgs &a, int hg, int L, bool appended, int chunk,
+                                           ChunkRegs<GP, NT> &r) {
     const int tid = threadIdx.x;
     const long long cbase = (long long)hg * a.Lmax;
     const float *lg = a.logits + (long long)hg * a.Lcap * GP;
@@ -636,7 +664,7 @@ __device__ __forceinline__ void load_chunk(const AttnArgs &a, int hg, int L, int
         if (j < L) {
 #pragma unroll
             for (int h = 0; h < GP; ++h) r.lv[i][h] = lg[(long long)j * GP + h];
-            if (!(a.append && j == L - 1)) r.old[i] = a.score[cbase + j];
+            if (!(appended && j == L - 1)) r.old[i] = a.score[cbase + j];
             if (EVICT) r.kd[i] = a.kind[cbase + j];
         }
     }
@@ -680,16 +708,17 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(AttnArgs a) {
     __shared__ CombineLds<GP> c;
     const int g = blockIdx.y, b = blockIdx.z;
     const int hg = b * a.Hkv + g;
-    const int L = a.cur_len[hg];
+    const int L = a.cur_len[2 * hg];
+    const bool appended = a.cur_len[2 * hg + 1] & kAppended;
     fold_normalisers<GP, NT>(a, c, hg);
     if (blockIdx.x == 0) {
         write_output<DT, HD, GP, NT>(a, c, b, g, hg);
-        if (threadIdx.x == 0 && a.append) a.len[hg] = L;
+        if (threadIdx.x == 0 && appended) a.len[hg] = L;
         return;
     }
     unsigned long long unused = ~0ull;
     ChunkRegs<GP, NT> r;
-    load_chunk<GP, false, NT>(a, hg, L, blockIdx.x - 1, r);
+    load_chunk<GP, false, NT>(a, hg, L, appended, blockIdx.x - 1, r);
     apply_chunk<GP, false, NT>(a, c, hg, L, blockIdx.x - 1, r, 0, unused);
 }
 
@@ -707,8 +736,10 @@ __global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int g = blockIdx.x, b = blockIdx.y;
     const int hg = b * a.Hkv + g;
-    const int L = a.cur_len[hg];
-    const bool evict = L > a.evict_budget;
+    const int L = a.cur_len[2 * hg];
+    const int flags = a.cur_len[2 * hg + 1];
+    const bool appended = flags & kAppended;
+    const bool evict = L > a.evict_budget && !(flags & kTruncated);
     // The entry that will fill the victim's slot is known before the victim is: its K and V rows, kind and
     // position are fetched now (nothing in this kernel changes them), its new importance comes through LDS,
     // so the move at the end is stores only.
@@ -732,7 +763,7 @@ __global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a) {
     unsigned long long best = ~0ull;
     for (int chunk = 0; chunk * 1024 < L; ++chunk) {
         ChunkRegs<GP, NT> r;
-        load_chunk<GP, true, NT>(a, hg, L, chunk, r);
+        load_chunk<GP, true, NT>(a, hg, L, appended, chunk, r);
         apply_chunk<GP, true, NT>(a, c, hg, L, chunk, r, recent_lo, best, &last_ns);
     }
     int new_len = L;
@@ -760,7 +791,7 @@ __global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a) {
             }
         }
     }
-    if (tid == 0 && (a.append || new_len != L)) a.len[hg] = new_len;
+    if (tid == 0 && (appended || new_len != L)) a.len[hg] = new_len;
 }
 
 template <int DT, int HD, int GP>
@@ -834,7 +865,7 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     w.logits = align_up(w.part_o + (size_t)heads * n_split * gp * d.hd * sizeof(float), 256);
     w.lcap = lcap;
     w.cur_len = align_up(w.logits + (size_t)heads * gp * lcap * sizeof(float), 256);
-    w.total = align_up(w.cur_len + (size_t)heads * sizeof(int32_t), 256);
+    w.total = align_up(w.cur_len + (size_t)heads * 2 * sizeof(int32_t), 256);
     return w;
 }
 
@@ -855,7 +886,7 @@ hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const A
     a.part_o = reinterpret_cast<float *>(ws + w.part_o);
     a.logits = reinterpret_cast<float *>(ws + w.logits);
     a.cur_len = reinterpret_cast<int32_t *>(ws + w.cur_len);
-    a.Hq = d.Hq; a.Hkv = d.Hkv; a.G = G; a.Lmax = d.Lmax; a.Lcap = w.lcap;
+    a.Hq = d.Hq; a.Hkv = d.Hkv; a.G = G; a.Lmax = d.Lmax; a.Lcap = w.lcap; a.bound = bound;
     a.n_split = w.n_split; a.split_len = w.split_len;
     a.append = k_new != nullptr;
     a.new_kind = d.new_kind; a.new_pos = d.new_pos;

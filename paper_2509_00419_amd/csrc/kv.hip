@@ -3,11 +3,11 @@
 // Neither rule needs a sort.  Both ask for "the best entries until a quota is
 // met", where the quota is a number of entries (fixed budget) or an amount of
 // score mass (threshold beta).  A most-significant-digit radix descent over the
-// order-preserving 32-bit image of the score finds, in four histogram passes,
+// order-preserving 32-bit image of the score finds, in at most four histogram passes,
 // the key K* at which the quota is met: entries above K* stay, entries below go,
 // and among the entries equal to K* the lowest slots stay.  Score mass is summed
-// as exact integers, so the result does not depend on summation order.  (Four
-// 8-bit digits: four histogram passes over the scores; the first also gives the totals.)
+// as exact integers, so the result does not depend on summation order.  (Digits of
+// 9 bits over the bits in which the head's keys differ: at most four histogram passes.)
 //
 //   kv_select_kernel  one workgroup per head: totals, radix descent, then one
 //                     pass in slot order that numbers survivors / holes.  With
@@ -37,7 +37,7 @@ struct KvArgs {
     int32_t *list_a;   // [B*Hkv, Lmax]  STABLE: source slot of each new slot; FILL: holes
     int32_t *list_b;   // [B*Hkv, Lmax]  FILL: survivors beyond the new length
     int32_t *meta;     // [B*Hkv, 2]     STABLE: {new length, first destination slot that moves}
-    int Hkv, Lmax, row_bytes, mode, order, budget, n_recent;
+    int Hkv, Lmax, bound, row_bytes, mode, order, budget, n_recent;   // bound: the caller's len_bound (<= Lmax)
     double beta;
     int fill_external;   // FILL order: the moves are left to kv_fill_kernel (meta[1] = their number)
 };
@@ -192,8 +192,10 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
     const long long base = (long long)hg * a.Lmax;
     const float *score = a.score + base;
     const uint8_t *kind = a.kind + base;
-    int L = min(a.len[hg], a.Lmax);
-    if (KPT > 0) L = min(L, NT * KPT);
+    // The launch (keys per thread, list sizes) was sized for heads of at most `bound` entries.  A head that is
+    // longer than the caller said is left exactly as it is: nothing evicted, length untouched.
+    const int len0 = a.len[hg];
+    const int L = len0 > a.bound ? 0 : len0;
     const bool budget_mode = a.mode == LVLM_KV_BUDGET;
 
     auto nothing_to_do = [&]() {
@@ -724,6 +726,7 @@ hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvW
     a.list_b = a.list_a + heads * d.Lmax;
     a.meta = reinterpret_cast<int32_t *>(ws + align_up(2 * heads * d.Lmax * sizeof(int32_t), 256));
     a.Hkv = d.Hkv; a.Lmax = d.Lmax;
+    a.bound = d.len_bound > 0 ? d.len_bound : d.Lmax;
     a.row_bytes = d.hd * (d.dtype == LVLM_BF16 ? 2 : 4);
     a.mode = d.mode; a.order = d.order; a.budget = d.budget; a.n_recent = d.n_recent; a.beta = d.beta;
     hipStream_t stream = prof.stream;

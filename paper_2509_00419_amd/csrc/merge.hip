@@ -266,8 +266,11 @@ __device__ __forceinline__ void gather_plane(const GatherArgs &a, const PlaneDev
             int dest = n < a.img_begin ? n : n - r;                  // rows outside the image span
             if (in_img) dest = code[x] >= 0 ? a.img_begin + code[x] : (code[x] == -1 && !weighted ? new_row : -1);
             if (valid && dest >= 0) *reinterpret_cast<U *>(dst + (long long)dest * p.row_bytes) = val[x];
+            // Only the rows of P_merged enter the sum (a kept or text row must not, whatever it holds: 0 * inf
+            // would poison the merged token).  A row is shared by whole waves for all but the narrowest planes,
+            // so the test is uniform there.
             if constexpr (DT != LVLM_I32) {
-                if (weighted) accumulate<DT, UB>(acc, val[x], valid && in_img ? wk[x] : 0.f);
+                if (weighted && valid && in_img && code[x] < 0) accumulate<DT, UB>(acc, val[x], wk[x]);
             }
         }
     }

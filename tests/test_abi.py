@@ -107,15 +107,18 @@ def test_argument_errors_are_reported_before_any_launch():
     assert st == 1 and b"together" in bd.lib.lvlm_last_error(ctx._h)
 
 
-def test_bench_launch_model_uses_the_library_constants():
-    """bench.py restates the library's rule for scoring in one launch (only to credit flops to the right kernel
-    name); its numbers must be the ones in the source of that rule."""
-    import inspect
-    import bench
-    src = open(os.path.join(os.path.dirname(bd.__file__), "csrc", "score.hip")).read()
-    const = {k: int(v) for k, v in re.findall(r"constexpr int (kSingleMaxChunks|kSharedMinWgs|kSingleMaxRows|kSharedMaxRows) = (\d+);", src)}
-    assert len(const) == 4
-    model = inspect.getsource(bench.score_in_one_launch)
-    assert f">= {const['kSharedMinWgs']} and rows <= {const['kSharedMaxRows']}" in model
-    assert f"n_chunks <= {const['kSingleMaxChunks']} and rows <= {const['kSingleMaxRows']}" in model
-    assert f"3 <= n_chunks <= {const['kSingleMaxChunks']}" in model
+def test_score_plan_reports_the_launch_form():
+    """lvlm_score_plan is the library's own launch decision (bench.py asks it instead of restating the rule)."""
+    ctx = _ctx()
+
+    def form(B, N, T, Hq, Hkv, n_img):
+        d = bd.ScoreDesc(bd.BF16, B, N, T, N - T, Hq, Hkv, 128, 0, n_img, 1, 0.088, T * Hq * 128, Hq * 128, 128,
+                         N * Hkv * 128, Hkv * 128, 128)
+        return ctx.score_plan(d)
+
+    assert form(1, 16512, 128, 48, 8, 16384) == 0          # one long sequence: two passes
+    assert form(1, 845, 64, 28, 4, 717) == 1               # one short sequence: one launch, a chunk per workgroup
+    assert form(64, 986, 96, 32, 8, 890) == 2              # many short sequences: shared key tiles
+    bad = bd.ScoreDesc(bd.BF16, 1, 100, 4, 96, 6, 4, 128, 0, 50, 1, 1.0, 0, 0, 128, 0, 0, 128)
+    with pytest.raises(lv.LvlmError):
+        ctx.score_plan(bad)

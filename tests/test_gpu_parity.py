@@ -228,6 +228,35 @@ def test_merge_compact_ties_and_special_scores(ctx):
     _merge_case(ctx, torch.float32, 2, 2, n_img, 2, 64, 123, score=s, seed=7)
 
 
+def test_merge_compact_non_finite_rows_outside_p_merged(ctx):
+    # Sec. 3.2.1: P_new = W_v x P_merged touches the r+1 merged rows only.  An inf / NaN in a kept image row, in a
+    # text row or in a system row must be copied as it is and must not leak into the merged token.
+    B, n_sys, n_img, n_txt, C, n_keep = 2, 3, 400, 5, 264, 150
+    N = n_sys + n_img + n_txt
+    for dtype in (torch.bfloat16, torch.float32):
+        hid = _rand((B, N, C), dtype, 130)
+        score = torch.rand(B, n_img, generator=torch.Generator().manual_seed(131))
+        order = torch.argsort(score, dim=1, descending=True)
+        for b in range(B):
+            kept = order[b, :n_keep - 1]
+            hid[b, n_sys + int(kept[0]), 7] = float("inf")
+            hid[b, n_sys + int(kept[5]), 0] = float("nan")
+            hid[b, n_sys + int(kept[-1]), C - 1] = float("-inf")
+        hid[:, 1, 3] = float("inf")                      # a system row
+        hid[:, N - 2, 100] = float("-inf")               # an instruction row
+        (out,), keep, merged = ctx.merge_compact([hid.to(DEV)], score.to(DEV), img_begin=n_sys, n_img=n_img, n_keep=n_keep)
+        (ref,), okeep, omerged = O.merge_compact([f64(hid)], score.numpy(), img_begin=n_sys, n_img=n_img, n_keep=n_keep,
+                                                 dtypes=["bf16" if dtype == torch.bfloat16 else "f32"])
+        assert np.array_equal(keep.cpu().numpy(), okeep) and np.array_equal(merged.cpu().numpy(), omerged)
+        got = f64(out.cpu())
+        new_row = n_sys + n_keep - 1
+        assert np.isfinite(got[:, new_row]).all() and np.isfinite(ref[:, new_row]).all()
+        assert rel_err(got[:, new_row], ref[:, new_row]) < TOL[dtype]
+        rest = np.ones(ref.shape[1], bool)
+        rest[new_row] = False
+        assert np.array_equal(got[:, rest], ref[:, rest], equal_nan=True)      # copied rows bit for bit, inf and NaN too
+
+
 def test_merge_compact_full_config2_stage_from_gpu_scores(ctx):
     # config 2, first merge layer at the 3 % schedule: 2048 -> 636, all planes a layer carries
     w = configs.CFG2
@@ -420,8 +449,93 @@ def test_decode_attn_shapes(ctx):
     _attn_case(ctx, torch.bfloat16, 2, 14, 2, 128, 1100, [1024, 37, 5, 700], 56, track=False)    # no importance
     _attn_case(ctx, torch.bfloat16, 2, 14, 2, 128, 4096, [1024, 37, 5, 700], 57, len_bound=1025)  # bound < Lmax
     _attn_case(ctx, torch.bfloat16, 1, 14, 2, 128, 9100, [9000, 8193], 58)                       # long cache: separate fold
-    for seed in (59, 60, 61):                                                                    # same shape again and again:
-        _attn_case(ctx, torch.bfloat16, 2, 14, 2, 128, 1100, [1024, 37, 0, 700], seed)           # the fold's tickets restart
+    for seed in (59, 60, 61):                                                                    # same shape, same workspace,
+        _attn_case(ctx, torch.bfloat16, 2, 14, 2, 128, 1100, [1024, 37, 0, 700], seed)           # again and again
+
+
+def test_decode_attn_heads_at_or_beyond_the_length_bound(ctx):
+    """The lengths live on the device, so a head can break the caller's len_bound promise without the host seeing
+    it (the fused eviction may find nothing to evict).  Such a head must be handled inside the bound: a full
+    head (len == bound) drops the new entry and attends to what it holds; a head longer than the bound attends to
+    its first `bound` entries; neither has its length, its cache or anything beyond the bound touched.  Heads that
+    keep the promise are unaffected.  Checked for the one-tile and several-tile forms, fp32, and with eviction."""
+    for dtype, d, Hq, Hkv, Lmax, bound, lens, budget in (
+            (torch.bfloat16, 128, 14, 2, 1100, 1025, [1025, 1040, 1024, 600], 0),      # 8 splits + the extra tile
+            (torch.bfloat16, 128, 14, 2, 1100, 1025, [1025, 1040, 1024, 600], 1024),   # ... with the fused eviction
+            (torch.bfloat16, 64, 8, 2, 700, 640, [640, 699, 639, 1], 0),               # whole 128-entry splits
+            (torch.float32, 64, 4, 4, 400, 300, [300, 350, 299, 17, 300, 301, 0, 128], 0),
+            (torch.bfloat16, 128, 4, 2, 5000, 4100, [4100, 4999, 4099, 2047], 4099)):  # long splits, eviction
+        B = len(lens) // Hkv
+        host = _cache(dtype, B, Hkv, Lmax, d, lens, 140)
+        q, kn, vn = _rand((B, Hq, d), dtype, 141), _rand((B, Hkv, d), dtype, 142), _rand((B, Hkv, d), dtype, 143)
+        dev = [t.to(DEV) for t in host]
+        out = ctx.decode_attn(q.to(DEV), kn.to(DEV), vn.to(DEV), *dev, score_decay=0.9, new_pos=9, len_bound=bound,
+                              evict_budget=budget, evict_recent=1)
+        got = [t.cpu() for t in dev]
+        G = Hq // Hkv
+        for b in range(B):
+            for h in range(Hkv):
+                n0 = lens[b * Hkv + h]
+                one = [f64(host[0][b:b + 1, h:h + 1]), f64(host[1][b:b + 1, h:h + 1]), host[2][b:b + 1, h:h + 1].numpy(),
+                       host[3][b:b + 1, h:h + 1].numpy(), host[4][b:b + 1, h:h + 1].numpy(),
+                       np.array([[min(n0, bound)]], dtype=np.int32)]
+                fits = n0 < bound
+                ref = O.decode_attn(f64(q[b:b + 1, h * G:(h + 1) * G]), f64(kn[b:b + 1, h:h + 1]) if fits else None,
+                                    f64(vn[b:b + 1, h:h + 1]) if fits else None, *one, score_decay=0.9, new_pos=9,
+                                    out_dtype="bf16" if dtype == torch.bfloat16 else "f32")
+                assert rel_err(f64(out[b, h * G:(h + 1) * G].cpu()), ref[0][0]) < TOL[dtype], (b, h)
+                n_att = int(ref[6][0, 0])
+                state = list(ref[1:])
+                if budget and n_att > budget and n0 <= bound:
+                    mid = [state[0], state[1], got[2][b:b + 1, h:h + 1].numpy().copy(), state[3], state[4], state[5]]
+                    # (the eviction is decided on the GPU's updated score bits; a slot already moved holds its
+                    # mover's score, so take the scores from a second, eviction-free call below)
+                    plain = [t.to(DEV) for t in host]
+                    ctx.decode_attn(q.to(DEV), kn.to(DEV), vn.to(DEV), *plain, score_decay=0.9, new_pos=9, len_bound=bound)
+                    mid[2] = plain[2][b:b + 1, h:h + 1].cpu().numpy()
+                    state = list(O.kv_compress(*mid, mode="budget", budget=n_att - 1, n_recent=1, order=O.ORDER_FILL)[:6])
+                    n_new = int(state[5][0, 0])
+                    assert int(got[5][b, h]) == n_new
+                    for i in (0, 1, 3, 4):
+                        want = state[i][0, 0, :n_new]
+                        have = got[i][b, h, :n_new]
+                        assert np.array_equal(f64(have) if i < 2 else have.numpy(), want), (b, h, i)
+                    assert np.array_equal(got[2][b, h, :n_new].numpy(), state[2][0, 0, :n_new])
+                else:
+                    # the length: grown by one where the entry fitted, else exactly what it was
+                    assert int(got[5][b, h]) == (n0 + 1 if fits else n0), (b, h)
+                    for i in (0, 1, 3, 4):
+                        want = state[i][0, 0, :n_att]
+                        have = got[i][b, h, :n_att]
+                        assert np.array_equal(f64(have) if i < 2 else have.numpy(), want), (b, h, i)
+                    if n_att:
+                        assert rel_err(got[2][b, h, :n_att].numpy(), state[2][0, 0, :n_att]) < 1e-5
+                # nothing at or beyond the attended entries was written (a dropped entry leaves no trace)
+                for i in range(5):
+                    assert torch.equal(got[i][b, h, n_att:], host[i][b, h, n_att:]), (b, h, i)
+
+
+def test_kv_compress_leaves_heads_beyond_the_length_bound_alone(ctx):
+    # a head longer than len_bound is not compressed at all (nothing evicted, nothing moved); the others are
+    host = _cache(torch.bfloat16, 2, 2, 3000, 64, [2000, 2500, 1999, 2049], 150)
+    for kw in (dict(mode=lv.KV_BUDGET, budget=1500, n_recent=1, order=lv.ORDER_FILL),
+               dict(mode=lv.KV_THRESHOLD, beta=0.9, order=lv.ORDER_STABLE)):
+        dev = [t.to(DEV) for t in host]
+        nev = ctx.kv_compress(*dev, len_bound=2000, **kw).cpu().numpy()
+        short = [t.clone() for t in host]
+        okw = dict(mode="threshold" if kw["mode"] == lv.KV_THRESHOLD else "budget", beta=kw.get("beta", 0.995),
+                   budget=kw.get("budget", 0), n_recent=kw.get("n_recent", 0), order=kw["order"])
+        ref = O.kv_compress(f64(short[0]), f64(short[1]), short[2].numpy(), short[3].numpy(), short[4].numpy(),
+                            short[5].numpy(), **okw)
+        for b, h in ((0, 1), (1, 1)):                                  # 2500 and 2049 entries: beyond the bound
+            assert nev[b, h] == 0 and int(dev[5][b, h]) == int(host[5][b, h])
+            for i in range(5):
+                assert torch.equal(dev[i][b, h].cpu(), host[i][b, h])
+        for b, h in ((0, 0), (1, 0)):
+            n = int(ref[5][b, h])
+            assert int(dev[5][b, h]) == n and nev[b, h] == ref[6][b, h] and n < int(host[5][b, h])
+            assert np.array_equal(dev[4][b, h, :n].cpu().numpy(), ref[4][b, h, :n])
+            assert np.array_equal(f64(dev[0][b, h, :n]), ref[0][b, h, :n])
 
 
 def test_decode_attn_config4_layer_step(ctx):
