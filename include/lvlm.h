@@ -397,6 +397,23 @@ LVLM_API lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_at
                              void *k_cache, void *v_cache, float *score, uint8_t *kind,
                              int32_t *orig_pos, int32_t *len, void *out);
 
+/* The same call for callers that cannot allocate device memory or attach a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Arguments, results and error behaviour are those of
+ * lvlm_decode_attn; the scratch (split partials, per-entry logits, lengths)
+ * lives in a fixed array inside the library, LVLM_STATIC_SCRATCH_BYTES per GPU,
+ * held from the first such call on that GPU until the process ends.  The
+ * context's workspace is neither needed nor touched.  A shape whose scratch
+ * (lvlm_workspace_bytes with LVLM_OP_DECODE_ATTN) exceeds the array is refused
+ * with LVLM_ERR_WORKSPACE before anything is launched.  The call itself calls no
+ * hipMalloc / hipFree.  All calls on one GPU share that GPU's array: calls that
+ * may overlap in time (different streams, different threads) race; order them. */
+#define LVLM_STATIC_SCRATCH_BYTES (8u << 20)
+LVLM_API lvlm_status lvlm_decode_attn_static(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *d,
+                                    const void *q, const void *k_new, const void *v_new,
+                                    void *k_cache, void *v_cache, float *score, uint8_t *kind,
+                                    int32_t *orig_pos, int32_t *len, void *out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -119,13 +119,14 @@ def _load():
     lib.lvlm_merge_similar.argtypes = [vp, vp, C.POINTER(MergeDesc), f32p, C.POINTER(Plane), f32p, f32p, i32p, i32p]
     lib.lvlm_kv_compress.argtypes = [vp, vp, C.POINTER(KvDesc), vp, vp, f32p, vp, i32p, i32p, i32p]
     lib.lvlm_decode_attn.argtypes = [vp, vp, C.POINTER(AttnDesc), vp, vp, vp, vp, vp, f32p, vp, i32p, i32p, vp]
+    lib.lvlm_decode_attn_static.argtypes = lib.lvlm_decode_attn.argtypes
     lib.lvlm_profile.argtypes = [C.c_void_p, C.c_int]
     lib.lvlm_profile_read.argtypes = [C.c_void_p, C.POINTER(ProfileEntry), C.c_int, C.POINTER(C.c_int)]
     for name in ("lvlm_profile", "lvlm_profile_read", "lvlm_create", "lvlm_destroy", "lvlm_workspace_bytes", "lvlm_set_workspace", "lvlm_schedule",
                  "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_score_plan", "lvlm_score_from_probs", "lvlm_prefill_attn", "lvlm_merge_compact",
                  "lvlm_merge_similar",
                  "lvlm_kv_compress",
-                 "lvlm_decode_attn"):
+                 "lvlm_decode_attn", "lvlm_decode_attn_static"):
         getattr(lib, name).restype = C.c_int
     return lib
 
@@ -366,8 +367,9 @@ class Context:
     # ---- step 6 ----
     def decode_attn(self, q, k_new, v_new, k_cache, v_cache, score, kind, orig_pos, length, *, scale=None,
                     score_decay=1.0, new_kind=KIND_GENERATED, new_pos=0, len_bound=0, evict_budget=0, evict_recent=0,
-                    out=None, reserve=True):
-        """lvlm_decode_attn.  q [B,Hq,d], k_new/v_new [B,Hkv,d] or None -> out [B,Hq,d]."""
+                    out=None, reserve=True, static_scratch=False):
+        """lvlm_decode_attn.  q [B,Hq,d], k_new/v_new [B,Hkv,d] or None -> out [B,Hq,d].
+        static_scratch: lvlm_decode_attn_static instead (the library's own fixed scratch array, no workspace)."""
         B, Hq, hd = q.shape
         _, Hkv, Lmax, _ = k_cache.shape
         assert q.is_contiguous() and k_cache.is_contiguous() and v_cache.is_contiguous()
@@ -375,9 +377,9 @@ class Context:
                      float(hd ** -0.5 if scale is None else scale), float(score_decay), evict_budget, evict_recent)
         if out is None:
             out = torch.empty_like(q)
-        if reserve:
+        if reserve and not static_scratch:
             self.reserve(self.workspace_bytes(OP_DECODE_ATTN, d))
-        self._check(lib.lvlm_decode_attn(self._h, _stream(), C.byref(d), _ptr(q), _ptr(k_new), _ptr(v_new),
-                                         _ptr(k_cache), _ptr(v_cache), _ptr(score), _ptr(kind), _ptr(orig_pos),
-                                         _ptr(length), _ptr(out)))
+        call = lib.lvlm_decode_attn_static if static_scratch else lib.lvlm_decode_attn
+        self._check(call(self._h, _stream(), C.byref(d), _ptr(q), _ptr(k_new), _ptr(v_new),
+                        _ptr(k_cache), _ptr(v_cache), _ptr(score), _ptr(kind), _ptr(orig_pos), _ptr(length), _ptr(out)))
         return out

@@ -458,7 +458,7 @@ lvlm_status lvlm_kv_compress(lvlm_ctx *ctx, void *stream, const lvlm_kv_desc *d,
                                                 k_cache, v_cache, score, kind, orig_pos, len, n_evicted));
 }
 
-lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *d, const void *q, const void *k_new,
+static lvlm_status decode_attn_call(lvlm_ctx *ctx, bool static_scratch, void *stream, const lvlm_attn_desc *d, const void *q, const void *k_new,
                              const void *v_new, void *k_cache, void *v_cache, float *score, uint8_t *kind,
                              int32_t *orig_pos, int32_t *len, void *out) {
     if (!ctx) return LVLM_ERR_INVALID_ARG;
@@ -476,10 +476,35 @@ lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *
         !aligned16(score) || !aligned16(kind) || !aligned16(orig_pos) || !aligned16(len) || !aligned16(out))
         return fail(ctx, LVLM_ERR_INVALID_ARG, "decode_attn: pointers must be 16-byte aligned");
     const AttnWs w = attn_ws(*d);
-    if (lvlm_status st = need_ws(ctx, w.total)) return st;
-    if (lvlm_status st = bind_device(ctx)) return st;
-    return after_launch(ctx, launch_decode_attn(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w, static_cast<char *>(ctx->ws),
+    char *ws = static_cast<char *>(ctx->ws);
+    if (static_scratch) {
+        // the fixed array inside the library instead of the caller's workspace: nothing is allocated here
+        if (w.total > (size_t)LVLM_STATIC_SCRATCH_BYTES)
+            return fail(ctx, LVLM_ERR_WORKSPACE,
+                        "decode_attn_static: this shape needs %zu bytes of scratch, the built-in array holds %zu "
+                        "(use lvlm_decode_attn with a workspace)", w.total, (size_t)LVLM_STATIC_SCRATCH_BYTES);
+        if (lvlm_status st = bind_device(ctx)) return st;
+        size_t have = 0;
+        const hipError_t e = attn_static_scratch(ctx->device, &ws, &have);
+        if (e != hipSuccess) return fail(ctx, LVLM_ERR_HIP, "decode_attn_static: scratch array: %s", hipGetErrorString(e));
+    } else {
+        if (lvlm_status st = need_ws(ctx, w.total)) return st;
+        if (lvlm_status st = bind_device(ctx)) return st;
+    }
+    return after_launch(ctx, launch_decode_attn(Prof{ctx, static_cast<hipStream_t>(stream)}, *d, w, ws,
                                                 q, k_new, v_new, k_cache, v_cache, score, kind, orig_pos, len, out));
+}
+
+lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *d, const void *q, const void *k_new,
+                             const void *v_new, void *k_cache, void *v_cache, float *score, uint8_t *kind,
+                             int32_t *orig_pos, int32_t *len, void *out) {
+    return decode_attn_call(ctx, false, stream, d, q, k_new, v_new, k_cache, v_cache, score, kind, orig_pos, len, out);
+}
+
+lvlm_status lvlm_decode_attn_static(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *d, const void *q,
+                                    const void *k_new, const void *v_new, void *k_cache, void *v_cache, float *score,
+                                    uint8_t *kind, int32_t *orig_pos, int32_t *len, void *out) {
+    return decode_attn_call(ctx, true, stream, d, q, k_new, v_new, k_cache, v_cache, score, kind, orig_pos, len, out);
 }
 
 }  // extern "C"

@@ -117,6 +117,10 @@ hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const A
                               void *v_cache, float *score, uint8_t *kind, int32_t *orig_pos,
                               int32_t *len, void *out);
 
+// Device address and size of the fixed scratch array that lvlm_decode_attn_static uses on the current device
+// (looked up once per device; no allocation).
+hipError_t attn_static_scratch(int device, char **ptr, size_t *bytes);
+
 #if defined(__HIPCC__)
 // ---- device helpers ----
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
