@@ -55,10 +55,10 @@ def same_entries(now, ref, exact_score=True, tol=1e-5):
                 assert rel_err(now[2][b, h, :n], ref[2][b, h, :n]) < tol, (b, h)
 
 
-def build(w, given_lse=False):
+def build(w, given_lse=False, prefill_order="fill"):
     layers = bench.plan(w, lv)
     master = bench.build_master(w, layers, torch, synth, DEV, given_lse)
-    return layers, master, bench.StepState(w, layers, master, torch, given_lse=given_lse)
+    return layers, master, bench.StepState(w, layers, master, torch, prefill_order=prefill_order, given_lse=given_lse)
 
 
 def layer_slices(st, i, B):
@@ -117,42 +117,111 @@ def test_prefill_and_decode_step_in_bench_configuration(name, every_layer, given
     assert n_merges == 3
 
     # ---- prefill, threshold compression of the caches of all compressed layers in one call, on the GPU's
-    # score bits
+    # score bits (holes filled from the tail: the order the bench runs by default)
     compressed = [i for i in sample if layers[i]["kv_threshold"]]
     before = {i: snapshot(*layer_slices(st, i, B)) for i in compressed}
     bench.run_prefill_compress(ctx, lv, w, st, reserve=True)
     torch.cuda.synchronize()
     shrunk = False
     for i in compressed:
-        ref = O.kv_compress(*before[i], mode="threshold", beta=w.kv_beta, order=O.ORDER_STABLE)
+        ref = O.kv_compress(*before[i], mode="threshold", beta=w.kv_beta, order=O.ORDER_FILL)
         now = snapshot(*layer_slices(st, i, B))
         same_entries(now, ref[:6])
         assert np.array_equal(st.n_evicted[i * B:(i + 1) * B].cpu().numpy(), ref[6])
         shrunk = shrunk or bool((now[5] < before[i][5]).any())
     assert shrunk
 
-    # ---- one decode step: attention layer by layer, then the budget eviction of all caches in one call
-    assert not bench.decode_evicts_in_attention(w, st)
+    # ---- prefill, last call: every cache of every layer down to the budget before generation starts
     before = {i: snapshot(*layer_slices(st, i, B)) for i in sample}
-    bench.run_decode_layers(ctx, lv, w, st, reserve=True)
-    torch.cuda.synchronize()
-    mid = {i: snapshot(*layer_slices(st, i, B)) for i in sample}
-    for i in sample:
-        m = master[i]
-        ref = O.decode_attn(f64(m["q_dec"]), f64(m["k_dec"]), f64(m["v_dec"]), *before[i], score_decay=0.9,
-                            new_pos=w.seq_len, out_dtype="bf16")
-        assert rel_err(f64(st[i].out_dec), ref[0]) < tol, i
-        same_entries(mid[i], list(ref[1:]), exact_score=False)
-    bench.run_decode_compress(ctx, lv, w, st, reserve=True)
+    bench.run_prefill_budget(ctx, lv, w, st, reserve=True)
     torch.cuda.synchronize()
     for i in sample:
         now = snapshot(*layer_slices(st, i, B))
         if w.kv_budget > 0:
-            ref = O.kv_compress(*mid[i], mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
+            ref = O.kv_compress(*before[i], mode="budget", budget=w.kv_budget, n_recent=0, order=O.ORDER_FILL)
             same_entries(now, ref[:6])
             assert int(now[5].max()) <= w.kv_budget
         else:
-            same_entries(now, mid[i])
+            same_entries(now, before[i])
+    if name in ("cfg5", "cfg6"):
+        # shallow layers full, deep ones short: what the pyramid and the threshold rule left of 492 + text entries
+        assert int(st.len.max()) == w.kv_budget and 128 < int(st.len.min()) <= 492 + w.n_text
+
+    # ---- the first decode step after prefill: attention layer by layer with the eviction of one entry inside the
+    # call where a head is over its budget afterwards (else one budget eviction over all caches, which finds
+    # nothing to do where the budget does not bind).  The same calls without eviction on copies of the sampled
+    # layers give the GPU's updated score bits for the oracle to evict on.
+    fused = bench.decode_evicts_in_attention(w, st)
+    assert fused == (name in ("cfg5", "cfg6"))
+    before, mid = {}, {}
+    for i in sample:
+        L, m = st[i], master[i]
+        before[i] = snapshot(*layer_slices(st, i, B))
+        cp = [t.clone() for t in layer_slices(st, i, B)]
+        plain = ctx.decode_attn(L.q_dec, L.k_dec, L.v_dec, *cp, score_decay=0.9, new_pos=w.seq_len, len_bound=L.dec_bound)
+        torch.cuda.synchronize()
+        mid[i] = (snapshot(*cp), plain)
+        ref = O.decode_attn(f64(m["q_dec"]), f64(m["k_dec"]), f64(m["v_dec"]), *before[i], score_decay=0.9,
+                            new_pos=w.seq_len, out_dtype="bf16")
+        assert rel_err(f64(plain), ref[0]) < tol, i
+        same_entries(mid[i][0], list(ref[1:]), exact_score=False)
+    bench.run_decode(ctx, lv, w, st, reserve=True)
+    torch.cuda.synchronize()
+    for i in sample:
+        assert torch.equal(st[i].out_dec, mid[i][1]), i
+        now = snapshot(*layer_slices(st, i, B))
+        if w.kv_budget > 0:
+            ref = O.kv_compress(*mid[i][0], mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
+            same_entries(now, ref[:6])
+            assert int(now[5].max()) <= w.kv_budget
+        else:
+            same_entries(now, mid[i][0])
+
+
+def test_steady_state_caches_of_config5_and_one_step_on_them():
+    """The decode phase the bench times at config 5: caches that the path itself filled to the budget (1428 decode
+    steps with eviction run forward from the prefilled state on every layer), then one more step, checked on the
+    first and the last layer against the oracle applied to the GPU state just before it."""
+    w = configs.CFG5
+    ctx = lv.Context(0)
+    layers, master, st = build(w)
+    bench.run_prefill(ctx, lv, w, st, reserve=True)
+    torch.cuda.synchronize()
+    shortest = int(st.len.min())
+    assert 128 < shortest <= 492 + w.n_text
+    steady = bench.SteadyState.from_prefilled(w, torch, synth, ctx, lv, st)
+    assert steady.steps_run == w.kv_budget - shortest
+    assert int(steady.len.min()) == w.kv_budget == int(steady.len.max())
+    assert bench.decode_evicts_in_attention(w, steady)
+    B = w.batch
+    # generated entries have displaced image entries in the deep layers, protected text entries are all still there
+    for i in (0, len(layers) - 1):
+        kinds = steady[i].kind[:, :, :w.kv_budget]
+        assert int((kinds == lv.KIND_PROTECTED).sum()) == B * w.n_kv_heads * w.n_text
+    assert int((steady[len(layers) - 1].kind[:, :, :w.kv_budget] == lv.KIND_GENERATED).sum()) > 0
+    sample = (0, len(layers) - 1)
+    before, mid = {}, {}
+    for i in sample:
+        L = steady[i]
+        state = (L.k, L.v, L.score, L.kind, L.pos, L.len)
+        before[i] = snapshot(*state)
+        cp = [t.clone() for t in state]
+        plain = ctx.decode_attn(L.q_dec, L.k_dec, L.v_dec, *cp, score_decay=0.9, new_pos=w.seq_len + steady.steps_run + 1,
+                                len_bound=w.kv_budget + 1)
+        torch.cuda.synchronize()
+        mid[i] = (snapshot(*cp), plain)
+        ref = O.decode_attn(f64(L.q_dec), f64(L.k_dec), f64(L.v_dec), *before[i], score_decay=0.9,
+                            new_pos=w.seq_len + steady.steps_run + 1, out_dtype="bf16")
+        assert rel_err(f64(plain), ref[0]) < 2e-2, i
+        same_entries(mid[i][0], list(ref[1:]), exact_score=False)
+    bench.run_decode(ctx, lv, w, steady, reserve=True, step_pos=steady.steps_run + 1)
+    torch.cuda.synchronize()
+    for i in sample:
+        L = steady[i]
+        assert torch.equal(L.out_dec, mid[i][1])
+        ref = O.kv_compress(*mid[i][0], mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
+        same_entries(snapshot(L.k, L.v, L.score, L.kind, L.pos, L.len), ref[:6])
+    assert int(steady.len.min()) == w.kv_budget == int(steady.len.max())
 
 
 def test_config4_step_in_bench_configuration():

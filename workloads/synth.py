@@ -141,3 +141,19 @@ class DecodeStream:
         k = self.mean + torch.randn(B, H, d, generator=self.g, device=self.device)
         v = torch.randn(B, H, d, generator=self.g, device=self.device)
         return q.to(dt), k.to(dt), v.to(dt)
+
+    def many(self, n: int):
+        """n consecutive steps drawn in one go: q [n,B,Hq,d], k, v [n,B,Hkv,d].  The same law as n calls of
+        next() and the running mean carries on, but the draws come in another order, so the values are not
+        those n calls would give."""
+        w, dt = self.w, TORCH_DTYPE[self.w.dtype]
+        B, H, d, G = w.batch, w.n_kv_heads, w.head_dim, w.group
+        mean = self.mean[None].expand(n, B, H, d)
+        if w.drift_sigma > 0:
+            walk = torch.cumsum(w.drift_sigma * torch.randn(n, B, H, d, generator=self.g, device=self.device), dim=0)
+            mean = mean + walk
+            self.mean = mean[-1].clone()
+        q = mean.repeat_interleave(G, dim=2) + torch.randn(n, B, H * G, d, generator=self.g, device=self.device)
+        k = mean + torch.randn(n, B, H, d, generator=self.g, device=self.device)
+        v = torch.randn(n, B, H, d, generator=self.g, device=self.device)
+        return q.to(dt), k.to(dt), v.to(dt)
