@@ -61,21 +61,28 @@ struct AttnArgs {
     char *out;
     float *part_ml;     // [B*Hkv][n_split][GP][2]
     float *part_o;      // [B*Hkv][n_split][GP][HD]
-    float *logits;      // [B*Hkv][Lcap][GP]  log2-domain logits of every entry and head
+    float *logits;      // [B*Hkv][GP][Lcap]  log2-domain logits of every head and entry (Lcap: whole tiles)
     int32_t *cur_len;   // [B*Hkv][2]  entries attended to; flags (kAppended, kTruncated)
     int Hq, Hkv, G, Lmax, Lcap, bound, n_split, split_len, append, new_kind, new_pos, update_score;
     int evict_budget, evict_recent;
+    int tail_entry;     // the last split's wave 0 also takes the single entry at slot n_split * split_len
     float scale_log2, decay;
 };
 
 
-// One operand fragment of the P.V product: 8 probabilities as bf16 (round-to-nearest-even).
+// One operand fragment of the P.V product: 8 probabilities as bf16 (round-to-nearest-even, the packed conversion
+// instruction of this chip: one instruction per pair).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
+}
 __device__ __forceinline__ bf16x8 pack_bf16x8(const float *p) {
     uint4 u;
-    u.x = (uint32_t)f32_to_bf16(p[0]) | ((uint32_t)f32_to_bf16(p[1]) << 16);
-    u.y = (uint32_t)f32_to_bf16(p[2]) | ((uint32_t)f32_to_bf16(p[3]) << 16);
-    u.z = (uint32_t)f32_to_bf16(p[4]) | ((uint32_t)f32_to_bf16(p[5]) << 16);
-    u.w = (uint32_t)f32_to_bf16(p[6]) | ((uint32_t)f32_to_bf16(p[7]) << 16);
+    u.x = pack_bf16x2(p[0], p[1]);
+    u.y = pack_bf16x2(p[2], p[3]);
+    u.z = pack_bf16x2(p[4], p[5]);
+    u.w = pack_bf16x2(p[6], p[7]);
     return __builtin_bit_cast(bf16x8, u);
 }
 
@@ -219,13 +226,14 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         tmax = fmaxf(tmax, other_half(tmax));
         const float m_new = fmaxf(m_run, tmax);          // finite: the tile holds at least one entry
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        // (rows of a tile beyond the range lie beyond the head's length, and the logit rows are whole tiles
+        // long: the four consecutive entries of a register quad go out as one 16-byte word, masked or not)
         if (a.update_score && l32 < a.G) {
-            float *lg = a.logits + (long long)hg * a.Lcap * GP + l32;
+            float *lg = a.logits + ((long long)hg * GP + l32) * a.Lcap + j0 + 4 * hf;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int j = j0 + acc_row(r, hf);
-                if (j < s_hi) lg[(long long)j * GP] = acc[r];
-            }
+            for (int r4 = 0; r4 < 4; ++r4)
+                *reinterpret_cast<float4 *>(lg + 8 * r4) =
+                    make_float4(acc[4 * r4], acc[4 * r4 + 1], acc[4 * r4 + 2], acc[4 * r4 + 3]);
         }
         float p[16];
         float psum = 0.f;
@@ -337,10 +345,17 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 // row, so the loads are as coalesced as a row copy -- and turns its 8 x CPL block around in registers
 // (byte permutes) into the CPL operands "8 entries of one channel".  Output block nb, row l16 is then
 // channel CPL l16 + nb.
+// The queries are requested first, then K, then V: loads come back in the order they went out, so the
+// logits and the softmax of a tile run while its V rows are still on the way.
 // MULTI: a wave may have several tiles (splits longer than 128 entries) and requests the next one while it
-// works on the current one.  With 128 channels the kernel is built for two workgroups per CU: squeezed
-// into the register budget of three it spills and measured slower.
-template <int HD, int GP, bool MULTI>
+// works on the current one; with one tile per wave there is no running maximum to rescale by.
+// TAIL: whole 128-entry splits plus exactly one more entry (steady-state decode: a cache at its budget
+// plus the entry just appended).  That entry is not worth a tile pass of every workgroup: wave 0 of the last
+// split takes it by itself after its tile -- its K row fills every row of one more A operand, so each lane
+// has the logit of its head, and its V row is accumulated on the vector ALU.
+// With 128 channels the kernel is built for two workgroups per CU: squeezed into the register budget of
+// three it spills and measured slower.
+template <int HD, int GP, bool MULTI, bool TAIL>
 __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kernel(AttnArgs a) {
     constexpr int ROWB = HD * 2;
     constexpr int UPR = ROWB / 16;
@@ -348,6 +363,7 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
     constexpr int NB = HD / 16;           // output blocks = channels per lane (CPL)
     constexpr int VW = NB / 2;            // 32-bit words of V per lane and entry
     using vrow_t = typename std::conditional<VW == 4, uint4, uint2>::type;
+    static_assert(!(MULTI && TAIL), "the single extra entry goes with one-tile waves");
 
     __shared__ float wm[4][GP], wl[4][GP];
     __shared__ __attribute__((aligned(16))) float wo[4][GP][HD];
@@ -362,6 +378,16 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
     const int s_lo = split * a.split_len;
     const int j_first = s_lo + 32 * wave;
     auto v_entry = [&](int s) { return 16 * (s >> 2) + 4 * kg + (s & 3); };   // entry (within the tile) of slot s
+
+    uint4 qf[QV];
+    if (l16 < a.G) {
+        const char *src = a.q + ((long long)b * a.Hq + g * a.G + l16) * ROWB + 16 * kg;
+#pragma unroll
+        for (int i = 0; i < QV; ++i) qf[i] = *reinterpret_cast<const uint4 *>(src + 64 * i);
+    } else {
+#pragma unroll
+        for (int i = 0; i < QV; ++i) qf[i] = make_uint4(0, 0, 0, 0);
+    }
 
     uint4 kf[2][QV];
     vrow_t vv[8];
@@ -384,20 +410,26 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
     };
     if (j_first < a.Lmax) load_tile(j_first);
 
-    uint4 qf[QV];
-    if (l16 < a.G) {
-        const char *src = a.q + ((long long)b * a.Hq + g * a.G + l16) * ROWB + 16 * kg;
-#pragma unroll
-        for (int i = 0; i < QV; ++i) qf[i] = *reinterpret_cast<const uint4 *>(src + 64 * i);
-    } else {
-#pragma unroll
-        for (int i = 0; i < QV; ++i) qf[i] = make_uint4(0, 0, 0, 0);
-    }
-
     const HeadLen hl = head_len(a.len[hg], a.bound, a.append);
     const int L = hl.L, new_slot = hl.new_slot;
     // the last split takes the remainder (only the form whose waves fetch a second tile can)
     const int s_hi = (MULTI && split == a.n_split - 1) ? L : min(L, s_lo + a.split_len);
+
+    // TAIL: the operands of the one entry beyond the whole splits, from the cache or, if it is the entry
+    // being appended, from k_new / v_new (the length is known by now; these loads queue behind the tile's)
+    const int jt = a.n_split * a.split_len;
+    const bool tail = TAIL && split == a.n_split - 1 && wave == 0 && jt < L;
+    uint4 kt[QV], tv[NB / 2];
+    if (tail) {
+        const bool fresh = jt == new_slot;
+        const char *ks = (fresh ? a.k_new + (long long)hg * ROWB : kc + (long long)jt * ROWB) + 16 * kg;
+        const char *vs = (fresh ? a.v_new + (long long)hg * ROWB : a.v + (cbase + jt) * ROWB) + 8 * NB * kg;
+#pragma unroll
+        for (int i = 0; i < QV; ++i) kt[i] = *reinterpret_cast<const uint4 *>(ks + 64 * i);
+#pragma unroll
+        for (int i = 0; i < NB / 2; ++i) tv[i] = *reinterpret_cast<const uint4 *>(vs + 16 * i);
+    }
+
     if (split == 0) {
         // the appended entry goes into the cache here; every reader below takes it from k_new / v_new
         if (new_slot >= 0) {
@@ -422,10 +454,13 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
     f32x4 oacc[NB];                         // O^T block nb: channels NB (4 kg + r) + nb, head l16
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) oacc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float *lg = a.logits + ((long long)hg * GP + l16) * a.Lcap;      // this lane's head, one float per entry
 
-    for (int j0 = j_first; j0 < s_hi; j0 += 128) {
+    // one tile (a branch, so that the first product starts from a constant zero) or a loop over the wave's tiles
+    for (int j0 = j_first; j0 < s_hi; j0 = MULTI ? j0 + 128 : s_hi) {
+        const bool whole = j0 + 32 <= s_hi;
         // the appended entry comes from k_new / v_new; rows beyond the range must not reach the MFMA
-        if (j0 + 32 > s_hi || (new_slot >= j0 && new_slot < j0 + 32)) {
+        if (!whole || (new_slot >= j0 && new_slot < j0 + 32)) {
 #pragma unroll
             for (int blk = 0; blk < 2; ++blk) {
                 if (j0 + 16 * blk + l16 == new_slot) {
@@ -443,7 +478,7 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
         }
         // this tile's V block, turned around: vt[nb][m] = channel nb of entries 2m and 2m+1.  With several
         // tiles per wave it is done now, before the next tile's loads overwrite vv; with one tile it waits
-        // until the logits are done, which keeps fewer registers alive at the same time.
+        // until the logits are done (the V rows arrive last).
         uint32_t vt[NB][4];
         auto turn = [&]() {
 #pragma unroll
@@ -473,24 +508,31 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
 
         float t[8];
         float tmax = -INFINITY;
+        if (whole) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int j = j0 + 16 * (i >> 2) + 4 * kg + (i & 3);
-            t[i] = (j < s_hi) ? acc[i >> 2][i & 3] * a.scale_log2 : -INFINITY;
-            tmax = fmaxf(tmax, t[i]);
-        }
-        tmax = fmaxf(tmax, other_row(tmax));
-        tmax = fmaxf(tmax, other_half(tmax));
-        const float m_new = fmaxf(m_run, tmax);          // finite: the tile holds at least one entry
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        if (a.update_score && l16 < a.G) {
-            float *lg = a.logits + (long long)hg * a.Lcap * GP + l16;
+            for (int i = 0; i < 8; ++i) {
+                t[i] = acc[i >> 2][i & 3] * a.scale_log2;
+                tmax = fmaxf(tmax, t[i]);
+            }
+        } else {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int j = j0 + 16 * (i >> 2) + 4 * kg + (i & 3);
-                if (j < s_hi) lg[(long long)j * GP] = t[i];
+                t[i] = (j < s_hi) ? acc[i >> 2][i & 3] * a.scale_log2 : -INFINITY;
+                tmax = fmaxf(tmax, t[i]);
             }
         }
+        tmax = fmaxf(tmax, other_row(tmax));
+        tmax = fmaxf(tmax, other_half(tmax));
+        // a tile's rows beyond the range lie beyond the head's length, and the logit rows are whole tiles long:
+        // the four entries of a block a lane holds go out as one 16-byte word, masked or not
+        if (a.update_score && l16 < a.G) {
+#pragma unroll
+            for (int blk = 0; blk < 2; ++blk)
+                *reinterpret_cast<float4 *>(lg + j0 + 16 * blk + 4 * kg) =
+                    make_float4(t[4 * blk], t[4 * blk + 1], t[4 * blk + 2], t[4 * blk + 3]);
+        }
+        const float m_new = MULTI ? fmaxf(m_run, tmax) : tmax;    // finite: the tile holds at least one entry
         float p[8];
         float psum = 0.f;
 #pragma unroll
@@ -500,11 +542,16 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
         }
         psum += other_row(psum);
         psum += other_half(psum);
-        l_run = l_run * alpha + psum;
+        if (MULTI) {
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+            l_run = l_run * alpha + psum;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) oacc[nb] *= alpha;
+        } else {
+            l_run = psum;
+        }
         m_run = m_new;
         const bf16x8 pb = pack_bf16x8(p);
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) oacc[nb] *= alpha;
 
         if (!MULTI) turn();
 #pragma unroll
@@ -512,6 +559,31 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
             const bf16x8 va = __builtin_bit_cast(bf16x8, make_uint4(vt[nb][0], vt[nb][1], vt[nb][2], vt[nb][3]));
             oacc[nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb, oacc[nb], 0, 0, 0);
         }
+    }
+
+    if (TAIL && tail) {
+        f32x4 at = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < QV; ++i)
+            at = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kt[i]), __builtin_bit_cast(bf16x8, qf[i]),
+                                                         at, 0, 0, 0);
+        const float t = at[0] * a.scale_log2;        // every row of the operand was the same entry
+        if (a.update_score && l16 < a.G && kg == 0) lg[jt] = t;
+        const float m_new = fmaxf(m_run, t);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        const float p = __builtin_amdgcn_exp2f(t - m_new);
+        l_run = l_run * alpha + p;
+        m_run = m_new;
+        // the lane's channels NB (4 kg + r) + nb are the 4 NB consecutive ones from 4 NB kg on
+        const uint32_t *tw = reinterpret_cast<const uint32_t *>(tv);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const uint32_t w2 = tw[(NB * r + nb) >> 1];
+                const float v = __uint_as_float((nb & 1) ? (w2 & 0xffff0000u) : (w2 << 16));
+                oacc[nb][r] = fmaf(p, v, oacc[nb][r] * alpha);
+            }
     }
 
     // ---- fold the four waves
@@ -530,16 +602,20 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
     }
     __syncthreads();
     float *po = a.part_o + ((long long)hg * a.n_split + split) * GP * HD;
-    for (int idx = tid; idx < GP * HD; idx += 256) {
-        const int h = idx / HD, e = idx % HD;
+    for (int i4 = tid; i4 < GP * HD / 4; i4 += 256) {                  // four channels of one head per thread
+        const int h = i4 / (HD / 4), e = 4 * (i4 % (HD / 4));
         float mx = wm[0][h];
 #pragma unroll
         for (int w = 1; w < 4; ++w) mx = fmaxf(mx, wm[w][h]);
         const float ms = (mx == -INFINITY) ? 0.f : mx;
-        float sacc = 0.f;
+        float4 sacc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int w = 0; w < 4; ++w) sacc += wo[w][h][e] * __builtin_amdgcn_exp2f(wm[w][h] - ms);
-        po[idx] = sacc;
+        for (int w = 0; w < 4; ++w) {
+            const float wgt = __builtin_amdgcn_exp2f(wm[w][h] - ms);
+            const float4 x = *reinterpret_cast<const float4 *>(&wo[w][h][e]);
+            sacc.x += x.x * wgt; sacc.y += x.y * wgt; sacc.z += x.z * wgt; sacc.w += x.w * wgt;
+        }
+        *reinterpret_cast<float4 *>(po + 4 * i4) = sacc;
     }
     if (tid < GP) {
         float mx = wm[0][tid];
@@ -564,15 +640,27 @@ struct CombineLds {
     float m[GP], inv[GP];       // per head: max over the splits, 1 / normaliser
 };
 
-// Rebuilds the per-head normalisers of one (batch, KV head) from the splits' (max, sum) pairs.
-template <int GP, int NT>
-__device__ __forceinline__ void fold_normalisers(const AttnArgs &a, CombineLds<GP> &c, int hg) {
+// The fold kernels are chains of memory latencies, so each of them requests everything it will read --
+// the splits' (max, sum) pairs and partial outputs, the logits, importance and kind of its entries --
+// before it waits for anything; indices are clamped into the arrays instead of tested against the length,
+// which is itself still on its way.
+
+// (max, sum) pair `tid` of the head's n_split x GP pairs.
+template <int GP>
+__device__ __forceinline__ float2 load_pair(const AttnArgs &a, int hg) {
     const int tid = threadIdx.x;
     const float *pml = a.part_ml + (long long)hg * a.n_split * GP * 2;
-    for (int i = tid; i < a.n_split * GP; i += NT) {
-        const float2 ml = *reinterpret_cast<const float2 *>(pml + 2 * i);
-        c.pm[i / GP][i % GP] = ml.x;
-        c.pl[i / GP][i % GP] = ml.y;
+    return tid < a.n_split * GP ? *reinterpret_cast<const float2 *>(pml + 2 * tid) : make_float2(0.f, 0.f);
+}
+
+// Rebuilds the per-head normalisers of one (batch, KV head) from the splits' (max, sum) pairs.
+template <int GP, int NT>
+__device__ __forceinline__ void fold_normalisers(const AttnArgs &a, CombineLds<GP> &c, float2 ml) {
+    const int tid = threadIdx.x;
+    static_assert(NT >= kMaxSplit * GP, "one pair per thread");
+    if (tid < a.n_split * GP) {
+        c.pm[tid / GP][tid % GP] = ml.x;
+        c.pl[tid / GP][tid % GP] = ml.y;
     }
     __syncthreads();
     // Few splits: one thread per head walks them.  Many (up to 64): one wave per head, one lane per split, two wave
@@ -609,95 +697,85 @@ __device__ __forceinline__ void fold_normalisers(const AttnArgs &a, CombineLds<G
     __syncthreads();
 }
 
-// Folds the splits' partial outputs into the output rows of the head group.
-template <int DT, int HD, int GP, int NT>
-__device__ __forceinline__ void write_output(const AttnArgs &a, const CombineLds<GP> &c, int b, int g, int hg) {
-    const int tid = threadIdx.x;
-    const float *po = a.part_o + (long long)hg * a.n_split * GP * HD;
-    for (int idx = tid; idx < a.G * HD; idx += NT) {
-        const int h = idx / HD, e = idx % HD;
-        float acc = 0.f;
-        auto rounds = [&](auto width) {                    // W loads in flight per round
-            constexpr int W = decltype(width)::value;
-            for (int s0 = 0; s0 < a.n_split; s0 += W) {
-                float v[W];
+// Output element idx0 + tid (head idx / HD, channel idx % HD) of the head group: the first 16 splits' partial values.
+constexpr int kOutRegs = 16;
+template <int HD, int GP>
+__device__ __forceinline__ void load_output(const AttnArgs &a, int hg, int idx0, float (&v)[kOutRegs]) {
+    const int idx = min(idx0 + (int)threadIdx.x, a.G * HD - 1);
+    const int h = idx / HD, e = idx % HD;
+    const float *po = a.part_o + (long long)hg * a.n_split * GP * HD + (long long)h * HD + e;
 #pragma unroll
-                for (int u = 0; u < W; ++u)
-                    v[u] = s0 + u < a.n_split ? po[((long long)(s0 + u) * GP + h) * HD + e] : 0.f;
-#pragma unroll
-                for (int u = 0; u < W; ++u) acc += s0 + u < a.n_split ? v[u] * c.pl[s0 + u][h] : 0.f;
-            }
-        };
-        if (a.n_split <= 8) rounds(std::integral_constant<int, 8>{});
-        else rounds(std::integral_constant<int, 16>{});     // one round for up to 16 splits
-        acc *= c.inv[h];
-        const long long oi = ((long long)b * a.Hq + g * a.G + h) * HD + e;
-        if constexpr (DT == LVLM_BF16)
-            reinterpret_cast<uint16_t *>(a.out)[oi] = f32_to_bf16(acc);
-        else
-            reinterpret_cast<float *>(a.out)[oi] = acc;
-    }
+    for (int u = 0; u < kOutRegs; ++u) v[u] = u < a.n_split ? po[(long long)u * GP * HD] : 0.f;
 }
 
-// Importance update of the 1024 entries of one chunk, in two parts so that a caller can have the loads of
-// several chunks in flight before it needs the normalisers.
-template <int GP, int NT>
-struct ChunkRegs {
-    static constexpr int PER = 1024 / NT;     // entries per thread
-    float old[PER];
-    float lv[PER][GP];
-    uint8_t kd[PER];
+// Folds the splits' partial outputs into output elements [idx0, idx1) of the head group (one per thread).
+template <int DT, int HD, int GP, int NT>
+__device__ __forceinline__ void write_output(const AttnArgs &a, const CombineLds<GP> &c, int b, int g, int hg, int idx0,
+                                             int idx1, const float (&v)[kOutRegs]) {
+    static_assert(NT >= 8 * HD, "one output element per thread");
+    const int idx = idx0 + threadIdx.x;
+    if (idx >= idx1) return;
+    const int h = idx / HD, e = idx % HD;
+    float acc = 0.f;
+#pragma unroll
+    for (int u = 0; u < kOutRegs; ++u) acc = u < a.n_split ? fmaf(v[u], c.pl[u][h], acc) : acc;
+    const float *po = a.part_o + (long long)hg * a.n_split * GP * HD + (long long)h * HD + e;
+    for (int s0 = kOutRegs; s0 < a.n_split; s0 += kOutRegs) {           // long caches: further rounds of 16 loads
+        float x[kOutRegs];
+#pragma unroll
+        for (int u = 0; u < kOutRegs; ++u) x[u] = s0 + u < a.n_split ? po[(long long)(s0 + u) * GP * HD] : 0.f;
+#pragma unroll
+        for (int u = 0; u < kOutRegs; ++u) acc = s0 + u < a.n_split ? fmaf(x[u], c.pl[s0 + u][h], acc) : acc;
+    }
+    acc *= c.inv[h];
+    const long long oi = ((long long)b * a.Hq + g * a.G + h) * HD + e;
+    if constexpr (DT == LVLM_BF16)
+        reinterpret_cast<uint16_t *>(a.out)[oi] = f32_to_bf16(acc);
+    else
+        reinterpret_cast<float *>(a.out)[oi] = acc;
+}
+
+// What the importance update reads of one entry.
+template <int GP>
+struct EntryRegs {
+    float old;
+    float lv[GP];
+    uint8_t kd;
 };
 
-template <int GP, bool EVICT, int NT>
-__device__ __forceinline__ void load_chunk(const AttnArgs &a, int hg, int L, bool appended, int chunk,
-                                           ChunkRegs<GP, NT> &r) {
-    const int tid = threadIdx.x;
+template <int GP, bool EVICT>
+__device__ __forceinline__ void load_entry(const AttnArgs &a, int hg, int j, EntryRegs<GP> &r) {
     const long long cbase = (long long)hg * a.Lmax;
-    const float *lg = a.logits + (long long)hg * a.Lcap * GP;
+    const int jl = min(j, a.Lcap - 1), jc = min(j, a.Lmax - 1);
+    const float *lg = a.logits + (long long)hg * GP * a.Lcap + jl;
 #pragma unroll
-    for (int i = 0; i < 1024 / NT; ++i) {
-        const int j = chunk * 1024 + NT * i + tid;
-        r.old[i] = 0.f;
-        r.kd[i] = LVLM_KIND_PROTECTED;
-#pragma unroll
-        for (int h = 0; h < GP; ++h) r.lv[i][h] = 0.f;
-        if (j < L) {
-#pragma unroll
-            for (int h = 0; h < GP; ++h) r.lv[i][h] = lg[(long long)j * GP + h];
-            if (!(appended && j == L - 1)) r.old[i] = a.score[cbase + j];
-            if (EVICT) r.kd[i] = a.kind[cbase + j];
-        }
-    }
+    for (int h = 0; h < GP; ++h) r.lv[h] = h < a.G ? lg[(long long)h * a.Lcap] : 0.f;
+    r.old = a.score[cbase + jc];
+    r.kd = EVICT ? a.kind[cbase + jc] : (uint8_t)0;
 }
 
 // The stored logits become normalised probabilities.  With EVICT the least important evictable entry seen
 // so far is tracked in `best` (importance key in the high half, inverted slot in the low half: the minimum
 // is the lowest score, highest slot among equals).
-template <int GP, bool EVICT, int NT>
-__device__ __forceinline__ void apply_chunk(const AttnArgs &a, const CombineLds<GP> &c, int hg, int L, int chunk,
-                                            const ChunkRegs<GP, NT> &r, int recent_lo, unsigned long long &best,
+template <int GP, bool EVICT>
+__device__ __forceinline__ void apply_entry(const AttnArgs &a, const CombineLds<GP> &c, int hg, int L, bool appended,
+                                            int j, const EntryRegs<GP> &r, int recent_lo, unsigned long long &best,
                                             float *last_ns = nullptr) {
-    const int tid = threadIdx.x;
+    if (j >= L) return;
     const long long cbase = (long long)hg * a.Lmax;
-    const float inv_g = 1.0f / (float)a.G;
+    // (every product-sum is an explicit fused multiply-add: the two fold kernels must give the same bits)
+    float pm = 0.f;
 #pragma unroll
-    for (int i = 0; i < 1024 / NT; ++i) {
-        const int j = chunk * 1024 + NT * i + tid;
-        if (j < L) {
-            float pm = 0.f;
-#pragma unroll
-            for (int h = 0; h < GP; ++h)
-                if (h < a.G) pm += exp2f(r.lv[i][h] - c.m[h]) * c.inv[h];
-            const float ns = a.decay * r.old[i] + pm * inv_g;
-            a.score[cbase + j] = ns;
-            if (EVICT && j == L - 1) *last_ns = ns;          // the entry that fills the victim's slot
-            if (EVICT && r.kd[i] != LVLM_KIND_PROTECTED && j < recent_lo) {
-                const unsigned long long cand =
-                    ((unsigned long long)score_key(ns) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)j);
-                best = cand < best ? cand : best;
-            }
-        }
+    for (int h = 0; h < GP; ++h)
+        if (h < a.G) pm = fmaf(exp2f(r.lv[h] - c.m[h]), c.inv[h], pm);
+    const float old = (appended && j == L - 1) ? 0.f : r.old;        // the new entry starts from nothing
+    const float ns = fmaf(a.decay, old, pm * (1.0f / (float)a.G));
+    a.score[cbase + j] = ns;
+    if (EVICT && j == L - 1) *last_ns = ns;          // the entry that fills the victim's slot
+    if (EVICT && r.kd != LVLM_KIND_PROTECTED && j < recent_lo) {
+        const unsigned long long cand =
+            ((unsigned long long)score_key(ns) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)j);
+        best = cand < best ? cand : best;
     }
 }
 
@@ -709,34 +787,61 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(AttnArgs a) {
     __shared__ CombineLds<GP> c;
     const int g = blockIdx.y, b = blockIdx.z;
     const int hg = b * a.Hkv + g;
-    const int L = a.cur_len[2 * hg];
-    const bool appended = a.cur_len[2 * hg + 1] & kAppended;
-    fold_normalisers<GP, NT>(a, c, hg);
+    const float2 ml = load_pair<GP>(a, hg);
     if (blockIdx.x == 0) {
-        write_output<DT, HD, GP, NT>(a, c, b, g, hg);
+        float v[kOutRegs];
+        load_output<HD, GP>(a, hg, 0, v);
+        const int L = a.cur_len[2 * hg];
+        const bool appended = a.cur_len[2 * hg + 1] & kAppended;
+        fold_normalisers<GP, NT>(a, c, ml);
+        write_output<DT, HD, GP, NT>(a, c, b, g, hg, 0, a.G * HD, v);
         if (threadIdx.x == 0 && appended) a.len[hg] = L;
         return;
     }
+    const int j = (blockIdx.x - 1) * NT + threadIdx.x;
+    EntryRegs<GP> r;
+    load_entry<GP, false>(a, hg, j, r);
+    const int L = a.cur_len[2 * hg];
+    const bool appended = a.cur_len[2 * hg + 1] & kAppended;
+    fold_normalisers<GP, NT>(a, c, ml);
     unsigned long long unused = ~0ull;
-    ChunkRegs<GP, NT> r;
-    load_chunk<GP, false, NT>(a, hg, L, appended, blockIdx.x - 1, r);
-    apply_chunk<GP, false, NT>(a, c, hg, L, blockIdx.x - 1, r, 0, unused);
+    apply_entry<GP, false>(a, c, hg, L, appended, j, r, 0, unused);
 }
 
-// Per-step cache compression in the same launch as the fold (Sec. 3.2.2, steady state): one workgroup per
-// (batch, KV head) writes the output rows, updates every entry's importance, and, if the head is now
-// longer than evict_budget, evicts its least important evictable entry (not protected, not among the last
-// evict_recent slots): the last entry takes its slot, as LVLM_ORDER_FILL does.
-template <int DT, int HD, int GP>
-__global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a) {
+// Per-step cache compression in the same launch as the fold (Sec. 3.2.2, steady state).  A compute unit streams
+// only some tens of GB/s however many threads it runs, so what a (batch, KV head) pair has to read is spread
+// over several workgroups: n_out of them fold the splits' partial outputs into the output rows (a share of
+// the group's heads each), one more updates every entry's importance and, if the head is now longer than
+// evict_budget, evicts its least important evictable entry (not protected, not among the last evict_recent
+// slots): the last entry takes its slot, as LVLM_ORDER_FILL does.
+// NCH > 0: the head has at most 1024 NCH entries (the caller's bound) and a thread keeps its NCH entries in
+// registers, requested at the very start; NCH == 0: any length, 1024 entries at a time.
+template <int DT, int HD, int GP, int NCH>
+__global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a, int n_out) {
     constexpr int ROWB = HD * esize<DT>();
     constexpr int NT = 1024;
+    constexpr int NR = NCH > 0 ? NCH : 1;
     __shared__ CombineLds<GP> c;
     __shared__ unsigned long long w_best[NT / 64];
     __shared__ float last_ns;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int g = blockIdx.x, b = blockIdx.y;
+    const int g = blockIdx.y, b = blockIdx.z;
     const int hg = b * a.Hkv + g;
+    const float2 ml = load_pair<GP>(a, hg);
+    if ((int)blockIdx.x < n_out) {
+        // output elements [idx0, idx1): whole channels-of-a-head runs, at most 1024
+        const int per = (a.G * HD + n_out - 1) / n_out;
+        const int idx0 = blockIdx.x * per, idx1 = min(a.G * HD, idx0 + per);
+        float v[kOutRegs];
+        load_output<HD, GP>(a, hg, idx0, v);
+        fold_normalisers<GP, NT>(a, c, ml);
+        write_output<DT, HD, GP, NT>(a, c, b, g, hg, idx0, idx1, v);
+        return;
+    }
+    EntryRegs<GP> er[NR];
+#pragma unroll
+    for (int x = 0; x < NR; ++x) load_entry<GP, true>(a, hg, NT * x + tid, er[x]);
+
     const int L = a.cur_len[2 * hg];
     const int flags = a.cur_len[2 * hg + 1];
     const bool appended = flags & kAppended;
@@ -758,14 +863,17 @@ __global__ __launch_bounds__(1024) void attn_combine_evict_kernel(AttnArgs a) {
             last_pos = a.pos[last];
         }
     }
-    fold_normalisers<GP, NT>(a, c, hg);
-    write_output<DT, HD, GP, NT>(a, c, b, g, hg);
+    fold_normalisers<GP, NT>(a, c, ml);
     const int recent_lo = evict ? L - a.evict_recent : 0;      // nothing is a candidate when nothing is evicted
     unsigned long long best = ~0ull;
-    for (int chunk = 0; chunk * 1024 < L; ++chunk) {
-        ChunkRegs<GP, NT> r;
-        load_chunk<GP, true, NT>(a, hg, L, appended, chunk, r);
-        apply_chunk<GP, true, NT>(a, c, hg, L, chunk, r, recent_lo, best, &last_ns);
+#pragma unroll
+    for (int x = 0; x < NR; ++x) apply_entry<GP, true>(a, c, hg, L, appended, NT * x + tid, er[x], recent_lo, best, &last_ns);
+    if (NCH == 0) {
+        for (int j = NT + tid; j - tid < L; j += NT) {
+            EntryRegs<GP> r;
+            load_entry<GP, true>(a, hg, j, r);
+            apply_entry<GP, true>(a, c, hg, L, appended, j, r, recent_lo, best, &last_ns);
+        }
     }
     int new_len = L;
     if (evict) {
@@ -801,17 +909,28 @@ void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
     prof.begin("attn_partial");
     if constexpr (DT == LVLM_BF16)
     {
-        if (a.split_len > 128 || a.n_split * a.split_len < len_bound)      // some wave has a second tile
-            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, true>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
+        const dim3 grid(a.n_split, a.Hkv, B);
+        if (a.tail_entry)
+            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, false, true>), grid, dim3(256), 0, stream, a);
+        else if (a.split_len > 128 || a.n_split * a.split_len < len_bound)      // some wave has a second tile
+            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, true, false>), grid, dim3(256), 0, stream, a);
         else
-            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, false>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, false, false>), grid, dim3(256), 0, stream, a);
     }
     else
         hipLaunchKernelGGL((attn_partial_kernel<DT, HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
     prof.end();
     if (a.evict_budget > 0) {
         prof.begin("attn_combine_evict");
-        hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP>), dim3(a.Hkv, B), dim3(1024), 0, stream, a);
+        // output workgroups per head: as many as keep the launch within one round of the chip, at most one per
+        // query head of the group
+        int n_out = 256 / (a.Hkv * B) - 1;
+        n_out = n_out < 1 ? 1 : (n_out > a.G ? a.G : n_out);
+        const dim3 grid(n_out + 1, a.Hkv, B);
+        if (len_bound <= 1024) hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP, 1>), grid, dim3(1024), 0, stream, a, n_out);
+        else if (len_bound <= 2048) hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP, 2>), grid, dim3(1024), 0, stream, a, n_out);
+        else if (len_bound <= 3072) hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP, 3>), grid, dim3(1024), 0, stream, a, n_out);
+        else hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP, 0>), grid, dim3(1024), 0, stream, a, n_out);
         prof.end();
         return;
     }
@@ -850,17 +969,20 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     if (split_len < 128) split_len = 128;
     n_split = (bound + split_len - 1) / split_len;
     // A remainder of at most one tile beyond whole 128-entry splits (steady-state decode: budget + 1 entries)
-    // goes to the last split as one extra tile of one wave, instead of lengthening every split by a tile.
+    // does not lengthen every split by a tile: a single extra entry is taken by one wave of the last split on
+    // its own (tail_entry), a longer remainder goes to the last split as one extra tile of one wave.
     const int full = bound / 128;
+    w.tail_entry = 0;
     if (full >= 1 && want >= full && bound - 128 * full <= 32 && full <= 64) {
         n_split = full;
         split_len = 128;
+        w.tail_entry = d.dtype == LVLM_BF16 && bound - 128 * full == 1;
     }
     if (n_split < 1) n_split = 1;
     w.n_split = n_split;
     w.split_len = split_len;
     const int G = d.Hq / d.Hkv, gp = group_pad(G);
-    const int lcap = (bound + 3) / 4 * 4;
+    const int lcap = (bound + 31) / 32 * 32;       // whole tiles: a tile's logits are stored without a bound test
     w.part_ml = 0;
     w.part_o = align_up(w.part_ml + (size_t)heads * n_split * gp * 2 * sizeof(float), 256);
     w.logits = align_up(w.part_o + (size_t)heads * n_split * gp * d.hd * sizeof(float), 256);
@@ -916,7 +1038,7 @@ hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const A
     a.logits = reinterpret_cast<float *>(ws + w.logits);
     a.cur_len = reinterpret_cast<int32_t *>(ws + w.cur_len);
     a.Hq = d.Hq; a.Hkv = d.Hkv; a.G = G; a.Lmax = d.Lmax; a.Lcap = w.lcap; a.bound = bound;
-    a.n_split = w.n_split; a.split_len = w.split_len;
+    a.n_split = w.n_split; a.split_len = w.split_len; a.tail_entry = w.tail_entry;
     a.append = k_new != nullptr;
     a.new_kind = d.new_kind; a.new_pos = d.new_pos;
     a.update_score = score != nullptr;

@@ -73,7 +73,7 @@ KvWs kv_ws(const lvlm_kv_desc &d);
 
 struct AttnWs {
     size_t part_ml, part_o, logits, cur_len, total;
-    int n_split, split_len, lcap;
+    int n_split, split_len, lcap, tail_entry;
 };
 AttnWs attn_ws(const lvlm_attn_desc &d);
 
