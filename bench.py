@@ -553,9 +553,13 @@ def main():
     p0, l0 = sets[0].pos.clone(), sets[0].len.clone()
     run_prefill_compress(ctx, lv, w, sets[0], reserve=True)
     p1, l1 = sets[0].pos.clone(), sets[0].len.clone()
+    kept_fraction = None
     if sets[0].kv_from is not None:
         moved["threshold_scanned"] = int(l0[sets[0].kv_from:].sum())
         moved["threshold_moved"] = moved_entries(p0, p1, l1, torch)
+        # share of its image entries each compressed layer keeps under the one threshold (mean over heads)
+        kept_fraction = [round(float((st.len.double().mean() - w.n_sys - w.n_text) / st.n_img), 4)
+                         for st in sets[0] if st.entry["kv_threshold"]]
     run_prefill_budget(ctx, lv, w, sets[0], reserve=True)
     p2, l2 = sets[0].pos.clone(), sets[0].len.clone()
     if w.kv_budget > 0 and int(l1.max()) > w.kv_budget:
@@ -739,7 +743,8 @@ def main():
                                     f"{steady_steps} decode steps of the path during set-up)") if steady else
                                    ("steady state: every head at its budget as prefill leaves it" if fused else
                                     "caches as prefill leaves them (the budget does not bind)"),
-                   "eviction": "inside lvlm_decode_attn" if fused else "none needed"},
+                   "eviction": "inside lvlm_decode_attn" if fused else "none needed",
+                   "image_entries_kept_by_threshold_per_layer": kept_fraction},
         "prefill_ms": round(prefill_ms, 4), "decode_step_ms": round(decode_ms, 4),
         "prefill_image_tokens_per_s": round(w.batch * w.n_img / (prefill_ms * 1e-3), 1) if prefill_ms > 0 else None,
         "decode_steps_per_s": round(1e3 / decode_ms, 1),

@@ -409,6 +409,46 @@ def test_kv_compress_special_scores(ctx, order):
             assert np.array_equal(np.isnan(got), np.isnan(want)) and np.array_equal(got[~np.isnan(got)], want[~np.isnan(want)])
 
 
+def test_one_threshold_keeps_fewer_entries_the_deeper_the_layer(ctx):
+    """Sec. 3.2.2: one threshold beta for every layer keeps many entries where attention is spread out (shallow
+    layers) and few where it is concentrated (deep layers; Sec. 3.1, Fig. 2b).  Pilot-study shape (1476 image tokens
+    at every layer, concentration growing with depth): GPU scores, GPU compression at the paper's beta = 0.995, the
+    oracle deciding on the GPU's score bits -- kept sets identical, kept counts falling with depth in every head."""
+    w = configs.CFG7
+    N, H, d, img0 = w.seq_len, w.n_kv_heads, w.head_dim, w.n_sys
+    kept = []
+    for layer in (1, 9, 18, 27):
+        x = synth.layer_inputs(w, layer=layer)
+        Lmax = N + 8
+        kc = torch.zeros(1, H, Lmax, d, dtype=torch.bfloat16, device=DEV)
+        vc = torch.zeros_like(kc)
+        kc[:, :, :N] = x["k"].to(DEV).permute(0, 2, 1, 3)
+        vc[:, :, :N] = x["v"].to(DEV).permute(0, 2, 1, 3)
+        score = torch.zeros(1, H, Lmax, device=DEV)
+        ctx.score_tokens(x["q"].to(DEV), x["k"].to(DEV), q_pos0=img0 + w.n_img, img_begin=img0, n_img=w.n_img,
+                         score_head=score[:, :, img0:img0 + w.n_img])
+        osh, _ = O.score_tokens(f64(x["q"]), f64(x["k"]), q_pos0=img0 + w.n_img, img_begin=img0, n_img=w.n_img)
+        assert rel_err(score[:, :, img0:img0 + w.n_img].cpu(), osh) < 1e-5
+        kind = torch.zeros(1, H, Lmax, dtype=torch.uint8, device=DEV)
+        kind[:, :, img0:img0 + w.n_img] = lv.KIND_IMAGE
+        pos = torch.arange(Lmax, dtype=torch.int32, device=DEV).view(1, 1, Lmax).expand(1, H, Lmax).contiguous()
+        length = torch.full((1, H), N, dtype=torch.int32, device=DEV)
+        state = [kc, vc, score, kind, pos, length]
+        before = [f64(kc), f64(vc), score.cpu().numpy().copy(), kind.cpu().numpy(), pos.cpu().numpy(), length.cpu().numpy()]
+        ctx.kv_compress(*state, mode=lv.KV_THRESHOLD, beta=w.kv_beta, order=lv.ORDER_STABLE, len_bound=N)
+        ref = O.kv_compress(*before, mode="threshold", beta=w.kv_beta, order=O.ORDER_STABLE)
+        new_len = length.cpu().numpy()
+        assert np.array_equal(new_len, ref[5])
+        for h in range(H):
+            n = int(new_len[0, h])
+            assert np.array_equal(pos[0, h, :n].cpu().numpy(), ref[4][0, h, :n])          # the same entries, in order
+            assert np.array_equal(f64(kc[0, h, :n]), ref[0][0, h, :n])
+        kept.append(new_len[0] - (w.n_sys + w.n_text))                                    # image entries kept per head
+    kept = np.stack(kept)
+    assert (kept[:-1] > kept[1:]).all(), kept
+    assert kept[0].min() > 1.15 * kept[-1].max()
+
+
 # --------------------------------------------------------------------------- step 6
 def _attn_case(ctx, dtype, B, Hq, Hkv, d, Lmax, lens, seed, append=True, decay=0.9, track=True, len_bound=0):
     host = _cache(dtype, B, Hkv, Lmax, d, lens, seed)

@@ -84,6 +84,26 @@ def layer_inputs(w: Workload, layer: int = 0, n_img: int | None = None, device="
         mask.scatter_(1, (sal + w.n_sys)[:, :, None, None], 1.0)
         k = k + a * mask * u
         q = q + a * u.repeat_interleave(w.group, dim=2)
+    if w.concentration:
+        # Attention concentration that grows with depth (the paper's pilot study): every image token j gets a
+        # salience z_j (standard normal over the tokens) shared by all heads and all instruction rows.  Per KV head a unit direction u:
+        # the instruction queries get their component along u replaced by a = d^(1/4), the image keys get
+        # a * sigma(layer) * z_j * u added, so every (row, head) logit of token j is shifted by sigma * z_j and the
+        # attention the tokens receive is close to log-normal with spread sigma (linear in relative depth).
+        s0, s1 = w.concentration
+        sigma = s0 + (s1 - s0) * (layer / max(w.layers - 1, 1))
+        a = float(d) ** 0.25
+        u = torch.randn(B, 1, w.n_kv_heads, d, generator=g, device=device)
+        u = u / u.norm(dim=-1, keepdim=True)
+        # the saliences are the normal quantiles of an even grid, dealt to the tokens at random -- the same deal at
+        # every layer (a token that stands out early stands out later), so that only sigma changes with depth
+        gz = _gen(_mix(w.seed, 5, n_img), device)
+        grid = (torch.arange(n_img, device=device, dtype=torch.float64) + 0.5) / n_img
+        zq = torch.special.ndtri(grid).float()
+        z = torch.stack([zq[torch.randperm(n_img, generator=gz, device=device)] for _ in range(B)]).view(B, n_img, 1, 1)
+        k[:, w.n_sys:w.n_sys + n_img] = k[:, w.n_sys:w.n_sys + n_img] + a * sigma * z * u
+        uq = u.repeat_interleave(w.group, dim=2)
+        q = q - (q * uq).sum(dim=-1, keepdim=True) * uq + a * uq
     out = {"hidden": hidden, "q": q.to(dt).contiguous(), "k": k.to(dt).contiguous(),
            "pos": torch.arange(N, dtype=torch.int32, device=device).view(1, N, 1).expand(B, N, 1).contiguous()}
     if with_v:
