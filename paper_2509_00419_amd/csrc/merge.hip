@@ -6,7 +6,8 @@
 //                    the counting definition itself, spread over the chip:
 //                    64 tokens per workgroup, the keys staged in LDS and split
 //                    over the 16 waves.  Nothing iterative or data dependent.
-//   index_kernel     one workgroup per sequence: prefix-scans the "kept" flags
+//   index_kernel     one workgroup per 4096 tokens: counts the kept tokens in
+//                    front of its chunk, prefix-scans its own "kept" flags
 //                    in index order and emits
 //                    keep_idx (ascending), merged_idx (rank order) and, per
 //                    source token, where it goes (row of P_unmerged or its
@@ -105,88 +106,73 @@ struct IndexArgs {
     int n, n_keep;
 };
 
-// One workgroup per sequence.  Tokens are taken 16384 at a time as four coalesced 4096-token chunks
-// (thread t holds tokens 4t..4t+3 of each chunk, all loads issued together); one block-wide scan of the
-// four per-chunk counts gives every kept token its row in P_unmerged.  Then keep_idx (ascending),
-// merged_idx (by rank) and the per-token destination are written.
+// One workgroup per 4096 tokens of a sequence (thread t holds tokens 4t..4t+3 of its chunk).  The workgroup
+// first counts the kept tokens in front of its chunk -- a pass over the ranks before it, all loads in flight
+// together -- so the chunks need nothing from each other; one block-wide scan then gives every kept token its
+// row in P_unmerged.  Then keep_idx (ascending), merged_idx (by rank) and the per-token destination are written.
+constexpr int kIndexChunk = 4096;
 __global__ __launch_bounds__(1024) void index_kernel(IndexArgs a) {
-    constexpr int NC = 4;
-    __shared__ int wave_tot[NC][16];
-    __shared__ int base_s;
+    __shared__ int wave_tot[16], wave_before[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int b = blockIdx.x;
+    const int b = blockIdx.y;
+    const int s0 = blockIdx.x * kIndexChunk;
     const int n_unmerged = a.n_keep - 1;
     const int32_t *rank = a.rank + (long long)b * a.n;
     int32_t *dst_of = a.dst_of + (long long)b * a.n;
     float *wgt = a.wgt + (long long)b * a.n;
     const int m = a.n - n_unmerged;
-    if (tid == 0) base_s = 0;
+
+    // this chunk's ranks
+    int rk[4];
+    const int j0 = s0 + 4 * tid;
+    if (j0 + 3 < a.n && (a.n & 3) == 0) {
+        const int4 v = *reinterpret_cast<const int4 *>(rank + j0);
+        rk[0] = v.x; rk[1] = v.y; rk[2] = v.z; rk[3] = v.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) rk[e] = j0 + e < a.n ? rank[j0 + e] : 0x7fffffff;
+    }
+    // kept tokens before the chunk (s0 is a multiple of 4096: whole 16-byte words when the rows are aligned)
+    int before = 0;
+    if ((a.n & 3) == 0) {
+        for (int i = 4 * tid; i < s0; i += 4 * 1024) {
+            const int4 v = *reinterpret_cast<const int4 *>(rank + i);
+            before += (v.x < n_unmerged) + (v.y < n_unmerged) + (v.z < n_unmerged) + (v.w < n_unmerged);
+        }
+    } else {
+        for (int i = tid; i < s0; i += 1024) before += rank[i] < n_unmerged;
+    }
+    int cnt = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) cnt += rk[e] < n_unmerged;
+    int incl = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+        before += __shfl_xor(before, o);
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    if (lane == 0) wave_before[wave] = before;
     __syncthreads();
-    for (int s0 = 0; s0 < a.n; s0 += NC * 4096) {
-        int rk[NC][4];
-        int cnt[NC], incl[NC];
+    int p = incl - cnt;
 #pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            const int j = s0 + c * 4096 + 4 * tid;
-            if (j + 3 < a.n && (a.n & 3) == 0) {
-                const int4 v = *reinterpret_cast<const int4 *>(rank + j);
-                rk[c][0] = v.x; rk[c][1] = v.y; rk[c][2] = v.z; rk[c][3] = v.w;
-            } else {
+    for (int w = 0; w < 16; ++w) p += wave_before[w] + (w < wave ? wave_tot[w] : 0);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) rk[c][e] = j + e < a.n ? rank[j + e] : 0x7fffffff;
-            }
+    for (int e = 0; e < 4; ++e) {
+        const int j = j0 + e;
+        if (j >= a.n) continue;
+        if (rk[e] < n_unmerged) {
+            dst_of[j] = p;
+            wgt[j] = 0.f;
+            if (a.keep_idx) a.keep_idx[(long long)b * n_unmerged + p] = j;
+            ++p;
+        } else {
+            const int k = rk[e] - n_unmerged;
+            dst_of[j] = k == 0 ? -1 : -2;
+            wgt[j] = a.w ? a.w[k] : (float)(m - k) * a.lin_scale;
+            if (a.merged_idx) a.merged_idx[(long long)b * m + k] = j;
         }
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            cnt[c] = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) cnt[c] += rk[c][e] < n_unmerged;
-            incl[c] = cnt[c];
-        }
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-#pragma unroll
-            for (int c = 0; c < NC; ++c) {
-                const int t = __shfl_up(incl[c], o);
-                if (lane >= o) incl[c] += t;
-            }
-        }
-        if (lane == 63) {
-#pragma unroll
-            for (int c = 0; c < NC; ++c) wave_tot[c][wave] = incl[c];
-        }
-        __syncthreads();
-        int run = base_s;                    // kept tokens before this chunk
-#pragma unroll
-        for (int c = 0; c < NC; ++c) {
-            int p = run + incl[c] - cnt[c];
-            int chunk_tot = 0;
-            for (int w = 0; w < 16; ++w) {
-                const int t = wave_tot[c][w];
-                p += w < wave ? t : 0;
-                chunk_tot += t;
-            }
-            run += chunk_tot;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = s0 + c * 4096 + 4 * tid + e;
-                if (j >= a.n) continue;
-                if (rk[c][e] < n_unmerged) {
-                    dst_of[j] = p;
-                    wgt[j] = 0.f;
-                    if (a.keep_idx) a.keep_idx[(long long)b * n_unmerged + p] = j;
-                    ++p;
-                } else {
-                    const int k = rk[c][e] - n_unmerged;
-                    dst_of[j] = k == 0 ? -1 : -2;
-                    wgt[j] = a.w ? a.w[k] : (float)(m - k) * a.lin_scale;
-                    if (a.merged_idx) a.merged_idx[(long long)b * m + k] = j;
-                }
-            }
-        }
-        __syncthreads();
-        if (tid == 0) base_s = run;
-        __syncthreads();
     }
 }
 
@@ -417,7 +403,7 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
         ia.merged_idx = merged_idx;
         ia.n = d.n_img; ia.n_keep = d.n_keep;
         prof.begin("merge_index");
-        hipLaunchKernelGGL(index_kernel, dim3(d.B), dim3(1024), 0, stream, ia);
+        hipLaunchKernelGGL(index_kernel, dim3((d.n_img + kIndexChunk - 1) / kIndexChunk, d.B), dim3(1024), 0, stream, ia);
         prof.end();
     }
     prof.begin("merge_gather");
