@@ -76,7 +76,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run three plain 256 MiB device copies (a reference of known traffic for rocprofv3 --pmc)")
+                    help="also run three plain 1 GiB device copies (a reference of known traffic for rocprofv3 --pmc)")
     return ap.parse_args()
 
 
@@ -278,12 +278,16 @@ class SteadyState:
         for t0 in range(0, n_fill, chunk):
             n = min(chunk, n_fill - t0)
             draws = [s.many(n) for s in streams]
+            print(f"[bench] steady-state caches: decode step {t0} of {n_fill}", file=sys.stderr, flush=True)
             for j in range(n):
                 for i, L_ in enumerate(self.layers):
                     q, k, v = draws[i]
                     ctx.decode_attn(q[j], k[j], v[j], L_.k, L_.v, L_.score, L_.kind, L_.pos, L_.len, score_decay=0.9,
                                     new_pos=w.seq_len + 1 + t0 + j, len_bound=w.kv_budget + 1, out=L_.out_dec,
                                     evict_budget=w.kv_budget, evict_recent=1, reserve=(t0 == 0 and j == 0))
+                if j % 16 == 15:
+                    torch.cuda.synchronize()         # keeps the launch queue short (a counter-collecting profiler has
+                                                     # crashed on a queue some ten thousand launches deep)
         for i, L_ in enumerate(self.layers):             # the inputs of the timed step: the stream's next draw
             q, k, v = streams[i].next()
             L_.q_dec.copy_(q); L_.k_dec.copy_(k); L_.v_dec.copy_(v)
@@ -672,10 +676,11 @@ def main():
                     "avg_us": v[1] * 1e3 / max(v[0], 1)} for k, v in agg.items()}
 
     if args.copy_calibration:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        # a copy large enough that the lines still dirty in the L2s when it ends (tens of MB) do not matter
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)           # one elementwise copy kernel: reads 256 MiB, writes 256 MiB
+            dst.copy_(src)           # one device copy: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
 
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS

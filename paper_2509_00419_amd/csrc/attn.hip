@@ -17,7 +17,6 @@
 //   attn_combine_kernel  folds the splits, writes the output rows, turns the
 //       logits into normalised probabilities for the importance update and
 //       publishes the new length.
-#include <mutex>
 #include <type_traits>
 
 #include "common.h"
@@ -366,7 +365,8 @@ __global__ __launch_bounds__(256, HD == 128 ? 2 : 3) void attn_partial_bf16_kern
     static_assert(!(MULTI && TAIL), "the single extra entry goes with one-tile waves");
 
     __shared__ float wm[4][GP], wl[4][GP];
-    __shared__ __attribute__((aligned(16))) float wo[4][GP][HD];
+    __shared__ __attribute__((aligned(16))) float wo[4][GP][HD + 4];     // rows 16 bytes apart in the banks: the
+                                                                         // heads' 16-byte stores do not collide
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kg = lane >> 4;
@@ -990,34 +990,6 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     w.cur_len = align_up(w.logits + (size_t)heads * gp * lcap * sizeof(float), 256);
     w.total = align_up(w.cur_len + (size_t)heads * 2 * sizeof(int32_t), 256);
     return w;
-}
-
-// ---- scratch for callers that cannot allocate ---------------------------------------------------
-// A fixed device array takes the place of the caller's workspace in lvlm_decode_attn_static.  In host code the
-// array's name is only a handle: its device address differs per GPU and is asked for once per device, with that
-// device current, and kept; only that address is ever handed to kernels.
-static __device__ __align__(256) unsigned char scratch[LVLM_STATIC_SCRATCH_BYTES];
-
-namespace {
-constexpr int kMaxDevices = 64;
-std::mutex g_scratch_mutex;
-char *g_scratch_ptr[kMaxDevices] = {};
-}  // namespace
-
-hipError_t attn_static_scratch(int device, char **ptr, size_t *bytes) {
-    *ptr = nullptr;
-    *bytes = LVLM_STATIC_SCRATCH_BYTES;
-    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
-    std::lock_guard<std::mutex> lock(g_scratch_mutex);
-    if (!g_scratch_ptr[device]) {
-        void *p = nullptr;
-        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));     // the current device's copy
-        if (e != hipSuccess) return e;
-        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return hipErrorInvalidSymbol;
-        g_scratch_ptr[device] = static_cast<char *>(p);
-    }
-    *ptr = g_scratch_ptr[device];
-    return hipSuccess;
 }
 
 hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const AttnWs &w, char *ws, const void *q,
