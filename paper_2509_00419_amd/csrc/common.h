@@ -205,6 +205,36 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 #undef LVLM_MIN_STEP
     return v;
 }
+// Any associative, commutative OP over the wave's 32-bit or 64-bit values, in every lane, by the same moves.
+template <class OP>
+__device__ __forceinline__ uint32_t wave_reduce_u32(uint32_t v, OP op) {
+#define LVLM_RED_STEP(MOVE) v = op(v, __float_as_uint(MOVE(__uint_as_float(v))));
+    LVLM_RED_STEP(dpp_quad1)
+    LVLM_RED_STEP(dpp_quad2)
+    LVLM_RED_STEP(dpp_half_mirror)
+    LVLM_RED_STEP(dpp_row_mirror)
+    LVLM_RED_STEP(swap_rows)
+    LVLM_RED_STEP(swap_halves)
+#undef LVLM_RED_STEP
+    return v;
+}
+template <class OP>
+__device__ __forceinline__ unsigned long long wave_reduce_u64(unsigned long long v, OP op) {
+#define LVLM_RED_STEP(MOVE)                                                                          \
+    {                                                                                                \
+        const unsigned ph = __float_as_uint(MOVE(__uint_as_float((unsigned)(v >> 32))));             \
+        const unsigned pl = __float_as_uint(MOVE(__uint_as_float((unsigned)v)));                     \
+        v = op(v, ((unsigned long long)ph << 32) | pl);                                              \
+    }
+    LVLM_RED_STEP(dpp_quad1)
+    LVLM_RED_STEP(dpp_quad2)
+    LVLM_RED_STEP(dpp_half_mirror)
+    LVLM_RED_STEP(dpp_row_mirror)
+    LVLM_RED_STEP(swap_rows)
+    LVLM_RED_STEP(swap_halves)
+#undef LVLM_RED_STEP
+    return v;
+}
 #endif
 
 }  // namespace lvlm

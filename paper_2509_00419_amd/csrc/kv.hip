@@ -54,9 +54,15 @@ __device__ __forceinline__ unsigned long long key_mass(uint32_t key) {
     return (key & 0x80000000u) ? score_fixed(__uint_as_float(key & 0x7fffffffu)) : 0ull;
 }
 
+// Where digit d sits in a histogram: lane l of the wave that scans it owns digits 8 l .. 8 l + 7 and reads
+// them in eight steps; with digit d at row (d % 8) 64 + d / 8 the lanes of one step read neighbouring rows
+// (with the digits in order they would all meet in one LDS bank).
+static_assert(kBins == 512, "eight digits per lane");
+__device__ __forceinline__ uint32_t digit_row(uint32_t d) { return ((d & 7u) << 6) | (d >> 3); }
+
 struct SelectShared {
-    unsigned long long hist_m[2][kBins][kSub];   // two histograms: one is cleared while the other is in use
-    unsigned int hist_c[2][kBins][kSub];
+    unsigned long long hist_m[2][kBins][kSub];   // two histograms: one is cleared while the other is in use;
+    unsigned int hist_c[2][kBins][kSub];         // rows by digit_row()
     unsigned long long need_next, last_m;
     unsigned int cabove, digit, last_c;
     int first_hole;
@@ -83,8 +89,10 @@ __device__ __forceinline__ void pick_digit(SelectShared &sh, int cur, unsigned l
         hm[i] = 0ull;
         hc[i] = 0u;
         static_assert(kSub == 2, "two copies are added here");
-        if (!count_only) hm[i] = sh.hist_m[cur][PER * lane + i][0] + sh.hist_m[cur][PER * lane + i][1];
-        hc[i] = sh.hist_c[cur][PER * lane + i][0] + sh.hist_c[cur][PER * lane + i][1];
+        static_assert(PER == 8, "digit_row() places eight digits per lane");
+        const int row = 64 * i + lane;              // = digit_row(PER * lane + i)
+        if (!count_only) hm[i] = sh.hist_m[cur][row][0] + sh.hist_m[cur][row][1];
+        hc[i] = sh.hist_c[cur][row][0] + sh.hist_c[cur][row][1];
         if (count_only) hm[i] = hc[i];
         loc_m += hm[i];
         loc_c += hc[i];
@@ -184,7 +192,10 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
     constexpr int NW = NT / 64;
     __shared__ SelectShared sh;
     constexpr int NREG = KPT > 0 ? KPT : 1;
-    constexpr int CH = KPT > 0 ? KPT : 16;       // slots per thread in one round of the slot-order pass
+    // slots per thread in one round of the slot-order pass: register-resident keys go in one round, or in two
+    // when there are many (the numbering state of a round is live across its barriers)
+    constexpr int CH = KPT > 8 ? (KPT + 1) / 2 : KPT > 0 ? KPT : 16;
+    constexpr int NROUND = KPT > 0 ? (KPT + CH - 1) / CH : 1;
     static_assert(CH <= kChunkMax, "count table too small");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -262,12 +273,8 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
                 }
             }
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            const unsigned long long ob = __shfl_xor(best, o);
-            best = ob < best ? ob : best;
-            cnt += __shfl_xor(cnt, o);
-        }
+        best = wave_min_u64(best);
+        cnt = (int)wave_reduce_u32((uint32_t)cnt, [](uint32_t x, uint32_t y) { return x + y; });
         if (lane == 0) {
             sh.w_best[wave] = best;
             sh.w_cnt[wave] = cnt;
@@ -329,13 +336,10 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
             for (int slot = tid; slot < L; slot += NT)
                 if (is_cand(slot, kind[slot])) see(score_key(score[slot]));
         }
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            mass += __shfl_xor(mass, o);
-            cnt += __shfl_xor(cnt, o);
-            kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o));
-            kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o));
-        }
+        mass = wave_reduce_u64(mass, [](unsigned long long x, unsigned long long y) { return x + y; });
+        cnt = (int)wave_reduce_u32((uint32_t)cnt, [](uint32_t x, uint32_t y) { return x + y; });
+        kmin = wave_reduce_u32(kmin, [](uint32_t x, uint32_t y) { return x < y ? x : y; });
+        kmax = wave_reduce_u32(kmax, [](uint32_t x, uint32_t y) { return x > y ? x : y; });
         if (lane == 0) {
             sh.w_mass[wave] = mass;
             sh.w_cnt[wave] = cnt;
@@ -401,9 +405,9 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
         {
             const int sub = lane & (kSub - 1);
             auto add = [&](uint32_t k) {
-                const uint32_t dgt = (k >> shift) & dmask;
-                if (!budget_mode) atomicAdd(&sh.hist_m[cur][dgt][sub], key_mass(k));   // budget: mass = count
-                atomicAdd(&sh.hist_c[cur][dgt][sub], 1u);
+                const uint32_t row = digit_row((k >> shift) & dmask);
+                if (!budget_mode) atomicAdd(&sh.hist_m[cur][row][sub], key_mass(k));   // budget: mass = count
+                atomicAdd(&sh.hist_c[cur][row][sub], 1u);
             };
             // keys that agree with the prefix in every bit above the current digit
             auto matches = [&](uint32_t k) { return pass == 0 || ((k ^ prefix) >> top) == 0u; };
@@ -454,7 +458,8 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
     const bool stable = a.order == LVLM_ORDER_STABLE;
     int first_hole = L;                  // lowest new slot whose entry moves (STABLE)
     int base_tie = 0, base_keep = 0, base_hole = 0, base_tail = 0;
-    for (int s0 = 0; s0 < L; s0 += NT * CH) {
+    auto round = [&](int s0, auto round_tag) {
+        constexpr int R0 = decltype(round_tag)::value * CH;   // first register-resident key of the round
         uint32_t tiem = 0u, keepm = 0u;              // bit c: the thread's slot of chunk c is a tie / a sure survivor
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
@@ -463,8 +468,8 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
                 uint32_t k;
                 bool cand;
                 if constexpr (KPT > 0) {
-                    k = key[c < NREG ? c : 0];
-                    cand = (candm >> c) & 1u;
+                    k = key[R0 + c < NREG ? R0 + c : 0];
+                    cand = (candm >> (R0 + c)) & 1u;
                 } else {
                     cand = is_cand(slot, kind[slot]);
                     k = score_key(score[slot]);
@@ -520,6 +525,15 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
         base_tie += tot_tie;
         base_keep += tot_keep;
         __syncthreads();                             // the count table is reused by the next round
+    };
+    if constexpr (KPT > 0) {
+        round(0, std::integral_constant<int, 0>{});
+        if constexpr (NROUND > 1) {
+            if (NT * CH < L) round(NT * CH, std::integral_constant<int, 1>{});
+        }
+        static_assert(NROUND <= 2, "two rounds cover the register-resident keys");
+    } else {
+        for (int s0 = 0; s0 < L; s0 += NT * CH) round(s0, std::integral_constant<int, 0>{});
     }
     if (stable) {
 #pragma unroll
@@ -735,8 +749,10 @@ hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvW
     const int max_moves = d.mode == LVLM_KV_BUDGET ? (bound - d.budget < bound / 2 ? bound - d.budget : bound / 2) : bound / 2;
     a.fill_external = d.order == LVLM_ORDER_FILL && max_moves > kFillInKernel;
     prof.begin("kv_select");
-    // (smaller workgroups with more keys per thread were measured for short heads: no faster)
-    if (bound <= 2048) hipLaunchKernelGGL((kv_select_kernel<2, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    // Much of the selection is one wave's chain of latencies, so with more heads than the chip holds workgroups of
+    // 1024 threads, short heads go to workgroups of 256 threads: more heads are in flight at once.
+    if (bound <= 2048 && heads > 512) hipLaunchKernelGGL((kv_select_kernel<8, 256>), dim3((unsigned)heads), dim3(256), 0, stream, a);
+    else if (bound <= 2048) hipLaunchKernelGGL((kv_select_kernel<2, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
     else if (bound <= 4096) hipLaunchKernelGGL((kv_select_kernel<4, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
     else if (bound <= 8192) hipLaunchKernelGGL((kv_select_kernel<8, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
     else if (bound <= 17408) hipLaunchKernelGGL((kv_select_kernel<17, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);

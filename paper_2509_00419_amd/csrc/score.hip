@@ -689,6 +689,7 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
     // ---- sweep 2: column sums of the image keys for this wave's chunk
     const int key_lo = a.img_begin, key_hi = a.img_begin + a.n_img;
     float *out = a.colpart + (((long long)min(c, a.rs - 1) * a.B + b) * a.Hkv + g) * a.n_img;
+    float lse_r[16];                                      // the normalisers of this lane's 16 accumulator rows
     auto colsum = [&](int j0, const HalfRow<DT, HD> &kf) {
         f32x16 acc;
 #pragma unroll
@@ -698,14 +699,12 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
         float sum = 0.f;
         if (j0 + 31 <= pos_min) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                sum += __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_s[wave][acc_row(r, hf)]));
+            for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_r[r]));
         } else {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = acc_row(r, hf);
-                const float p = __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_s[wave][row]));
-                sum += (j <= pos_s[wave][row]) ? p : 0.f;
+                const float p = __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -lse_r[r]));
+                sum += (j <= pos_s[wave][acc_row(r, hf)]) ? p : 0.f;
             }
         }
         sum += other_half(sum);
@@ -752,6 +751,8 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
         lse_s[wave][l32] = (live && rho < GT) ? a.row_lse[rowbase + rho] * kLog2e : INFINITY;
     }
     __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 16; ++r) lse_r[r] = lse_s[wave][acc_row(r, hf)];
     sweep(key_lo, key_hi, true, std::true_type{});
 }
 

@@ -373,6 +373,19 @@ def test_kv_compress_every_length_class(ctx, order):
 
 
 @pytest.mark.parametrize("order", [lv.ORDER_STABLE, lv.ORDER_FILL])
+def test_kv_compress_many_short_heads(ctx, order):
+    # more than 512 short heads take workgroups of 256 threads with eight keys per thread: ragged lengths,
+    # both rules, ties included
+    B, H, Lmax = 36, 16, 1100
+    g = torch.Generator().manual_seed(77)
+    lens = torch.randint(0, Lmax + 1, (B * H,), generator=g).tolist()
+    lens[:6] = [1100, 1099, 1, 0, 257, 1025]
+    _kv_case(ctx, torch.bfloat16, B, H, Lmax, 64, lens, 78, mode=lv.KV_THRESHOLD, beta=0.9, order=order)
+    _kv_case(ctx, torch.bfloat16, B, H, Lmax, 64, lens, 79, mode=lv.KV_BUDGET, budget=400, n_recent=3, order=order,
+             dyadic=True)
+
+
+@pytest.mark.parametrize("order", [lv.ORDER_STABLE, lv.ORDER_FILL])
 def test_kv_compress_special_scores(ctx, order):
     # NaN, negative, infinite, zero and tied scores: NaN ranks lowest and weighs nothing, negatives weigh
     # nothing, +inf is clamped to 2^16 in the mass; both rules must still agree with the oracle bit for bit
