@@ -655,7 +655,8 @@ def main():
             tot += ta.elapsed_time(tb)
         first_ms = tot / len(first_graphs)
 
-    # per-kernel durations: eager steps with every launch bracketed by HIP events on the launch stream
+    # per-kernel durations: eager steps in which every launch carries HIP events bound to the kernel itself, on the
+    # launch stream (first wave to last wave, as a kernel trace reports it)
     prof = {}
     if args.profile_steps > 0:
         ctx.profile(True)

@@ -107,10 +107,12 @@ LVLM_API lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const
 LVLM_API lvlm_status lvlm_set_workspace(lvlm_ctx *ctx, void *dev_ptr, size_t bytes);
 
 /* Per-kernel timing for benchmarks (not on the hot path, not usable during
- * stream capture).  While enabled, every kernel the four calls launch is
- * bracketed by a HIP event pair on the caller's stream (at most 4096 launches
- * between reads).  lvlm_profile_read waits for those events, adds them up per
- * kernel name into the caller's HOST array and clears the record. */
+ * stream capture).  While enabled, every kernel the calls launch carries a HIP
+ * event pair bound to the kernel itself (start of its first wave, end of its
+ * last: the duration a kernel trace reports, without the gaps between
+ * dispatches), at most 4096 launches between reads.  lvlm_profile_read waits
+ * for those events, adds them up per kernel name into the caller's HOST array
+ * and clears the record. */
 typedef struct {
     char name[48];
     int32_t calls;

@@ -179,6 +179,7 @@ lvlm_status lvlm_create(lvlm_ctx **ctx, int device) {
     c->ws_bytes = 0;
     c->err[0] = '\0';
     c->prof_on = false;
+    c->prof_open = c->prof_first = false;
     c->prof_n = c->prof_cap = 0;
     c->prof_ev = nullptr;
     c->prof_name = nullptr;
@@ -211,6 +212,7 @@ lvlm_status lvlm_profile(lvlm_ctx *ctx, int enable) {
         }
     }
     ctx->prof_on = enable != 0;
+    ctx->prof_open = false;
     if (enable) ctx->prof_n = 0;
     return LVLM_OK;
 }

@@ -911,14 +911,14 @@ void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
     {
         const dim3 grid(a.n_split, a.Hkv, B);
         if (a.tail_entry)
-            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, false, true>), grid, dim3(256), 0, stream, a);
+            LVLM_LAUNCH(prof, (attn_partial_bf16_kernel<HD, GP, false, true>), grid, dim3(256), 0, stream, a);
         else if (a.split_len > 128 || a.n_split * a.split_len < len_bound)      // some wave has a second tile
-            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, true, false>), grid, dim3(256), 0, stream, a);
+            LVLM_LAUNCH(prof, (attn_partial_bf16_kernel<HD, GP, true, false>), grid, dim3(256), 0, stream, a);
         else
-            hipLaunchKernelGGL((attn_partial_bf16_kernel<HD, GP, false, false>), grid, dim3(256), 0, stream, a);
+            LVLM_LAUNCH(prof, (attn_partial_bf16_kernel<HD, GP, false, false>), grid, dim3(256), 0, stream, a);
     }
     else
-        hipLaunchKernelGGL((attn_partial_kernel<DT, HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
+        LVLM_LAUNCH(prof, (attn_partial_kernel<DT, HD, GP>), dim3(a.n_split, a.Hkv, B), dim3(256), 0, stream, a);
     prof.end();
     if (a.evict_budget > 0) {
         prof.begin("attn_combine_evict");
@@ -927,16 +927,16 @@ void launch_both(const Prof &prof, const AttnArgs &a, int B, int len_bound) {
         int n_out = 256 / (a.Hkv * B) - 1;
         n_out = n_out < 1 ? 1 : (n_out > a.G ? a.G : n_out);
         const dim3 grid(n_out + 1, a.Hkv, B);
-        if (len_bound <= 1024) hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP, 1>), grid, dim3(1024), 0, stream, a, n_out);
-        else if (len_bound <= 2048) hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP, 2>), grid, dim3(1024), 0, stream, a, n_out);
-        else if (len_bound <= 3072) hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP, 3>), grid, dim3(1024), 0, stream, a, n_out);
-        else hipLaunchKernelGGL((attn_combine_evict_kernel<DT, HD, GP, 0>), grid, dim3(1024), 0, stream, a, n_out);
+        if (len_bound <= 1024) LVLM_LAUNCH(prof, (attn_combine_evict_kernel<DT, HD, GP, 1>), grid, dim3(1024), 0, stream, a, n_out);
+        else if (len_bound <= 2048) LVLM_LAUNCH(prof, (attn_combine_evict_kernel<DT, HD, GP, 2>), grid, dim3(1024), 0, stream, a, n_out);
+        else if (len_bound <= 3072) LVLM_LAUNCH(prof, (attn_combine_evict_kernel<DT, HD, GP, 3>), grid, dim3(1024), 0, stream, a, n_out);
+        else LVLM_LAUNCH(prof, (attn_combine_evict_kernel<DT, HD, GP, 0>), grid, dim3(1024), 0, stream, a, n_out);
         prof.end();
         return;
     }
     const int chunks = a.update_score ? (len_bound + 1023) / 1024 : 0;
     prof.begin("attn_combine");
-    hipLaunchKernelGGL((attn_combine_kernel<DT, HD, GP>), dim3(1 + chunks, a.Hkv, B), dim3(1024), 0, stream, a);
+    LVLM_LAUNCH(prof, (attn_combine_kernel<DT, HD, GP>), dim3(1 + chunks, a.Hkv, B), dim3(1024), 0, stream, a);
     prof.end();
 }
 

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stdio.h>
 
@@ -13,8 +14,9 @@ struct lvlm_ctx {
     void *ws;
     size_t ws_bytes;
     char err[256];
-    // optional per-kernel timing (eager launches only): one event pair per launch
+    // optional per-kernel timing (eager launches only): one event pair per bracket of launches
     bool prof_on;
+    bool prof_open, prof_first;  // a bracket is open / it has launched nothing yet
     int prof_n, prof_cap;
     hipEvent_t *prof_ev;        // 2 * prof_cap events
     const char **prof_name;     // prof_cap static strings
@@ -77,24 +79,45 @@ struct AttnWs {
 };
 AttnWs attn_ws(const lvlm_attn_desc &d);
 
-// Brackets one kernel launch with a HIP event pair when profiling is on.
+// Names the kernel launches between begin() and end() for the optional timing.  The events are bound to the
+// kernels themselves (the start event to the first launch of the bracket, the stop event to its last), so what
+// is read back is the time from that kernel's first wave to its last -- the duration a kernel trace reports --
+// without the dispatch gaps that events recorded around a launch would add.
 struct Prof {
     lvlm_ctx *ctx;
     hipStream_t stream;
     void begin(const char *name) const {
         if (!ctx->prof_on || ctx->prof_n >= ctx->prof_cap) return;
         ctx->prof_name[ctx->prof_n] = name;
-        (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n], stream);
+        ctx->prof_open = ctx->prof_first = true;
     }
     void end() const {
-        if (!ctx->prof_on || ctx->prof_n >= ctx->prof_cap) return;
-        (void)hipEventRecord(ctx->prof_ev[2 * ctx->prof_n + 1], stream);
-        ++ctx->prof_n;
+        if (!ctx->prof_open) return;
+        ctx->prof_open = false;
+        if (!ctx->prof_first) ++ctx->prof_n;     // a bracket without a launch leaves no entry
+    }
+    // the events the next launch carries (null: none), or false when no bracket is open
+    bool events(hipEvent_t *start, hipEvent_t *stop) const {
+        if (!ctx->prof_open) return false;
+        *start = ctx->prof_first ? ctx->prof_ev[2 * ctx->prof_n] : nullptr;
+        *stop = ctx->prof_ev[2 * ctx->prof_n + 1];
+        ctx->prof_first = false;
+        return true;
     }
 };
 
+// hipLaunchKernelGGL with a Prof in front: the same launch, carrying the open bracket's events if there is one.
+#define LVLM_LAUNCH(prof, kernel, grid, block, lds_bytes, stream_, ...)                                      \
+    do {                                                                                                     \
+        hipEvent_t lvlm_ev0_, lvlm_ev1_;                                                                     \
+        if ((prof).events(&lvlm_ev0_, &lvlm_ev1_))                                                           \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, stream_, lvlm_ev0_, lvlm_ev1_, 0, __VA_ARGS__); \
+        else                                                                                                 \
+            hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream_, __VA_ARGS__);                        \
+    } while (0)
+
 // ---- launches (defined in the .hip files; all asynchronous on `stream`) ----
-void launch_rank(hipStream_t stream, const float *score, int32_t *rank, int n, int B);
+void launch_rank(const Prof &prof, const float *score, int32_t *rank, int n, int B);
 hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreWs &w, char *ws,
                         const void *q, const void *k, const float *row_lse, float *score_head,
                         float *score_mean);

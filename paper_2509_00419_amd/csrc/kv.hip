@@ -751,26 +751,26 @@ hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvW
     prof.begin("kv_select");
     // Much of the selection is one wave's chain of latencies, so with more heads than the chip holds workgroups of
     // 1024 threads, short heads go to workgroups of 256 threads: more heads are in flight at once.
-    if (bound <= 2048 && heads > 512) hipLaunchKernelGGL((kv_select_kernel<8, 256>), dim3((unsigned)heads), dim3(256), 0, stream, a);
-    else if (bound <= 2048) hipLaunchKernelGGL((kv_select_kernel<2, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
-    else if (bound <= 4096) hipLaunchKernelGGL((kv_select_kernel<4, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
-    else if (bound <= 8192) hipLaunchKernelGGL((kv_select_kernel<8, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
-    else if (bound <= 17408) hipLaunchKernelGGL((kv_select_kernel<17, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
-    else hipLaunchKernelGGL((kv_select_kernel<0, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    if (bound <= 2048 && heads > 512) LVLM_LAUNCH(prof, (kv_select_kernel<8, 256>), dim3((unsigned)heads), dim3(256), 0, stream, a);
+    else if (bound <= 2048) LVLM_LAUNCH(prof, (kv_select_kernel<2, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else if (bound <= 4096) LVLM_LAUNCH(prof, (kv_select_kernel<4, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else if (bound <= 8192) LVLM_LAUNCH(prof, (kv_select_kernel<8, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else if (bound <= 17408) LVLM_LAUNCH(prof, (kv_select_kernel<17, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
+    else LVLM_LAUNCH(prof, (kv_select_kernel<0, 1024>), dim3((unsigned)heads), dim3(1024), 0, stream, a);
     prof.end();
     if (d.order == LVLM_ORDER_STABLE) {
         prof.begin("kv_move");
         const int s64 = a.row_bytes / 64;
         if (heads * (2 * s64 + 1) >= 1024)
-            hipLaunchKernelGGL((kv_move_kernel<256, 64>), dim3(2 * s64 + 1, (unsigned)heads), dim3(256), 0, stream, a);
+            LVLM_LAUNCH(prof, (kv_move_kernel<256, 64>), dim3(2 * s64 + 1, (unsigned)heads), dim3(256), 0, stream, a);
         else if (heads * (2 * s64 + 1) >= 256)
-            hipLaunchKernelGGL((kv_move_kernel<1024, 64>), dim3(2 * s64 + 1, (unsigned)heads), dim3(1024), 0, stream, a);
+            LVLM_LAUNCH(prof, (kv_move_kernel<1024, 64>), dim3(2 * s64 + 1, (unsigned)heads), dim3(1024), 0, stream, a);
         else
-            hipLaunchKernelGGL((kv_move_kernel<1024, 32>), dim3(4 * s64 + 1, (unsigned)heads), dim3(1024), 0, stream, a);
+            LVLM_LAUNCH(prof, (kv_move_kernel<1024, 32>), dim3(4 * s64 + 1, (unsigned)heads), dim3(1024), 0, stream, a);
         prof.end();
     } else if (a.fill_external) {
         prof.begin("kv_fill");
-        hipLaunchKernelGGL(kv_fill_kernel, dim3((max_moves + kFillRows - 1) / kFillRows, (unsigned)heads), dim3(256), 0, stream, a);
+        LVLM_LAUNCH(prof, kv_fill_kernel, dim3((max_moves + kFillRows - 1) / kFillRows, (unsigned)heads), dim3(256), 0, stream, a);
         prof.end();
     }
     return hipGetLastError();

@@ -326,12 +326,13 @@ __global__ __launch_bounds__(256) void finalize_kernel(GatherArgs a) {
 
 }  // namespace
 
-void launch_rank(hipStream_t stream, const float *score, int32_t *rank, int n, int B) {
+void launch_rank(const Prof &prof, const float *score, int32_t *rank, int n, int B) {
+    hipStream_t stream = prof.stream;
     RankArgs ra{};
     ra.score = score;
     ra.rank = rank;
     ra.n = n;
-    hipLaunchKernelGGL(rank_kernel, dim3((n + kRankBlock - 1) / kRankBlock, B), dim3(1024), 0, stream, ra);
+    LVLM_LAUNCH(prof, rank_kernel, dim3((n + kRankBlock - 1) / kRankBlock, B), dim3(1024), 0, stream, ra);
 }
 
 MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes) {
@@ -391,7 +392,7 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
     if (r > 0) {
         int32_t *rank = reinterpret_cast<int32_t *>(ws + w.rank_part);
         prof.begin("merge_rank");
-        launch_rank(stream, score_mean, rank, d.n_img, d.B);
+        launch_rank(prof, score_mean, rank, d.n_img, d.B);
         prof.end();
         IndexArgs ia{};
         ia.rank = rank;
@@ -403,15 +404,15 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
         ia.merged_idx = merged_idx;
         ia.n = d.n_img; ia.n_keep = d.n_keep;
         prof.begin("merge_index");
-        hipLaunchKernelGGL(index_kernel, dim3((d.n_img + kIndexChunk - 1) / kIndexChunk, d.B), dim3(1024), 0, stream, ia);
+        LVLM_LAUNCH(prof, index_kernel, dim3((d.n_img + kIndexChunk - 1) / kIndexChunk, d.B), dim3(1024), 0, stream, ia);
         prof.end();
     }
     prof.begin("merge_gather");
-    hipLaunchKernelGGL(gather_kernel, dim3(grid_x, grid_y, d.B * d.n_planes), dim3(256), 0, stream, g);
+    LVLM_LAUNCH(prof, gather_kernel, dim3(grid_x, grid_y, d.B * d.n_planes), dim3(256), 0, stream, g);
     prof.end();
     if (r > 0 && any_weighted) {
         prof.begin("merge_finalize");
-        hipLaunchKernelGGL(finalize_kernel, dim3((w.max_row_elems + 15) / 16, d.B * d.n_planes), dim3(256), 0,
+        LVLM_LAUNCH(prof, finalize_kernel, dim3((w.max_row_elems + 15) / 16, d.B * d.n_planes), dim3(256), 0,
                            stream, g);
         prof.end();
     }

@@ -556,16 +556,16 @@ hipError_t launch_prefill_attn(const Prof &prof, const lvlm_prefill_desc &d, con
     if (d.dtype == LVLM_BF16) {
         const long long grid = (long long)a.heads_per_xcd * 8 * a.nqb;
         if (d.hd == 128) {
-            hipLaunchKernelGGL((prefill_attn_bf16_kernel<128, false>), dim3((unsigned)grid), dim3(128), 0, stream, a);
-            hipLaunchKernelGGL((prefill_attn_bf16_kernel<128, true>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+            LVLM_LAUNCH(prof, (prefill_attn_bf16_kernel<128, false>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+            LVLM_LAUNCH(prof, (prefill_attn_bf16_kernel<128, true>), dim3((unsigned)grid), dim3(128), 0, stream, a);
         } else {
-            hipLaunchKernelGGL((prefill_attn_bf16_kernel<64, false>), dim3((unsigned)grid), dim3(128), 0, stream, a);
-            hipLaunchKernelGGL((prefill_attn_bf16_kernel<64, true>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+            LVLM_LAUNCH(prof, (prefill_attn_bf16_kernel<64, false>), dim3((unsigned)grid), dim3(128), 0, stream, a);
+            LVLM_LAUNCH(prof, (prefill_attn_bf16_kernel<64, true>), dim3((unsigned)grid), dim3(128), 0, stream, a);
         }
     } else {
         const dim3 grid((unsigned)a.nqb, (unsigned)d.Hq, (unsigned)d.B);
-        if (d.hd == 128) hipLaunchKernelGGL((prefill_attn_f32_kernel<128>), grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((prefill_attn_f32_kernel<64>), grid, dim3(256), 0, stream, a);
+        if (d.hd == 128) LVLM_LAUNCH(prof, (prefill_attn_f32_kernel<128>), grid, dim3(256), 0, stream, a);
+        else LVLM_LAUNCH(prof, (prefill_attn_f32_kernel<64>), grid, dim3(256), 0, stream, a);
     }
     prof.end();
     hipError_t e = hipGetLastError();

@@ -518,26 +518,26 @@ hipError_t launch_merge_similar(const Prof &prof, const lvlm_merge_desc &d, cons
         a.assign = assign;
         c.n_rows = d.N; c.split = d.N; c.src_shift = 0; c.dst_shift = 0;
         prof.begin("sim_copy");
-        hipLaunchKernelGGL(sim_copy_kernel, dim3(d.N < 2048 ? d.N : 2048, col_blocks, d.B * d.n_planes), dim3(256), 0,
+        LVLM_LAUNCH(prof, sim_copy_kernel, dim3(d.N < 2048 ? d.N : 2048, col_blocks, d.B * d.n_planes), dim3(256), 0,
                            stream, c);
         prof.end();
         if (keep_idx || assign || size_out)
-            hipLaunchKernelGGL(sim_identity_kernel, dim3((d.n_img + 255) / 256, d.B), dim3(256), 0, stream, a);
+            LVLM_LAUNCH(prof, sim_identity_kernel, dim3((d.n_img + 255) / 256, d.B), dim3(256), 0, stream, a);
         return hipGetLastError();
     }
 
     const dim3 per_token((d.n_img + 255) / 256, d.B);
     prof.begin("sim_rank");
-    launch_rank(stream, score_mean, a.rank, d.n_img, d.B);
+    launch_rank(prof, score_mean, a.rank, d.n_img, d.B);
     prof.end();
     prof.begin("sim_index");
-    hipLaunchKernelGGL(sim_index_kernel, dim3(d.B), dim3(1024), 0, stream, a);
+    LVLM_LAUNCH(prof, sim_index_kernel, dim3(d.B), dim3(1024), 0, stream, a);
     prof.end();
     prof.begin("sim_norm");
     if (planes[0].dtype == LVLM_BF16)
-        hipLaunchKernelGGL(sim_norm_kernel<LVLM_BF16>, dim3((d.n_img + 3) / 4, d.B), dim3(256), 0, stream, a);
+        LVLM_LAUNCH(prof, sim_norm_kernel<LVLM_BF16>, dim3((d.n_img + 3) / 4, d.B), dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL(sim_norm_kernel<LVLM_F32>, dim3((d.n_img + 3) / 4, d.B), dim3(256), 0, stream, a);
+        LVLM_LAUNCH(prof, sim_norm_kernel<LVLM_F32>, dim3((d.n_img + 3) / 4, d.B), dim3(256), 0, stream, a);
     prof.end();
     prof.begin("sim_gemm");
     {
@@ -548,9 +548,9 @@ hipError_t launch_merge_similar(const Prof &prof, const lvlm_merge_desc &d, cons
         const bool ragged = (planes[0].row_elems * (bf ? 2 : 4)) % 128 != 0;
 #define LVLM_GEMM(DT, NWN, NWM, TR, TC)                                                                              \
     if (ragged)                                                                                                      \
-        hipLaunchKernelGGL((sim_gemm_kernel<DT, NWN, NWM, TR, TC, true>), ggrid, dim3(64 * NWN * NWM), 0, stream, a);  \
+        LVLM_LAUNCH(prof, (sim_gemm_kernel<DT, NWN, NWM, TR, TC, true>), ggrid, dim3(64 * NWN * NWM), 0, stream, a);  \
     else                                                                                                             \
-        hipLaunchKernelGGL((sim_gemm_kernel<DT, NWN, NWM, TR, TC, false>), ggrid, dim3(64 * NWN * NWM), 0, stream, a)
+        LVLM_LAUNCH(prof, (sim_gemm_kernel<DT, NWN, NWM, TR, TC, false>), ggrid, dim3(64 * NWN * NWM), 0, stream, a)
         if (w.tile == 256) {
             if (bf) { LVLM_GEMM(LVLM_BF16, 2, 4, 4, 2); } else { LVLM_GEMM(LVLM_F32, 2, 4, 4, 2); }
         } else {
@@ -560,22 +560,22 @@ hipError_t launch_merge_similar(const Prof &prof, const lvlm_merge_desc &d, cons
     }
     prof.end();
     prof.begin("sim_assign");
-    hipLaunchKernelGGL(sim_assign_kernel, per_token, dim3(256), 0, stream, a);
+    LVLM_LAUNCH(prof, sim_assign_kernel, per_token, dim3(256), 0, stream, a);
     prof.end();
     prof.begin("sim_rank2");
-    launch_rank(stream, a.key, a.rank2, d.n_img, d.B);
+    launch_rank(prof, a.key, a.rank2, d.n_img, d.B);
     prof.end();
     prof.begin("sim_order");
-    hipLaunchKernelGGL(sim_order_kernel, per_token, dim3(256), 0, stream, a);
+    LVLM_LAUNCH(prof, sim_order_kernel, per_token, dim3(256), 0, stream, a);
     prof.end();
     prof.begin("sim_merge");
-    hipLaunchKernelGGL(sim_merge_kernel, dim3(d.n_keep, col_blocks, d.B * d.n_planes), dim3(256), 0, stream, a);
+    LVLM_LAUNCH(prof, sim_merge_kernel, dim3(d.n_keep, col_blocks, d.B * d.n_planes), dim3(256), 0, stream, a);
     prof.end();
     const int outside = d.N - d.n_img;
     if (outside > 0) {
         c.n_rows = outside; c.split = d.img_begin; c.src_shift = d.n_img; c.dst_shift = d.n_keep;
         prof.begin("sim_copy");
-        hipLaunchKernelGGL(sim_copy_kernel, dim3(outside < 2048 ? outside : 2048, col_blocks, d.B * d.n_planes),
+        LVLM_LAUNCH(prof, sim_copy_kernel, dim3(outside < 2048 ? outside : 2048, col_blocks, d.B * d.n_planes),
                            dim3(256), 0, stream, c);
         prof.end();
     }
