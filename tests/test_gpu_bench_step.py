@@ -179,8 +179,8 @@ def test_prefill_and_decode_step_in_bench_configuration(name, every_layer, given
 
 
 def test_steady_state_caches_of_config5_and_one_step_on_them():
-    """The decode phase the bench times at config 5: caches that the path itself filled to the budget (1428 decode
-    steps with eviction run forward from the prefilled state on every layer), then one more step, checked on the
+    """The decode phase the bench times at config 5: caches that the path itself filled to the budget (budget minus the
+    shortest head's length decode steps with eviction, run forward from the prefilled state on every layer), then one more step, checked on the
     first and the last layer against the oracle applied to the GPU state just before it."""
     w = configs.CFG5
     ctx = lv.Context(0)

@@ -163,7 +163,7 @@ def test_config4_long_decode():
 
 def test_config5_long_decode_two_layers():
     """Config 5: layer 0 (16512 entries cut to the 2048 budget before generation) and the last layer (what the pyramid
-    and the threshold rule leave of 620 entries: it grows for some 1400 steps, then evicts), 2048 generated tokens."""
+    and the threshold rule leave of 620 entries, some 260: it grows until it reaches the budget, then evicts), 2048 generated tokens."""
     w = configs.CFG5
     ctx = lv.Context(0)
     layers = bench.plan(w, lv)
