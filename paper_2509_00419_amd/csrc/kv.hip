@@ -458,6 +458,7 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
     const bool stable = a.order == LVLM_ORDER_STABLE;
     int first_hole = L;                  // lowest new slot whose entry moves (STABLE)
     int base_tie = 0, base_keep = 0, base_hole = 0, base_tail = 0;
+    const bool ties_all_kept = evict_all_cand || tie_keep >= (unsigned long long)last_c;
     auto round = [&](int s0, auto round_tag) {
         constexpr int R0 = decltype(round_tag)::value * CH;   // first register-resident key of the round
         uint32_t tiem = 0u, keepm = 0u;              // bit c: the thread's slot of chunk c is a tie / a sure survivor
@@ -479,13 +480,19 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
             }
         }
         uint32_t before[CH];                         // ties (low half) and sure survivors (high half) before the slot
-        int tot_tie, tot_keep;
-        chunk_scan2<CH, NT>(sh, tiem, keepm, before, tot_tie, tot_keep);
-        uint32_t keptm = 0u;
+        int tot_tie = 0, tot_keep = 0;
+        uint32_t keptm = keepm | tiem;
+        // FILL order with every entry of the cut's key kept (the usual case: scores are distinct) needs no
+        // numbering of ties or survivors; uniform over the workgroup
+        if (stable || !ties_all_kept) {
+            chunk_scan2<CH, NT>(sh, tiem, keepm, before, tot_tie, tot_keep);
+            keptm = 0u;
 #pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            const unsigned long long tb = (unsigned long long)(base_tie + (int)(before[c] & 0xffffu));
-            if (((keepm >> c) & 1u) || (((tiem >> c) & 1u) && tb < tie_keep)) keptm |= 1u << c;
+            for (int c = 0; c < CH; ++c) {
+                const unsigned long long tb = (unsigned long long)(base_tie + (int)(before[c] & 0xffffu));
+                if (((keepm >> c) & 1u) || (((tiem >> c) & 1u) && tb < tie_keep)) keptm |= 1u << c;
+            }
+            if (!stable) __syncthreads();            // the count table is reused
         }
         if (stable) {
 #pragma unroll
@@ -510,7 +517,6 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
                 if (!kept && slot < n_new) holem |= 1u << c;
                 if (kept && slot >= n_new) tailm |= 1u << c;
             }
-            __syncthreads();                         // the count table is reused
             int tot_hole, tot_tail;
             chunk_scan2<CH, NT>(sh, holem, tailm, before, tot_hole, tot_tail);
 #pragma unroll
