@@ -53,7 +53,7 @@ PrefillWs prefill_ws(const lvlm_prefill_desc &d);
 lvlm_score_desc prefill_score_desc(const lvlm_prefill_desc &d);   // the score call the last T rows amount to
 
 struct MergeWs {
-    size_t rank_part, dst_of, wgt, partial, total;
+    size_t rank_part, dst_of, wgt, partial, sorted, total;
     int n_split;   // always 1: the rank kernel leaves complete ranks
     int n_chunk;   // source-row chunks of the gather kernel (partial sums per chunk)
     int rows_per_chunk;
@@ -117,7 +117,9 @@ struct Prof {
     } while (0)
 
 // ---- launches (defined in the .hip files; all asynchronous on `stream`) ----
-void launch_rank(const Prof &prof, const float *score, int32_t *rank, int n, int B);
+// scratch: rank_scratch_bytes(n, B) bytes for the sorted blocks of long sequences, or null (counting at any length)
+size_t rank_scratch_bytes(int n, int B);
+void launch_rank(const Prof &prof, const float *score, int32_t *rank, int n, int B, void *scratch);
 hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreWs &w, char *ws,
                         const void *q, const void *k, const float *row_lse, float *score_head,
                         float *score_mean);

@@ -6,6 +6,9 @@
 //                    the counting definition itself, spread over the chip:
 //                    64 tokens per workgroup, the keys staged in LDS and split
 //                    over the 16 waves.  Nothing iterative or data dependent.
+//                    Long sequences: rank_block_kernel + rank_search_kernel
+//                    (blocks of 1024 tokens sorted by counting, then one
+//                    binary search per token and block).
 //   index_kernel     one workgroup per 4096 tokens: counts the kept tokens in
 //                    front of its chunk, prefix-scans its own "kept" flags
 //                    in index order and emits
@@ -91,6 +94,115 @@ __global__ __launch_bounds__(1024) void rank_kernel(RankArgs a) {
 #pragma unroll
         for (int w = 0; w < 16; ++w) tot += cnt_lds[w][lane];
         a.rank[(long long)b * a.n + j] = tot;
+    }
+}
+
+// ---- ranks of long sequences: sorted blocks + binary searches ------------------------------------
+// Counting costs n^2 comparisons; from kSortMinTokens tokens on the ranks come in two launches instead.
+// A token's place in the order is told by one 64-bit word, key in the high half and inverted index in the low
+// half: i precedes j  <=>  word_i > word_j (higher key, or the same key and the lower index).
+//   rank_block_kernel   every block of 1024 tokens is sorted by counting WITHIN the block (1024 comparisons per
+//                       token, spread over all workgroups): a token's word goes to its place in the block's
+//                       descending order; places past the last token of a partly filled block hold 0 (below every word)
+//   rank_search_kernel  a token's rank = over all sorted blocks, the number of words above its own, each found by
+//                       a binary search (11 probes) in LDS; a workgroup stages eight blocks and searches them for
+//                       256 tokens, the groups of eight add their counts into the rank
+constexpr int kSortBlock = 1024;
+constexpr int kSortMinTokens = 4096;
+constexpr int kSortStage = 8;        // sorted blocks held in LDS at a time (64 KB)
+
+__device__ __forceinline__ unsigned long long order_word(float score, int idx) {
+    return ((unsigned long long)score_key(score) << 32) | (unsigned long long)(0xffffffffu - (uint32_t)idx);
+}
+
+struct SortArgs {
+    const float *score;             // [B, n]
+    unsigned long long *sorted;     // [B, n_blocks, 1024]
+    int32_t *rank;                  // [B, n]
+    int n, n_blocks;
+};
+
+// 64 tokens per workgroup (one per lane, the same in all 16 waves); wave w counts over words 64 w .. 64 w + 63 of
+// the tokens' own block, read from LDS as broadcast 128-bit pairs.
+__global__ __launch_bounds__(1024) void rank_block_kernel(SortArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned long long words[kSortBlock];
+    __shared__ int cnt_lds[16][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b = blockIdx.y;
+    const int j0 = blockIdx.x * 64, j = j0 + lane;
+    const int blk = j0 / kSortBlock, r0 = blk * kSortBlock;
+    const float *score = a.score + (long long)b * a.n;
+    unsigned long long *out = a.sorted + ((long long)b * a.n_blocks + blk) * kSortBlock;
+    if (j0 >= a.n) {                              // nothing but padding here (uniform over the workgroup)
+        if (wave == 0) out[j - r0] = 0ull;
+        return;
+    }
+    {
+        const int i = r0 + tid;
+        words[tid] = i < a.n ? order_word(score[i], i) : 0ull;
+    }
+    const unsigned long long mine = j < a.n ? order_word(score[j], j) : 0ull;
+    __syncthreads();
+    int cnt = 0;
+#pragma unroll 8
+    for (int x = 64 * wave; x < 64 * wave + 64; x += 2) {
+        const ulonglong2 w2 = *reinterpret_cast<const ulonglong2 *>(&words[x]);
+        cnt += (w2.x > mine) + (w2.y > mine);
+    }
+    cnt_lds[wave][lane] = cnt;
+    __syncthreads();
+    if (wave == 0) {
+        int place = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) place += cnt_lds[w][lane];
+        // tokens past the end fill the places past the last token (the real ones take 0 .. count-1 between them)
+        if (j < a.n) {
+            out[place] = mine;
+            a.rank[(long long)b * a.n + j] = 0;          // the searches add to it
+        } else {
+            out[j - r0] = 0ull;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void rank_search_kernel(SortArgs a) {
+    __shared__ __attribute__((aligned(16))) unsigned long long words[kSortStage * kSortBlock];
+    const int tid = threadIdx.x;
+    const int b = blockIdx.y;
+    const int j = blockIdx.x * 256 + tid;
+    const unsigned long long mine = j < a.n ? order_word(a.score[(long long)b * a.n + j], j) : ~0ull;
+    const uint4 *src = reinterpret_cast<const uint4 *>(a.sorted + (long long)b * a.n_blocks * kSortBlock);
+    int rank = 0;
+    {
+        // one group of eight sorted blocks per workgroup (blockIdx.z): the groups' counts meet in rank[j], which
+        // rank_block_kernel has set to 0, by an atomic add -- a CU streams too slowly to stage them all in turn
+        const int g0 = blockIdx.z * kSortStage;
+        const int nb = min(kSortStage, a.n_blocks - g0);
+        const int units = nb * (kSortBlock / 2);                       // 16-byte units to stage
+        constexpr int kUnits = kSortStage * (kSortBlock / 2), kPer = kUnits / 256;
+        uint4 v[kPer];                                                 // all of a thread's loads in flight together
+#pragma unroll
+        for (int x = 0; x < kPer; ++x) v[x] = src[(long long)g0 * (kSortBlock / 2) + min(256 * x + tid, units - 1)];
+#pragma unroll
+        for (int x = 0; x < kPer; ++x)                                 // blocks past the last one: words of 0
+            reinterpret_cast<uint4 *>(words)[256 * x + tid] = 256 * x + tid < units ? v[x] : make_uint4(0, 0, 0, 0);
+        __syncthreads();
+        // words above `mine` in each staged block: the blocks descend, so that is the first place whose word is
+        // not above it.  Branch-free bisections, the eight blocks' side by side: their probes are independent.
+        int pos[kSortStage];
+#pragma unroll
+        for (int bb = 0; bb < kSortStage; ++bb) pos[bb] = 0;
+#pragma unroll
+        for (int step = kSortBlock / 2; step >= 1; step >>= 1) {
+#pragma unroll
+            for (int bb = 0; bb < kSortStage; ++bb) pos[bb] += words[bb * kSortBlock + pos[bb] + step - 1] > mine ? step : 0;
+        }
+#pragma unroll
+        for (int bb = 0; bb < kSortStage; ++bb) rank += pos[bb] + (words[bb * kSortBlock + pos[bb]] > mine ? 1 : 0);   // place 1023 itself
+    }
+    if (j < a.n) {
+        if (gridDim.z == 1) a.rank[(long long)b * a.n + j] = rank;
+        else atomicAdd(&a.rank[(long long)b * a.n + j], rank);
     }
 }
 
@@ -326,8 +438,25 @@ __global__ __launch_bounds__(256) void finalize_kernel(GatherArgs a) {
 
 }  // namespace
 
-void launch_rank(const Prof &prof, const float *score, int32_t *rank, int n, int B) {
+size_t rank_scratch_bytes(int n, int B) {
+    if (n < kSortMinTokens) return 0;
+    return (size_t)B * ((n + kSortBlock - 1) / kSortBlock) * kSortBlock * sizeof(unsigned long long);
+}
+
+void launch_rank(const Prof &prof, const float *score, int32_t *rank, int n, int B, void *scratch) {
     hipStream_t stream = prof.stream;
+    if (scratch && n >= kSortMinTokens) {
+        SortArgs sa{};
+        sa.score = score;
+        sa.sorted = static_cast<unsigned long long *>(scratch);
+        sa.rank = rank;
+        sa.n = n;
+        sa.n_blocks = (n + kSortBlock - 1) / kSortBlock;
+        LVLM_LAUNCH(prof, rank_block_kernel, dim3(sa.n_blocks * (kSortBlock / 64), B), dim3(1024), 0, stream, sa);
+        LVLM_LAUNCH(prof, rank_search_kernel, dim3((n + 255) / 256, B, (sa.n_blocks + kSortStage - 1) / kSortStage), dim3(256), 0,
+                    stream, sa);
+        return;
+    }
     RankArgs ra{};
     ra.score = score;
     ra.rank = rank;
@@ -356,7 +485,8 @@ MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes) {
     w.dst_of = align_up(w.rank_part + (size_t)d.B * w.n_split * d.n_img * sizeof(int32_t), 256);
     w.wgt = align_up(w.dst_of + (size_t)d.B * d.n_img * sizeof(int32_t), 256);
     w.partial = align_up(w.wgt + (size_t)d.B * d.n_img * sizeof(float), 256);
-    w.total = align_up(w.partial + (size_t)d.B * d.n_planes * w.n_chunk * max_elems * sizeof(float), 256);
+    w.sorted = align_up(w.partial + (size_t)d.B * d.n_planes * w.n_chunk * max_elems * sizeof(float), 256);
+    w.total = align_up(w.sorted + rank_scratch_bytes(d.n_img, d.B), 256);
     return w;
 }
 
@@ -392,7 +522,7 @@ hipError_t launch_merge(const Prof &prof, const lvlm_merge_desc &d, const MergeW
     if (r > 0) {
         int32_t *rank = reinterpret_cast<int32_t *>(ws + w.rank_part);
         prof.begin("merge_rank");
-        launch_rank(prof, score_mean, rank, d.n_img, d.B);
+        launch_rank(prof, score_mean, rank, d.n_img, d.B, ws + w.sorted);
         prof.end();
         IndexArgs ia{};
         ia.rank = rank;

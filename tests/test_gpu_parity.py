@@ -228,6 +228,19 @@ def test_merge_compact_ties_and_special_scores(ctx):
     _merge_case(ctx, torch.float32, 2, 2, n_img, 2, 64, 123, score=s, seed=7)
 
 
+@pytest.mark.parametrize("n_img", [8192, 8193, 9000, 17000])
+def test_merge_compact_long_sequences_rank_by_sorted_blocks(ctx, n_img):
+    # from 8192 image tokens on the ranks come from sorted blocks of 1024 tokens and binary searches instead of
+    # counting: whole and ragged block counts, heavy ties (eight distinct scores), NaN / inf / signed zeros, two
+    # sequences; the index lists must equal the oracle's, order included
+    s = torch.rand(2, n_img, generator=torch.Generator().manual_seed(n_img))
+    s[1] = (s[1] * 8).floor() / 8
+    s[0, 5], s[0, 1030], s[1, 7], s[1, 2048], s[0, n_img - 1] = float("nan"), float("-inf"), -0.0, float("inf"), 0.0
+    _merge_case(ctx, torch.bfloat16, 2, 2, n_img, 3, 64, n_img // 3, score=s, extra_planes=False, seed=n_img)
+    if n_img == 8192:       # all scores equal: the order is the index order
+        _merge_case(ctx, torch.float32, 1, 0, n_img, 0, 64, 100, score=torch.full((1, n_img), 0.5), extra_planes=False, seed=9)
+
+
 def test_merge_compact_non_finite_rows_outside_p_merged(ctx):
     # Sec. 3.2.1: P_new = W_v x P_merged touches the r+1 merged rows only.  An inf / NaN in a kept image row, in a
     # text row or in a system row must be copied as it is and must not leak into the merged token.
