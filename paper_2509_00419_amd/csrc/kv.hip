@@ -459,7 +459,7 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
     int first_hole = L;                  // lowest new slot whose entry moves (STABLE)
     int base_tie = 0, base_keep = 0, base_hole = 0, base_tail = 0;
     const bool ties_all_kept = evict_all_cand || tie_keep >= (unsigned long long)last_c;
-    auto round = [&](int s0, auto round_tag) {
+    auto number_round = [&](int s0, auto round_tag) {
         constexpr int R0 = decltype(round_tag)::value * CH;   // first register-resident key of the round
         uint32_t tiem = 0u, keepm = 0u;              // bit c: the thread's slot of chunk c is a tie / a sure survivor
 #pragma unroll
@@ -533,13 +533,13 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
         __syncthreads();                             // the count table is reused by the next round
     };
     if constexpr (KPT > 0) {
-        round(0, std::integral_constant<int, 0>{});
+        number_round(0, std::integral_constant<int, 0>{});
         if constexpr (NROUND > 1) {
-            if (NT * CH < L) round(NT * CH, std::integral_constant<int, 1>{});
+            if (NT * CH < L) number_round(NT * CH, std::integral_constant<int, 1>{});
         }
         static_assert(NROUND <= 2, "two rounds cover the register-resident keys");
     } else {
-        for (int s0 = 0; s0 < L; s0 += NT * CH) round(s0, std::integral_constant<int, 0>{});
+        for (int s0 = 0; s0 < L; s0 += NT * CH) number_round(s0, std::integral_constant<int, 0>{});
     }
     if (stable) {
 #pragma unroll
