@@ -102,6 +102,9 @@ LVLM_API const char *lvlm_last_error(const lvlm_ctx *ctx);
  * n_keep either, except for LVLM_OP_MERGE_SIMILAR (whose scratch holds one entry
  * per dominant token: there n_keep must already be the value of the call). */
 LVLM_API lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const void *desc, size_t *bytes);
+/* Size limits, checked with the other descriptor fields (LVLM_ERR_INVALID_ARG beyond them): B <= 65536, Hq and
+ * Hkv <= 1024, N <= 4194304 tokens, Lmax <= 16777216 slots, row_elems <= 1048576.  Within them no size or grid
+ * computation of the library can overflow. */
 /* Attaches caller-owned device scratch (256-byte aligned).  May be replaced at
  * any time between calls; the library never frees it. */
 LVLM_API lvlm_status lvlm_set_workspace(lvlm_ctx *ctx, void *dev_ptr, size_t bytes);

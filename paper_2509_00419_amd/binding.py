@@ -14,7 +14,8 @@ from typing import Optional, Sequence
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "liblvlm.so")
+# the in-tree build, or another build of the same sources named by LVLM_LIBRARY (e.g. one with a sanitized host side)
+LIB_PATH = os.environ.get("LVLM_LIBRARY") or os.path.join(HERE, "liblvlm.so")
 
 # ---- enums (include/lvlm.h) ----
 BF16, F32, I32 = 0, 1, 2

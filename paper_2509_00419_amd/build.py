@@ -49,5 +49,27 @@ def build_library(verbose: bool = True) -> str:
     return LIB_PATH
 
 
+def build_host_sanitized(out_dir: str) -> str:
+    """The same sources with the HOST side under the undefined-behaviour sanitizer in trap mode (no runtime library:
+    undefined behaviour in the library's host code ends the process with an illegal-instruction signal).  The device
+    code is compiled as always, at -O1.  Returns the path of the library written into out_dir."""
+    os.makedirs(out_dir, exist_ok=True)
+    flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+                                                "-fsanitize-trap=undefined"]
+    procs, objs = [], []
+    for src in SOURCES:
+        obj = os.path.join(out_dir, src.replace(".hip", ".o"))
+        procs.append((src, subprocess.Popen([HIPCC, *flags, "-c", os.path.join(CSRC, src), "-o", obj],
+                                            stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs.append(obj)
+    for src, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+    lib = os.path.join(out_dir, "liblvlm_ubsan.so")
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], check=True)
+    return lib
+
+
 if __name__ == "__main__":
     print(build_library())

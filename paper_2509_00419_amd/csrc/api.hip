@@ -30,11 +30,17 @@ bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0
 bool float_dtype(int dt) { return dt == LVLM_BF16 || dt == LVLM_F32; }
 int elem_bytes(int dt) { return dt == LVLM_BF16 ? 2 : 4; }
 
+// Upper limits of the size fields (include/lvlm.h states them): generous for any cache or sequence that fits a GPU,
+// and tight enough that no size or grid computation in the library can overflow.
+constexpr int kMaxBatch = 1 << 16, kMaxHeads = 1 << 10, kMaxTokens = 1 << 22, kMaxSlots = 1 << 24, kMaxRowElems = 1 << 20;
+const char *kTooLarge = "size beyond the documented limits (B 65536, heads 1024, N 4194304, Lmax 16777216, row_elems 1048576)";
+
 const char *check_score(const lvlm_score_desc *d) {
     if (!d) return "null descriptor";
     if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
     if (d->hd != 64 && d->hd != 128) return "head dimension must be 64 or 128";
     if (d->B < 1 || d->N < 1 || d->T < 1 || d->Hq < 1 || d->Hkv < 1) return "sizes must be positive";
+    if (d->B > kMaxBatch || d->N > kMaxTokens || d->Hq > kMaxHeads) return kTooLarge;
     if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
     if ((long long)(d->Hq / d->Hkv) * d->T >= 65536) return "query rows per KV head (Hq/Hkv * T) must be below 65536";
     if (d->img_begin < 0 || d->n_img < 1 || (long long)d->img_begin + d->n_img > d->N) return "image span outside [0, N)";
@@ -56,6 +62,7 @@ const char *check_prefill(const lvlm_prefill_desc *d) {
     if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
     if (d->hd != 64 && d->hd != 128) return "head dimension must be 64 or 128";
     if (d->B < 1 || d->N < 1 || d->Hq < 1 || d->Hkv < 1) return "sizes must be positive";
+    if (d->B > kMaxBatch || d->N > kMaxTokens || d->Hq > kMaxHeads) return kTooLarge;
     if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
     if (d->T < 0 || d->T > d->N) return "T must be in [0, N]";
     if (!(d->scale > 0.0f)) return "scale must be positive";
@@ -80,6 +87,7 @@ const char *check_probs(const lvlm_probs_desc *d) {
     if (!d) return "null descriptor";
     if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
     if (d->B < 1 || d->N < 1 || d->T < 1 || d->Hq < 1 || d->Hkv < 1) return "sizes must be positive";
+    if (d->B > kMaxBatch || d->N > kMaxTokens || d->Hq > kMaxHeads) return kTooLarge;
     if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
     if ((long long)(d->Hq / d->Hkv) * d->T >= 65536) return "query rows per KV head (Hq/Hkv * T) must be below 65536";
     if (d->img_begin < 0 || d->n_img < 1 || (long long)d->img_begin + d->n_img > d->N) return "image span outside [0, N)";
@@ -94,6 +102,7 @@ const char *check_probs(const lvlm_probs_desc *d) {
 const char *check_merge(const lvlm_merge_desc *d, const lvlm_plane *planes) {
     if (!d) return "null descriptor";
     if (d->B < 1 || d->N < 1) return "sizes must be positive";
+    if (d->B > kMaxBatch || d->N > kMaxTokens) return kTooLarge;
     if (d->img_begin < 0 || d->n_img < 1 || (long long)d->img_begin + d->n_img > d->N) return "image span outside [0, N)";
     if (d->n_keep < 1 || d->n_keep > d->n_img) return "n_keep must be in [1, n_img]";
     if (d->n_planes < 1 || d->n_planes > LVLM_MAX_PLANES) return "n_planes must be in [1, LVLM_MAX_PLANES]";
@@ -104,6 +113,7 @@ const char *check_merge(const lvlm_merge_desc *d, const lvlm_plane *planes) {
         if (!p.src || !p.dst) return "null plane pointer";
         if (!aligned16(p.src) || !aligned16(p.dst)) return "plane pointers must be 16-byte aligned";
         if (p.row_elems < 1) return "row_elems must be positive";
+        if (p.row_elems > kMaxRowElems) return kTooLarge;
         if (p.dtype != LVLM_BF16 && p.dtype != LVLM_F32 && p.dtype != LVLM_I32) return "unknown plane dtype";
         if (p.merge_rule != LVLM_RULE_WEIGHTED && p.merge_rule != LVLM_RULE_TOP) return "unknown merge rule";
         if (p.dtype == LVLM_I32 && p.merge_rule != LVLM_RULE_TOP) return "integer planes need LVLM_RULE_TOP";
@@ -124,6 +134,7 @@ const char *check_kv(const lvlm_kv_desc *d) {
     if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
     if (d->hd != 64 && d->hd != 128) return "head dimension must be 64 or 128";
     if (d->B < 1 || d->Hkv < 1 || d->Lmax < 1) return "sizes must be positive";
+    if (d->B > kMaxBatch || d->Hkv > kMaxHeads || d->Lmax > kMaxSlots) return kTooLarge;
     if (d->len_bound < 0 || d->len_bound > d->Lmax) return "len_bound must be in [0, Lmax]";
     if (d->mode != LVLM_KV_THRESHOLD && d->mode != LVLM_KV_BUDGET) return "unknown mode";
     if (d->order != LVLM_ORDER_STABLE && d->order != LVLM_ORDER_FILL) return "unknown order";
@@ -138,6 +149,7 @@ const char *check_attn(const lvlm_attn_desc *d) {
     if (!float_dtype(d->dtype)) return "dtype must be LVLM_BF16 or LVLM_F32";
     if (d->hd != 64 && d->hd != 128) return "head dimension must be 64 or 128";
     if (d->B < 1 || d->Hq < 1 || d->Hkv < 1 || d->Lmax < 1) return "sizes must be positive";
+    if (d->B > kMaxBatch || d->Hq > kMaxHeads || d->Lmax > kMaxSlots) return kTooLarge;
     if (d->Hq % d->Hkv != 0) return "Hq must be a multiple of Hkv";
     if (d->len_bound < 0 || d->len_bound > d->Lmax) return "len_bound must be in [0, Lmax]";
     if (d->new_kind < 0 || d->new_kind > 255) return "new_kind out of range";
@@ -280,8 +292,11 @@ lvlm_status lvlm_workspace_bytes(const lvlm_ctx *ctx, lvlm_op op, const void *de
             if (!d || !qy->planes) { why = "null merge query member"; break; }
             if (d->B < 1 || d->N < 1 || d->n_img < 1 || d->n_img > d->N || d->n_planes < 1 ||
                 d->n_planes > LVLM_MAX_PLANES) { why = "bad merge descriptor"; break; }
-            for (int i = 0; i < d->n_planes; ++i)
+            if (d->B > kMaxBatch || d->N > kMaxTokens) { why = kTooLarge; break; }
+            for (int i = 0; i < d->n_planes; ++i) {
                 if (qy->planes[i].row_elems < 1) why = "row_elems must be positive";
+                else if (qy->planes[i].row_elems > kMaxRowElems) why = kTooLarge;
+            }
             if (why) break;
             if (op == LVLM_OP_MERGE_SIMILAR) {
                 if (d->n_keep < 1 || d->n_keep > d->n_img) { why = "n_keep must be in [1, n_img]"; break; }

@@ -122,3 +122,54 @@ def test_score_plan_reports_the_launch_form():
     bad = bd.ScoreDesc(bd.BF16, 1, 100, 4, 96, 6, 4, 128, 0, 50, 1, 1.0, 0, 0, 128, 0, 0, 128)
     with pytest.raises(lv.LvlmError):
         ctx.score_plan(bad)
+
+
+def test_size_arithmetic_survives_extreme_shapes():
+    """Sizes at the documented limits are answered, sizes beyond them are refused -- and neither may overflow
+    anything on the way (this file runs a second time against a build whose host code traps on signed overflow
+    and other undefined behaviour)."""
+    ctx = _ctx()
+    big = 1 << 30
+
+    def ask(op, d):
+        n = C.c_size_t()
+        st = bd.lib.lvlm_workspace_bytes(ctx._h, op, C.byref(d), C.byref(n))
+        return st, n.value
+
+    def score_desc(B, N, T, Hq, Hkv):
+        n_img = max(1, N - T) if N > T else 1
+        return bd.ScoreDesc(bd.BF16, B, N, T, max(0, N - T), Hq, Hkv, 128, 0, n_img, 1, 0.088, T * Hq * 128, Hq * 128, 128,
+                            N * Hkv * 128, Hkv * 128, 128)
+
+    # at the limits: B 65536, heads 1024, N 2^22, Lmax 2^24, row_elems 2^20
+    for B, N, T, Hq, Hkv in ((65536, 1 << 22, 8191, 1024, 128), (65536, 1 << 22, 63, 1024, 1), (1, 1 << 22, 65535, 1024, 1024),
+                             (65536, 1, 1, 8, 8)):
+        st, n = ask(bd.OP_SCORE, score_desc(B, N, T, Hq, Hkv))
+        assert st == 0 and n > 0, (B, N, T, Hq, Hkv)
+        form = C.c_int32()
+        assert bd.lib.lvlm_score_plan(ctx._h, C.byref(score_desc(B, N, T, Hq, Hkv)), C.byref(form)) == 0
+    for B, H, Lmax in ((65536, 1024, 1 << 24), (1, 1, 1 << 24), (65536, 128, 1)):
+        assert ask(bd.OP_KV_COMPRESS, bd.KvDesc(bd.BF16, B, H, 128, Lmax, 0, bd.KV_BUDGET, bd.ORDER_FILL, 1024, 1, 0.995))[0] == 0
+        assert ask(bd.OP_KV_COMPRESS, bd.KvDesc(bd.F32, B, H, 64, Lmax, Lmax, bd.KV_THRESHOLD, bd.ORDER_STABLE, 0, 0, 0.5))[0] == 0
+        Hq = min(8 * H, 1024)
+        assert ask(bd.OP_DECODE_ATTN, bd.AttnDesc(bd.BF16, B, Hq, Hq // 8 if Hq >= 8 else Hq, 128, Lmax, 0, 2, 0, 0.088, 0.9))[0] == 0
+        assert ask(bd.OP_DECODE_ATTN, bd.AttnDesc(bd.F32, B, H, H, 64, Lmax, Lmax, 2, 0, 0.088, 0.9,
+                                                  Lmax - 1 if Lmax > 1 else 0, 1))[0] == 0
+    for B, N, n_img, n_keep, C_ in ((65536, 1 << 22, 1 << 22, 1, 1 << 20), (1, 1 << 22, (1 << 22) - 5, 1 << 21, 8),
+                                    (1, 17000, 16384, 5091, 6144)):
+        md = bd.MergeDesc(B, N, 0, n_img, n_keep, 1)
+        planes = (bd.Plane * 1)(bd.Plane(0, 0, N * C_, N * C_, C_, bd.BF16, 0, 0))
+        assert ask(bd.OP_MERGE, bd.MergeQuery(C.pointer(md), planes))[0] == 0
+        assert ask(bd.OP_MERGE_SIMILAR, bd.MergeQuery(C.pointer(md), planes))[0] == 0
+    # beyond them: refused, with the limits in the message
+    assert ask(bd.OP_SCORE, score_desc(1, big, 128, 48, 8))[0] == 1 and b"limits" in bd.lib.lvlm_last_error(ctx._h)
+    assert ask(bd.OP_SCORE, score_desc(2 ** 31 - 1, 2 ** 31 - 1, 1, 2 ** 31 - 1, 1))[0] == 1
+    assert ask(bd.OP_KV_COMPRESS, bd.KvDesc(bd.BF16, 2 ** 31 - 1, 2 ** 31 - 1, 128, 2 ** 31 - 1, 0, bd.KV_BUDGET, bd.ORDER_FILL,
+                                            1024, 1, 0.995))[0] == 1
+    assert ask(bd.OP_DECODE_ATTN, bd.AttnDesc(bd.BF16, 1, 8, 8, 128, 2 ** 31 - 1, 0, 2, 0, 0.088, 0.9))[0] == 1
+    md = bd.MergeDesc(2 ** 31 - 1, 2 ** 31 - 1, 0, 2 ** 31 - 1, 1, 1)
+    planes = (bd.Plane * 1)(bd.Plane(0, 0, 0, 0, 2 ** 31 - 1, bd.BF16, 0, 0))
+    assert ask(bd.OP_MERGE, bd.MergeQuery(C.pointer(md), planes))[0] == 1
+    for m in (1, 2, 100000):
+        assert lv.merge_weights(lv.MERGE_LINEAR_RANK, m).numel() == m
+    assert lv.schedule(2 ** 31 - 1, 0.5, 8)[-1] > 0
