@@ -581,6 +581,64 @@ def test_decode_attn_heads_at_or_beyond_the_length_bound(ctx):
                     assert torch.equal(got[i][b, h, n_att:], host[i][b, h, n_att:]), (b, h, i)
 
 
+def _guarded(call):
+    """Runs call(ctx, reserve) twice on fresh inputs: once to learn the scratch size the library asks for, once with
+    a workspace of exactly that size in front of a guard band, which must come back untouched."""
+    import ctypes as C
+    from paper_2509_00419_amd import binding as bd
+    probe = lv.Context(0)
+    call(probe, True)
+    torch.cuda.synchronize()
+    need = 0 if probe._ws is None else probe._ws.numel()
+    own = lv.Context(0)
+    guard = 1 << 16
+    ws = torch.full((need + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    own._ws = ws
+    own._check(bd.lib.lvlm_set_workspace(own._h, C.c_void_p(ws.data_ptr()), need))
+    call(own, False)
+    torch.cuda.synchronize()
+    assert bool((ws[need:] == 0xA5).all())
+
+
+def test_no_call_writes_past_the_workspace_it_asked_for(ctx):
+    # decode attention: heads at and beyond the bound, ragged short heads, every launch form
+    for dtype, d, Hq, Hkv, Lmax, bound, lens, budget in (
+            (torch.bfloat16, 128, 14, 2, 1100, 1025, [1025, 1040, 1024, 600], 1024),
+            (torch.bfloat16, 64, 8, 2, 700, 640, [640, 699, 639, 1], 0),
+            (torch.float32, 64, 4, 4, 400, 300, [300, 350, 299, 17, 300, 301, 0, 128], 0),
+            (torch.bfloat16, 128, 4, 2, 5000, 4100, [4100, 4999, 4099, 2047], 4099),
+            (torch.bfloat16, 128, 8, 1, 2100, 2049, [2049], 2048)):
+        B = len(lens) // Hkv
+
+        def decode(c, reserve):
+            dev = [t.to(DEV) for t in _cache(dtype, B, Hkv, Lmax, d, lens, 160)]
+            q, kn, vn = (_rand(sh, dtype, 161 + i).to(DEV) for i, sh in enumerate(((B, Hq, d), (B, Hkv, d), (B, Hkv, d))))
+            c.decode_attn(q, kn, vn, *dev, score_decay=0.9, new_pos=9, len_bound=bound, evict_budget=budget, evict_recent=1,
+                          reserve=reserve)
+        _guarded(decode)
+    # cache compression: both rules and orders, ragged heads, a head beyond the bound, the long-head form
+    for Lmax, bound, lens, kw in ((2048, 0, [1500, 1, 0, 777, 1024, 2047], dict(mode=lv.KV_THRESHOLD, beta=0.9, order=lv.ORDER_FILL)),
+                                  (3000, 2000, [2000, 2500, 1999, 2049, 5, 0], dict(mode=lv.KV_BUDGET, budget=700, n_recent=2, order=lv.ORDER_STABLE)),
+                                  (12000, 0, [11111, 8193, 12000, 1, 4096, 9000], dict(mode=lv.KV_BUDGET, budget=5000, n_recent=0, order=lv.ORDER_FILL))):
+        def compress(c, reserve):
+            dev = [t.to(DEV) for t in _cache(torch.bfloat16, 3, 2, Lmax, 64, lens, 170)]
+            c.kv_compress(*dev, len_bound=bound, reserve=reserve, **kw)
+        _guarded(compress)
+    # merge: counting ranks and sorted blocks; scoring: the three launch forms
+    for n_img, n_keep, B in ((1333, 400, 3), (9000, 3000, 2)):
+        def merge(c, reserve):
+            hid = _rand((B, n_img + 12, 264), torch.bfloat16, 180).to(DEV)
+            score = torch.rand(B, n_img, generator=torch.Generator().manual_seed(181)).to(DEV)
+            c.merge_compact([hid], score, img_begin=5, n_img=n_img, n_keep=n_keep, reserve=reserve)
+        _guarded(merge)
+    for B, N, T, n_img in ((1, 5000, 64, 4800), (1, 845, 64, 717), (48, 986, 96, 890)):
+        def score(c, reserve):
+            q = _rand((B, T, 8, 128), torch.bfloat16, 190).to(DEV)
+            k = _rand((B, N, 2, 128), torch.bfloat16, 191).to(DEV)
+            c.score_tokens(q, k, q_pos0=N - T, img_begin=N - T - n_img, n_img=n_img, reserve=reserve)
+        _guarded(score)
+
+
 def test_kv_compress_leaves_heads_beyond_the_length_bound_alone(ctx):
     # a head longer than len_bound is not compressed at all (nothing evicted, nothing moved); the others are
     host = _cache(torch.bfloat16, 2, 2, 3000, 64, [2000, 2500, 1999, 2049], 150)
