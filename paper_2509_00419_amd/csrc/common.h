@@ -62,7 +62,7 @@ struct MergeWs {
 MergeWs merge_ws(const lvlm_merge_desc &d, const lvlm_plane *planes);
 
 struct SimWs {
-    size_t rank, dom_of, keep_idx, rest_idx, inv_norm, pbest_val, pbest_idx, assign, key, rank2, order, total;
+    size_t rank, dom_of, keep_idx, rest_idx, inv_norm, pbest_val, pbest_idx, assign, key, rank2, order, sorted, total;
     int tile;      // rows of dominant (and of other) tokens per workgroup tile of the similarity product
     int NB;        // blocks of `tile` dominant tokens
 };

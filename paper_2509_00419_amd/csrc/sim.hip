@@ -478,6 +478,7 @@ SimWs sim_ws(const lvlm_merge_desc &d) {
     w.key = take(n * 4);
     w.rank2 = take(n * 4);
     w.order = take(n * 4);
+    w.sorted = take(rank_scratch_bytes(d.n_img, d.B));     // sorted blocks of the two rankings, used in turn
     w.total = off;
     return w;
 }
@@ -528,7 +529,7 @@ hipError_t launch_merge_similar(const Prof &prof, const lvlm_merge_desc &d, cons
 
     const dim3 per_token((d.n_img + 255) / 256, d.B);
     prof.begin("sim_rank");
-    launch_rank(prof, score_mean, a.rank, d.n_img, d.B, nullptr);
+    launch_rank(prof, score_mean, a.rank, d.n_img, d.B, ws + w.sorted);
     prof.end();
     prof.begin("sim_index");
     LVLM_LAUNCH(prof, sim_index_kernel, dim3(d.B), dim3(1024), 0, stream, a);
@@ -563,7 +564,7 @@ hipError_t launch_merge_similar(const Prof &prof, const lvlm_merge_desc &d, cons
     LVLM_LAUNCH(prof, sim_assign_kernel, per_token, dim3(256), 0, stream, a);
     prof.end();
     prof.begin("sim_rank2");
-    launch_rank(prof, a.key, a.rank2, d.n_img, d.B, nullptr);
+    launch_rank(prof, a.key, a.rank2, d.n_img, d.B, ws + w.sorted);
     prof.end();
     prof.begin("sim_order");
     LVLM_LAUNCH(prof, sim_order_kernel, per_token, dim3(256), 0, stream, a);

@@ -968,6 +968,7 @@ def test_merge_similar(ctx):
     _similar_case(ctx, torch.float32, 1, 2, 200, 2, 64, 200, 105)                                # nothing removed
     _similar_case(ctx, torch.bfloat16, 1, 1, 500, 1, 128, 130, 106, identical=True)              # all ties
     _similar_case(ctx, torch.bfloat16, 1, 2, 150, 2, 72, 40, 107, clusters=4)                    # 144-byte rows: partial slice
+    _similar_case(ctx, torch.bfloat16, 1, 2, 4500, 2, 64, 1200, 108, clusters=16)               # ranks by sorted blocks
 
 
 # --------------------------------------------------------------------------- seeded random shapes, every entry point
