@@ -594,7 +594,8 @@ __global__ __launch_bounds__(NT) void kv_select_kernel(KvArgs a) {
 }
 
 constexpr int kFillInKernel = 64;  // most FILL moves per head that the selection kernel performs itself
-constexpr int kFillRows = 32;      // moves per workgroup of kv_fill_kernel (at most 4 row units per thread)
+constexpr int kFillRows = 32;      // moves per batch of kv_fill_kernel (at most 4 row units per thread)
+constexpr int kFillWgs = 16384;    // workgroups the fill launch aims for
 
 // LVLM_ORDER_FILL with many moves per head: entry list_b[i] (at or beyond the new length) goes to hole
 // list_a[i] (below it).  Sources and destinations are disjoint, so the moves are independent.
@@ -602,15 +603,16 @@ __global__ __launch_bounds__(256) void kv_fill_kernel(KvArgs a) {
     const int tid = threadIdx.x;
     const int hg = blockIdx.y;
     const int n_moves = a.meta[2 * hg + 1];
-    const int i0 = blockIdx.x * kFillRows;
-    if (i0 >= n_moves) return;
-    const int cnt = min(kFillRows, n_moves - i0);
     const long long base = (long long)hg * a.Lmax;
-    const int32_t *holes = a.list_a + base + i0;
-    const int32_t *tails = a.list_b + base + i0;
     const int units = a.row_bytes / 16;
     char *kc = a.k + base * a.row_bytes;
     char *vc = a.v + base * a.row_bytes;
+    // The head's workgroups take batches of 32 moves in turn (how many moves a head has is known only on the
+    // device: a grid sized for the most there can be would start tens of thousands of workgroups that find nothing).
+    for (int i0 = blockIdx.x * kFillRows; i0 < n_moves; i0 += gridDim.x * kFillRows) {
+    const int cnt = min(kFillRows, n_moves - i0);
+    const int32_t *holes = a.list_a + base + i0;
+    const int32_t *tails = a.list_b + base + i0;
     // rows have at most 32 units (fp32, 128 channels): 32 rows are at most 4 units per thread
     const int n_units = cnt * units;
     uint4 kv0, kv1, kv2, kv3, vv0, vv1, vv2, vv3;
@@ -638,6 +640,7 @@ __global__ __launch_bounds__(256) void kv_fill_kernel(KvArgs a) {
         a.score[base + dst] = a.score[base + src];
         a.kind[base + dst] = a.kind[base + src];
         a.pos[base + dst] = a.pos[base + src];
+    }
     }
 }
 
@@ -776,7 +779,11 @@ hipError_t launch_kv_compress(const Prof &prof, const lvlm_kv_desc &d, const KvW
         prof.end();
     } else if (a.fill_external) {
         prof.begin("kv_fill");
-        LVLM_LAUNCH(prof, kv_fill_kernel, dim3((max_moves + kFillRows - 1) / kFillRows, (unsigned)heads), dim3(256), 0, stream, a);
+        // about 16384 workgroups in all, at most one per batch of moves the longest head can have
+        const long long most = (max_moves + kFillRows - 1) / kFillRows;
+        long long per_head = (kFillWgs + (long long)heads - 1) / (long long)heads;
+        per_head = per_head < 1 ? 1 : (per_head > most ? most : per_head);
+        LVLM_LAUNCH(prof, kv_fill_kernel, dim3((unsigned)per_head, (unsigned)heads), dim3(256), 0, stream, a);
         prof.end();
     }
     return hipGetLastError();
