@@ -72,6 +72,9 @@ def parse():
                     help="step: the token-reduction path (the default, the headline metric); prefill_attn: "
                          "lvlm_prefill_attn alone over the layer stack -- the layers' own attention at the token "
                          "counts the pyramid leaves, with the scores as its by-product where the path scores")
+    ap.add_argument("--decode-evict", choices=["batched", "fused"], default="batched",
+                    help="steady-state decode: one lvlm_kv_compress over all layers' caches at the end of the step "
+                         "(batched), or the eviction inside every layer's lvlm_decode_attn call (fused)")
     ap.add_argument("--profile-steps", type=int, default=3, help="eager steps timed per kernel with HIP events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
@@ -419,8 +422,11 @@ def run_decode(ctx, lv, w, states, reserve, step_pos=0):
 
 
 def decode_evicts_in_attention(w, states):
-    """A cache that can be exactly one entry over its budget is compressed by the attention call itself."""
-    return w.kv_budget > 0 and states.dec_bound == w.kv_budget + 1
+    """A cache that can be exactly one entry over its budget can be compressed by the attention call itself
+    (states.evict == "fused", the default of a state); with "batched" the layers' calls only update the importance
+    and ONE lvlm_kv_compress over the stacked caches of all layers evicts at the end of the step -- a layer's cache
+    is not read again before the next step."""
+    return w.kv_budget > 0 and states.dec_bound == w.kv_budget + 1 and getattr(states, "evict", "fused") == "fused"
 
 
 def run_decode_layers(ctx, lv, w, states, reserve, step_pos=0):
@@ -463,7 +469,8 @@ def moved_entries(pos_before, pos_after, len_after, torch):
     return int(((pos_before != pos_after) & live).sum())
 
 
-def kernel_work(ctx, lv, w, layers, dec_lens, moved, merge="rank", per_layer=False, given_lse=False, fused=False):
+def kernel_work(ctx, lv, w, layers, dec_lens, moved, merge="rank", per_layer=False, given_lse=False, fused=False,
+                decode_compress=False):
     """Algorithmic bytes / flops of every kernel of one step (summed over its launches), by the profiler's kernel
     names.  HBM kernels: what the method must move, counted once (inputs read once, outputs written once);
     contractions: their multiply-adds.  dec_lens[i]: entries per head of layer i's cache when the decode step
@@ -515,6 +522,8 @@ def kernel_work(ctx, lv, w, layers, dec_lens, moved, merge="rank", per_layer=Fal
         add("attn_partial", "hbm", 2.0 * B * H * L * d * e)                  # K and V of every retained entry, once
         # the fold: importance read-modify-write of every entry, the queries in, the output rows out
         add("attn_combine_evict" if fused else "attn_combine", "hbm", 8.0 * B * H * L + 2.0 * B * Hq * d * e)
+        if decode_compress:                                                  # score and kind of every entry, one entry moved
+            add("kv_select", "hbm", B * H * (5.0 * L + 2 * d * e + 9), launches=1.0 / len(layers))
     entry = 2 * d * e + 9                                                   # K row, V row, score, kind, position
     for key in ("threshold", "budget"):
         if moved.get(key + "_scanned", 0) > 0:
@@ -587,9 +596,14 @@ def main():
         dec_lens = [st.len.clone() for st in base]
     else:
         dec_lens = lens_after_prefill
+    for st_ in set(dec_sets) | set(sets):
+        st_.evict = args.decode_evict
     run_decode(ctx, lv, w, sets[0], reserve=True)            # (also the first decode step's workspace)
+    if steady:
+        run_decode(ctx, lv, w, dec_sets[0], reserve=True, step_pos=steady_steps + 1)     # the steady-state shapes' workspace
     torch.cuda.synchronize()
     fused = decode_evicts_in_attention(w, dec_sets[1])
+    binds = w.kv_budget > 0 and dec_sets[1].dec_bound == w.kv_budget + 1      # one eviction per head and step
 
     # capture one (prefill, decode) graph pair per remaining set
     use_graph = not args.no_graph
@@ -685,7 +699,8 @@ def main():
         torch.cuda.synchronize()
 
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
-    work = kernel_work(ctx, lv, w, layers, dec_lens, moved, args.merge, args.per_layer, args.row_lse == "given", fused)
+    work = kernel_work(ctx, lv, w, layers, dec_lens, moved, args.merge, args.per_layer, args.row_lse == "given", fused,
+                       decode_compress=binds and not fused)
     kernels = {}
     for name, p in sorted(prof.items(), key=lambda kv: -kv[1]["us_per_step"]):
         row = {"avg_us": round(p["avg_us"], 2), "launches_per_step": p["launches_per_step"],
@@ -749,7 +764,8 @@ def main():
                                     f"{steady_steps} decode steps of the path during set-up)") if steady else
                                    ("steady state: every head at its budget as prefill leaves it" if fused else
                                     "caches as prefill leaves them (the budget does not bind)"),
-                   "eviction": "inside lvlm_decode_attn" if fused else "none needed",
+                   "eviction": "inside lvlm_decode_attn" if fused else
+                               ("one lvlm_kv_compress over all layers' caches at the end of the step" if binds else "none needed"),
                    "image_entries_kept_by_threshold_per_layer": kept_fraction},
         "prefill_ms": round(prefill_ms, 4), "decode_step_ms": round(decode_ms, 4),
         "prefill_image_tokens_per_s": round(w.batch * w.n_img / (prefill_ms * 1e-3), 1) if prefill_ms > 0 else None,

@@ -222,6 +222,25 @@ def test_steady_state_caches_of_config5_and_one_step_on_them():
         ref = O.kv_compress(*mid[i][0], mode="budget", budget=w.kv_budget, n_recent=1, order=O.ORDER_FILL)
         same_entries(snapshot(L.k, L.v, L.score, L.kind, L.pos, L.len), ref[:6])
     assert int(steady.len.min()) == w.kv_budget == int(steady.len.max())
+    # the form the bench times by default -- the layers' calls update the importance, ONE lvlm_kv_compress over the
+    # stacked caches of all layers evicts at the end of the step -- must leave exactly what the fused form leaves
+    other = steady.clone(torch)
+    for name in ("k", "v", "score", "kind", "pos", "len"):
+        getattr(other, name).copy_(getattr(steady, name))
+    other.evict, steady.evict = "batched", "fused"
+    assert not bench.decode_evicts_in_attention(w, other)
+    for L, M in zip(steady, other):
+        for name in ("q_dec", "k_dec", "v_dec"):
+            getattr(M, name).copy_(getattr(L, name))
+    bench.run_decode(ctx, lv, w, steady, reserve=True, step_pos=steady.steps_run + 2)
+    bench.run_decode(ctx, lv, w, other, reserve=True, step_pos=steady.steps_run + 2)
+    torch.cuda.synchronize()
+    n = w.kv_budget
+    for name in ("k", "v", "score", "kind", "pos"):
+        assert torch.equal(getattr(steady, name)[:, :, :n], getattr(other, name)[:, :, :n]), name
+    assert torch.equal(steady.len, other.len)
+    for L, M in zip(steady, other):
+        assert torch.equal(L.out_dec, M.out_dec)
 
 
 def test_config4_step_in_bench_configuration():
