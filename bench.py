@@ -68,10 +68,12 @@ def parse():
     ap.add_argument("--merge", default="rank", choices=["rank", "similar"],
                     help="merge rule at the pyramid layers: the paper's rank weights (lvlm_merge_compact) or the "
                          "similarity merge (lvlm_merge_similar)")
-    ap.add_argument("--op", default="step", choices=["step", "prefill_attn"],
+    ap.add_argument("--op", default="step", choices=["step", "prefill_attn", "stream"],
                     help="step: the token-reduction path (the default, the headline metric); prefill_attn: "
                          "lvlm_prefill_attn alone over the layer stack -- the layers' own attention at the token "
-                         "counts the pyramid leaves, with the scores as its by-product where the path scores")
+                         "counts the pyramid leaves, with the scores as its by-product where the path scores; "
+                         "stream: lvlm_stream_probe over buffers of the size of one decode layer's K and V rows -- what "
+                         "a launch of that size can stream at all, by workgroup count")
     ap.add_argument("--decode-evict", choices=["batched", "fused"], default="batched",
                     help="steady-state decode: one lvlm_kv_compress over all layers' caches at the end of the step "
                          "(batched), or the eviction inside every layer's lvlm_decode_attn call (fused)")
@@ -550,6 +552,8 @@ def main():
     ctx = lv.Context(0)
     if args.op == "prefill_attn":
         return main_prefill_attn(args, w, layers, ctx, lv, torch, dev)
+    if args.op == "stream":
+        return main_stream(args, w, layers, ctx, lv, torch, dev)
     t_setup = time.time()
     master = build_master(w, layers, torch, synth, dev, args.row_lse == "given")
     n_first = 3                                   # sets whose first decode step after prefill is timed as well
@@ -775,6 +779,53 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
     }
     print(json.dumps(out))
+
+
+# ----------------------------------------------------------------------------- what a launch can stream
+def main_stream(args, w, layers, ctx, lv, torch, dev):
+    """--op stream: the read-only probe over one buffer per layer, each as large as the K and V rows one decode
+    launch of the workload reads (B x Hkv x (budget or sequence) x 2 rows), launched back to back over the layers
+    like the decode step, for a range of workgroup counts; then ONE workgroup over 1 MiB (what one compute unit
+    streams).  Durations from events bound to the kernels."""
+    e = 2 if w.dtype == "bf16" else 4
+    entries = (w.kv_budget + 1) if w.kv_budget > 0 else w.seq_len + 1
+    nbytes = w.batch * w.n_kv_heads * entries * 2 * w.head_dim * e // 16 * 16
+    bufs = [torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(len(layers))]
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    rows = []
+    ctx.profile(True)
+    for n_wg in (64, 128, 256, 512, 1024, 2048, 4096):
+        for rep in range(1 + args.steps):
+            for b in bufs:
+                ctx.stream_probe(b, n_wg, sink)
+            torch.cuda.synchronize()
+            got = ctx.profile_read()["stream_probe"]
+            if rep == 0:
+                continue                                   # warm-up round
+            rows.append((n_wg, got[0], got[1] * 1e3 / got[0]))
+    one = torch.empty(1 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+    for rep in range(1 + args.steps):
+        for _ in range(16):
+            ctx.stream_probe(one, 1, sink)
+        torch.cuda.synchronize()
+        got = ctx.profile_read()["stream_probe"]
+        single_us = got[1] * 1e3 / got[0]
+    ctx.profile(False)
+    table = {}
+    for n_wg, calls, us in rows:
+        table.setdefault(n_wg, []).append(us)
+    by_wg = {str(k): {"us_per_launch": round(sum(v) / len(v), 2), "GBs": round(nbytes / (sum(v) / len(v)) / 1e3, 1),
+                      "frac_of_peak": round(nbytes / (sum(v) / len(v)) / 1e3 / HBM_PEAK_GBS, 4)} for k, v in table.items()}
+    best = max(by_wg.values(), key=lambda r: r["GBs"])
+    print(json.dumps({
+        "metric": "read-only streaming probe (lvlm_stream_probe)", "value": best["GBs"], "unit": "GB/s (best workgroup count)",
+        "n_gpus": 1, "steps": args.steps, "warmup": 1, "higher_is_better": True, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": w.name, "bytes_per_launch": nbytes, "launches": len(layers),
+                   "what": "one decode layer's K and V rows per launch, a different buffer per launch"},
+        "by_workgroups": by_wg,
+        "one_workgroup_1MiB": {"us": round(single_us, 2), "GBs": round((1 << 20) / single_us / 1e3, 1)},
+        "roofline": {"bound": "hbm", "achieved": best["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": best["frac_of_peak"], "traffic": None}}))
 
 
 # ----------------------------------------------------------------------------- the layers' own attention

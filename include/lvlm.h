@@ -419,6 +419,14 @@ LVLM_API lvlm_status lvlm_decode_attn_static(lvlm_ctx *ctx, void *stream, const 
                                     void *k_cache, void *v_cache, float *score, uint8_t *kind,
                                     int32_t *orig_pos, int32_t *len, void *out);
 
+/* Diagnostic, not part of the path: one read-only pass over `bytes` (a multiple of 16) of device memory at src by
+ * n_workgroups workgroups of 256 threads (contiguous shares, 16-byte loads, eight in flight per thread), timed like
+ * any other kernel under lvlm_profile as "stream_probe".  It answers what a launch of a given size and shape can
+ * stream on the device at hand -- the yardstick for the decode-attention launches, which move a few to a few tens of
+ * MB each.  sink: one device word the kernel may write (it never does for ordinary data). */
+LVLM_API lvlm_status lvlm_stream_probe(lvlm_ctx *ctx, void *stream, const void *src, size_t bytes, int32_t n_workgroups,
+                                       uint32_t *sink);
+
 #ifdef __cplusplus
 }
 #endif

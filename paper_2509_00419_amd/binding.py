@@ -121,13 +121,14 @@ def _load():
     lib.lvlm_kv_compress.argtypes = [vp, vp, C.POINTER(KvDesc), vp, vp, f32p, vp, i32p, i32p, i32p]
     lib.lvlm_decode_attn.argtypes = [vp, vp, C.POINTER(AttnDesc), vp, vp, vp, vp, vp, f32p, vp, i32p, i32p, vp]
     lib.lvlm_decode_attn_static.argtypes = lib.lvlm_decode_attn.argtypes
+    lib.lvlm_stream_probe.argtypes = [vp, vp, vp, C.c_size_t, C.c_int32, vp]
     lib.lvlm_profile.argtypes = [C.c_void_p, C.c_int]
     lib.lvlm_profile_read.argtypes = [C.c_void_p, C.POINTER(ProfileEntry), C.c_int, C.POINTER(C.c_int)]
     for name in ("lvlm_profile", "lvlm_profile_read", "lvlm_create", "lvlm_destroy", "lvlm_workspace_bytes", "lvlm_set_workspace", "lvlm_schedule",
                  "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_score_plan", "lvlm_score_from_probs", "lvlm_prefill_attn", "lvlm_merge_compact",
                  "lvlm_merge_similar",
                  "lvlm_kv_compress",
-                 "lvlm_decode_attn", "lvlm_decode_attn_static"):
+                 "lvlm_decode_attn", "lvlm_decode_attn_static", "lvlm_stream_probe"):
         getattr(lib, name).restype = C.c_int
     return lib
 
@@ -199,6 +200,11 @@ class Context:
     def set_workspace(self, ws: Optional[torch.Tensor]):
         self._ws = ws
         self._check(lib.lvlm_set_workspace(self._h, _ptr(ws), 0 if ws is None else ws.numel()))
+
+    def stream_probe(self, src: torch.Tensor, n_workgroups: int, sink: torch.Tensor):
+        """lvlm_stream_probe: a read-only pass over src (diagnostic)."""
+        self._check(lib.lvlm_stream_probe(self._h, _stream(), _ptr(src), src.numel() * src.element_size(), n_workgroups,
+                                          _ptr(sink)))
 
     def profile(self, enable: bool):
         """lvlm_profile: bracket every kernel launch with HIP events (eager mode only)."""

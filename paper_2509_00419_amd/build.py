@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "liblvlm.so")
-SOURCES = ["api.hip", "score.hip", "merge.hip", "sim.hip", "kv.hip", "attn.hip", "prefill.hip", "scratch.hip"]
+SOURCES = ["api.hip", "score.hip", "merge.hip", "sim.hip", "kv.hip", "attn.hip", "prefill.hip", "scratch.hip", "probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

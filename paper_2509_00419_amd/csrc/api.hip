@@ -512,6 +512,16 @@ static lvlm_status decode_attn_call(lvlm_ctx *ctx, bool static_scratch, void *st
                                                 q, k_new, v_new, k_cache, v_cache, score, kind, orig_pos, len, out));
 }
 
+lvlm_status lvlm_stream_probe(lvlm_ctx *ctx, void *stream, const void *src, size_t bytes, int32_t n_workgroups,
+                              uint32_t *sink) {
+    if (!ctx) return LVLM_ERR_INVALID_ARG;
+    if (!src || !sink || bytes < 16 || n_workgroups < 1 || n_workgroups > (1 << 20))
+        return fail(ctx, LVLM_ERR_INVALID_ARG, "stream_probe: null pointer, fewer than 16 bytes or a workgroup count outside [1, 2^20]");
+    if (!aligned16(src) || !aligned4(sink)) return fail(ctx, LVLM_ERR_INVALID_ARG, "stream_probe: src must be 16-byte aligned");
+    if (lvlm_status st = bind_device(ctx)) return st;
+    return after_launch(ctx, launch_stream_probe(Prof{ctx, static_cast<hipStream_t>(stream)}, src, bytes, n_workgroups, sink));
+}
+
 lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *d, const void *q, const void *k_new,
                              const void *v_new, void *k_cache, void *v_cache, float *score, uint8_t *kind,
                              int32_t *orig_pos, int32_t *len, void *out) {

@@ -808,9 +808,9 @@ __global__ __launch_bounds__(1024) void attn_combine_kernel(AttnArgs a) {
     apply_entry<GP, false>(a, c, hg, L, appended, j, r, 0, unused);
 }
 
-// Per-step cache compression in the same launch as the fold (Sec. 3.2.2, steady state).  A compute unit streams
-// only some tens of GB/s however many threads it runs, so what a (batch, KV head) pair has to read is spread
-// over several workgroups: n_out of them fold the splits' partial outputs into the output rows (a share of
+// Per-step cache compression in the same launch as the fold (Sec. 3.2.2, steady state).  One compute unit
+// fetches the 4-byte words this kernel reads at some tens of GB/s only, so what a (batch, KV head) pair has to
+// read is spread over several workgroups: n_out of them fold the splits' partial outputs into the output rows (a share of
 // the group's heads each), one more updates every entry's importance and, if the head is now longer than
 // evict_budget, evicts its least important evictable entry (not protected, not among the last evict_recent
 // slots): the last entry takes its slot, as LVLM_ORDER_FILL does.

@@ -142,6 +142,8 @@ hipError_t launch_decode_attn(const Prof &prof, const lvlm_attn_desc &d, const A
                               void *v_cache, float *score, uint8_t *kind, int32_t *orig_pos,
                               int32_t *len, void *out);
 
+hipError_t launch_stream_probe(const Prof &prof, const void *src, size_t bytes, int n_workgroups, unsigned int *sink);
+
 // Device address and size of the fixed scratch array that lvlm_decode_attn_static uses on the current device
 // (looked up once per device; no allocation).
 hipError_t attn_static_scratch(int device, char **ptr, size_t *bytes);
