@@ -639,6 +639,19 @@ def test_no_call_writes_past_the_workspace_it_asked_for(ctx):
         _guarded(score)
 
 
+def test_stream_probe_reads_and_leaves_everything_as_it_is(ctx):
+    # the diagnostic read-only pass: any size that is a multiple of 16 bytes, any workgroup count; it writes nothing
+    for nbytes, n_wg in ((16, 1), (4096 + 16, 3), (1 << 20, 1), (33587200, 512), (8392704, 4096)):
+        src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device=DEV)
+        keep = src.clone()
+        sink = torch.zeros(4, dtype=torch.int32, device=DEV)
+        ctx.stream_probe(src, n_wg, sink)
+        torch.cuda.synchronize()
+        assert torch.equal(src, keep) and int(sink.abs().sum()) == 0
+    with pytest.raises(lv.LvlmError):
+        ctx.stream_probe(torch.zeros(8, dtype=torch.uint8, device=DEV), 1, torch.zeros(1, dtype=torch.int32, device=DEV))
+
+
 def test_kv_compress_leaves_heads_beyond_the_length_bound_alone(ctx):
     # a head longer than len_bound is not compressed at all (nothing evicted, nothing moved); the others are
     host = _cache(torch.bfloat16, 2, 2, 3000, 64, [2000, 2500, 1999, 2049], 150)
