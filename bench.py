@@ -811,6 +811,24 @@ def main_stream(args, w, layers, ctx, lv, torch, dev):
         got = ctx.profile_read()["stream_probe"]
         single_us = got[1] * 1e3 / got[0]
     ctx.profile(False)
+    # the yardstick of the gather: a plain device copy (torch's) that moves as many bytes, read + written, as each
+    # merge stage of the workload does (hidden and position planes: every source row in, every surviving row out)
+    copies = []
+    for en in layers:
+        if en["merge_to"] is None or en["merge_to"] >= en["n_img"]:
+            continue
+        Nq = w.n_sys + en["n_img"] + w.n_text
+        moved = w.batch * (Nq + Nq - (en["n_img"] - en["merge_to"])) * (w.hidden * e + 12)
+        half = moved // 2 // 16 * 16
+        src_, dst_ = (torch.empty(half, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(2))
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(1 + args.steps)]
+        for a_, b_ in evs:
+            a_.record(); dst_.copy_(src_); b_.record()
+        torch.cuda.synchronize()
+        us = sum(a_.elapsed_time(b_) for a_, b_ in evs[1:]) * 1e3 / args.steps
+        copies.append({"stage": f"{en['n_img']} -> {en['merge_to']}", "bytes_read_plus_written": 2 * half, "us": round(us, 2),
+                       "GBs": round(2 * half / us / 1e3, 1), "frac_of_peak": round(2 * half / us / 1e3 / HBM_PEAK_GBS, 4)})
+        del src_, dst_
     table = {}
     for n_wg, calls, us in rows:
         table.setdefault(n_wg, []).append(us)
@@ -824,6 +842,7 @@ def main_stream(args, w, layers, ctx, lv, torch, dev):
                    "what": "one decode layer's K and V rows per launch, a different buffer per launch"},
         "by_workgroups": by_wg,
         "one_workgroup_1MiB": {"us": round(single_us, 2), "GBs": round((1 << 20) / single_us / 1e3, 1)},
+        "device_copy_of_merge_stage_bytes": copies,
         "roofline": {"bound": "hbm", "achieved": best["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": best["frac_of_peak"], "traffic": None}}))
 
