@@ -820,15 +820,22 @@ def main_stream(args, w, layers, ctx, lv, torch, dev):
         Nq = w.n_sys + en["n_img"] + w.n_text
         moved = w.batch * (Nq + Nq - (en["n_img"] - en["merge_to"])) * (w.hidden * e + 12)
         half = moved // 2 // 16 * 16
-        src_, dst_ = (torch.empty(half, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(2))
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(1 + args.steps)]
-        for a_, b_ in evs:
+        # (a different pair of buffers per copy, a GiB of them in all: a repeated copy of one pair would be served
+        # in part by the last-level cache, which the gather's rows, written by other kernels long before, are not)
+        n_pairs = max(2, -(-(1 << 30) // (2 * half)))
+        pairs = [tuple(torch.empty(half, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(2))
+                 for _ in range(n_pairs)]
+        reps = n_pairs * (1 + args.steps)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for i_, (a_, b_) in enumerate(evs):
+            src_, dst_ = pairs[i_ % n_pairs]
             a_.record(); dst_.copy_(src_); b_.record()
         torch.cuda.synchronize()
-        us = sum(a_.elapsed_time(b_) for a_, b_ in evs[1:]) * 1e3 / args.steps
+        timed = evs[n_pairs:]
+        us = sum(a_.elapsed_time(b_) for a_, b_ in timed) * 1e3 / len(timed)
         copies.append({"stage": f"{en['n_img']} -> {en['merge_to']}", "bytes_read_plus_written": 2 * half, "us": round(us, 2),
                        "GBs": round(2 * half / us / 1e3, 1), "frac_of_peak": round(2 * half / us / 1e3 / HBM_PEAK_GBS, 4)})
-        del src_, dst_
+        del pairs, src_, dst_
     table = {}
     for n_wg, calls, us in rows:
         table.setdefault(n_wg, []).append(us)
