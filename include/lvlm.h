@@ -15,7 +15,7 @@
  *     16-byte aligned (score_mean alone needs only 4 bytes, so that rows of a
  *     larger array can be passed).  Descriptors, plane tables and "host" outputs are HOST
  *     memory.  Strides are in elements; the innermost dimension is contiguous.
- *   - The four hot-path calls only enqueue kernels on the caller's stream
+ *   - The calls of the path only enqueue kernels on the caller's stream
  *     (a hipStream_t passed as void*; NULL = the default stream).  They do not
  *     allocate, free or synchronise.  Scratch memory comes from the workspace
  *     the caller attached with lvlm_set_workspace; its size is queried with
