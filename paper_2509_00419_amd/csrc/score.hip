@@ -69,7 +69,10 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
     // blockIdx.x % 8 names the XCD (and its private L2).  The row splits of one key block are placed on
     // the same XCD: they read the same keys.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int kb = (slot / a.rs) * 8 + xcd, rs = slot % a.rs;
+    // The normaliser pass takes its key blocks from the last one down: the blocks at the end of the sequence are the
+    // ones that need the mask (the slow path), and a slow workgroup started last would run on after all the others.
+    const int kslot = PASS == 0 ? (int)(gridDim.x / (8 * a.rs)) - 1 - slot / a.rs : slot / a.rs;
+    const int kb = kslot * 8 + xcd, rs = slot % a.rs;
     const int g = blockIdx.y, b = blockIdx.z;
     if (kb * BN >= (PASS == 0 ? a.N : a.n_img)) return;      // padding of the key-block count to a multiple of 8
     const int GT = a.G * a.T;
