@@ -68,12 +68,14 @@ def parse():
     ap.add_argument("--merge", default="rank", choices=["rank", "similar"],
                     help="merge rule at the pyramid layers: the paper's rank weights (lvlm_merge_compact) or the "
                          "similarity merge (lvlm_merge_similar)")
-    ap.add_argument("--op", default="step", choices=["step", "prefill_attn", "stream"],
+    ap.add_argument("--op", default="step", choices=["step", "prefill_attn", "stream", "score_load"],
                     help="step: the token-reduction path (the default, the headline metric); prefill_attn: "
                          "lvlm_prefill_attn alone over the layer stack -- the layers' own attention at the token "
                          "counts the pyramid leaves, with the scores as its by-product where the path scores; "
                          "stream: lvlm_stream_probe over buffers of the size of one decode layer's K and V rows -- what "
-                         "a launch of that size can stream at all, by workgroup count")
+                         "a launch of that size can stream at all, by workgroup count; score_load: lvlm_score_tokens "
+                         "alone at the workload's scoring shapes for 4 to 32 sequences per call -- how the time of the "
+                         "one-launch score kernel steps with the workgroups per compute unit")
     ap.add_argument("--decode-evict", choices=["batched", "fused"], default="batched",
                     help="steady-state decode: one lvlm_kv_compress over all layers' caches at the end of the step "
                          "(batched), or the eviction inside every layer's lvlm_decode_attn call (fused)")
@@ -554,6 +556,8 @@ def main():
         return main_prefill_attn(args, w, layers, ctx, lv, torch, dev)
     if args.op == "stream":
         return main_stream(args, w, layers, ctx, lv, torch, dev)
+    if args.op == "score_load":
+        return main_score_load(args, w, layers, ctx, lv, torch, dev)
     t_setup = time.time()
     master = build_master(w, layers, torch, synth, dev, args.row_lse == "given")
     n_first = 3                                   # sets whose first decode step after prefill is timed as well
@@ -779,6 +783,56 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "kernels": kernels,
     }
     print(json.dumps(out))
+
+
+# ----------------------------------------------------------------------------- the score call against its load
+def main_score_load(args, w, layers, ctx, lv, torch, dev):
+    """--op score_load: lvlm_score_tokens alone, random queries and keys of the workload's head shape, at every
+    token count the pyramid leaves behind its merge layers, for 4 to 32 sequences per call (the bench's own calls
+    stack the layers of a run on that axis).  Reports the main kernel's duration (events bound to the kernels),
+    the workgroups the one-launch form starts (a workgroup = four 32-row query chunks of one KV head) and the
+    fraction of the bf16 MFMA peak: the time is a staircase in the workgroups per compute unit."""
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else MFMA_F32_PEAK_TFLOPS
+    Hq, Hkv, d, T = w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_text
+    n_chunks = (Hq // Hkv * T + 31) // 32
+    shapes = sorted({en["merge_to"] for en in layers if en["merge_to"] is not None}, reverse=True)
+    rows = []
+    for n_img in shapes:
+        N = w.n_sys + n_img + T
+        for B in (4, 8, 10, 12, 14, 16, 20, 24, 32):
+            torch.manual_seed(B)
+            q = torch.randn(B, T, Hq, d, device=dev, dtype=dt)
+            k = torch.randn(B, N, Hkv, d, device=dev, dtype=dt)
+            sh = torch.empty(B, Hkv, n_img, dtype=torch.float32, device=dev)
+            sm = torch.empty(B, n_img, dtype=torch.float32, device=dev)
+            kw = dict(q_pos0=w.n_sys + n_img, img_begin=w.n_sys, n_img=n_img, score_head=sh, score_mean=sm)
+            form = ctx.score_plan(ctx.score_desc(q, k, q_pos0=kw["q_pos0"], img_begin=kw["img_begin"], n_img=n_img))
+            ctx.score_tokens(q, k, **kw)
+            torch.cuda.synchronize()
+            ctx.profile(True)
+            for _ in range(args.steps):
+                ctx.score_tokens(q, k, **kw)
+            torch.cuda.synchronize()
+            got = ctx.profile_read()
+            ctx.profile(False)
+            us = sum(v[1] for kk, v in got.items() if kk in ("score_single", "score_pass0", "score_pass1")) * 1e3 / args.steps
+            flops = 2.0 * B * Hq * T * d * (N + n_img)
+            wgs = B * Hkv * ((n_chunks + 3) // 4)
+            rows.append({"n_img": n_img, "keys": N, "sequences": B, "form": ["two passes", "one launch, a chunk per workgroup",
+                                                                           "one launch, shared tiles"][form],
+                         "workgroups": wgs if form == 2 else None,
+                         "workgroups_per_cu": round(wgs / 256, 2) if form == 2 else None, "us": round(us, 1),
+                         "TFLOPs": round(flops / us / 1e6, 1), "frac_of_peak": round(flops / us / 1e6 / peak, 4)})
+            del q, k, sh, sm
+    best = max(rows, key=lambda r: r["TFLOPs"])
+    print(json.dumps({
+        "metric": "lvlm_score_tokens alone against the sequences per call", "value": best["TFLOPs"],
+        "unit": "TFLOP/s (best sequence count)", "n_gpus": 1, "steps": args.steps, "warmup": 1, "higher_is_better": True,
+        "dtype": w.dtype, "data": "synthetic (random queries and keys)",
+        "config": {"workload": w.name, "Hq": Hq, "Hkv": Hkv, "head_dim": d, "instruction_rows": T,
+                   "query_chunks_per_kv_head": n_chunks},
+        "rows": rows}))
 
 
 # ----------------------------------------------------------------------------- what a launch can stream
