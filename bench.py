@@ -797,6 +797,7 @@ def main_score_load(args, w, layers, ctx, lv, torch, dev):
     Hq, Hkv, d, T = w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_text
     n_chunks = (Hq // Hkv * T + 31) // 32
     shapes = sorted({en["merge_to"] for en in layers if en["merge_to"] is not None}, reverse=True)
+    shapes = shapes or [w.n_img]                       # a workload that merges nothing: its full image span
     rows = []
     for n_img in shapes:
         N = w.n_sys + n_img + T

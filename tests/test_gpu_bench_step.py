@@ -297,6 +297,23 @@ def test_prefill_attention_bench_mode_prints_its_line(capsys):
     assert out["cpu_baseline"]["kind"] == "oracle" and out["value"] > 0
 
 
+def test_score_load_bench_mode_prints_its_table(capsys):
+    """bench.py --op score_load on the one-sequence configuration: the mode runs, names the launch form the library
+    takes for every row (its own decision, read back through lvlm_score_plan) and reports a positive rate."""
+    import json
+    import types
+    w = configs.CFG2
+    args = types.SimpleNamespace(steps=2, warmup=1)
+    bench.main_score_load(args, w, bench.plan(w, lv), lv.Context(0), lv, torch, DEV)
+    out = json.loads([l for l in capsys.readouterr().out.splitlines() if l.startswith("{")][-1])
+    stages = {en["merge_to"] for en in bench.plan(w, lv) if en["merge_to"] is not None}
+    assert {r["n_img"] for r in out["rows"]} == stages and len(out["rows"]) == 9 * len(stages)
+    for r in out["rows"]:
+        assert r["us"] > 0 and 0 < r["frac_of_peak"] < 1
+        assert (r["workgroups"] is not None) == (r["form"] == "one launch, shared tiles")
+    assert out["value"] == max(r["TFLOPs"] for r in out["rows"])
+
+
 @pytest.mark.parametrize("name", ["cfg2", "cfg4"])
 def test_graph_replays_equal_the_eager_step(name):
     """The bench times HIP-graph replays of the step.  A captured (prefill, decode) pair is replayed three times on
