@@ -314,7 +314,7 @@ __device__ __forceinline__ void gather_plane(const GatherArgs &a, const PlaneDev
     const int groups = 256 >> p.tpr_log2;
     const int sub = blockIdx.x * groups + group;
     const int row_units = p.row_bytes / UB;
-    if (sub >= p.n_sub || blockIdx.y >= p.col_blocks) return;
+    if (sub >= p.n_sub || (int)blockIdx.y >= p.col_blocks) return;
     const int unit_raw = blockIdx.y * 256 + (tid & (tpr - 1));
     const bool active = unit_raw < row_units;
     const int unit = active ? unit_raw : row_units - 1;
@@ -413,7 +413,7 @@ __global__ __launch_bounds__(256) void finalize_kernel(GatherArgs a) {
     if (p.rule != LVLM_RULE_WEIGHTED) return;
     const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
     const int c = blockIdx.x * 16 + col;
-    if (blockIdx.x * 16 >= p.row_elems) return;
+    if ((int)blockIdx.x * 16 >= p.row_elems) return;
     const int per = (p.n_sub + 15) / 16;
     const int i_lo = grp * per, i_hi = min(p.n_sub, i_lo + per);
     float s = 0.f;

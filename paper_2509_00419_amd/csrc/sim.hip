@@ -375,7 +375,7 @@ __device__ __forceinline__ void merge_plane(const SimArgs &a, const PlaneDev &p,
             tot += st;
         }
         store_mean<DT, UB>(dst, acc, 1.0f / tot);
-        if (size && blockIdx.y == 0 && threadIdx.x == 0 && blockIdx.z < a.B && a.size_out)
+        if (size && blockIdx.y == 0 && threadIdx.x == 0 && (int)blockIdx.z < a.B && a.size_out)
             a.size_out[(long long)b * a.n_keep + i] = tot;
     }
 }
@@ -385,7 +385,7 @@ __global__ __launch_bounds__(256) void sim_merge_kernel(SimArgs a) {
     const int i = blockIdx.x;
     const int pi = blockIdx.z / a.B, b = blockIdx.z % a.B;
     const PlaneDev &p = a.plane[pi];
-    if (blockIdx.y >= p.col_blocks) return;
+    if ((int)blockIdx.y >= p.col_blocks) return;
     if (threadIdx.x == 0) {
         // the tokens assigned to dominant position i form the segment [lo, hi) of the sorted order
         const int32_t *order = a.order + (long long)b * a.n;
