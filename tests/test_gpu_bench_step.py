@@ -297,6 +297,35 @@ def test_prefill_attention_bench_mode_prints_its_line(capsys):
     assert out["cpu_baseline"]["kind"] == "oracle" and out["value"] > 0
 
 
+def test_bench_command_line_prints_the_contract_line():
+    """`python bench.py` as the driver runs it (a child process, small workload, two timed steps): exactly one JSON line on
+    stdout with every field of the contract, the roofline of the dominant kernel and the oracle's CPU baseline; more than
+    one GPU is refused with a message."""
+    import json
+    import subprocess
+    run = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "cfg1", "--steps", "2", "--warmup", "1"],
+                         cwd=ROOT, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=600)
+    assert run.returncode == 0, run.stderr[-2000:]
+    lines = [l for l in run.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1, lines
+    out = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in out, key
+    assert out["n_gpus"] == 1 and out["steps"] == 2 and out["warmup"] == 1 and out["higher_is_better"] is True
+    assert out["value"] > 0 and out["ms_per_step"] > 0 and out["vs_baseline"] is None
+    assert out["config"]["workload"].startswith("cfg1") and "model" not in out["config"]
+    roof = out["roofline"]
+    assert roof["bound"] in ("hbm", "mfma", "alu") and roof["unit"] in ("GB/s", "TFLOP/s")
+    assert roof["achieved"] > 0 and roof["peak"] > 0 and abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3
+    assert "traffic" in roof
+    cpu = out["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["value"] > 0 and cpu["cores"] >= 1 and cpu["unit"] and cpu["sample"]
+    two = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], cwd=ROOT, stdout=subprocess.PIPE,
+                         stderr=subprocess.PIPE, text=True, timeout=300)
+    assert two.returncode != 0 and "one GPU" in two.stderr and not two.stdout.strip()
+
+
 def test_score_load_bench_mode_prints_its_table(capsys):
     """bench.py --op score_load on the one-sequence configuration: the mode runs, names the launch form the library
     takes for every row (its own decision, read back through lvlm_score_plan) and reports a positive rate."""
