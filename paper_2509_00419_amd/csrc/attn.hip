@@ -962,7 +962,13 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     // least one pass of the four waves (128 entries) and a whole number of 32-entry tiles; measured: a
     // second, partly filled round costs more than longer splits do.
     const int max_split = (bound + 127) / 128;
-    long long want = 512 / heads;
+    const long long want_round = 512 / heads;
+    long long want = want_round;
+    // The bf16 kernel whose waves take ONE tile is lean enough for four workgroups per compute unit (122 registers):
+    // where splits of 128 entries are still one round that way (at most 1024 workgroups), they beat half as many
+    // splits of two tiles per wave by a little (64 heads: 15.3 against 15.9 us at 1889 entries, 11.4 against 12.0 us
+    // at 1360).
+    if (d.dtype == LVLM_BF16 && heads * max_split <= 1024 && max_split > want) want = max_split;
     int n_split = (int)(want < 1 ? 1 : (want > max_split ? max_split : want));
     if (n_split > 64) n_split = 64;               // kMaxSplit of the combine kernel
     int split_len = ((bound + n_split - 1) / n_split + 31) / 32 * 32;
@@ -973,7 +979,7 @@ AttnWs attn_ws(const lvlm_attn_desc &d) {
     // its own (tail_entry), a longer remainder goes to the last split as one extra tile of one wave.
     const int full = bound / 128;
     w.tail_entry = 0;
-    if (full >= 1 && want >= full && bound - 128 * full <= 32 && full <= 64) {
+    if (full >= 1 && want_round >= full && bound - 128 * full <= 32 && full <= 64) {
         n_split = full;
         split_len = 128;
         w.tail_entry = d.dtype == LVLM_BF16 && bound - 128 * full == 1;
