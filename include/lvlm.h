@@ -402,6 +402,15 @@ LVLM_API lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_at
                              void *k_cache, void *v_cache, float *score, uint8_t *kind,
                              int32_t *orig_pos, int32_t *len, void *out);
 
+/* How lvlm_decode_attn cuts a shape into launches (host arithmetic; for benchmarks and tests that reason about
+ * the launch): every (batch, KV head) pair is split over *n_split workgroups of *split_len entries each (a multiple
+ * of 32; a workgroup's four waves take 32-entry tiles in turn); *form = 0 every wave has at most one tile, 1 some
+ * wave has a second tile (splits longer than 128 entries, or a remainder of up to one tile on the last split),
+ * 2 whole 128-entry splits plus exactly one more entry, which one wave of the last split takes on its own (the
+ * steady state of a cache at its budget, bf16 only). */
+LVLM_API lvlm_status lvlm_decode_plan(const lvlm_ctx *ctx, const lvlm_attn_desc *d, int32_t *n_split, int32_t *split_len,
+                                      int32_t *form);
+
 /* The same call for callers that cannot allocate device memory or attach a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Arguments, results and error behaviour are those of

@@ -121,6 +121,7 @@ def _load():
     lib.lvlm_kv_compress.argtypes = [vp, vp, C.POINTER(KvDesc), vp, vp, f32p, vp, i32p, i32p, i32p]
     lib.lvlm_decode_attn.argtypes = [vp, vp, C.POINTER(AttnDesc), vp, vp, vp, vp, vp, f32p, vp, i32p, i32p, vp]
     lib.lvlm_decode_attn_static.argtypes = lib.lvlm_decode_attn.argtypes
+    lib.lvlm_decode_plan.argtypes = [vp, C.POINTER(AttnDesc), C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     lib.lvlm_stream_probe.argtypes = [vp, vp, vp, C.c_size_t, C.c_int32, vp]
     lib.lvlm_profile.argtypes = [C.c_void_p, C.c_int]
     lib.lvlm_profile_read.argtypes = [C.c_void_p, C.POINTER(ProfileEntry), C.c_int, C.POINTER(C.c_int)]
@@ -128,7 +129,7 @@ def _load():
                  "lvlm_merge_weights", "lvlm_score_tokens", "lvlm_score_plan", "lvlm_score_from_probs", "lvlm_prefill_attn", "lvlm_merge_compact",
                  "lvlm_merge_similar",
                  "lvlm_kv_compress",
-                 "lvlm_decode_attn", "lvlm_decode_attn_static", "lvlm_stream_probe"):
+                 "lvlm_decode_attn", "lvlm_decode_attn_static", "lvlm_decode_plan", "lvlm_stream_probe"):
         getattr(lib, name).restype = C.c_int
     return lib
 
@@ -372,6 +373,13 @@ class Context:
         return n_evicted
 
     # ---- step 6 ----
+    def decode_plan(self, desc: AttnDesc):
+        """lvlm_decode_plan: (n_split, split_len, form); form 0 = one tile per wave, 1 = some wave has a second tile,
+        2 = whole 128-entry splits plus one entry taken by one wave."""
+        n, sl, form = C.c_int32(), C.c_int32(), C.c_int32()
+        self._check(lib.lvlm_decode_plan(self._h, C.byref(desc), C.byref(n), C.byref(sl), C.byref(form)))
+        return n.value, sl.value, form.value
+
     def decode_attn(self, q, k_new, v_new, k_cache, v_cache, score, kind, orig_pos, length, *, scale=None,
                     score_decay=1.0, new_kind=KIND_GENERATED, new_pos=0, len_bound=0, evict_budget=0, evict_recent=0,
                     out=None, reserve=True, static_scratch=False):

@@ -522,6 +522,19 @@ lvlm_status lvlm_stream_probe(lvlm_ctx *ctx, void *stream, const void *src, size
     return after_launch(ctx, launch_stream_probe(Prof{ctx, static_cast<hipStream_t>(stream)}, src, bytes, n_workgroups, sink));
 }
 
+lvlm_status lvlm_decode_plan(const lvlm_ctx *ctx, const lvlm_attn_desc *d, int32_t *n_split, int32_t *split_len,
+                             int32_t *form) {
+    lvlm_ctx *c = const_cast<lvlm_ctx *>(ctx);
+    if (!ctx || !n_split || !split_len || !form) return fail(c, LVLM_ERR_INVALID_ARG, "decode_plan: null argument");
+    if (const char *why = check_attn(d)) return fail(c, LVLM_ERR_INVALID_ARG, "decode_plan: %s", why);
+    const AttnWs w = attn_ws(*d);
+    const int bound = d->len_bound > 0 ? d->len_bound : d->Lmax;
+    *n_split = w.n_split;
+    *split_len = w.split_len;
+    *form = w.tail_entry ? 2 : ((w.split_len > 128 || w.n_split * w.split_len < bound) ? 1 : 0);
+    return LVLM_OK;
+}
+
 lvlm_status lvlm_decode_attn(lvlm_ctx *ctx, void *stream, const lvlm_attn_desc *d, const void *q, const void *k_new,
                              const void *v_new, void *k_cache, void *v_cache, float *score, uint8_t *kind,
                              int32_t *orig_pos, int32_t *len, void *out) {

@@ -124,6 +124,35 @@ def test_score_plan_reports_the_launch_form():
         ctx.score_plan(bad)
 
 
+def test_decode_plan_reports_the_split_of_a_launch():
+    """lvlm_decode_plan is the library's own cut of a decode launch: one round of workgroups, whole 32-entry tiles, the
+    steady-state shape (budget + 1 entries) as whole 128-entry splits plus one entry, and splits of ONE tile per wave
+    wherever 128-entry splits are at most 1024 workgroups (bf16)."""
+    ctx = _ctx()
+
+    def plan(B, Hq, Hkv, Lmax, bound, dtype=bd.BF16, hd=128):
+        return ctx.decode_plan(bd.AttnDesc(dtype, B, Hq, Hkv, hd, Lmax, bound, 2, 0, 0.088, 0.9))
+
+    assert plan(16, 28, 4, 1152, 1025) == (8, 128, 2)             # config 4: 64 heads, budget 1024 + 1
+    assert plan(1, 48, 8, 16640, 2049) == (16, 128, 2)            # config 5, steady state
+    assert plan(8, 32, 8, 2048, 1889) == (15, 128, 0)             # config 3's longest layers: 960 one-tile workgroups
+    assert plan(8, 32, 8, 2048, 1360) == (11, 128, 0)
+    assert plan(8, 32, 8, 2048, 987) == (8, 128, 0)
+    assert plan(8, 32, 8, 4096, 3000) == (8, 384, 1)              # 24 x 64 > 1024 workgroups: eight splits of three tiles
+    assert plan(8, 32, 8, 2048, 1889, dtype=bd.F32) == (8, 256, 1)     # the fp32 kernel keeps one round of 512
+    assert plan(8, 32, 8, 2048, 1820) == (15, 128, 0)             # a remainder of one tile no longer makes a two-tile launch
+    assert plan(1, 48, 8, 16640, 16513)[0] == 58                  # 8 heads: at most 64 splits, here of 288 entries
+    assert plan(1, 28, 4, 2304, 2178) == (17, 128, 1)             # one sequence: two entries past 17 whole splits go to one wave
+    assert plan(1, 28, 4, 2304, 2240) == (18, 128, 0)             # ... a longer remainder is a split of its own
+    for B, Hq, Hkv, Lmax, bound in ((3, 12, 4, 700, 0), (2, 8, 8, 129, 129), (1, 4, 1, 40000, 33000), (64, 32, 8, 520, 513)):
+        n, sl, form = plan(B, Hq, Hkv, Lmax, bound)
+        L = bound or Lmax
+        assert 1 <= n <= 64 and sl % 32 == 0 and sl >= 128 and form in (0, 1, 2)
+        assert n * sl >= L - (32 if form == 1 and sl == 128 else (1 if form == 2 else 0))
+    with pytest.raises(lv.LvlmError):
+        plan(1, 6, 4, 128, 0)                                      # heads not a multiple of KV heads
+
+
 def test_size_arithmetic_survives_extreme_shapes():
     """Sizes at the documented limits are answered, sizes beyond them are refused -- and neither may overflow
     anything on the way (this file runs a second time against a build whose host code traps on signed overflow
