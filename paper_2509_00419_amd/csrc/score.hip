@@ -175,7 +175,9 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
             const int rho = c * 32 + tid;
             if (rho < GT) {
                 pos = a.causal ? a.q_pos0 + (rho - div_t(rho) * a.T) : INT_MAX;
-                if (PASS == 1) lse = a.row_lse ? a.row_lse[rowbase + rho] * kLog2e : a.lse2[rowbase + rho];
+                // (as loaded: the change of base waits for store time -- a use right here would stall the wave on the
+                // load, with the chunk's own loads just issued in front of it)
+                if (PASS == 1) lse = a.row_lse ? a.row_lse[rowbase + rho] : a.lse2[rowbase + rho];
             }
         }
     };
@@ -199,7 +201,7 @@ __global__ __launch_bounds__(256, 3) void score_pass_kernel(ScoreArgs a) {
         if constexpr (UPT > 3) *chunk_dst(buf, 3) = st##S##3;            \
         if (tid < 32) {                                                  \
             pos_lds[buf][tid] = st##S##_pos;                             \
-            lse_lds[buf][tid] = st##S##_lse;                             \
+            lse_lds[buf][tid] = a.row_lse ? st##S##_lse * kLog2e : st##S##_lse;   /* a caller's are natural logarithms */ \
         }                                                                \
     };
     LVLM_STAGE_FUNCS(A)
