@@ -456,7 +456,8 @@ def run_decode_compress(ctx, lv, w, states, reserve):
 
 # ----------------------------------------------------------------------------- algorithmic work per kernel
 def score_form(ctx, lv, w, N, n_img, batch):
-    """The launch form the library takes for `batch` sequences of N keys (lvlm_score_plan: 0 two passes, 1 / 2 one launch)."""
+    """The launch form the library takes for `batch` sequences of N keys (lvlm_score_plan: 0 two passes, 1 / 2 one launch,
+    3 the shared-tile kernel with the keys in runs, one launch per sweep)."""
     from paper_2509_00419_amd import binding as bd
     d = bd.ScoreDesc(bd.BF16 if w.dtype == "bf16" else bd.F32, batch, N, w.n_text, w.n_sys + n_img, w.n_q_heads,
                      w.n_kv_heads, w.head_dim, w.n_sys, n_img, 1, w.head_dim ** -0.5,
@@ -491,8 +492,12 @@ def kernel_work(ctx, lv, w, layers, dec_lens, moved, merge="rank", per_layer=Fal
     for first, last in score_groups(layers, per_layer):
         n_img = layers[last]["n_img"]
         N, gb = w.n_sys + n_img + T, (last - first + 1) * B
-        if score_form(ctx, lv, w, N, n_img, gb) != 0:
-            add("score_single", "mfma", 2.0 * gb * T * ((0 if given_lse else N) + n_img) * d * Hq)
+        form = score_form(ctx, lv, w, N, n_img, gb)
+        if form != 0:
+            launches = 2 if form == 3 and not given_lse else 1               # form 3: one launch per sweep
+            add("score_single", "mfma", 2.0 * gb * T * ((0 if given_lse else N) + n_img) * d * Hq, launches=launches)
+            if form == 3 and not given_lse:
+                add("score_lse", "hbm", 4.0 * gb * Hq * T)                   # the row normalisers folded in between
         else:
             if not given_lse:
                 add("score_pass0", "mfma", 2.0 * gb * T * N * d * Hq)
@@ -821,9 +826,10 @@ def main_score_load(args, w, layers, ctx, lv, torch, dev):
             flops = 2.0 * B * Hq * T * d * (N + n_img)
             wgs = B * Hkv * ((n_chunks + 3) // 4)
             rows.append({"n_img": n_img, "keys": N, "sequences": B, "form": ["two passes", "one launch, a chunk per workgroup",
-                                                                           "one launch, shared tiles"][form],
-                         "workgroups": wgs if form == 2 else None,
-                         "workgroups_per_cu": round(wgs / 256, 2) if form == 2 else None, "us": round(us, 1),
+                                                                           "one launch, shared tiles",
+                                                                           "shared tiles, keys in runs"][form],
+                         "workgroups": wgs if form >= 2 else None,
+                         "workgroups_per_cu": round(wgs / 256, 2) if form >= 2 else None, "us": round(us, 1),
                          "TFLOPs": round(flops / us / 1e6, 1), "frac_of_peak": round(flops / us / 1e6 / peak, 4)})
             del q, k, sh, sm
     best = max(rows, key=lambda r: r["TFLOPs"])

@@ -172,7 +172,8 @@ LVLM_API lvlm_status lvlm_score_tokens(lvlm_ctx *ctx, void *stream, const lvlm_s
 /* Which kernels lvlm_score_tokens takes for a shape (host arithmetic; for benchmarks that credit work to
  * kernels by name): *form = 0 two passes over the keys in separate launches (normalisers, then column
  * sums), 1 both sweeps in one launch with one query chunk per workgroup, 2 both sweeps in one launch with
- * four query chunks per workgroup sharing the key tiles. */
+ * four query chunks per workgroup sharing the key tiles, 3 the kernel of form 2 with the keys cut into runs
+ * (one launch per sweep, the runs' normaliser partials folded in between: launches of few workgroups). */
 LVLM_API lvlm_status lvlm_score_plan(const lvlm_ctx *ctx, const lvlm_score_desc *d, int32_t *form);
 
 /* The same scores from attention probabilities the caller already holds -- a

@@ -231,7 +231,8 @@ class Context:
                          0 if score_head is None else score_head.stride(1))
 
     def score_plan(self, desc: ScoreDesc) -> int:
-        """lvlm_score_plan: 0 = two-pass kernels, 1 = one launch (a chunk per workgroup), 2 = one launch (shared tiles)."""
+        """lvlm_score_plan: 0 = two-pass kernels, 1 = one launch (a chunk per workgroup), 2 = one launch (shared tiles),
+        3 = the shared-tile kernel with the keys cut into runs (one launch per sweep)."""
         form = C.c_int32()
         self._check(lib.lvlm_score_plan(self._h, C.byref(desc), C.byref(form)))
         return form.value

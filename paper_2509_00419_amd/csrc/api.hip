@@ -369,7 +369,7 @@ lvlm_status lvlm_score_plan(const lvlm_ctx *ctx, const lvlm_score_desc *d, int32
     if (!ctx || !form) return fail(c, LVLM_ERR_INVALID_ARG, "score_plan: null argument");
     if (const char *why = check_score(d)) return fail(c, LVLM_ERR_INVALID_ARG, "score_plan: %s", why);
     const ScoreWs w = score_ws(*d);
-    *form = w.shared_tiles ? 2 : (w.single ? 1 : 0);
+    *form = w.shared_tiles ? (w.key_segs > 1 ? 3 : 2) : (w.single ? 1 : 0);
     return LVLM_OK;
 }
 

@@ -37,6 +37,7 @@ struct ScoreWs {
     int rs, cps;   // row splits per key block, query chunks per split
     bool single;   // short sequence: both passes in one launch, one part of column sums per query chunk
     bool shared_tiles;   // ... with four query chunks per workgroup sharing the key tiles through LDS
+    int key_segs;        // ... and the keys cut into this many runs, a launch per sweep (1 = one launch)
 };
 ScoreWs score_ws(const lvlm_score_desc &d);
 

@@ -41,6 +41,7 @@ struct ScoreArgs {
     int B, N, T, q_pos0, Hq, Hkv, G, img_begin, n_img, causal, nkb;
     int rs;             // row splits: workgroups that share a key block and take different query chunks
     int cps;            // chunks per split
+    int n_seg;          // shared-tile form: runs the keys are cut into (1 = both sweeps in one launch)
     unsigned t_magic;   // floor(2^32 / T) + 1: rho / T == umulhi(rho, t_magic) for rho, T < 65536
     float scale_log2;
     long long qsb, qst, qsh, ksb, ksn, ksh, shb, shh;
@@ -575,7 +576,11 @@ __global__ __launch_bounds__(64 * NW, (DT == LVLM_F32 && HD == 128) ? 2 : 3) voi
 // Sweep 1 (rows = keys, columns = queries) leaves each lane the online (max, sum) of its own query row: no
 // fold across waves; sweep 2 (rows = queries, columns = keys) over the image keys leaves each lane the
 // column sum of its key for this wave's chunk, which is that chunk's part of the result.
-template <int DT, int HD>
+// MODE 0: both sweeps in this launch.  MODE 1 / 2: the keys are cut into a.n_seg runs of whole tiles and a workgroup takes ONE
+// run -- MODE 1 the normaliser sweep over it, leaving each row's (max, sum) of the run for score_lse_kernel to fold, MODE 2
+// the column-sum sweep over it with the folded (or the caller's) normalisers.  A wave's unit of work is then a chunk over a
+// run instead of a chunk over all keys twice, which is what lets a launch of few workgroups load every SIMD evenly.
+template <int DT, int HD, int MODE>
 __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void score_chunks_kernel(ScoreArgs a) {
     constexpr int ES = esize<DT>();
     constexpr int ROWB = HD * ES;
@@ -593,7 +598,9 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
     const int hf = lane >> 5, l32 = lane & 31;
     // all workgroups of one (batch, KV head) pair on one XCD (ids with the same remainder modulo 8)
     const int wpp = (a.rs + 3) >> 2;                      // workgroups per pair
-    const int xcd = blockIdx.x & 7, seq = blockIdx.x >> 3;
+    const int xcd = blockIdx.x & 7;
+    const int seg = MODE == 0 ? 0 : (int)(blockIdx.x >> 3) % a.n_seg;      // this workgroup's run of keys
+    const int seq = MODE == 0 ? (int)(blockIdx.x >> 3) : (int)(blockIdx.x >> 3) / a.n_seg;
     const int pair = (seq / wpp) * 8 + xcd;
     if (pair >= a.B * a.Hkv) return;
     const int b = pair / a.Hkv, g = pair % a.Hkv;
@@ -650,14 +657,14 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
     // SAFE = false: after the first whole tile has set a finite reference m, later whole tiles take it as it is --
     // no maximum, no rescaling; a logit far above it shows as an overflowing sum, checked after the sweep, and the
     // workgroup then repeats the sweep with SAFE = true (the reference follows the running maximum on every tile).
-    auto stats = [&](int j0, const HalfRow<DT, HD> &kf, auto safe_tag) {
+    auto stats = [&](int j0, bool first, const HalfRow<DT, HD> &kf, auto safe_tag) {
         constexpr bool SAFE = decltype(safe_tag)::value;
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
         mma_tile<DT, HD>(acc, kf, qa);                    // rows = keys, columns = queries
         if (j0 + 32 <= a.N && j0 + 31 <= pos_min) {
-            if (!SAFE && j0 > 0) {                        // tile 0 was whole too (tiles ascend): m is finite
+            if (!SAFE && !first) {                        // the sweep's first tile was whole too (tiles ascend): m is finite
                 float sum = 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], a.scale_log2, -m));
@@ -731,17 +738,30 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
                 HalfRow<DT, HD> kf;
                 tile_operand(t & 1, kf);
                 if (second) colsum(j_begin + 32 * t, kf);
-                else stats(j_begin + 32 * t, kf, safe_tag);
+                else stats(j_begin + 32 * t, t == 0, kf, safe_tag);
             }
             __syncthreads();
         }
     };
 
-    if (a.row_lse == nullptr) {
-        sweep(0, a.N, false, std::false_type{});
-        if (__syncthreads_or(!(l < 1.0e30f))) {           // some sum ran away (or is not a number): the careful sweep
-            m = -INFINITY, l = 0.f;
-            sweep(0, a.N, false, std::true_type{});
+    // the tiles of [lo, hi) this workgroup takes: all of them, or its run (equal shares of whole tiles)
+    auto run_of = [&](int lo, int hi, int &jb, int &je) {
+        jb = lo, je = hi;
+        if (MODE != 0) {
+            const long long nt = (hi - lo + 31) >> 5;
+            jb = lo + 32 * (int)(nt * seg / a.n_seg);
+            je = min(hi, lo + 32 * (int)(nt * (seg + 1) / a.n_seg));
+        }
+    };
+    if (MODE == 1 || (MODE == 0 && a.row_lse == nullptr)) {
+        int jb, je;
+        run_of(0, a.N, jb, je);
+        if (jb < je) {
+            sweep(jb, je, false, std::false_type{});
+            if (__syncthreads_or(!(l < 1.0e30f))) {       // some sum ran away (or is not a number): the careful sweep
+                m = -INFINITY, l = 0.f;
+                sweep(jb, je, false, std::true_type{});
+            }
         }
         {
             const float mo = other_half(m), lo = other_half(l);
@@ -750,15 +770,26 @@ __global__ __launch_bounds__(256, (DT == LVLM_F32 && HD == 128) ? 2 : 4) void sc
             l = l * __builtin_amdgcn_exp2f(m - ms) + lo * __builtin_amdgcn_exp2f(mo - ms);
             m = mn;
         }
+        if (MODE == 1) {                                  // this run's share of the rows' normalisers
+            if (hf == 0 && live && rho < GT) {
+                const long long pidx = (long long)seg * a.B * a.Hq * a.T + rowbase + rho;
+                a.part_m[pidx] = m;
+                a.part_l[pidx] = l;
+            }
+            return;
+        }
         // no visible key, or a padding row: contributes nothing
         if (hf == 0) lse_s[wave][l32] = (l > 0.f && rho < GT) ? m + log2f(l) : INFINITY;
     } else if (hf == 0) {
-        lse_s[wave][l32] = (live && rho < GT) ? a.row_lse[rowbase + rho] * kLog2e : INFINITY;
+        const bool real = live && rho < GT;
+        lse_s[wave][l32] = !real ? INFINITY : (a.row_lse ? a.row_lse[rowbase + rho] * kLog2e : a.lse2[rowbase + rho]);
     }
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < 16; ++r) lse_r[r] = lse_s[wave][acc_row(r, hf)];
-    sweep(key_lo, key_hi, true, std::true_type{});
+    int jb, je;
+    run_of(key_lo, key_hi, jb, je);
+    if (jb < je) sweep(jb, je, true, std::true_type{});
 }
 
 // Fold the per-block, per-wave (max, sum) pairs of each row into a log2-domain LSE.  Eight lanes share a
@@ -932,8 +963,22 @@ void launch_passes(const Prof &prof, const ScoreArgs &a, bool need_lse, bool sin
     constexpr int BN = 4 * KPW * 32;
     if (single) {
         prof.begin("score_single");
-        if (shared_tiles)
-            LVLM_LAUNCH(prof, (score_chunks_kernel<DT, HD>), dim3((a.B * a.Hkv + 7) / 8 * 8 * ((a.rs + 3) / 4)), dim3(256), 0,
+        if (shared_tiles && a.n_seg > 1) {
+            // the keys in runs: the normaliser sweep, the fold of the runs' partials, then the column-sum sweep
+            const dim3 grid((a.B * a.Hkv + 7) / 8 * 8 * ((a.rs + 3) / 4) * a.n_seg);
+            if (need_lse) {
+                LVLM_LAUNCH(prof, (score_chunks_kernel<DT, HD, 1>), grid, dim3(256), 0, stream, a);
+                prof.end();
+                const int rows = a.B * a.Hq * a.T;
+                prof.begin("score_lse");
+                LVLM_LAUNCH(prof, score_lse_kernel, dim3((rows * 8 + 255) / 256), dim3(256), 0, stream, a.part_m, a.part_l,
+                                   a.lse2, rows, a.n_seg);
+                prof.end();
+                prof.begin("score_single");
+            }
+            LVLM_LAUNCH(prof, (score_chunks_kernel<DT, HD, 2>), grid, dim3(256), 0, stream, a);
+        } else if (shared_tiles)
+            LVLM_LAUNCH(prof, (score_chunks_kernel<DT, HD, 0>), dim3((a.B * a.Hkv + 7) / 8 * 8 * ((a.rs + 3) / 4)), dim3(256), 0,
                                stream, a);
         else
             LVLM_LAUNCH(prof, (score_small_kernel<DT, HD, 4>), dim3((a.B * a.Hkv + 7) / 8 * 8 * a.rs), dim3(256), 0, stream,
@@ -1049,14 +1094,39 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
     w.shared_tiles = n_chunks >= 3 && n_chunks <= kSingleMaxChunks && (long long)d.B * d.Hkv * ((n_chunks + 3) / 4) >= kSharedMinWgs &&
                      sweep_rows <= kSharedMaxRows;
     w.single = w.shared_tiles || (n_chunks <= kSingleMaxChunks && sweep_rows <= kSingleMaxRows);
+    // Shared tiles, few workgroups: a wave's unit of work is a chunk over ALL keys, twice, and a launch of 2.25 workgroups
+    // per compute unit takes the time of three (one of 0.75 the time of one whose lone wave per SIMD hides nothing).
+    // Cutting the keys into runs (a launch per sweep, the runs' normaliser partials folded in between) makes the units
+    // small enough to load every SIMD evenly; it costs each workgroup its start-up (about three tiles' time) per run and
+    // the call two more launches.  Taken when the estimate below says it saves more than 12 us.
+    w.key_segs = 1;
+    if (w.shared_tiles) {
+        const long long wgs = (long long)d.B * d.Hkv * ((n_chunks + 3) / 4);
+        const double tiles = (d.N + 31) / 32 + (d.n_img + 31) / 32;          // both sweeps
+        // (measured, in us per tile sweep of a workgroup, with k = 1..5 workgroups resident on every compute unit: a lone
+        // wave per SIMD hides nothing, from three on the SIMDs are saturated; five are resident at most, a launch of more
+        // runs in turns of 1280 workgroups plus the rest)
+        auto launch_us = [](long long n_wg, double tiles_per_wg) {
+            static const double per_tile[6] = {0.0, 0.53, 0.73, 0.95, 1.25, 1.5};
+            const long long turns = n_wg / 1280, rest = n_wg % 1280;
+            return tiles_per_wg * (1.5 * (double)turns + per_tile[(rest + 255) / 256]);
+        };
+        double best = launch_us(wgs, tiles) - 12.0;
+        for (int s = 2; s <= 8 && wgs <= 1280; s *= 2) {
+            if (tiles / 2 / s < 16) break;                                    // runs of at least 16 tiles
+            const double cut = launch_us(wgs * s, tiles / s + 2 * 3) + 10.0;
+            if (cut < best) best = cut, w.key_segs = s;
+        }
+    }
     if (w.single) {
         w.rs = n_chunks;
         w.cps = 1;
     }
     const size_t rows = (size_t)d.B * d.Hq * d.T;
     w.part_m = 0;
-    w.part_l = align_up(w.part_m + rows * w.nkb * 4 * sizeof(float), 256);
-    w.lse2 = align_up(w.part_l + rows * w.nkb * 4 * sizeof(float), 256);
+    const size_t n_part = (size_t)w.nkb * 4 > (size_t)w.key_segs ? (size_t)w.nkb * 4 : (size_t)w.key_segs;
+    w.part_l = align_up(w.part_m + rows * n_part * sizeof(float), 256);
+    w.lse2 = align_up(w.part_l + rows * n_part * sizeof(float), 256);
     w.colpart = align_up(w.lse2 + rows * sizeof(float), 256);
     w.total = align_up(w.colpart + (size_t)w.rs * d.B * d.Hkv * d.n_img * sizeof(float), 256);
     return w;
@@ -1074,6 +1144,7 @@ hipError_t launch_score(const Prof &prof, const lvlm_score_desc &d, const ScoreW
     a.colpart = reinterpret_cast<float *>(ws + w.colpart);
     a.rs = w.rs;
     a.cps = w.cps;
+    a.n_seg = w.key_segs;
     a.t_magic = (unsigned)(0x100000000ull / (unsigned long long)d.T) + 1u;
     a.score_head = score_head;
     a.score_mean = score_mean;

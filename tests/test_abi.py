@@ -119,6 +119,9 @@ def test_score_plan_reports_the_launch_form():
     assert form(1, 16512, 128, 48, 8, 16384) == 0          # one long sequence: two passes
     assert form(1, 845, 64, 28, 4, 717) == 1               # one short sequence: one launch, a chunk per workgroup
     assert form(64, 986, 96, 32, 8, 890) == 2              # many short sequences: shared key tiles
+    assert form(12, 5219, 128, 48, 8, 5091) == 3           # 2.25 workgroups per compute unit over 5219 keys: keys in runs
+    assert form(12, 1710, 128, 48, 8, 1582) == 2           # the same count over 1710 keys: too short to cut
+    assert form(16, 5219, 128, 48, 8, 5091) == 2           # three workgroups per compute unit: nothing to even out
     bad = bd.ScoreDesc(bd.BF16, 1, 100, 4, 96, 6, 4, 128, 0, 50, 1, 1.0, 0, 0, 128, 0, 0, 128)
     with pytest.raises(lv.LvlmError):
         ctx.score_plan(bad)

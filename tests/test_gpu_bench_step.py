@@ -339,7 +339,7 @@ def test_score_load_bench_mode_prints_its_table(capsys):
     assert {r["n_img"] for r in out["rows"]} == stages and len(out["rows"]) == 9 * len(stages)
     for r in out["rows"]:
         assert r["us"] > 0 and 0 < r["frac_of_peak"] < 1
-        assert (r["workgroups"] is not None) == (r["form"] == "one launch, shared tiles")
+        assert (r["workgroups"] is not None) == (r["form"] in ("one launch, shared tiles", "shared tiles, keys in runs"))
     assert out["value"] == max(r["TFLOPs"] for r in out["rows"])
 
 

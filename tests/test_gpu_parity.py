@@ -80,6 +80,35 @@ def test_score_tokens(ctx, dtype, B, T, Hq, Hkv, d, n_sys, n_img, causal):
     assert rel_err(sh2.cpu(), osh) < 1e-5 and rel_err(sm2.cpu(), osm) < 1e-5
 
 
+@pytest.mark.parametrize("B,T,Hq,Hkv,n_sys,n_img", [
+    (4, 128, 48, 8, 0, 2072),        # 192 workgroups of four chunks: three quarters of a workgroup per compute unit
+    (6, 100, 48, 8, 3, 2500),        # 19 chunks per KV head (the last workgroup of a head has three), image span from key 3
+    (4, 128, 48, 8, 5, 3001),        # an odd number of image keys: the last run ends inside a tile
+    (8, 100, 28, 4, 3, 3000),        # G = 7
+])
+def test_score_tokens_keys_in_runs(ctx, B, T, Hq, Hkv, n_sys, n_img):
+    """Launches of few workgroups over long sequences cut the keys into runs (one launch per sweep, the runs' normaliser
+    partials folded in between): the same scores, with the library's own normalisers and with the caller's, and with a
+    logit far above the rest in a late run (the sweep that takes the first tile's maximum as reference must notice)."""
+    d, N = 128, n_sys + n_img + T
+    q, k = _rand((B, T, Hq, d), torch.bfloat16, 11), _rand((B, N, Hkv, d), torch.bfloat16, 12)
+    kw = dict(q_pos0=n_sys + n_img, img_begin=n_sys, n_img=n_img, causal=True)
+    assert ctx.score_plan(ctx.score_desc(q, k, **kw)) == 3
+    for far in (False, True):
+        if far:                                          # one key of one head lines up with a query row, 40 times as long
+            k = k.clone()
+            k[B - 1, n_sys + (7 * n_img) // 8, Hkv - 1] = (40.0 * q[B - 1, T // 2, Hq - 1].float()).to(torch.bfloat16)
+        sh, sm = ctx.score_tokens(q.to(DEV), k.to(DEV), **kw)
+        osh, osm = O.score_tokens(f64(q), f64(k), **kw)
+        assert rel_err(sh.cpu(), osh) < 1e-5 and rel_err(sm.cpu(), osm) < 1e-5, far
+    tk = k.double().repeat_interleave(Hq // Hkv, dim=2)
+    s = torch.einsum("bthd,bnhd->bhtn", q.double(), tk) / math.sqrt(d)
+    mask = torch.arange(N)[None, :] > (n_sys + n_img + torch.arange(T))[:, None]
+    lse = torch.logsumexp(s.masked_fill(mask, float("-inf")), dim=-1).float().contiguous()
+    sh2, sm2 = ctx.score_tokens(q.to(DEV), k.to(DEV), row_lse=lse.to(DEV), **kw)
+    assert rel_err(sh2.cpu(), osh) < 1e-5 and rel_err(sm2.cpu(), osm) < 1e-5
+
+
 @pytest.mark.parametrize("N", [300, 1300])      # one launch for both passes / the two-pass kernels
 def test_score_tokens_mask_inside_span_and_strided_inputs(ctx, N):
     # query rows start INSIDE the scored span (all-rows reading): the causal mask bites in pass 1 too;
