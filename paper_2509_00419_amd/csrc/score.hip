@@ -1094,13 +1094,14 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
     w.shared_tiles = n_chunks >= 3 && n_chunks <= kSingleMaxChunks && (long long)d.B * d.Hkv * ((n_chunks + 3) / 4) >= kSharedMinWgs &&
                      sweep_rows <= kSharedMaxRows;
     w.single = w.shared_tiles || (n_chunks <= kSingleMaxChunks && sweep_rows <= kSingleMaxRows);
-    // Shared tiles, few workgroups: a wave's unit of work is a chunk over ALL keys, twice, and a launch of 2.25 workgroups
-    // per compute unit takes the time of three (one of 0.75 the time of one whose lone wave per SIMD hides nothing).
-    // Cutting the keys into runs (a launch per sweep, the runs' normaliser partials folded in between) makes the units
-    // small enough to load every SIMD evenly; it costs each workgroup its start-up (about three tiles' time) per run and
-    // the call two more launches.  Taken when the estimate below says it saves more than 12 us.
+    // The shared-tile kernel with the keys in runs.  A wave's unit of work is a chunk over ALL keys, twice: a launch of
+    // 2.25 workgroups per compute unit takes the time of three, one of 0.75 the time of one whose lone wave per SIMD hides
+    // nothing, and one long sequence has too few workgroups for the form at all.  Cutting the keys into runs (a launch
+    // per sweep, a workgroup per four chunks and run, the runs' normaliser partials folded in between) makes the units
+    // small and many; it costs each workgroup its start-up (about three tiles' time) per run and the call two more
+    // launches.  Taken when the estimate below says it saves more than 12 us over the form chosen so far.
     w.key_segs = 1;
-    if (w.shared_tiles) {
+    if (n_chunks >= 3 && n_chunks <= kSingleMaxChunks && (w.shared_tiles || !w.single)) {
         const long long wgs = (long long)d.B * d.Hkv * ((n_chunks + 3) / 4);
         const double tiles = (d.N + 31) / 32 + (d.n_img + 31) / 32;          // both sweeps
         // (measured, in us per tile sweep of a workgroup, with k = 1..5 workgroups resident on every compute unit: a lone
@@ -1111,12 +1112,17 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
             const long long turns = n_wg / 1280, rest = n_wg % 1280;
             return tiles_per_wg * (1.5 * (double)turns + per_tile[(rest + 255) / 256]);
         };
-        double best = launch_us(wgs, tiles) - 12.0;
-        for (int s = 2; s <= 8 && wgs <= 1280; s *= 2) {
+        // the form chosen so far: one launch of this kernel, or the two-pass kernels (0.53 PFLOP/s measured on one
+        // sequence of 16512 keys: 0.002 us per workgroup-tile of this kernel's size) with their fold
+        const double so_far = w.shared_tiles ? launch_us(wgs, tiles) : 0.002 * (double)wgs * tiles + 12.0;
+        double best = so_far - 12.0;
+        for (int s = 2; s <= 32 && (wgs <= 1280 || !w.shared_tiles); s *= 2) {
             if (tiles / 2 / s < 16) break;                                    // runs of at least 16 tiles
+            if (wgs * s < kSharedMinWgs || sweep_rows / s > kSharedMaxRows) continue;
             const double cut = launch_us(wgs * s, tiles / s + 2 * 3) + 10.0;
             if (cut < best) best = cut, w.key_segs = s;
         }
+        if (w.key_segs > 1) w.shared_tiles = w.single = true;
     }
     if (w.single) {
         w.rs = n_chunks;

@@ -116,7 +116,9 @@ def test_score_plan_reports_the_launch_form():
                          N * Hkv * 128, Hkv * 128, 128)
         return ctx.score_plan(d)
 
-    assert form(1, 16512, 128, 48, 8, 16384) == 0          # one long sequence: two passes
+    assert form(1, 2176, 64, 28, 4, 2048) == 0             # one sequence of config 2's length: two passes
+    assert form(1, 4608, 512, 32, 8, 4096) == 0            # 64 query chunks per KV head (more than a workgroup's waves hold in turn)
+    assert form(1, 16512, 128, 48, 8, 16384) == 3          # one long sequence: the shared-tile kernel, keys in sixteen runs
     assert form(1, 845, 64, 28, 4, 717) == 1               # one short sequence: one launch, a chunk per workgroup
     assert form(64, 986, 96, 32, 8, 890) == 2              # many short sequences: shared key tiles
     assert form(12, 5219, 128, 48, 8, 5091) == 3           # 2.25 workgroups per compute unit over 5219 keys: keys in runs
