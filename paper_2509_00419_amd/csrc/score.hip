@@ -1117,7 +1117,7 @@ ScoreWs score_ws(const lvlm_score_desc &d) {
         const double so_far = w.shared_tiles ? launch_us(wgs, tiles) : 0.002 * (double)wgs * tiles + 12.0;
         double best = so_far - 12.0;
         for (int s = 2; s <= 32 && (wgs <= 1280 || !w.shared_tiles); s *= 2) {
-            if (tiles / 2 / s < 16) break;                                    // runs of at least 16 tiles
+            if (tiles / 2 / s < 12) break;                                    // runs of at least 12 tiles
             if (wgs * s < kSharedMinWgs || sweep_rows / s > kSharedMaxRows) continue;
             const double cut = launch_us(wgs * s, tiles / s + 2 * 3) + 10.0;
             if (cut < best) best = cut, w.key_segs = s;
