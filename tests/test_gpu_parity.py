@@ -660,11 +660,15 @@ def test_no_call_writes_past_the_workspace_it_asked_for(ctx):
             score = torch.rand(B, n_img, generator=torch.Generator().manual_seed(181)).to(DEV)
             c.merge_compact([hid], score, img_begin=5, n_img=n_img, n_keep=n_keep, reserve=reserve)
         _guarded(merge)
-    for B, N, T, n_img in ((1, 5000, 64, 4800), (1, 845, 64, 717), (48, 986, 96, 890)):
+    # (two passes, a chunk per workgroup, shared tiles in one launch, shared tiles with the keys in runs)
+    for B, N, T, n_img, Hq, Hkv, form in ((1, 5000, 64, 4800, 8, 2, 0), (1, 845, 64, 717, 8, 2, 1), (48, 986, 96, 890, 8, 2, 2),
+                                          (4, 2200, 128, 2072, 48, 8, 3)):
         def score(c, reserve):
-            q = _rand((B, T, 8, 128), torch.bfloat16, 190).to(DEV)
-            k = _rand((B, N, 2, 128), torch.bfloat16, 191).to(DEV)
-            c.score_tokens(q, k, q_pos0=N - T, img_begin=N - T - n_img, n_img=n_img, reserve=reserve)
+            q = _rand((B, T, Hq, 128), torch.bfloat16, 190).to(DEV)
+            k = _rand((B, N, Hkv, 128), torch.bfloat16, 191).to(DEV)
+            kw = dict(q_pos0=N - T, img_begin=N - T - n_img, n_img=n_img)
+            assert c.score_plan(c.score_desc(q, k, **kw)) == form
+            c.score_tokens(q, k, reserve=reserve, **kw)
         _guarded(score)
 
 
